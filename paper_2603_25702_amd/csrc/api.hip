@@ -1,0 +1,407 @@
+// C ABI of libs2d2: argument validation, workspace carving, and the launch sequence of the
+// draft / verifier forward.  See include/s2d2.h for the contract of every entry point.
+#include "../../include/s2d2.h"
+#include "s2d2_internal.h"
+
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <stdarg.h>
+
+using namespace s2d2;
+
+static thread_local char g_err[512] = "";
+
+static int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+struct s2d2_ctx {
+  s2d2_model_desc desc;
+  s2d2_weights w;
+  s2d2_layer_weights* layers;
+  int32_t max_batch, max_block, rows_cap, logit_cap;
+  hipStream_t stream;
+  uint8_t* ws;
+  size_t ws_bytes;
+  // carved workspace
+  Plan plan;
+  int32_t* tmp_count;
+  float* h;
+  void* a;
+  float* qkv;
+  void* qbuf;
+  void* obuf;
+  void* ffn;
+  void* af;
+  void* kwin;
+  void* vwin;
+  VocabWs vws;
+};
+
+namespace {
+
+struct Carver {
+  uint8_t* base;
+  size_t off = 0;
+  template <typename T> T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+int elt_size(int dtype) { return dtype == S2D2_BF16 ? 2 : 4; }
+
+int32_t check_desc(const s2d2_model_desc* d) {
+  if (!d) return fail(S2D2_EINVAL, "model description is NULL");
+  if (d->dtype != S2D2_F32 && d->dtype != S2D2_BF16) return fail(S2D2_EINVAL, "dtype must be S2D2_F32 or S2D2_BF16");
+  if (d->n_layers < 1 || d->d_model < 32 || d->vocab < 2) return fail(S2D2_EINVAL, "n_layers, d_model or vocab out of range");
+  if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) return fail(S2D2_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (d->head_dim != 32 && d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return fail(S2D2_EINVAL, "head_dim must be 32, 64, 128 or 256");
+  const int kq = d->dtype == S2D2_BF16 ? 32 : 16;  // one MFMA fragment must not straddle the end of K
+  if (d->d_model % kq || (d->n_q_heads * d->head_dim) % kq) return fail(S2D2_EINVAL, "d_model and Hq*D must be multiples of %d", kq);
+  if (d->n_experts == 0) {
+    if (d->d_ffn < kq || d->d_ffn % kq) return fail(S2D2_EINVAL, "d_ffn must be a positive multiple of %d", kq);
+    if (d->top_k || d->d_expert) return fail(S2D2_EINVAL, "top_k and d_expert must be 0 for a dense model");
+  } else {
+    if (d->n_experts < 0 || d->top_k < 1 || d->top_k > d->n_experts || d->d_expert < kq || d->d_expert % kq)
+      return fail(S2D2_EINVAL, "MoE shape out of range");
+    return fail(S2D2_EINVAL, "MoE models are not supported by this build yet");
+  }
+  if (d->mask_id < 0 || d->mask_id >= d->vocab) return fail(S2D2_EINVAL, "mask_id outside the vocabulary");
+  if (d->vocab > 8192 * 256) return fail(S2D2_EINVAL, "vocab above 2097152 is not supported");
+  if (!(d->rope_theta > 1.0f) || !(d->rms_eps >= 0.0f)) return fail(S2D2_EINVAL, "rope_theta must exceed 1 and rms_eps be non-negative");
+  return S2D2_OK;
+}
+
+int32_t check_limits(int32_t max_batch, int32_t max_block) {
+  if (max_batch < 1 || max_batch > 1024) return fail(S2D2_EINVAL, "max_batch must be in [1, 1024]");
+  if (max_block < 1 || max_block > S2D2_MAX_BLOCK) return fail(S2D2_EINVAL, "max_block must be in [1, %d]", S2D2_MAX_BLOCK);
+  return S2D2_OK;
+}
+
+// Lays the workspace out; with base == NULL only measures.
+size_t carve(s2d2_ctx* c, uint8_t* base) {
+  const s2d2_model_desc& d = c->desc;
+  Carver cv{base};
+  const size_t R = c->rows_cap, LR = c->logit_cap, NB = c->max_batch;
+  const size_t es = elt_size(d.dtype);
+  c->plan.counts = cv.take<int32_t>(8);
+  c->tmp_count = cv.take<int32_t>(8);
+  c->plan.row_token = cv.take<int32_t>(R);
+  c->plan.row_pos = cv.take<int32_t>(R);
+  c->plan.row_seq = cv.take<int32_t>(R);
+  c->plan.row_lo = cv.take<int32_t>(R);
+  c->plan.row_hi = cv.take<int32_t>(R);
+  c->plan.logit_src = cv.take<int32_t>(LR);
+  c->plan.logit_seq = cv.take<int32_t>(LR);
+  c->plan.logit_idx = cv.take<int32_t>(LR);
+  c->plan.seq_row0 = cv.take<int32_t>(NB);
+  c->plan.seq_rows = cv.take<int32_t>(NB);
+  c->plan.seq_lead = cv.take<int32_t>(NB);
+  c->plan.seq_j = cv.take<int32_t>(NB);
+  c->plan.seq_L = cv.take<int32_t>(NB);
+  c->h = cv.take<float>(R * d.d_model);
+  c->a = cv.take<uint8_t>(R * d.d_model * es);
+  c->qkv = cv.take<float>(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim);
+  c->qbuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es);
+  c->obuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es);
+  c->ffn = cv.take<uint8_t>(R * (size_t)d.d_ffn * es);
+  c->af = cv.take<uint8_t>(LR * (size_t)d.d_model * es);
+  c->kwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
+  c->vwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
+  c->vws.chunks = vocab_chunks(d.vocab);
+  c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+int32_t check_launch(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(S2D2_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
+  return S2D2_OK;
+}
+
+int32_t check_kv(const s2d2_ctx* c, const s2d2_kv_view* kv) {
+  if (!kv || !kv->k_pages || !kv->v_pages || !kv->page_table || !kv->seq_len) return fail(S2D2_EINVAL, "kv view or one of its pointers is NULL");
+  if (kv->n_pages < 1 || kv->page_size < 1 || kv->max_pages_per_seq < 1) return fail(S2D2_EINVAL, "kv view: n_pages, page_size and max_pages_per_seq must be positive");
+  if (((uintptr_t)kv->k_pages | (uintptr_t)kv->v_pages) & 15) return fail(S2D2_EINVAL, "kv pages must be 16-byte aligned");
+  return S2D2_OK;
+}
+
+int32_t check_state(const s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t B) {
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (N < 1 || N > c->max_batch) return fail(S2D2_EINVAL, "N=%d outside [1, max_batch=%d]", N, c->max_batch);
+  if (B < 1 || B > c->max_block) return fail(S2D2_EINVAL, "B=%d outside [1, max_block=%d]", B, c->max_block);
+  if (!st || !st->block_tokens || !st->block_pos0 || !st->carry_tokens) return fail(S2D2_EINVAL, "block state or one of its pointers is NULL");
+  return S2D2_OK;
+}
+
+KvGeom geom(const s2d2_ctx* c, const s2d2_kv_view* kv) {
+  return KvGeom{kv->page_table, kv->seq_len, kv->n_pages, kv->page_size, kv->max_pages_per_seq,
+                c->desc.n_kv_heads, c->desc.head_dim};
+}
+
+// One forward over the planned window rows; K/V of every window row go to k_stage/v_stage
+// ([n_layers, rows_cap, Hkv, D]) if given, else to a one-layer scratch.
+int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void* k_stage, void* v_stage, float* logits) {
+  const s2d2_model_desc& d = c->desc;
+  const int dt = d.dtype, R = 3 * N * B, LR = N * B, es = elt_size(dt);  // grid bounds of this call
+  const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+  hipStream_t st = c->stream;
+  const KvGeom g = geom(c, kv);
+  const size_t lds = attention_generic_lds_bytes(g, 3 * B);
+  if (lds > 160 * 1024) return fail(S2D2_ENOSPC, "attention needs %zu bytes of LDS for max_pages_per_seq*page_size=%d keys (limit 163840)", lds, kv->max_pages_per_seq * kv->page_size);
+  const size_t stage_layer = (size_t)c->rows_cap * d.n_kv_heads * d.head_dim * es;
+  const size_t page_layer = (size_t)kv->n_pages * d.n_kv_heads * kv->page_size * d.head_dim * es;
+  const int32_t* n_rows = c->plan.counts;
+  launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h);
+  for (int l = 0; l < d.n_layers; ++l) {
+    const s2d2_layer_weights& L = c->layers[l];
+    void* kw = k_stage ? (uint8_t*)k_stage + l * stage_layer : c->kwin;
+    void* vw = v_stage ? (uint8_t*)v_stage + l * stage_layer : c->vwin;
+    launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a);
+    launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n);
+    launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw);
+    launch_attention_generic(st, dt, c->qbuf, kw, vw, (const uint8_t*)kv->k_pages + l * page_layer,
+                             (const uint8_t*)kv->v_pages + l * page_layer, g, c->plan, R, d.n_q_heads, c->obuf, lds);
+    launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model);
+    launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a);
+    launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn);
+    launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model);
+  }
+  const int32_t* n_logit = c->plan.counts + 1;
+  launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af);
+  launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab);
+  return check_launch("forward");
+}
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
+__global__ void clear_unplanned_kernel(int n, const int32_t* __restrict__ row_of, float* a, float* b) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n && row_of[i] < 0) { a[i] = 0.f; b[i] = 0.f; }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* s2d2_last_error(void) { return g_err; }
+const char* s2d2_version(void) { return "s2d2-gfx950 0.1"; }
+
+int64_t s2d2_stage_rows(int32_t max_batch, int32_t max_block) {
+  if (check_limits(max_batch, max_block)) return S2D2_EINVAL;
+  return (int64_t)3 * max_batch * max_block;
+}
+
+int64_t s2d2_workspace_bytes(const s2d2_model_desc* desc, int32_t max_batch, int32_t max_block) {
+  int32_t rc = check_desc(desc);
+  if (rc) return rc;
+  rc = check_limits(max_batch, max_block);
+  if (rc) return rc;
+  s2d2_ctx tmp;
+  memset(&tmp, 0, sizeof(tmp));
+  tmp.desc = *desc;
+  tmp.max_batch = max_batch;
+  tmp.max_block = max_block;
+  tmp.rows_cap = 3 * max_batch * max_block;
+  tmp.logit_cap = max_batch * max_block;
+  return (int64_t)carve(&tmp, nullptr);
+}
+
+int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, int32_t max_batch,
+                    int32_t max_block, void* stream, void* workspace, size_t workspace_bytes, s2d2_ctx** out) {
+  if (!out) return fail(S2D2_EINVAL, "out is NULL");
+  *out = nullptr;
+  int32_t rc = check_desc(desc);
+  if (rc) return rc;
+  rc = check_limits(max_batch, max_block);
+  if (rc) return rc;
+  if (!weights || !weights->embed || !weights->unembed || !weights->norm_f || !weights->layers) return fail(S2D2_EINVAL, "weights or one of its pointers is NULL");
+  for (int l = 0; l < desc->n_layers; ++l) {
+    const s2d2_layer_weights& L = weights->layers[l];
+    if (!L.norm1 || !L.wqkv || !L.wo || !L.norm2) return fail(S2D2_EINVAL, "layer %d: attention weights missing", l);
+    if (desc->n_experts == 0 && (!L.wgu || !L.wdown)) return fail(S2D2_EINVAL, "layer %d: FFN weights missing", l);
+    if (desc->n_experts > 0 && (!L.router || !L.e_wgu || !L.e_wdown)) return fail(S2D2_EINVAL, "layer %d: MoE weights missing", l);
+    if (((uintptr_t)L.wqkv | (uintptr_t)L.wo | (uintptr_t)L.wgu | (uintptr_t)L.wdown) & 15) return fail(S2D2_EINVAL, "layer %d: weights must be 16-byte aligned", l);
+  }
+  if (((uintptr_t)weights->embed | (uintptr_t)weights->unembed) & 15) return fail(S2D2_EINVAL, "embed/unembed must be 16-byte aligned");
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(S2D2_EINVAL, "workspace is NULL or not 256-byte aligned");
+  const int64_t need = s2d2_workspace_bytes(desc, max_batch, max_block);
+  if (need < 0) return (int32_t)need;
+  if (workspace_bytes < (size_t)need) return fail(S2D2_ENOSPC, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)need);
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(S2D2_EARCH, "no usable HIP device");
+  }
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(S2D2_EARCH, "device is %s, this library is built for gfx950", prop.gcnArchName);
+
+  s2d2_ctx* c = (s2d2_ctx*)calloc(1, sizeof(s2d2_ctx));
+  if (!c) return fail(S2D2_ENOSPC, "out of host memory");
+  c->desc = *desc;
+  c->w = *weights;
+  c->layers = (s2d2_layer_weights*)malloc(sizeof(s2d2_layer_weights) * desc->n_layers);
+  if (!c->layers) { free(c); return fail(S2D2_ENOSPC, "out of host memory"); }
+  memcpy(c->layers, weights->layers, sizeof(s2d2_layer_weights) * desc->n_layers);
+  c->w.layers = c->layers;
+  c->max_batch = max_batch;
+  c->max_block = max_block;
+  c->rows_cap = 3 * max_batch * max_block;
+  c->logit_cap = max_batch * max_block;
+  c->stream = (hipStream_t)stream;
+  c->ws = (uint8_t*)workspace;
+  c->ws_bytes = workspace_bytes;
+  carve(c, c->ws);
+  if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
+  *out = c;
+  return S2D2_OK;
+}
+
+int32_t s2d2_destroy(s2d2_ctx* ctx) {
+  if (!ctx) return fail(S2D2_EINVAL, "ctx is NULL");
+  free(ctx->layers);
+  free(ctx);
+  return S2D2_OK;
+}
+
+int32_t s2d2_set_stream(s2d2_ctx* ctx, void* stream) {
+  if (!ctx) return fail(S2D2_EINVAL, "ctx is NULL");
+  ctx->stream = (hipStream_t)stream;
+  return S2D2_OK;
+}
+
+static int32_t check_params(const s2d2_params* p) {
+  if (!p) return fail(S2D2_EINVAL, "params is NULL");
+  if (p->mode != S2D2_GREEDY) return fail(S2D2_EINVAL, "only S2D2_GREEDY drafting is supported by this build");
+  if (!(p->gamma > 0.f)) return fail(S2D2_EINVAL, "gamma must be positive");
+  if (!(p->tau >= 0.f)) return fail(S2D2_EINVAL, "tau must be non-negative");
+  return S2D2_OK;
+}
+
+static int32_t check_draft_out(const s2d2_draft_out* o) {
+  if (!o || !o->logits || !o->logit_row_of || !o->xhat || !o->p || !o->lse || !o->margin || !o->entropy_n ||
+      !o->unmask || !o->n_hi || !o->span_start || !o->span_len)
+    return fail(S2D2_EINVAL, "draft output or one of its pointers is NULL");
+  if ((uintptr_t)o->logits & 15) return fail(S2D2_EINVAL, "draft logits must be 16-byte aligned");
+  return S2D2_OK;
+}
+
+static int32_t check_verify_out(const s2d2_verify_out* o) {
+  if (!o || !o->logits_ver || !o->logit_row_of || !o->q || !o->lse_ver || !o->k_stage || !o->v_stage ||
+      !o->stage_row0 || !o->stage_lead)
+    return fail(S2D2_EINVAL, "verify output or one of its pointers is NULL");
+  if (((uintptr_t)o->logits_ver | (uintptr_t)o->k_stage | (uintptr_t)o->v_stage) & 15) return fail(S2D2_EINVAL, "verify logits and K/V stage must be 16-byte aligned");
+  return S2D2_OK;
+}
+
+int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
+                   const s2d2_params* prm, const s2d2_draft_out* out) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) || (rc = check_draft_out(out))) return rc;
+  const s2d2_model_desc& d = c->desc;
+  launch_plan(c->stream, false, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
+              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr);
+  if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
+  launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
+                     c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n);
+  launch_draft_finish(c->stream, N, B, d.mask_id, prm->tau, st->block_tokens, out->xhat, out->p, out->lse,
+                      out->margin, out->entropy_n, out->unmask, out->n_hi);
+  return check_launch("s2d2_draft");
+}
+
+int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
+                    const s2d2_params* prm, const s2d2_draft_out* draft, const s2d2_verify_out* out) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) ||
+      (rc = check_draft_out(draft)) || (rc = check_verify_out(out)))
+    return rc;
+  const s2d2_model_desc& d = c->desc;
+  launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead);
+  if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
+  hipLaunchKernelGGL(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
+                     out->logit_row_of, out->q, out->lse_ver);
+  launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
+                     c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver);
+  return check_launch("s2d2_verify");
+}
+
+int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t B, const s2d2_params* prm,
+                    const s2d2_draft_out* draft, const s2d2_verify_out* ver, const s2d2_accept_out* out) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_params(prm)) || (rc = check_draft_out(draft)) ||
+      (rc = check_verify_out(ver)))
+    return rc;
+  if (!out || !out->n_accept || !out->n_commit || !out->resampled || !out->u_used) return fail(S2D2_EINVAL, "accept output or one of its pointers is NULL");
+  launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
+                draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
+                ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
+                out->n_accept, out->n_commit, out->resampled, out->u_used);
+  return check_launch("s2d2_accept");
+}
+
+int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, const s2d2_draft_out* draft,
+                       const s2d2_verify_out* ver, const int32_t* n_accept) {
+  int32_t rc;
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (N < 1 || N > c->max_batch || B < 1 || B > c->max_block) return fail(S2D2_EINVAL, "N or B outside the limits given at create");
+  if ((rc = check_kv(c, kv)) || (rc = check_draft_out(draft)) || (rc = check_verify_out(ver))) return rc;
+  if (!n_accept) return fail(S2D2_EINVAL, "n_accept is NULL");
+  const KvGeom g = geom(c, kv);
+  launch_kv_append(c->stream, c->desc.dtype, c->desc.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
+                   ver->k_stage, ver->v_stage, ver->stage_row0, ver->stage_lead, draft->span_len, n_accept,
+                   kv->seq_len, kv->status, B);
+  return check_launch("s2d2_kv_append");
+}
+
+int32_t s2d2_block_advance(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
+                           uint32_t* step_dev) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv))) return rc;
+  launch_block_advance(c->stream, N, B, c->desc.mask_id, kv->seq_len, st->block_pos0, st->block_tokens,
+                       st->carry_tokens, step_dev);
+  return check_launch("s2d2_block_advance");
+}
+
+int32_t s2d2_commit_threshold(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t B,
+                              const s2d2_draft_out* draft) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_draft_out(draft))) return rc;
+  launch_commit_threshold(c->stream, N, B, st->block_tokens, draft->xhat, draft->unmask);
+  return check_launch("s2d2_commit_threshold");
+}
+
+int32_t s2d2_vocab_draft_stats(s2d2_ctx* c, const float* logits, int32_t rows, int32_t* xhat, float* p, float* lse,
+                               float* margin, float* entropy_n) {
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (rows < 0 || rows > c->logit_cap) return fail(S2D2_EINVAL, "rows=%d outside [0, max_batch*max_block=%d]", rows, c->logit_cap);
+  if (!logits || !xhat || !p || !lse || !margin || !entropy_n) return fail(S2D2_EINVAL, "NULL argument");
+  if ((uintptr_t)logits & 15) return fail(S2D2_EINVAL, "logits must be 16-byte aligned");
+  if (rows == 0) return S2D2_OK;
+  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
+  launch_vocab_draft(c->stream, logits, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, xhat, p, lse,
+                     margin, entropy_n);
+  return check_launch("s2d2_vocab_draft_stats");
+}
+
+int32_t s2d2_vocab_score(s2d2_ctx* c, const float* logits_ver, int32_t rows, const int32_t* token, float* q, float* lse) {
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (rows < 0 || rows > c->logit_cap) return fail(S2D2_EINVAL, "rows=%d outside [0, max_batch*max_block=%d]", rows, c->logit_cap);
+  if (!logits_ver || !token || !q || !lse) return fail(S2D2_EINVAL, "NULL argument");
+  if ((uintptr_t)logits_ver & 15) return fail(S2D2_EINVAL, "logits must be 16-byte aligned");
+  if (rows == 0) return S2D2_OK;
+  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
+  launch_vocab_score(c->stream, logits_ver, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, token, q, lse);
+  return check_launch("s2d2_vocab_score");
+}
+
+}  // extern "C"

@@ -1,0 +1,136 @@
+// Attention of one window row over the paged prefix cache plus the visible in-window keys.
+//
+// attn_generic_kernel: plain fp32 arithmetic, one workgroup per (window row, query head).  It is
+// the reference-quality path (used for fp32 models and as the cross-check of the MFMA kernel):
+// scores of all keys go to LDS, a block-wide softmax follows, then P*V with the head dimension
+// across lanes.  Visibility inside the window follows the plan (Eq. 3 / Eq. 4): window row w is
+// visible to row r iff row_lo[r] <= w < row_hi[r] or w == r; every cached position is visible.
+#include "s2d2_internal.h"
+#include "../../include/s2d2.h"
+
+namespace s2d2 {
+
+__device__ __forceinline__ float wave_max(float v) {
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_generic_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_win, const T* __restrict__ v_win,
+    const T* __restrict__ k_pages, const T* __restrict__ v_pages, KvGeom g, Plan p, int Hq,
+    T* __restrict__ o, float scale) {
+  extern __shared__ float smem[];
+  const int r = blockIdx.x, hq = blockIdx.y;
+  if (r >= p.counts[0]) return;
+  const int D = g.head_dim, Hkv = g.n_kv_heads, ps = g.page_size;
+  const int kvh = hq / (Hq / Hkv);
+  const int n = p.row_seq[r];
+  const int S = max(0, min(g.seq_len[n], g.max_pages_per_seq * ps));
+  const int row0 = p.seq_row0[n], nw = p.seq_rows[n];
+  const int lo = p.row_lo[r], hi = p.row_hi[r];
+  const int total = S + nw;
+  float* s_q = smem;            // [D]
+  float* s_red = smem + D;      // [256 + 8]
+  float* s_sc = s_red + 264;    // [total]
+  const int tid = threadIdx.x;
+
+  for (int d = tid; d < D; d += 256) s_q[d] = to_f32(q[((size_t)r * Hq + hq) * D + d]) * scale;
+  __syncthreads();
+
+  const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
+  float lmax = -INFINITY;
+  for (int s = tid; s < total; s += 256) {
+    const T* kp;
+    bool vis = true;
+    if (s < S) {
+      const int page = min(max(pt[s / ps], 0), g.n_pages - 1);
+      kp = k_pages + (((size_t)page * Hkv + kvh) * ps + (s % ps)) * D;
+    } else {
+      const int w = row0 + (s - S);
+      vis = (w >= lo && w < hi) || w == r;
+      kp = k_win + ((size_t)w * Hkv + kvh) * D;
+    }
+    float dot = -INFINITY;
+    if (vis) {
+      dot = 0.f;
+      for (int d = 0; d < D; ++d) dot += s_q[d] * to_f32(kp[d]);
+    }
+    s_sc[s] = dot;
+    lmax = fmaxf(lmax, dot);
+  }
+  lmax = wave_max(lmax);
+  if ((tid & 63) == 0) s_red[tid >> 6] = lmax;
+  __syncthreads();
+  const float m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  __syncthreads();
+  float lsum = 0.f;
+  for (int s = tid; s < total; s += 256) {
+    const float e = __expf(s_sc[s] - m);   // exp(-inf) = 0 for invisible keys
+    s_sc[s] = e;
+    lsum += e;
+  }
+  lsum = wave_sum(lsum);
+  if ((tid & 63) == 0) s_red[tid >> 6] = lsum;
+  __syncthreads();
+  const float denom = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+  __syncthreads();
+
+  const int nslice = 256 / D, d = tid % D, sl = tid / D;
+  float acc = 0.f;
+  if (sl < nslice) {
+    for (int s = sl; s < total; s += nslice) {
+      const float pw = s_sc[s];
+      if (pw == 0.f) continue;
+      const T* vp;
+      if (s < S) {
+        const int page = min(max(pt[s / ps], 0), g.n_pages - 1);
+        vp = v_pages + (((size_t)page * Hkv + kvh) * ps + (s % ps)) * D;
+      } else {
+        vp = v_win + ((size_t)(row0 + (s - S)) * Hkv + kvh) * D;
+      }
+      acc += pw * to_f32(vp[d]);
+    }
+  }
+  s_red[tid] = acc;
+  __syncthreads();
+  if (tid < D) {
+    float t = 0.f;
+    for (int i = 0; i < nslice; ++i) t += s_red[i * D + tid];
+    o[((size_t)r * Hq + hq) * D + tid] = from_f32<T>(t / denom);
+  }
+}
+
+// Raises the dynamic-LDS limit of the kernels once (160 KB per workgroup on gfx950).
+int attention_init() {
+  hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_generic_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  return e == hipSuccess ? 0 : -1;
+}
+
+size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows) {
+  const size_t keys = (size_t)g.max_pages_per_seq * g.page_size + max_window_rows;
+  return (g.head_dim + 264 + keys) * sizeof(float);
+}
+
+void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,
+                              const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,
+                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes) {
+  const float scale = 1.0f / sqrtf((float)g.head_dim);
+  dim3 grid(rows_cap, Hq), block(256);
+  if (dtype == S2D2_BF16) {
+    hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds_bytes, st, (const bf16_t*)q,
+                       (const bf16_t*)k_win, (const bf16_t*)v_win, (const bf16_t*)k_pages_layer,
+                       (const bf16_t*)v_pages_layer, g, p, Hq, (bf16_t*)o, scale);
+  } else {
+    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds_bytes, st, (const float*)q,
+                       (const float*)k_win, (const float*)v_win, (const float*)k_pages_layer,
+                       (const float*)v_pages_layer, g, p, Hq, (float*)o, scale);
+  }
+}
+
+}  // namespace s2d2

@@ -1,0 +1,238 @@
+// Window construction and per-sequence state kernels (integer work only).
+//
+// plan_kernel builds, on the device and without host involvement, the packed list of window
+// rows of a draft forward (block positions not yet cached, Eq. 4 visibility) or of a verifier
+// forward (the 2L window of Eq. 3 with uncached committed tokens riding in front as causal
+// rows).  kv_append / block_advance / commit_threshold update the per-sequence state
+// (Algorithm 1 append and new block; Algorithm 2 commit).
+#include "s2d2_internal.h"
+#include "../../include/s2d2.h"
+
+namespace s2d2 {
+
+__global__ __launch_bounds__(1024) void plan_kernel(
+    int verify, int N, int B, int mask_id, int ar_mask, const int32_t* __restrict__ seq_len,
+    const int32_t* __restrict__ pos0, const int32_t* __restrict__ block,
+    const int32_t* __restrict__ carry, const int32_t* __restrict__ xhat, Plan p,
+    int32_t* __restrict__ logit_row_of, int32_t* __restrict__ span_start,
+    int32_t* __restrict__ span_len, int32_t* __restrict__ stage_row0, int32_t* __restrict__ stage_lead) {
+  __shared__ int32_t s_rows[1024];
+  __shared__ int32_t s_lrows[1024];
+  const int n = threadIdx.x;
+  int S = 0, c = 0, nc = 0, j = B, L = 0, n_masked = 0, rows = 0, lrows = 0, lead = 0;
+  if (n < N) {
+    S = seq_len[n];
+    const int P0 = pos0[n];
+    c = max(0, min(B, S - P0));
+    nc = max(0, min(B, P0 - S));
+    const int32_t* blk = block + (size_t)n * B;
+    for (int i = 0; i < B; ++i) {
+      const bool m = blk[i] == mask_id;
+      n_masked += m;
+      if (m && j == B) j = i;
+    }
+    while (j + L < B && blk[j + L] == mask_id) ++L;
+    c = min(c, j);
+    lead = nc + (j - c);
+    if (verify) { rows = lead + 2 * L; lrows = L; }
+    else        { rows = nc + (B - c); lrows = n_masked; }
+  }
+  s_rows[n] = rows;
+  s_lrows[n] = lrows;
+  __syncthreads();
+  // inclusive Hillis-Steele scan over the 1024 slots
+  for (int off = 1; off < 1024; off <<= 1) {
+    int a = 0, b = 0;
+    if (n >= off) { a = s_rows[n - off]; b = s_lrows[n - off]; }
+    __syncthreads();
+    s_rows[n] += a;
+    s_lrows[n] += b;
+    __syncthreads();
+  }
+  if (n == 1023) { p.counts[0] = s_rows[1023]; p.counts[1] = s_lrows[1023]; }
+  if (n >= N) return;
+  const int row0 = s_rows[n] - rows;
+  int k = s_lrows[n] - lrows;
+  p.seq_row0[n] = row0;
+  p.seq_rows[n] = rows;
+  p.seq_lead[n] = lead;
+  p.seq_j[n] = j;
+  p.seq_L[n] = L;
+  const int32_t* blk = block + (size_t)n * B;
+  const int32_t* car = carry + (size_t)n * B;
+  if (!verify) {
+    span_start[n] = j;
+    span_len[n] = L;
+    for (int i = 0; i < B; ++i) logit_row_of[(size_t)n * B + i] = -1;
+    for (int t = 0; t < rows; ++t) {
+      const int r = row0 + t;
+      int tok, hi;
+      if (t < nc) {                       // carried token of a finished block: causal
+        tok = car[t];
+        hi = r + 1;
+      } else {
+        const int i = c + (t - nc);
+        tok = blk[i];
+        hi = (i < j && ar_mask) ? r + 1 : row0 + rows;   // Eq. 4: committed prefix causal, rest sees all
+        if (tok == mask_id) {
+          p.logit_src[k] = r;
+          p.logit_seq[k] = n;
+          p.logit_idx[k] = i;
+          logit_row_of[(size_t)n * B + i] = k;
+          ++k;
+        }
+      }
+      p.row_token[r] = tok;
+      p.row_pos[r] = S + t;
+      p.row_seq[r] = n;
+      p.row_lo[r] = row0;
+      p.row_hi[r] = hi;
+    }
+  } else {
+    stage_row0[n] = row0;
+    stage_lead[n] = lead;
+    for (int i = 0; i < B; ++i) logit_row_of[(size_t)n * B + i] = -1;
+    const int32_t* xh = xhat + (size_t)n * B;
+    for (int t = 0; t < lead + L; ++t) {  // causal half: carry, pending committed, drafted C_t
+      const int r = row0 + t;
+      int tok;
+      if (t < nc) tok = car[t];
+      else if (t < lead) tok = blk[c + (t - nc)];
+      else tok = xh[j + (t - lead)];
+      p.row_token[r] = tok;
+      p.row_pos[r] = S + t;
+      p.row_seq[r] = n;
+      p.row_lo[r] = row0;
+      p.row_hi[r] = r + 1;
+    }
+    for (int q = 0; q < L; ++q) {         // [MASK] copies: see causal rows strictly left, and themselves
+      const int r = row0 + lead + L + q;
+      p.row_token[r] = mask_id;
+      p.row_pos[r] = S + lead + q;
+      p.row_seq[r] = n;
+      p.row_lo[r] = row0;
+      p.row_hi[r] = row0 + lead + q;
+      p.logit_src[k] = r;
+      p.logit_seq[k] = n;
+      p.logit_idx[k] = j + q;
+      logit_row_of[(size_t)n * B + j + q] = k;
+      ++k;
+    }
+  }
+}
+
+void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
+                 const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
+                 const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
+                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, verify ? 1 : 0, N, B, mask_id, ar_mask,
+                     seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
+                     stage_row0, stage_lead);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cache append: copy staged K/V rows [0, lead + n_accept) of each sequence to its next logical
+// positions.  One workgroup per (sequence, staged row, layer); 16-byte copies.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void kv_append_copy_kernel(
+    int elt_bytes, int per_seq, int rows_cap, KvGeom g, uint8_t* __restrict__ k_pages,
+    uint8_t* __restrict__ v_pages, const uint8_t* __restrict__ k_stage, const uint8_t* __restrict__ v_stage,
+    const int32_t* __restrict__ stage_row0, const int32_t* __restrict__ stage_lead,
+    const int32_t* __restrict__ n_accept, const int32_t* __restrict__ span_len) {
+  const int n = blockIdx.x / per_seq, t = blockIdx.x % per_seq, l = blockIdx.y;
+  const int acc = max(0, min(n_accept[n], span_len[n]));
+  const int rows = stage_lead[n] + acc;
+  if (t >= rows) return;
+  const int S = g.seq_len[n];
+  const int cap = g.max_pages_per_seq * g.page_size;
+  if (S + rows > cap) return;  // whole sequence skipped; the update kernel flags it
+  const int s = S + t;
+  const int page = g.page_table[(size_t)n * g.max_pages_per_seq + s / g.page_size];
+  if (page < 0 || page >= g.n_pages) return;
+  const int slot = s % g.page_size;
+  const size_t head_bytes = (size_t)g.head_dim * elt_bytes;
+  const size_t src = ((size_t)l * rows_cap + (stage_row0[n] + t)) * g.n_kv_heads * head_bytes;
+  const size_t layer_off = (size_t)l * g.n_pages * g.n_kv_heads * g.page_size * head_bytes;
+  const int vec_per_head = (int)(head_bytes / 16);
+  for (int v = threadIdx.x; v < g.n_kv_heads * vec_per_head; v += blockDim.x) {
+    const int h = v / vec_per_head, e = v % vec_per_head;
+    const size_t dst = layer_off + (((size_t)page * g.n_kv_heads + h) * g.page_size + slot) * head_bytes + (size_t)e * 16;
+    const size_t so = src + (size_t)h * head_bytes + (size_t)e * 16;
+    *(uint4*)(k_pages + dst) = *(const uint4*)(k_stage + so);
+    *(uint4*)(v_pages + dst) = *(const uint4*)(v_stage + so);
+  }
+}
+
+__global__ void kv_append_commit_kernel(int N, KvGeom g, const int32_t* __restrict__ stage_lead,
+                                        const int32_t* __restrict__ n_accept,
+                                        const int32_t* __restrict__ span_len, int32_t* __restrict__ seq_len,
+                                        int32_t* __restrict__ status) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  const int acc = max(0, min(n_accept[n], span_len[n]));
+  const int rows = stage_lead[n] + acc;
+  const int S = seq_len[n];
+  if (S + rows > g.max_pages_per_seq * g.page_size) {
+    if (status) status[n] = S2D2_ENOSPC;
+    return;
+  }
+  seq_len[n] = S + rows;
+}
+
+void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
+                      void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
+                      const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
+                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B) {
+  const int elt = dtype == S2D2_BF16 ? 2 : 4;
+  const int per_seq = 2 * B;  // upper bound of staged causal rows per sequence (carry + block)
+  hipLaunchKernelGGL(kv_append_copy_kernel, dim3(N * per_seq, n_layers), dim3(256), 0, st, elt, per_seq,
+                     rows_cap, g, (uint8_t*)k_pages, (uint8_t*)v_pages, (const uint8_t*)k_stage,
+                     (const uint8_t*)v_stage, stage_row0, stage_lead, n_accept, span_len);
+  hipLaunchKernelGGL(kv_append_commit_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, g, stage_lead,
+                     n_accept, span_len, seq_len, status);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Alg. 1: replace a block that holds no [MASK] by a fresh [MASK]^B block right after it.
+// Uncached committed tokens of the finished block move to the carry list (capacity B); if they
+// would not fit, the block is left as it is.
+// ---------------------------------------------------------------------------------------------
+__global__ void block_advance_kernel(int N, int B, int mask_id, const int32_t* __restrict__ seq_len,
+                                     int32_t* __restrict__ pos0, int32_t* __restrict__ block,
+                                     int32_t* __restrict__ carry, uint32_t* step_dev) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n == 0 && step_dev) *step_dev += 1u;
+  if (n >= N) return;
+  int32_t* blk = block + (size_t)n * B;
+  int32_t* car = carry + (size_t)n * B;
+  for (int i = 0; i < B; ++i)
+    if (blk[i] == mask_id) return;
+  const int S = seq_len[n], P0 = pos0[n];
+  const int c = max(0, min(B, S - P0)), nc = max(0, min(B, P0 - S));
+  if (nc + (B - c) > B) return;
+  for (int i = c; i < B; ++i) car[nc + (i - c)] = blk[i];
+  for (int i = 0; i < B; ++i) blk[i] = mask_id;
+  pos0[n] = P0 + B;
+}
+
+void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
+                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev) {
+  hipLaunchKernelGGL(block_advance_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, B, mask_id, seq_len,
+                     pos0, block, carry, step_dev);
+}
+
+__global__ void commit_threshold_kernel(int N, int B, int32_t* __restrict__ block,
+                                        const int32_t* __restrict__ xhat, const uint64_t* __restrict__ unmask) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= N * B) return;
+  const int n = idx / B, i = idx % B;
+  if ((unmask[n] >> i) & 1ull) block[idx] = xhat[idx];
+}
+
+void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const int32_t* xhat,
+                             const uint64_t* unmask) {
+  hipLaunchKernelGGL(commit_threshold_kernel, dim3((N * B + 255) / 256), dim3(256), 0, st, N, B, block, xhat,
+                     unmask);
+}
+
+}  // namespace s2d2

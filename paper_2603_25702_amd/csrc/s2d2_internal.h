@@ -1,0 +1,117 @@
+// Internal declarations shared by the HIP translation units of libs2d2.  Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace s2d2 {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+
+// ---- device-resident description of one forward's window rows (built by the plan kernel) ----
+// Rows of all sequences are packed back to back; the rows of sequence n are
+// [seq_row0[n], seq_row0[n] + seq_rows[n]).  Row r attends to every cached position of its
+// sequence, to the window rows [row_lo[r], row_hi[r]) and to itself.
+struct Plan {
+  int32_t* counts;      // [0] = number of window rows, [1] = number of logit rows
+  int32_t* row_token;   // [rows_cap]
+  int32_t* row_pos;     // [rows_cap] absolute position (RoPE phase)
+  int32_t* row_seq;     // [rows_cap]
+  int32_t* row_lo;      // [rows_cap]
+  int32_t* row_hi;      // [rows_cap]
+  int32_t* logit_src;   // [logit_cap] window row whose hidden state feeds logit row k
+  int32_t* logit_seq;   // [logit_cap]
+  int32_t* logit_idx;   // [logit_cap] block index scored by logit row k
+  int32_t* seq_row0;    // [max_batch]
+  int32_t* seq_rows;    // [max_batch]
+  int32_t* seq_lead;    // [max_batch] leading causal rows before C_t (carry + pending)
+  int32_t* seq_j;       // [max_batch] first masked block index (B if none)
+  int32_t* seq_L;       // [max_batch] |C_t|
+};
+
+struct KvGeom {
+  const int32_t* page_table;
+  const int32_t* seq_len;
+  int32_t n_pages, page_size, max_pages_per_seq;
+  int32_t n_kv_heads, head_dim;
+};
+
+enum GemmEpilogue {
+  EPI_STORE_F32 = 0,   // out_f32[m, n] = acc                       (ldo floats per row)
+  EPI_ADD_F32 = 1,     // out_f32[m, n] += acc                      (residual stream)
+  EPI_SWIGLU = 2,      // out_act[m, n] = silu(acc_gate) * acc_up   (W holds [2, N, K])
+};
+
+// plan.hip
+void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
+                 const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
+                 const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
+                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead);
+void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
+                      void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
+                      const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
+                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B);
+void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
+                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev);
+void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const int32_t* xhat,
+                             const uint64_t* unmask);
+
+// elementwise.hip
+void launch_embed(hipStream_t st, int dtype, const void* embed, int d, const Plan& p, int rows_cap, float* h);
+// out[r] = rmsnorm(h[src(r)]) * gain as `dtype`; src = gather[r] if gather else r; rows from *count.
+void launch_rmsnorm(hipStream_t st, int dtype, const float* h, const float* gain, int d, float eps,
+                    const int32_t* count, const int32_t* gather, int rows_cap, void* out);
+void launch_rope_split(hipStream_t st, int dtype, const float* qkv, const Plan& p, int rows_cap, int Hq,
+                       int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out);
+
+// gemm.hip : Y[m, n] = sum_k X[m, k] * W[n, k], X and W in `dtype`, fp32 accumulation.
+void launch_gemm(hipStream_t st, int dtype, GemmEpilogue epi, const void* X, int ldx, const void* W, int K,
+                 int N, const int32_t* m_count, int m_cap, void* out, int ldo);
+
+// attention.hip
+void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,
+                              const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,
+                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes);
+int attention_init();
+size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
+
+// vocab.hip
+struct VocabWs {
+  float* part;       // [rows_cap_logits, chunks, 8] partial statistics
+  int32_t chunks;
+};
+int vocab_chunks(int V);
+void launch_vocab_draft(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
+                        const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
+                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n);
+void launch_vocab_score(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
+                        const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
+                        const int32_t* token, float* q, float* lse);
+void launch_draft_finish(hipStream_t st, int N, int B, int mask_id, float tau, const int32_t* block,
+                         int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n,
+                         uint64_t* unmask, int32_t* n_hi);
+void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t step, const uint32_t* step_dev,
+                   float gamma, int resample, const int32_t* span_start, const int32_t* span_len,
+                   const float* logits_d, const int32_t* row_of_d, const float* logits_v,
+                   const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
+                   const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
+                   int32_t* resampled, float* u_used);
+
+}  // namespace s2d2

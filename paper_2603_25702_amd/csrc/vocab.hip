@@ -1,0 +1,394 @@
+// Vocabulary-wide kernels: SampleFromLogits / ScoreFromLogits statistics, the threshold set of
+// Algorithm 2, and the accept scan + residual resampling of Algorithm 3.
+//
+// The statistics kernels stream each fp32 logit row exactly once with 16-byte coalesced loads
+// (HBM-bound: rows * V * 4 bytes), keep an online (max, sum-exp, entropy numerator, arg-max,
+// second max) per lane, and reduce with wavefront shuffles, then LDS, then a fixed-order merge
+// over the row's chunks, so results do not depend on scheduling.
+#include "s2d2_internal.h"
+#include "../../include/s2d2.h"
+
+namespace s2d2 {
+
+static constexpr int VCHUNK = 4096;  // logits per workgroup: 256 lanes x 4 float4
+
+int vocab_chunks(int V) { return (V + VCHUNK - 1) / VCHUNK; }
+
+struct Stat {
+  float m;    // max logit
+  float z;    // sum exp(l - m)
+  float e;    // sum exp(l - m) * (l - m)
+  float m2;   // second largest logit (equals m if the max is attained twice)
+  int arg;    // lowest index attaining m
+};
+
+__device__ __forceinline__ Stat stat_empty() { return Stat{-INFINITY, 0.f, 0.f, -INFINITY, 0x7fffffff}; }
+
+__device__ __forceinline__ Stat stat_merge(const Stat& a, const Stat& b) {
+  Stat r;
+  r.m = fmaxf(a.m, b.m);
+  r.arg = a.m > b.m ? a.arg : (b.m > a.m ? b.arg : min(a.arg, b.arg));
+  r.m2 = fmaxf(fminf(a.m, b.m), fmaxf(a.m2, b.m2));
+  const float da = a.m - r.m, db = b.m - r.m;  // <= 0, or NaN when both are -inf
+  const float fa = a.z > 0.f ? __expf(da) : 0.f, fb = b.z > 0.f ? __expf(db) : 0.f;
+  r.z = a.z * fa + b.z * fb;
+  r.e = (a.z > 0.f ? fa * (a.e + da * a.z) : 0.f) + (b.z > 0.f ? fb * (b.e + db * b.z) : 0.f);
+  return r;
+}
+
+__device__ __forceinline__ Stat stat_shfl_xor(const Stat& s, int off) {
+  Stat r;
+  r.m = __shfl_xor(s.m, off, 64);
+  r.z = __shfl_xor(s.z, off, 64);
+  r.e = __shfl_xor(s.e, off, 64);
+  r.m2 = __shfl_xor(s.m2, off, 64);
+  r.arg = __shfl_xor(s.arg, off, 64);
+  return r;
+}
+
+// part[row][chunk][8] = {m, z, e, m2, arg}
+__global__ __launch_bounds__(256) void vocab_partial_kernel(const float* __restrict__ logits, int V,
+                                                            const int32_t* __restrict__ count, int chunks,
+                                                            float* __restrict__ part) {
+  __shared__ Stat s_w[4];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  if (row >= *count) return;
+  const float* x = logits + (size_t)row * V;
+  const int base = chunk * VCHUNK;
+  const int tid = threadIdx.x;
+  float v[16];
+  int idx0[4];
+  const bool vec_ok = (V & 3) == 0;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int i = base + t * 1024 + tid * 4;
+    idx0[t] = i;
+    if (vec_ok && i + 3 < V) {
+      const float4 f = *(const float4*)(x + i);
+      v[4 * t] = f.x; v[4 * t + 1] = f.y; v[4 * t + 2] = f.z; v[4 * t + 3] = f.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[4 * t + e] = (i + e < V) ? x[i + e] : -INFINITY;
+    }
+  }
+  Stat s = stat_empty();
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const float l = v[t];
+    const int i = idx0[t >> 2] + (t & 3);
+    if (l > s.m) { s.m2 = s.m; s.m = l; s.arg = i; }
+    else if (l > s.m2) s.m2 = l;
+  }
+  if (s.m > -INFINITY) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const float d = v[t] - s.m;
+      const float ex = __expf(d);          // exp(-inf) = 0 for padded slots
+      s.z += ex;
+      s.e += ex > 0.f ? ex * d : 0.f;
+    }
+  }
+  for (int off = 1; off < 64; off <<= 1) s = stat_merge(s, stat_shfl_xor(s, off));
+  if ((tid & 63) == 0) s_w[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    Stat r = stat_merge(stat_merge(s_w[0], s_w[1]), stat_merge(s_w[2], s_w[3]));
+    float* o = part + ((size_t)row * chunks + chunk) * 8;
+    o[0] = r.m; o[1] = r.z; o[2] = r.e; o[3] = r.m2; o[4] = __int_as_float(r.arg);
+  }
+}
+
+__device__ __forceinline__ Stat merge_chunks(const float* part, int row, int chunks) {
+  Stat r = stat_empty();
+  for (int c = 0; c < chunks; ++c) {
+    const float* o = part + ((size_t)row * chunks + c) * 8;
+    Stat s{o[0], o[1], o[2], o[3], __float_as_int(o[4])};
+    r = stat_merge(r, s);
+  }
+  return r;
+}
+
+// SampleFromLogits (greedy): x_hat = arg-max, p = softmax probability of it, plus lse, margin, H/ln V.
+__global__ void vocab_draft_final_kernel(const float* __restrict__ part, int chunks, int V,
+                                         const int32_t* __restrict__ count,
+                                         const int32_t* __restrict__ logit_seq,
+                                         const int32_t* __restrict__ logit_idx, int B,
+                                         int32_t* __restrict__ xhat, float* __restrict__ p,
+                                         float* __restrict__ lse, float* __restrict__ margin,
+                                         float* __restrict__ entropy_n) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= *count) return;
+  const Stat s = merge_chunks(part, row, chunks);
+  const int o = logit_seq ? logit_seq[row] * B + logit_idx[row] : row;
+  const float inv = 1.0f / s.z;
+  xhat[o] = s.arg;
+  p[o] = inv;
+  lse[o] = s.m + logf(s.z);
+  margin[o] = inv - expf(s.m2 - s.m) * inv;
+  entropy_n[o] = fmaxf(0.f, logf(s.z) - s.e * inv) / logf((float)V);
+}
+
+// ScoreFromLogits: q = softmax(logits_ver)[token], lse.
+__global__ void vocab_score_final_kernel(const float* __restrict__ part, int chunks, int V,
+                                         const float* __restrict__ logits, const int32_t* __restrict__ count,
+                                         const int32_t* __restrict__ logit_seq,
+                                         const int32_t* __restrict__ logit_idx, int B,
+                                         const int32_t* __restrict__ token, float* __restrict__ q,
+                                         float* __restrict__ lse) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= *count) return;
+  const Stat s = merge_chunks(part, row, chunks);
+  const int o = logit_seq ? logit_seq[row] * B + logit_idx[row] : row;
+  const float l = s.m + logf(s.z);
+  const int tok = token[o];
+  lse[o] = l;
+  q[o] = (tok >= 0 && tok < V) ? expf(logits[(size_t)row * V + tok] - l) : 0.f;
+}
+
+void launch_vocab_draft(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
+                        const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
+                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n) {
+  hipLaunchKernelGGL(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
+                     ws.chunks, ws.part);
+  hipLaunchKernelGGL(vocab_draft_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
+                     count, logit_seq, logit_idx, B, xhat, p, lse, margin, entropy_n);
+}
+
+void launch_vocab_score(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
+                        const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
+                        const int32_t* token, float* q, float* lse) {
+  hipLaunchKernelGGL(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
+                     ws.chunks, ws.part);
+  hipLaunchKernelGGL(vocab_score_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
+                     logits, count, logit_seq, logit_idx, B, token, q, lse);
+}
+
+// Per sequence: defaults for committed positions, threshold set S = {i in M: p_i > tau} U {argmax p}.
+__global__ void draft_finish_kernel(int N, int B, int mask_id, float tau, const int32_t* __restrict__ block,
+                                    int32_t* __restrict__ xhat, float* __restrict__ p, float* __restrict__ lse,
+                                    float* __restrict__ margin, float* __restrict__ entropy_n,
+                                    uint64_t* __restrict__ unmask, int32_t* __restrict__ n_hi) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  uint64_t bits = 0;
+  int hi = 0, best = -1;
+  float best_p = -1.f;
+  for (int i = 0; i < B; ++i) {
+    const int o = n * B + i;
+    if (block[o] == mask_id) {
+      const float pi = p[o];
+      if (pi > tau) { bits |= 1ull << i; ++hi; }
+      if (pi > best_p) { best_p = pi; best = i; }   // strict: lowest index wins ties
+    } else {
+      xhat[o] = -1; p[o] = 0.f; lse[o] = 0.f; margin[o] = 0.f; entropy_n[o] = 0.f;
+    }
+  }
+  if (best >= 0) bits |= 1ull << best;
+  unmask[n] = bits;
+  n_hi[n] = hi;
+}
+
+void launch_draft_finish(hipStream_t st, int N, int B, int mask_id, float tau, const int32_t* block,
+                         int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n,
+                         uint64_t* unmask, int32_t* n_hi) {
+  hipLaunchKernelGGL(draft_finish_kernel, dim3((N + 63) / 64), dim3(64), 0, st, N, B, mask_id, tau, block, xhat, p,
+                     lse, margin, entropy_n, unmask, n_hi);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Counter-based uniforms: Philox-4x32 with 10 rounds (Salmon et al., SC'11), written from the
+// published round function.  key = seed, counter = (step, sequence, block index, stream).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                      uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+__device__ __forceinline__ float uniform01(uint64_t seed, uint32_t step, uint32_t seq, uint32_t idx, uint32_t stream) {
+  const uint32_t w = philox_first_word(step, seq, idx, stream, (uint32_t)seed, (uint32_t)(seed >> 32));
+  return ((float)(w >> 9) + 0.5f) * (1.0f / 8388608.0f);  // odd multiple of 2^-24: exact
+}
+
+// Scan of one non-negative float per thread over a 256-thread block with a fixed tree.
+// Returns the inclusive prefix; *excl is the inclusive prefix of the previous thread (0 for
+// thread 0), so the intervals [excl, incl) of consecutive threads tile [0, total) exactly;
+// *total is the inclusive prefix of the last thread.  s_w needs 4 floats.
+__device__ __forceinline__ float block_scan_256(float v, float* s_w, float* excl, float* total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int off = 1; off < 64; off <<= 1) {
+    const float t = __shfl_up(v, off, 64);
+    if (lane >= off) v += t;
+  }
+  __syncthreads();
+  if (lane == 63) s_w[w] = v;
+  __syncthreads();
+  float pre = 0.f;
+  for (int i = 0; i < w; ++i) pre += s_w[i];
+  const float incl = v + pre;
+  const float prev = __shfl_up(incl, 1, 64);
+  *excl = lane == 0 ? pre : prev;
+  *total = s_w[3] + ((s_w[0] + s_w[1]) + s_w[2]);
+  return incl;
+}
+
+static constexpr int RTILE = 256;     // residual tile: one wavefront x float4
+static constexpr int RMAX_TILES = 8192;
+
+// One workgroup per sequence: accept scan over C_t (thread 0), then, if a drafted token failed,
+// draw from the residual (P_ver - P_draft)_+ by inverse CDF in ascending vocabulary order.
+__global__ __launch_bounds__(256) void accept_kernel(
+    int B, int V, uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev, float gamma, int resample,
+    const int32_t* __restrict__ span_start, const int32_t* __restrict__ span_len,
+    const float* __restrict__ logits_d, const int32_t* __restrict__ row_of_d,
+    const float* __restrict__ logits_v, const int32_t* __restrict__ row_of_v,
+    const int32_t* __restrict__ xhat, const float* __restrict__ p, const float* __restrict__ lse_d,
+    const float* __restrict__ q, const float* __restrict__ lse_v, int32_t* __restrict__ block,
+    int32_t* __restrict__ n_accept, int32_t* __restrict__ n_commit, int32_t* __restrict__ resampled,
+    float* __restrict__ u_used) {
+  __shared__ float s_tile[RMAX_TILES];
+  __shared__ float s_w[4];
+  __shared__ int s_nacc;
+  __shared__ int s_tile_sel;
+  __shared__ float s_before;
+  const int n = blockIdx.x, tid = threadIdx.x;
+  const int j = span_start[n], L = span_len[n];
+  const uint32_t stp = step + (step_dev ? *step_dev : 0u);
+  for (int i = tid; i < B; i += 256) u_used[(size_t)n * B + i] = 0.f;
+  __syncthreads();
+  if (tid == 0) {
+    int acc = 0;
+    for (; acc < L; ++acc) {
+      const int o = n * B + j + acc;
+      const float u = uniform01(seed, stp, (uint32_t)n, (uint32_t)(j + acc), 0u);
+      u_used[o] = u;
+      const float pi = p[o], qi = q[o];
+      const bool ok = gamma == 1.0f ? (u * pi < qi) : (u < fminf(1.0f, powf(qi / pi, gamma)));
+      if (!ok) break;
+    }
+    s_nacc = acc;
+  }
+  __syncthreads();
+  const int acc = s_nacc;
+  for (int i = tid; i < acc; i += 256) block[n * B + j + i] = xhat[n * B + j + i];
+  if (acc >= L || !resample) {
+    if (tid == 0) { n_accept[n] = acc; n_commit[n] = acc; resampled[n] = -1; }
+    return;
+  }
+  // ---- residual at block index i: r(v) = max(0, Q(v) - P(v)) ----
+  const int o = n * B + j + acc;
+  const float* ld = logits_d + (size_t)row_of_d[o] * V;
+  const float* lv = logits_v + (size_t)row_of_v[o] * V;
+  const float zd = lse_d[o], zv = lse_v[o];
+  const int tiles = (V + RTILE - 1) / RTILE;
+  const int lane = tid & 63, w = tid >> 6;
+  const bool vec_ok = (V & 3) == 0;
+  for (int t = w; t < tiles; t += 4) {
+    const int i0 = t * RTILE + lane * 4;
+    float r = 0.f;
+    if (vec_ok && i0 + 3 < V) {
+      const float4 a = *(const float4*)(ld + i0), b = *(const float4*)(lv + i0);
+      r = ((fmaxf(0.f, __expf(b.x - zv) - __expf(a.x - zd)) + fmaxf(0.f, __expf(b.y - zv) - __expf(a.y - zd))) +
+           fmaxf(0.f, __expf(b.z - zv) - __expf(a.z - zd))) + fmaxf(0.f, __expf(b.w - zv) - __expf(a.w - zd));
+    } else {
+      for (int e = 0; e < 4; ++e)
+        if (i0 + e < V) r += fmaxf(0.f, __expf(lv[i0 + e] - zv) - __expf(ld[i0 + e] - zd));
+    }
+    for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
+    if (lane == 0) s_tile[t] = r;
+  }
+  __syncthreads();
+  // scan tile sums: thread t owns tiles [t*per, (t+1)*per)
+  const int per = (tiles + 255) / 256;
+  float mine = 0.f;
+  for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) mine += s_tile[t];
+  float total, excl;
+  const float incl = block_scan_256(mine, s_w, &excl, &total);
+  const float u2 = uniform01(seed, stp, (uint32_t)n, (uint32_t)(j + acc), 1u);
+  const float target = u2 * total;
+  if (tid == 0) { s_tile_sel = -1; s_before = 0.f; }
+  __syncthreads();
+  if (excl <= target && target < incl) {  // exactly one thread: the intervals tile [0, total)
+    float run = excl, before = excl;
+    int sel = -1, last = -1;
+    for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) {
+      const float ts = s_tile[t];
+      if (ts > 0.f) { last = t; before = run; }
+      if (ts > 0.f && run + ts > target) { sel = t; break; }
+      run += ts;
+    }
+    if (sel < 0) sel = last;          // rounding: take the thread's last tile that has mass
+    s_tile_sel = sel;
+    s_before = before;
+  }
+  __syncthreads();
+  int sel = s_tile_sel;
+  int token = -1;
+  if (total > 0.f && sel < 0) {  // target landed at or beyond the total by rounding: last tile with mass
+    if (tid == 0) {
+      for (int t = tiles - 1; t >= 0; --t)
+        if (s_tile[t] > 0.f) { s_tile_sel = t; break; }
+      float run = 0.f;
+      for (int t = 0; t < s_tile_sel; ++t) run += s_tile[t];
+      s_before = run;
+    }
+    __syncthreads();
+    sel = s_tile_sel;
+  }
+  if (total > 0.f && sel >= 0 && w == 0) {  // wave 0 walks the selected tile in index order
+    const int i0 = sel * RTILE + lane * 4;
+    float r4[4];
+    float ls = 0.f;
+    for (int e = 0; e < 4; ++e) {
+      r4[e] = (i0 + e < V) ? fmaxf(0.f, __expf(lv[i0 + e] - zv) - __expf(ld[i0 + e] - zd)) : 0.f;
+      ls += r4[e];
+    }
+    float inc = ls;
+    for (int off = 1; off < 64; off <<= 1) {
+      const float t = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += t;
+    }
+    float run = s_before + (inc - ls);
+    int cand = 0x7fffffff, last_pos = -1;
+    for (int e = 0; e < 4; ++e) {
+      if (r4[e] > 0.f) last_pos = i0 + e;
+      run += r4[e];
+      if (cand == 0x7fffffff && r4[e] > 0.f && run > target) cand = i0 + e;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      cand = min(cand, __shfl_xor(cand, off, 64));
+      last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
+    }
+    token = cand != 0x7fffffff ? cand : last_pos;
+  }
+  if (tid == 0) {
+    if (token < 0) token = xhat[o];  // residual without mass in fp32 (p and q equal to rounding): keep the draft
+    block[o] = token;
+    n_accept[n] = acc;
+    n_commit[n] = acc + 1;
+    resampled[n] = token;
+  }
+}
+
+void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t step, const uint32_t* step_dev,
+                   float gamma, int resample, const int32_t* span_start, const int32_t* span_len,
+                   const float* logits_d, const int32_t* row_of_d, const float* logits_v,
+                   const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
+                   const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
+                   int32_t* resampled, float* u_used) {
+  hipLaunchKernelGGL(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample,
+                     span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
+                     n_accept, n_commit, resampled, u_used);
+}
+
+}  // namespace s2d2

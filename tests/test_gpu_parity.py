@@ -1,0 +1,115 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle (see harness.py)."""
+import numpy as np
+import pytest
+import torch
+
+import s2d2_inputs as I
+from paper_2603_25702_amd import Params
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TINY = I.CONFIGS[1].cfg
+SMALL_BF16 = I.ModelCfg("small-bf16", 2, 512, 8, 4, 128, 1536, 32000)
+
+
+def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True):
+    run = H.GpuRun(case)
+    rep = H.Report()
+    for s in range(steps):
+        prm = Params(step=s, seed=1234, **(prm_kw or {}))
+        run.step(prm, advance=False)
+        g = run.fetch()
+        H.check_step(case, run, g, prm, seqs=seqs, rep=rep, check_logits=check_logits)
+        if advance:
+            run.eng.s2d2_block_advance(run.kv, run.st, case.N, case.B, None)
+        H.sync_case_from_gpu(case, run)
+    return run, rep
+
+
+def test_config1_tiny_fp32_one_step_free_running():
+    wl = I.CONFIGS[1]
+    case = H.make_case(wl.cfg, wl.batch, wl.block, [wl.prefix_min], seed=0, synthetic_kv=False)
+    run, rep = run_steps(case, 1)
+    print("config1:", rep)
+    assert rep.max_logit_err_draft < 1e-4 and rep.max_logit_err_verify < 1e-4
+    assert rep.exempt_xhat == rep.exempt_ratio == rep.exempt_resample == rep.exempt_tau == 0
+    assert rep.n_commit[0] >= 1
+
+
+def test_tiny_fp32_many_steps_cross_block_boundaries_with_jittered_norms():
+    cfg = TINY
+    case = H.make_case(cfg, 2, 3, [37, 64], seed=5, synthetic_kv=False, norm_jitter=0.2, page_size=8, room=64)
+    run, rep = run_steps(case, 8)
+    print("tiny multi-step:", rep)
+    assert max(s.pos0 for s in case.states) > 64  # some block was completed and rolled
+    assert rep.max_logit_err_draft < 1e-4
+
+
+def test_small_bf16_ragged_batch_paged():
+    case = H.make_case(SMALL_BF16, 3, 8, [100, 257, 31], seed=2, synthetic_kv=True, page_size=16, room=64)
+    run, rep = run_steps(case, 3)
+    print("small bf16:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL
+
+
+def test_small_bf16_real_prefill_b4():
+    case = H.make_case(SMALL_BF16, 1, 4, [96], seed=3, synthetic_kv=False, page_size=16, room=64)
+    run, rep = run_steps(case, 4)
+    print("small bf16 prefill:", rep)
+
+
+def test_draft_mask_flag_and_block_size_one():
+    # B = 1: drafter and verifier see the same thing, every token is accepted (q == p up to rounding)
+    case = H.make_case(TINY, 2, 1, [20, 33], seed=7, synthetic_kv=False, page_size=8, room=32)
+    run = H.GpuRun(case)
+    prm = Params(step=0, seed=9)
+    run.step(prm, advance=False)
+    g = run.fetch()
+    np.testing.assert_allclose(g["logits_ver"][:2], g["logits"][:2], rtol=0, atol=1e-4)
+    np.testing.assert_allclose(g["q"], g["p"], atol=1e-5)
+    H.check_step(case, run, g, prm)
+    # ar_mask = 0: committed in-block prefix sees the whole block
+    case = H.make_case(TINY, 1, 4, [16], seed=8, synthetic_kv=False, page_size=8, room=32)
+    case.states[0].block[:2] = [5, 6]
+    run = H.GpuRun(case)
+    for ar in (1, 0):
+        prm = Params(step=0, seed=9, ar_mask=ar)
+        run.push_state()
+        run.eng.s2d2_draft(run.kv, run.st, 1, 4, prm, run.d)
+        g = run.fetch()
+        st = case.states[0]
+        ck, cv = case.oracle_cache(0)
+        from oracle import s2d2_oracle as O
+        od = O.draft(TINY, case.W, st, ck, cv, 0.9, bool(ar))
+        rows = [g["logit_row_of"][0][i] for i in od.win.logit_index]
+        np.testing.assert_allclose(g["logits"][rows], od.logits, atol=2e-4 * np.abs(od.logits).max())
+
+
+def test_same_inputs_give_bit_identical_outputs():
+    case = H.make_case(SMALL_BF16, 2, 4, [50, 70], seed=4, synthetic_kv=True, page_size=16, room=32)
+    outs = []
+    for _ in range(2):
+        run = H.GpuRun(case)
+        run.step(Params(step=3, seed=77), advance=True)
+        g = run.fetch()
+        outs.append(g)
+    for k in outs[0]:
+        if k in ("logits", "logits_ver"):  # rows beyond the planned count are unspecified
+            n = int((outs[0]["logit_row_of"] >= 0).sum()) if k == "logits" else int((outs[0]["logit_row_of_ver"] >= 0).sum())
+            assert np.array_equal(outs[0][k][:n], outs[1][k][:n]), k
+        else:
+            assert np.array_equal(outs[0][k], outs[1][k]), k
+
+
+def test_kv_append_reports_enospc_without_writing():
+    case = H.make_case(TINY, 1, 4, [30], seed=1, synthetic_kv=True, page_size=8, room=1)  # capacity 32
+    run = H.GpuRun(case)
+    before = run.kv.k.clone()
+    run.step(Params(step=0, seed=2), advance=False)
+    g = run.fetch()
+    lead_plus_acc = int(g["n_accept"][0])
+    if 30 + lead_plus_acc > 32:
+        assert g["status"][0] == -2 and g["seq_len"][0] == 30 and torch.equal(before, run.kv.k)
+    else:
+        assert g["status"][0] == 0 and g["seq_len"][0] == 30 + lead_plus_acc
