@@ -243,6 +243,24 @@ int32_t s2d2_vocab_draft_stats(s2d2_ctx* ctx, const float* logits, int32_t rows,
 int32_t s2d2_vocab_score(s2d2_ctx* ctx, const float* logits_ver, int32_t rows,
                          const int32_t* token, float* q, float* lse);
 
+/* Measurement aid (not part of the method): while profiling is on, every kernel launch of a
+ * forward is bracketed by HIP events on the context's stream and attributed to a class.
+ * s2d2_profile_stop synchronises the stream, sums the event times and turns profiling off.
+ *   launches    kernel launches of the class
+ *   ms          summed event-to-event time
+ *   bytes       algorithmic HBM bytes of those launches: weight matrix once for a GEMM, K and V
+ *               of the cached prefix once for attention, the fp32 logit rows once for the
+ *               vocabulary kernels (window rows and tiny outputs are not counted)
+ * Classes: 0 GEMM (weight streaming), 1 attention, 2 vocabulary, 3 everything else. */
+#define S2D2_PROFILE_CLASSES 4
+typedef struct {
+  int64_t launches;
+  double ms;
+  double bytes;
+} s2d2_profile;
+int32_t s2d2_profile_start(s2d2_ctx* ctx, int32_t max_launches);
+int32_t s2d2_profile_stop(s2d2_ctx* ctx, s2d2_profile* out /* host [S2D2_PROFILE_CLASSES] */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,8 +22,9 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
-    "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score",
+    "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
+PROFILE_CLASSES = ("gemm", "attention", "vocab", "other")
 
 
 class S2D2Error(RuntimeError):
@@ -75,6 +76,10 @@ class AcceptOutC(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("n_accept", "n_commit", "resampled", "u_used")]
 
 
+class ProfileC(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double)]
+
+
 def lib_path() -> str:
     return os.path.join(HERE, "libs2d2.so")
 
@@ -115,7 +120,9 @@ def load_library():
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
     lib.s2d2_vocab_draft_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 5
     lib.s2d2_vocab_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
-    for name in ("s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
+    lib.s2d2_profile_start.argtypes = [C.c_void_p, C.c_int32]
+    lib.s2d2_profile_stop.argtypes = [C.c_void_p, C.POINTER(ProfileC)]
+    for name in ("s2d2_profile_start", "s2d2_profile_stop", "s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
                  "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
@@ -325,6 +332,15 @@ class Engine:
 
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
+
+    def s2d2_profile_start(self, max_launches: int):
+        _check(self.lib, self.lib.s2d2_profile_start(self.ctx, max_launches))
+
+    def s2d2_profile_stop(self):
+        out = (ProfileC * len(PROFILE_CLASSES))()
+        _check(self.lib, self.lib.s2d2_profile_stop(self.ctx, out))
+        return {n: dict(launches=int(out[i].launches), ms=float(out[i].ms), bytes=float(out[i].bytes))
+                for i, n in enumerate(PROFILE_CLASSES)}
 
     def s2d2_vocab_draft_stats(self, logits: torch.Tensor):
         rows = logits.shape[0]

@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <stdarg.h>
+#include <vector>
 
 using namespace s2d2;
 
@@ -41,6 +42,12 @@ struct s2d2_ctx {
   void* kwin;
   void* vwin;
   VocabWs vws;
+  // profiling (measurement aid)
+  bool prof_on;
+  int32_t prof_cap;
+  struct ProfRec { int cls; double bytes; hipEvent_t a, b; };
+  std::vector<ProfRec>* prof;
+  std::vector<hipEvent_t>* prof_pool;
 };
 
 namespace {
@@ -121,6 +128,19 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   return (cv.off + 255) & ~(size_t)255;
 }
 
+struct ProfScope {
+  s2d2_ctx* c;
+  hipEvent_t stop = nullptr;
+  ProfScope(s2d2_ctx* ctx, int cls, double bytes) : c(ctx) {
+    if (!c->prof_on || (int32_t)c->prof->size() >= c->prof_cap) return;
+    hipEvent_t a = (*c->prof_pool)[2 * c->prof->size()], b = (*c->prof_pool)[2 * c->prof->size() + 1];
+    (void)hipEventRecord(a, c->stream);
+    c->prof->push_back({cls, bytes, a, b});
+    stop = b;
+  }
+  ~ProfScope() { if (stop) (void)hipEventRecord(stop, c->stream); }
+};
+
 int32_t check_launch(const char* what) {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(S2D2_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
@@ -160,24 +180,24 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const size_t stage_layer = (size_t)c->rows_cap * d.n_kv_heads * d.head_dim * es;
   const size_t page_layer = (size_t)kv->n_pages * d.n_kv_heads * kv->page_size * d.head_dim * es;
   const int32_t* n_rows = c->plan.counts;
-  launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h);
+  { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   for (int l = 0; l < d.n_layers; ++l) {
     const s2d2_layer_weights& L = c->layers[l];
     void* kw = k_stage ? (uint8_t*)k_stage + l * stage_layer : c->kwin;
     void* vw = v_stage ? (uint8_t*)v_stage + l * stage_layer : c->vwin;
-    launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a);
-    launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n);
-    launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw);
-    launch_attention_generic(st, dt, c->qbuf, kw, vw, (const uint8_t*)kv->k_pages + l * page_layer,
-                             (const uint8_t*)kv->v_pages + l * page_layer, g, c->plan, R, d.n_q_heads, c->obuf, lds);
-    launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model);
-    launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a);
-    launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn);
-    launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model);
+    { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
+    { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
+    { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw); }
+    { ProfScope ps(c, 1, 0.0); launch_attention_generic(st, dt, c->qbuf, kw, vw, (const uint8_t*)kv->k_pages + l * page_layer,
+                             (const uint8_t*)kv->v_pages + l * page_layer, g, c->plan, R, d.n_q_heads, c->obuf, lds); }
+    { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
+    { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
+    { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
+    { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model); }
   }
   const int32_t* n_logit = c->plan.counts + 1;
-  launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af);
-  launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab);
+  { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af); }
+  { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
   return check_launch("forward");
 }
 
@@ -268,6 +288,11 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
 
 int32_t s2d2_destroy(s2d2_ctx* ctx) {
   if (!ctx) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (ctx->prof_pool) {
+    for (hipEvent_t e : *ctx->prof_pool) (void)hipEventDestroy(e);
+    delete ctx->prof_pool;
+    delete ctx->prof;
+  }
   free(ctx->layers);
   free(ctx);
   return S2D2_OK;
@@ -308,13 +333,13 @@ int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* 
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) || (rc = check_draft_out(out))) return rc;
   const s2d2_model_desc& d = c->desc;
-  launch_plan(c->stream, false, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
-              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr);
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, false, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
+              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
-  launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
-                     c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n);
-  launch_draft_finish(c->stream, N, B, d.mask_id, prm->tau, st->block_tokens, out->xhat, out->p, out->lse,
-                      out->margin, out->entropy_n, out->unmask, out->n_hi);
+  { ProfScope ps(c, 2, 0.0); launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
+                     c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n); }
+  { ProfScope ps(c, 2, 0.0); launch_draft_finish(c->stream, N, B, d.mask_id, prm->tau, st->block_tokens, out->xhat, out->p, out->lse,
+                      out->margin, out->entropy_n, out->unmask, out->n_hi); }
   return check_launch("s2d2_draft");
 }
 
@@ -325,13 +350,13 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
       (rc = check_draft_out(draft)) || (rc = check_verify_out(out)))
     return rc;
   const s2d2_model_desc& d = c->desc;
-  launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
-              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead);
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
   hipLaunchKernelGGL(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
                      out->logit_row_of, out->q, out->lse_ver);
-  launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
-                     c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver);
+  { ProfScope ps(c, 2, 0.0); launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
+                     c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver); }
   return check_launch("s2d2_verify");
 }
 
@@ -342,10 +367,10 @@ int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t 
       (rc = check_verify_out(ver)))
     return rc;
   if (!out || !out->n_accept || !out->n_commit || !out->resampled || !out->u_used) return fail(S2D2_EINVAL, "accept output or one of its pointers is NULL");
-  launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
+  { ProfScope ps(c, 2, 0.0); launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
                 draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
                 ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
-                out->n_accept, out->n_commit, out->resampled, out->u_used);
+                out->n_accept, out->n_commit, out->resampled, out->u_used); }
   return check_launch("s2d2_accept");
 }
 
@@ -357,9 +382,9 @@ int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B
   if ((rc = check_kv(c, kv)) || (rc = check_draft_out(draft)) || (rc = check_verify_out(ver))) return rc;
   if (!n_accept) return fail(S2D2_EINVAL, "n_accept is NULL");
   const KvGeom g = geom(c, kv);
-  launch_kv_append(c->stream, c->desc.dtype, c->desc.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
+  { ProfScope ps(c, 3, 0.0); launch_kv_append(c->stream, c->desc.dtype, c->desc.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
                    ver->k_stage, ver->v_stage, ver->stage_row0, ver->stage_lead, draft->span_len, n_accept,
-                   kv->seq_len, kv->status, B);
+                   kv->seq_len, kv->status, B); }
   return check_launch("s2d2_kv_append");
 }
 
@@ -378,6 +403,37 @@ int32_t s2d2_commit_threshold(s2d2_ctx* c, const s2d2_block_state* st, int32_t N
   if ((rc = check_state(c, st, N, B)) || (rc = check_draft_out(draft))) return rc;
   launch_commit_threshold(c->stream, N, B, st->block_tokens, draft->xhat, draft->unmask);
   return check_launch("s2d2_commit_threshold");
+}
+
+int32_t s2d2_profile_start(s2d2_ctx* c, int32_t max_launches) {
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(S2D2_EINVAL, "max_launches must be in [1, 2^20]");
+  if (!c->prof) { c->prof = new std::vector<s2d2_ctx::ProfRec>(); c->prof_pool = new std::vector<hipEvent_t>(); }
+  while ((int32_t)c->prof_pool->size() < 2 * max_launches) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return fail(S2D2_ELAUNCH, "hipEventCreate failed");
+    c->prof_pool->push_back(e);
+  }
+  c->prof->clear();
+  c->prof_cap = max_launches;
+  c->prof_on = true;
+  return S2D2_OK;
+}
+
+int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
+  if (!c || !out) return fail(S2D2_EINVAL, "NULL argument");
+  if (!c->prof_on) return fail(S2D2_EINVAL, "profiling is not on");
+  c->prof_on = false;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(S2D2_ELAUNCH, "stream synchronize failed");
+  for (int k = 0; k < S2D2_PROFILE_CLASSES; ++k) out[k] = s2d2_profile{0, 0.0, 0.0};
+  for (const auto& r : *c->prof) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return fail(S2D2_ELAUNCH, "hipEventElapsedTime failed");
+    out[r.cls].launches += 1;
+    out[r.cls].ms += ms;
+    out[r.cls].bytes += r.bytes;
+  }
+  return S2D2_OK;
 }
 
 int32_t s2d2_vocab_draft_stats(s2d2_ctx* c, const float* logits, int32_t rows, int32_t* xhat, float* p, float* lse,

@@ -1,0 +1,95 @@
+"""Device-side session around the C ABI: buffers, prefix prefill through the library, step loop.
+
+Host logic only (allocation, state set-up, call order).  All arithmetic happens in libs2d2.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .binding import AcceptOut, BlockState, DraftOut, Engine, KvCache, Params, VerifyOut
+
+PREFILL_BLOCK = 64  # window used to push prompt tokens through the causal rows of the verifier
+
+
+class Session:
+    def __init__(self, cfg, weights: Dict[str, torch.Tensor], N: int, B: int, max_seq: int, page_size: int = 16,
+                 device: str = "cuda:0", page_table: Optional[np.ndarray] = None, max_block: Optional[int] = None):
+        self.cfg, self.N, self.B = cfg, N, B
+        self.dev = torch.device(device)
+        self.eng = Engine(cfg, weights, N, max_block or max(B, PREFILL_BLOCK), device)
+        i32 = torch.int32
+        max_pages = (max_seq + page_size - 1) // page_size
+        if page_table is None:
+            page_table = np.arange(N * max_pages, dtype=np.int32).reshape(N, max_pages)
+        n_pages = int(page_table.max()) + 1
+        shape = (cfg.n_layers, n_pages, cfg.n_kv_heads, page_size, cfg.head_dim)
+        self.kv = KvCache(torch.zeros(shape, dtype=cfg.torch_dtype, device=self.dev),
+                          torch.zeros(shape, dtype=cfg.torch_dtype, device=self.dev),
+                          torch.as_tensor(page_table, dtype=i32, device=self.dev),
+                          torch.zeros(N, dtype=i32, device=self.dev), torch.zeros(N, dtype=i32, device=self.dev))
+        mb = self.eng.max_block
+        self._blk = torch.full((N, mb), cfg.mask_id, dtype=i32, device=self.dev)
+        self._car = torch.zeros((N, mb), dtype=i32, device=self.dev)
+        self.pos0 = torch.zeros(N, dtype=i32, device=self.dev)
+        self.d = self.eng.alloc_draft_out(N, B)
+        self.v = self.eng.alloc_verify_out(N, B)
+        self.a = self.eng.alloc_accept_out(N, B)
+        self.step_dev = torch.zeros(1, dtype=i32, device=self.dev)
+        self.st = self._state(B)
+
+    def _state(self, B: int) -> BlockState:
+        # [N, B] views over the front of flat storage, so any B <= max_block is contiguous
+        n = self.N * B
+        return BlockState(self._blk.view(-1)[:n].view(self.N, B), self.pos0, self._car.view(-1)[:n].view(self.N, B))
+
+    def prefill(self, ids: Sequence[np.ndarray]):
+        """Fills the cache with the causal K/V of the prompts by pushing them through the verifier's
+        causal rows (committed tokens left of a [MASK]) and appending with n_accept = 0."""
+        N, mb, mask = self.N, self.eng.max_block, self.cfg.mask_id
+        lens = [len(x) for x in ids]
+        done = [0] * N
+        zeros = torch.zeros(N, dtype=torch.int32, device=self.dev)
+        prm = Params()
+        pd, pv = self.eng.alloc_draft_out(N, mb), self.eng.alloc_verify_out(N, mb)  # released after the prefill
+        while any(done[n] < lens[n] for n in range(N)):
+            T = [min(mb - 1, lens[n] - done[n]) for n in range(N)]
+            Bc = max(T) + 1
+            st = self._state(Bc)
+            blk = np.full((N, Bc), mask, dtype=np.int32)
+            for n in range(N):
+                blk[n, :T[n]] = ids[n][done[n]:done[n] + T[n]]
+            st.block_tokens.copy_(torch.from_numpy(blk))
+            st.block_pos0.copy_(torch.as_tensor(done, dtype=torch.int32))
+            self.kv.seq_len.copy_(torch.as_tensor(done, dtype=torch.int32))
+            pd.xhat.zero_()
+            pd.span_len.zero_()
+            self.eng.s2d2_verify(self.kv, st, N, Bc, prm, pd, pv)
+            self.eng.s2d2_kv_append(self.kv, N, Bc, pd, pv, zeros)
+            done = [done[n] + T[n] for n in range(N)]
+        torch.cuda.synchronize(self.dev)
+        self.reset_blocks(lens)
+
+    def reset_blocks(self, seq_lens: Sequence[int]):
+        """Fresh [MASK]^B block right after the cached prefix of every sequence."""
+        self.st = self._state(self.B)
+        self.st.block_tokens.fill_(self.cfg.mask_id)
+        self.st.carry_tokens.zero_()
+        t = torch.as_tensor(list(seq_lens), dtype=torch.int32)
+        self.st.block_pos0.copy_(t)
+        self.kv.seq_len.copy_(t)
+        self.kv.status.zero_()
+        self.step_dev.zero_()
+
+    def step(self, prm: Params, n_accept: Optional[torch.Tensor] = None, n_commit: Optional[torch.Tensor] = None):
+        """draft -> verify -> accept -> kv_append -> block_advance, enqueued without any sync."""
+        N, B, e = self.N, self.B, self.eng
+        if n_accept is not None:
+            self.a.t["n_accept"], self.a.t["n_commit"] = n_accept, n_commit
+        e.s2d2_draft(self.kv, self.st, N, B, prm, self.d)
+        e.s2d2_verify(self.kv, self.st, N, B, prm, self.d, self.v)
+        e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
+        e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
+        e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)

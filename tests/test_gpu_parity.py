@@ -113,3 +113,35 @@ def test_kv_append_reports_enospc_without_writing():
         assert g["status"][0] == -2 and g["seq_len"][0] == 30 and torch.equal(before, run.kv.k)
     else:
         assert g["status"][0] == 0 and g["seq_len"][0] == 30 + lead_plus_acc
+
+
+def test_config2_full_size_step_in_the_benchmark_launch_configuration():
+    """Full-size dense 1.7B-shaped model, the session bench.py times: prefix prefilled through the
+    library, then one draft+verify+accept+append step checked against the oracle (all logit rows,
+    all layers of the appended K/V), plus the first prefix positions of the cache."""
+    from oracle import s2d2_oracle as O
+    from paper_2603_25702_amd.runner import Session
+    wl = I.CONFIGS[2]
+    cfg, N, B = wl.cfg, wl.batch, wl.block
+    W = I.gen_weights(cfg, 0)
+    lens = I.gen_prefix_lengths(wl, 0)
+    ids = [I.gen_prefix_ids(cfg, int(lens[n]), 0, n) for n in range(N)]
+    max_seq = int(lens.max()) + 66 * B + 64
+    table = I.gen_page_table(N, (max_seq + wl.page_size - 1) // wl.page_size, 0)
+    ses = Session(cfg, W, N, B, max_seq, wl.page_size, "cuda:0", page_table=table)
+    ses.prefill(ids)
+    case = H.Case(cfg, W, N, B, wl.page_size, table, [], [], lens.copy())
+    case.states = [O.SeqState(int(lens[n]), int(lens[n]), np.full(B, cfg.mask_id, dtype=np.int64)) for n in range(N)]
+    run = H.GpuRun(case, session=ses)
+    H.sync_case_from_gpu(case, run)
+    # sampled prefix check: the first positions of the prefilled cache against an oracle prefill
+    ck, cv = O.prefill(cfg, W, ids[0][:12])
+    for l in (0, cfg.n_layers // 2, cfg.n_layers - 1):
+        gk, gv = run.cache_rows(0, 0, 12, l)
+        assert np.abs(gk - ck[l]).max() <= H.LOGIT_RTOL * np.abs(ck[l]).max()
+        assert np.abs(gv - cv[l]).max() <= H.LOGIT_RTOL * np.abs(cv[l]).max()
+    prm = Params(tau=0.9, seed=0, step=0)
+    run.step(prm, advance=False)
+    g = run.fetch()
+    rep = H.check_step(case, run, g, prm, check_kv_layers=(0, 13, 27))
+    print("config2 full:", rep)
