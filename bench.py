@@ -129,7 +129,7 @@ def main():
             S = int(lens[n])
             pages = torch.as_tensor(tb[n, :(S + ps - 1) // ps].astype(np.int64))
             ck = [k_cpu[l][pages].permute(0, 2, 1, 3).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
-            cv = [v_cpu[l][pages].permute(0, 2, 1, 3).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
+            cv = [v_cpu[l][pages].permute(0, 3, 1, 2).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
             st = O.SeqState(S, S, np.full(B, cfg.mask_id, dtype=np.int64))
             _, _, a = O.step(cfg, weights, st, ck, cv, prm.tau, args.seed, 0, n)
             tokens += a.n_commit

@@ -99,9 +99,12 @@ typedef struct {
 } s2d2_weights;
 
 /* Paged prefix cache, shared page table for all layers.
- *   k_pages, v_pages  device [n_layers, n_pages, Hkv, page_size, D] in `dtype`; keys are stored
- *                     after RoPE.  Logical position s of sequence n lives in physical page
- *                     page_table[n, s / page_size], slot s % page_size.
+ *   k_pages   device [n_layers, n_pages, Hkv, page_size, D] in `dtype`, keys stored after RoPE
+ *   v_pages   device [n_layers, n_pages, Hkv, D, page_size] in `dtype`: values are stored key-minor
+ *             (transposed inside a page) so that the P*V contraction index is contiguous for MFMA
+ *             Logical position s of sequence n lives in physical page page_table[n, s / page_size],
+ *             slot s % page_size.  page_size % 8 == 0 selects the MFMA attention kernel for bf16
+ *             models with head_dim 128; other shapes run a plain fp32 kernel.
  *   status            device [N], set to S2D2_ENOSPC by s2d2_kv_append for a sequence whose
  *                     append would pass max_pages_per_seq * page_size (nothing is written for
  *                     it), else left unchanged.  May be NULL. */

@@ -163,7 +163,8 @@ class Params:
 
 @dataclass
 class KvCache:
-    """Paged cache tensors: k, v [n_layers, n_pages, Hkv, page_size, D]; page_table [N, max_pages]; seq_len [N]."""
+    """Paged cache tensors: k [n_layers, n_pages, Hkv, page_size, D], v [n_layers, n_pages, Hkv, D, page_size];
+    page_table [N, max_pages]; seq_len [N]."""
     k: torch.Tensor
     v: torch.Tensor
     page_table: torch.Tensor

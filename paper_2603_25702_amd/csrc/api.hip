@@ -8,6 +8,7 @@
 #include <string.h>
 #include <stdarg.h>
 #include <vector>
+#include <algorithm>
 
 using namespace s2d2;
 
@@ -41,6 +42,10 @@ struct s2d2_ctx {
   void* af;
   void* kwin;
   void* vwin;
+  void* vT_win;      // [max_batch, Hkv, D, wpad] key-minor V of the window (MFMA attention)
+  float* attn_part;  // split-key partial outputs
+  int32_t wpad, attn_zmax, attn_z_override;
+  bool force_generic_attention;
   VocabWs vws;
   // profiling (measurement aid)
   bool prof_on;
@@ -123,6 +128,14 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   c->af = cv.take<uint8_t>(LR * (size_t)d.d_model * es);
   c->kwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
   c->vwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
+  c->wpad = (3 * c->max_block + 31) / 32 * 32;
+  c->attn_zmax = 64;
+  c->vT_win = cv.take<uint8_t>(NB * (size_t)d.n_kv_heads * d.head_dim * c->wpad * es);
+  {
+    const int q_tiles = (3 * c->max_block * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
+    // Z * items * q_tiles < 512 + items * q_tiles by the choice of Z in forward()
+    c->attn_part = cv.take<float>(attention_flash_partial_floats(512 + NB * d.n_kv_heads * q_tiles));
+  }
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   return (cv.off + 255) & ~(size_t)255;
@@ -175,7 +188,17 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
   hipStream_t st = c->stream;
   const KvGeom g = geom(c, kv);
-  const size_t lds = attention_generic_lds_bytes(g, 3 * B);
+  // MFMA flash attention for bf16 / head_dim 128 / pages that hold whole 8-key groups; else the generic kernel
+  const bool flash = dt == S2D2_BF16 && d.head_dim == 128 && kv->page_size % 8 == 0 && !c->force_generic_attention;
+  const int q_tiles = (3 * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
+  int Z = 1;
+  if (flash) {  // enough workgroups to fill the chip, but at least ~8 key tiles (256 keys) per workgroup
+    const int cap_tiles = (kv->max_pages_per_seq * kv->page_size + 31) / 32;
+    const int want = (512 + N * d.n_kv_heads * q_tiles - 1) / (N * d.n_kv_heads * q_tiles);
+    Z = std::max(1, std::min(std::min(want, (cap_tiles + 7) / 8), c->attn_zmax));
+    if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, want));
+  }
+  const size_t lds = flash ? 0 : attention_generic_lds_bytes(g, 3 * B);
   if (lds > 160 * 1024) return fail(S2D2_ENOSPC, "attention needs %zu bytes of LDS for max_pages_per_seq*page_size=%d keys (limit 163840)", lds, kv->max_pages_per_seq * kv->page_size);
   const size_t stage_layer = (size_t)c->rows_cap * d.n_kv_heads * d.head_dim * es;
   const size_t page_layer = (size_t)kv->n_pages * d.n_kv_heads * kv->page_size * d.head_dim * es;
@@ -187,9 +210,16 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     void* vw = v_stage ? (uint8_t*)v_stage + l * stage_layer : c->vwin;
     { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
     { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
-    { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw); }
-    { ProfScope ps(c, 1, 0.0); launch_attention_generic(st, dt, c->qbuf, kw, vw, (const uint8_t*)kv->k_pages + l * page_layer,
-                             (const uint8_t*)kv->v_pages + l * page_layer, g, c->plan, R, d.n_q_heads, c->obuf, lds); }
+    { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw, flash ? c->vT_win : nullptr, c->wpad); }
+    const void* kp = (const uint8_t*)kv->k_pages + l * page_layer;
+    const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
+    if (flash) {
+      ProfScope ps(c, 1, 0.0);
+      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, c->attn_part);
+    } else {
+      ProfScope ps(c, 1, 0.0);
+      launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
+    }
     { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
     { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
     { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
@@ -281,6 +311,8 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   c->ws = (uint8_t*)workspace;
   c->ws_bytes = workspace_bytes;
   carve(c, c->ws);
+  if (const char* e = getenv("S2D2_ATTN_Z")) c->attn_z_override = atoi(e);
+  if (const char* e = getenv("S2D2_GENERIC_ATTENTION")) c->force_generic_attention = atoi(e) != 0;
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;

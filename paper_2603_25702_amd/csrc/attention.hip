@@ -89,11 +89,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(
       const T* vp;
       if (s < S) {
         const int page = min(max(pt[s / ps], 0), g.n_pages - 1);
-        vp = v_pages + (((size_t)page * Hkv + kvh) * ps + (s % ps)) * D;
+        vp = v_pages + (((size_t)page * Hkv + kvh) * D + d) * ps + (s % ps);   // cache V is stored [D, page_size]
       } else {
-        vp = v_win + ((size_t)(row0 + (s - S)) * Hkv + kvh) * D;
+        vp = v_win + ((size_t)(row0 + (s - S)) * Hkv + kvh) * D + d;
       }
-      acc += pw * to_f32(vp[d]);
+      acc += pw * to_f32(*vp);
     }
   }
   s_red[tid] = acc;
@@ -105,10 +105,306 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// attn_flash_kernel (bf16, head_dim 128): split-key flash attention on 32x32x16 MFMA.
+//
+// Work item = (sequence, KV head, tile of 32 query rows, key split).  A "query row" is a
+// (window row, query head of the group) pair, so GQA groups share every K/V byte.  Each of the
+// NW wavefronts of a workgroup takes every NW-th tile of 32 keys of its split, streams K and V
+// straight from global memory into MFMA operands (no LDS on the K/V path), and keeps an online
+// softmax state.  Scores are computed transposed, S^T = K Q^T, so that one lane owns one query
+// row: its running max / sum and the rescaling of its output column need no cross-lane traffic
+// beyond one exchange between the two half-waves.  The rows of the K tile are fed in a permuted
+// order chosen so that the fp32 S^T accumulators of a lane, packed to bf16, are exactly the B
+// operand (8 consecutive keys) of O^T = V^T P^T; the cache stores V key-minor ([D, page_size])
+// so that the matching A operand is one 16-byte load.  Wavefronts merge through LDS in a fixed
+// tree; splits merge in attn_combine_kernel (fixed order) unless there is only one split.
+// ---------------------------------------------------------------------------------------------
+static constexpr int FA_D = 128;
+
+__device__ __forceinline__ int fa_perm(int rr) {  // MFMA row -> key offset inside the 32-key tile
+  const int a = rr >> 3, hh = (rr >> 2) & 1, b = rr & 3;
+  return (a >> 1) * 16 + hh * 8 + (a & 1) * 4 + b;
+}
+
+__device__ __forceinline__ uint4 mask_keys(uint4 v, int nv) {  // keep the first nv of 8 bf16, zero the rest
+  if (nv >= 8) return v;
+  if (nv <= 0) return make_uint4(0, 0, 0, 0);
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int k = nv - 2 * e;  // valid halves in this dword
+    w[e] = k >= 2 ? w[e] : (k == 1 ? (w[e] & 0xffffu) : 0u);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+struct FaState {
+  float m, l;
+  f32x16_t o[4];
+};
+
+__device__ __forceinline__ void fa_merge(FaState& a, float m2, float l2, const f32x16_t* o2) {
+  const float M = fmaxf(a.m, m2);
+  const float f1 = a.m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(a.m - M);
+  const float f2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - M);
+  a.l = a.l * f1 + l2 * f2;
+  a.m = M;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a.o[t][i] = a.o[t][i] * f1 + o2[t][i] * f2;
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
+    const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
+    int wpad, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ part_o, float* __restrict__ part_ml) {
+  extern __shared__ float smem[];
+  constexpr int D = FA_D;
+  const int z = blockIdx.x, qt = blockIdx.y;
+  const int Hkv = g.n_kv_heads, ps = g.page_size;
+  const int n = blockIdx.z / Hkv, kvh = blockIdx.z % Hkv;
+  const int grp = Hq / Hkv;
+  const int row0 = p.seq_row0[n], nw = p.seq_rows[n];
+  const int nq = nw * grp, q0 = qt * 32;
+  if (q0 >= nq) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, h = lane >> 5;
+  const int qi = min(q0 + c, nq - 1);
+  const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+  const int lo = p.row_lo[r], hi = p.row_hi[r];
+  const int S = max(0, min(g.seq_len[n], g.max_pages_per_seq * ps));
+  const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
+
+  uint4 qf[8];
+  {
+    const bf16_t* qp = q + ((size_t)r * Hq + head) * D + 8 * h;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) qf[ds] = *(const uint4*)(qp + ds * 16);
+  }
+  FaState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
+
+  // tiles of this split: cached tiles [t0, t1) then, for the last split, the window tiles
+  const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
+  const int t0 = (int)((long long)z * Tc / Z), t1 = (int)((long long)(z + 1) * Tc / Z);
+  const int n_tiles = (t1 - t0) + (z == Z - 1 ? Tw : 0);
+  const int kperm = fa_perm(c);
+
+  for (int it = wave; it < n_tiles; it += NW) {
+    const bool win = it >= (t1 - t0);
+    const int tile = win ? it - (t1 - t0) : t0 + it;
+    const int limit = win ? nw : S;             // keys of this region
+    const int kbase = tile * 32;
+    // ---- S^T = K Q^T ----
+    const bf16_t* kp;
+    {
+      const int key = min(kbase + kperm, limit - 1);
+      if (win) {
+        kp = k_win + ((size_t)(row0 + key) * Hkv + kvh) * D;
+      } else {
+        const int page = min(max(pt[key / ps], 0), g.n_pages - 1);
+        kp = k_pages + (((size_t)page * Hkv + kvh) * ps + key % ps) * D;
+      }
+    }
+    uint4 kf[8];
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) kf[ds] = *(const uint4*)(kp + ds * 16 + 8 * h);
+    // ---- V^T fragments: [dt][j]: d = dt*32 + c, keys kbase + 16 j + 8 h .. +8 ----
+    uint4 vf[4][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int key0 = kbase + 16 * j + 8 * h;
+      const int nv = limit - key0;
+      const bf16_t* vp;
+      size_t dstride;
+      if (win) {
+        vp = vT_win + ((size_t)(n * Hkv + kvh) * D + c) * wpad + min(key0, wpad - 8);
+        dstride = (size_t)32 * wpad;
+      } else {
+        const int kc = min(key0, max(S - 1, 0));
+        const int page = min(max(pt[kc / ps], 0), g.n_pages - 1);
+        vp = v_pages + (((size_t)page * Hkv + kvh) * D + c) * ps + (kc % ps & ~7);
+        dstride = (size_t)32 * ps;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) vf[dt][j] = mask_keys(*(const uint4*)(vp + dt * dstride), nv);
+    }
+    f32x16_t sacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds)
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ds]), __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
+    // sacc[i]: key kbase + 16 (i / 8) + 8 h + (i % 8), query row c
+    float sv[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = kbase + 16 * (i >> 3) + 8 * h + (i & 7);
+      bool ok = key < limit;
+      if (win) {
+        const int w = row0 + key;
+        ok = ok && ((w >= lo && w < hi) || w == r);
+      }
+      sv[i] = ok ? sacc[i] * scale_log2e : -INFINITY;
+      mx = fmaxf(mx, sv[i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // no divergent control flow around the MFMAs: a query row that sees nothing yet keeps m = -inf
+    // and uses 0 as the reference, which makes every p below exp2(-inf) = 0
+    const float m_new = fmaxf(st.m, mx);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
+    float ls = 0.f;
+    bf16x8_t pb[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pv = __builtin_amdgcn_exp2f(sv[i] - m_ref);
+      ls += pv;
+      pb[i >> 3][i & 7] = (__bf16)pv;
+    }
+    ls += __shfl_xor(ls, 32, 64);
+    st.l = st.l * alpha + ls;
+    st.m = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.o[dt][i] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[dt][j]), pb[j], st.o[dt], 0, 0, 0);
+    }
+  }
+  // ---- merge the wavefronts of the workgroup: fixed tree, through LDS ----
+  // slot layout: [slot][66][64]: 64 accumulator registers + m + l per lane
+  for (int s = NW / 2; s >= 1; s >>= 1) {
+    if (wave >= s && wave < 2 * s) {
+      float* dst = smem + (size_t)(wave - s) * 66 * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dst[(t * 16 + i) * 64] = st.o[t][i];
+      dst[64 * 64] = st.m;
+      dst[65 * 64] = st.l;
+    }
+    __syncthreads();
+    if (wave < s) {
+      const float* src = smem + (size_t)wave * 66 * 64 + lane;
+      f32x16_t o2[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o2[t][i] = src[(t * 16 + i) * 64];
+      fa_merge(st, src[64 * 64], src[65 * 64], o2);
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;
+  // st.o[dt][i]: d = dt*32 + 8 (i/4) + 4 h + (i%4), query row c
+  const bool q_ok = (q0 + c) < nq;
+  if (Z == 1) {
+    if (!q_ok) return;
+    const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
+    bf16_t* op = o + ((size_t)r * Hq + head) * D;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d0 = dt * 32 + 8 * i4 + 4 * h;
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(st.o[dt][4 * i4] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 1] * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 2] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 3] * inv) << 16);
+        *(uint2*)(op + d0) = pk;
+      }
+  } else {
+    const size_t item = ((size_t)blockIdx.z * gridDim.y + qt) * Z + z;
+    float* po = part_o + item * 32 * D + (size_t)c * D;
+    if (h == 0) {
+      part_ml[item * 64 + c] = st.m;
+      part_ml[item * 64 + 32 + c] = st.l;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d0 = dt * 32 + 8 * i4 + 4 * h;
+        *(float4*)(po + d0) = make_float4(st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
+      }
+  }
+}
+
+// Merges the Z split partials of one (sequence, KV head, query tile) in split order.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_ml, KvGeom g, Plan p,
+                                                           int Hq, int Z, bf16_t* __restrict__ o) {
+  constexpr int D = FA_D;
+  const int qt = blockIdx.x;
+  const int Hkv = g.n_kv_heads;
+  const int n = blockIdx.y / Hkv, kvh = blockIdx.y % Hkv;
+  const int grp = Hq / Hkv;
+  const int row0 = p.seq_row0[n], nq = p.seq_rows[n] * grp;
+  if (qt * 32 >= nq) return;
+  const size_t item0 = ((size_t)blockIdx.y * gridDim.x + qt) * Z;
+  for (int e = threadIdx.x; e < 32 * (D / 4); e += 256) {
+    const int c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+    const int qi = qt * 32 + c;
+    if (qi >= nq) continue;
+    float M = -INFINITY;
+    for (int z = 0; z < Z; ++z) M = fmaxf(M, part_ml[(item0 + z) * 64 + c]);
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < Z; ++z) {
+      const float m = part_ml[(item0 + z) * 64 + c];
+      if (m == -INFINITY) continue;
+      const float f = __builtin_amdgcn_exp2f(m - M);
+      l += f * part_ml[(item0 + z) * 64 + 32 + c];
+      const float4 v = *(const float4*)(part_o + ((item0 + z) * 32 + c) * D + d0);
+      acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+    uint2 pk;
+    pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
+    pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
+    *(uint2*)(o + ((size_t)r * Hq + head) * D + d0) = pk;
+  }
+}
+
+static constexpr int FA_NW = 8;
+static constexpr size_t FA_LDS = (size_t)(FA_NW / 2) * 66 * 64 * sizeof(float);
+
+// Floats needed for `entries` split partials (one per (sequence, KV head, query tile, split)).
+size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * FA_D + 64); }
+
+// q_tiles = ceil(3 B grp / 32); Z key splits.  part must hold attention_flash_partial_floats().
+void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
+                            const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.head_dim);
+  const int items = N * g.n_kv_heads;
+  float* part_o = part;
+  float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
+  hipLaunchKernelGGL(attn_flash_kernel<FA_NW>, dim3(Z, q_tiles, items), dim3(FA_NW * 64), FA_LDS, st,
+                     (const bf16_t*)q, (const bf16_t*)k_win, (const bf16_t*)vT_win, (const bf16_t*)k_pages_layer,
+                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, part_o, part_ml);
+  if (Z > 1)
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(q_tiles, items), dim3(256), 0, st, part_o, part_ml, g, p, Hq, Z,
+                       (bf16_t*)o);
+}
+
 // Raises the dynamic-LDS limit of the kernels once (160 KB per workgroup on gfx950).
 int attention_init() {
   hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_generic_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<FA_NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FA_LDS);
   return e == hipSuccess ? 0 : -1;
 }
 

@@ -65,7 +65,8 @@ void launch_rmsnorm(hipStream_t st, int dtype, const float* h, const float* gain
 template <typename T>
 __global__ __launch_bounds__(256) void rope_split_kernel(const float* __restrict__ qkv, Plan p, int Hq, int Hkv,
                                                          int D, float theta, T* __restrict__ q_out,
-                                                         T* __restrict__ k_out, T* __restrict__ v_out) {
+                                                         T* __restrict__ k_out, T* __restrict__ v_out,
+                                                         T* __restrict__ vT_out, int wpad) {
   __shared__ float s_cos[128], s_sin[128];
   const int r = blockIdx.x;
   if (r >= p.counts[0]) return;
@@ -93,16 +94,21 @@ __global__ __launch_bounds__(256) void rope_split_kernel(const float* __restrict
   const float* xv = x + (size_t)(Hq + Hkv) * D;
   T* vd = v_out + (size_t)r * Hkv * D;
   for (int e = threadIdx.x; e < Hkv * D; e += 256) vd[e] = from_f32<T>(xv[e]);
+  if (vT_out) {  // key-minor copy of the window's V for the MFMA attention: [seq, Hkv, D, wpad]
+    const int n = p.row_seq[r], t = r - p.seq_row0[n];
+    T* vt = vT_out + (size_t)n * Hkv * D * wpad + t;
+    for (int e = threadIdx.x; e < Hkv * D; e += 256) vt[(size_t)e * wpad] = from_f32<T>(xv[e]);
+  }
 }
 
 void launch_rope_split(hipStream_t st, int dtype, const float* qkv, const Plan& p, int rows_cap, int Hq,
-                       int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out) {
+                       int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out, void* vT_out, int wpad) {
   if (dtype == S2D2_BF16)
     hipLaunchKernelGGL(rope_split_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
-                       (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out);
+                       (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out, (bf16_t*)vT_out, wpad);
   else
     hipLaunchKernelGGL(rope_split_kernel<float>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
-                       (float*)q_out, (float*)k_out, (float*)v_out);
+                       (float*)q_out, (float*)k_out, (float*)v_out, (float*)vT_out, wpad);
 }
 
 }  // namespace s2d2

@@ -157,9 +157,15 @@ __global__ __launch_bounds__(256) void kv_append_copy_kernel(
   for (int v = threadIdx.x; v < g.n_kv_heads * vec_per_head; v += blockDim.x) {
     const int h = v / vec_per_head, e = v % vec_per_head;
     const size_t dst = layer_off + (((size_t)page * g.n_kv_heads + h) * g.page_size + slot) * head_bytes + (size_t)e * 16;
-    const size_t so = src + (size_t)h * head_bytes + (size_t)e * 16;
-    *(uint4*)(k_pages + dst) = *(const uint4*)(k_stage + so);
-    *(uint4*)(v_pages + dst) = *(const uint4*)(v_stage + so);
+    *(uint4*)(k_pages + dst) = *(const uint4*)(k_stage + src + (size_t)h * head_bytes + (size_t)e * 16);
+  }
+  // V is cached key-minor: [page, Hkv, D, page_size]
+  for (int v = threadIdx.x; v < g.n_kv_heads * g.head_dim; v += blockDim.x) {
+    const int h = v / g.head_dim, d = v % g.head_dim;
+    const size_t dst = layer_off + ((((size_t)page * g.n_kv_heads + h) * g.head_dim + d) * g.page_size + slot) * elt_bytes;
+    const size_t so = src + (size_t)v * elt_bytes;
+    if (elt_bytes == 2) *(uint16_t*)(v_pages + dst) = *(const uint16_t*)(v_stage + so);
+    else *(uint32_t*)(v_pages + dst) = *(const uint32_t*)(v_stage + so);
   }
 }
 

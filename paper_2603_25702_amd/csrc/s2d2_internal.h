@@ -79,7 +79,7 @@ void launch_embed(hipStream_t st, int dtype, const void* embed, int d, const Pla
 void launch_rmsnorm(hipStream_t st, int dtype, const float* h, const float* gain, int d, float eps,
                     const int32_t* count, const int32_t* gather, int rows_cap, void* out);
 void launch_rope_split(hipStream_t st, int dtype, const float* qkv, const Plan& p, int rows_cap, int Hq,
-                       int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out);
+                       int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out, void* vT_out, int wpad);
 
 // gemm.hip : Y[m, n] = sum_k X[m, k] * W[n, k], X and W in `dtype`, fp32 accumulation.
 void launch_gemm(hipStream_t st, int dtype, GemmEpilogue epi, const void* X, int ldx, const void* W, int K,
@@ -90,6 +90,10 @@ void launch_attention_generic(hipStream_t st, int dtype, const void* q, const vo
                               const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,
                               const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes);
 int attention_init();
+size_t attention_flash_partial_floats(size_t entries);
+void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
+                            const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part);
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
 
 // vocab.hip

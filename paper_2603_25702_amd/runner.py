@@ -26,8 +26,9 @@ class Session:
             page_table = np.arange(N * max_pages, dtype=np.int32).reshape(N, max_pages)
         n_pages = int(page_table.max()) + 1
         shape = (cfg.n_layers, n_pages, cfg.n_kv_heads, page_size, cfg.head_dim)
+        vshape = (cfg.n_layers, n_pages, cfg.n_kv_heads, cfg.head_dim, page_size)  # V is cached key-minor
         self.kv = KvCache(torch.zeros(shape, dtype=cfg.torch_dtype, device=self.dev),
-                          torch.zeros(shape, dtype=cfg.torch_dtype, device=self.dev),
+                          torch.zeros(vshape, dtype=cfg.torch_dtype, device=self.dev),
                           torch.as_tensor(page_table, dtype=i32, device=self.dev),
                           torch.zeros(N, dtype=i32, device=self.dev), torch.zeros(N, dtype=i32, device=self.dev))
         mb = self.eng.max_block

@@ -45,7 +45,7 @@ class Case:
     page_size: int
     page_table: np.ndarray            # [N, max_pages]
     k_pages: List[torch.Tensor]       # per layer CPU [n_pages, Hkv, ps, D] storage dtype
-    v_pages: List[torch.Tensor]
+    v_pages: List[torch.Tensor]       # per layer CPU [n_pages, Hkv, D, ps] (the cache keeps V key-minor)
     seq_len: np.ndarray               # [N]
     states: List[O.SeqState] = field(default_factory=list)
 
@@ -57,7 +57,7 @@ class Case:
         ck, cv = [], []
         for l in range(self.cfg.n_layers):
             k = self.k_pages[l][pages].permute(0, 2, 1, 3).reshape(npg * ps, self.cfg.n_kv_heads, self.cfg.head_dim)[:S]
-            v = self.v_pages[l][pages].permute(0, 2, 1, 3).reshape(npg * ps, self.cfg.n_kv_heads, self.cfg.head_dim)[:S]
+            v = self.v_pages[l][pages].permute(0, 3, 1, 2).reshape(npg * ps, self.cfg.n_kv_heads, self.cfg.head_dim)[:S]
             ck.append(k)
             cv.append(v)
         return ck, cv
@@ -76,11 +76,12 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
     n_pages = N * max_pages
     if synthetic_kv:
         k_pages = [I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "k") for l in range(cfg.n_layers)]
-        v_pages = [I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "v") for l in range(cfg.n_layers)]
+        v_pages = [I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "v").permute(0, 1, 3, 2).contiguous()
+                   for l in range(cfg.n_layers)]
     else:
         shape = (n_pages, cfg.n_kv_heads, page_size, cfg.head_dim)
         k_pages = [torch.zeros(shape, dtype=cfg.torch_dtype) for _ in range(cfg.n_layers)]
-        v_pages = [torch.zeros(shape, dtype=cfg.torch_dtype) for _ in range(cfg.n_layers)]
+        v_pages = [torch.zeros(shape, dtype=cfg.torch_dtype).permute(0, 1, 3, 2).contiguous() for _ in range(cfg.n_layers)]
         for n in range(N):
             ids = I.gen_prefix_ids(cfg, int(prefix_lens[n]), seed, n)
             ck, cv = O.prefill(cfg, W, ids)
@@ -88,7 +89,7 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
                 for s in range(len(ids)):
                     pg, sl = int(table[n, s // page_size]), s % page_size
                     k_pages[l][pg, :, sl, :] = round_to_storage(ck[l][s], cfg)
-                    v_pages[l][pg, :, sl, :] = round_to_storage(cv[l][s], cfg)
+                    v_pages[l][pg, :, :, sl] = round_to_storage(cv[l][s], cfg)
     case = Case(cfg, W, N, B, page_size, table, k_pages, v_pages, prefix_lens.copy())
     case.states = [O.SeqState(int(prefix_lens[n]), int(prefix_lens[n]), np.full(B, cfg.mask_id, dtype=np.int64)) for n in range(N)]
     return case
@@ -160,7 +161,7 @@ class GpuRun:
         for s in range(s0, s1):
             pg = int(self.case.page_table[n, s // ps])
             ks.append(self.kv.k[layer, pg, :, s % ps, :].to(torch.float64).cpu().numpy())
-            vs.append(self.kv.v[layer, pg, :, s % ps, :].to(torch.float64).cpu().numpy())
+            vs.append(self.kv.v[layer, pg, :, :, s % ps].to(torch.float64).cpu().numpy())
         return np.stack(ks), np.stack(vs)
 
 
