@@ -201,11 +201,21 @@ int64_t s2d2_stage_rows(int32_t max_batch, int32_t max_block);
 /* Bytes of device workspace needed for these limits; negative S2D2_E* on a bad description. */
 int64_t s2d2_workspace_bytes(const s2d2_model_desc* desc, int32_t max_batch, int32_t max_block);
 
+/* Bytes of the packed copy of the projection weights that the streaming GEMM reads (bf16 dense
+ * models; 0 for other models).  The library does not allocate it: the caller passes a device buffer
+ * of this size to s2d2_create. */
+int64_t s2d2_packed_bytes(const s2d2_model_desc* desc);
+
 /* Bind weights, limits, stream (a hipStream_t, may be NULL for the default stream) and
- * workspace (device, 256-byte aligned).  The weights stay caller-owned and must outlive ctx. */
+ * workspace (device, 256-byte aligned).  `packed` (device, 256-byte aligned, s2d2_packed_bytes()
+ * or NULL): if given, s2d2_create enqueues kernels that copy wqkv, wo, wgu, wdown and unembed
+ * into it in MFMA tile order, and every forward reads that copy with the fused streaming GEMM;
+ * the canonical copies of those five tensors may be released once the stream has run.  With
+ * packed == NULL (and always for fp32 models) the canonical layouts are read by the plain
+ * kernels.  embed and the norm gains stay caller-owned and must outlive ctx. */
 int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, int32_t max_batch,
                     int32_t max_block, void* stream, void* workspace, size_t workspace_bytes,
-                    s2d2_ctx** out);
+                    void* packed, size_t packed_bytes, s2d2_ctx** out);
 int32_t s2d2_destroy(s2d2_ctx* ctx);
 int32_t s2d2_set_stream(s2d2_ctx* ctx, void* stream);
 

@@ -20,7 +20,7 @@ S2D2_F32, S2D2_BF16 = 0, 1
 S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 
 EXPORTS = [
-    "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_create", "s2d2_destroy",
+    "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
     "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
@@ -103,8 +103,10 @@ def load_library():
     lib.s2d2_workspace_bytes.restype = C.c_int64
     lib.s2d2_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.c_int32, C.c_int32]
     lib.s2d2_create.restype = C.c_int32
+    lib.s2d2_packed_bytes.restype = C.c_int64
+    lib.s2d2_packed_bytes.argtypes = [C.POINTER(ModelDesc)]
     lib.s2d2_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(Weights), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                C.c_size_t, C.POINTER(C.c_void_p)]
+                                C.c_size_t, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
     lib.s2d2_destroy.argtypes = [C.c_void_p]
     lib.s2d2_set_stream.argtypes = [C.c_void_p, C.c_void_p]
     lib.s2d2_draft.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
@@ -258,7 +260,7 @@ class Engine:
     """Owns a library context: weights on the device, workspace, stream.  Methods = C calls."""
 
     def __init__(self, cfg, weights: Dict[str, torch.Tensor], max_batch: int, max_block: int,
-                 device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
+                 device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None, packed: bool = True):
         self.lib = load_library()
         self.cfg, self.max_batch, self.max_block = cfg, max_batch, max_block
         self.device = torch.device(device)
@@ -276,9 +278,12 @@ class Engine:
             raise S2D2Error(int(need), self.lib.s2d2_last_error().decode())
         self.workspace = torch.empty(int(need), dtype=torch.uint8, device=self.device)
         self.stream = stream
+        pbytes = int(self.lib.s2d2_packed_bytes(C.byref(self.desc))) if packed else 0
+        self.packed = torch.empty(pbytes, dtype=torch.uint8, device=self.device) if pbytes > 0 else None
         ctx = C.c_void_p()
         _check(self.lib, self.lib.s2d2_create(C.byref(self.desc), C.byref(self._weights), max_batch, max_block,
-                                              self._stream_handle(), self.workspace.data_ptr(), int(need), C.byref(ctx)))
+                                              self._stream_handle(), self.workspace.data_ptr(), int(need),
+                                              _ptr(self.packed), pbytes, C.byref(ctx)))
         self.ctx = ctx
         self.stage_rows = int(self.lib.s2d2_stage_rows(max_batch, max_block))
 

@@ -47,6 +47,11 @@ struct s2d2_ctx {
   int32_t wpad, attn_zmax, attn_z_override;
   bool force_generic_attention;
   VocabWs vws;
+  float2* rope_cs;   // [rows_cap, D/2] cos / sin of the window rows
+  // packed bf16 weights (streaming GEMM); null when the caller gave no packed buffer
+  struct PackedLayer { const uint4 *wqkv, *wo, *wg, *wu, *wdown; };
+  PackedLayer* pk;
+  const uint4* pk_unembed;
   // profiling (measurement aid)
   bool prof_on;
   int32_t prof_cap;
@@ -136,6 +141,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     // Z * items * q_tiles < 512 + items * q_tiles by the choice of Z in forward()
     c->attn_part = cv.take<float>(attention_flash_partial_floats(512 + NB * d.n_kv_heads * q_tiles));
   }
+  c->rope_cs = cv.take<float2>(R * (size_t)(d.head_dim / 2));
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   return (cv.off + 255) & ~(size_t)255;
@@ -153,6 +159,14 @@ struct ProfScope {
   }
   ~ProfScope() { if (stop) (void)hipEventRecord(stop, c->stream); }
 };
+
+size_t packed_total_bytes(const s2d2_model_desc& d) {
+  if (d.dtype != S2D2_BF16 || d.n_experts > 0) return 0;
+  const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+  size_t per = packed_weight_bytes(qkv_n, d.d_model) + packed_weight_bytes(d.d_model, HqD) +
+               2 * packed_weight_bytes(d.d_ffn, d.d_model) + packed_weight_bytes(d.d_model, d.d_ffn);
+  return per * d.n_layers + packed_weight_bytes(d.vocab, d.d_model);
+}
 
 int32_t check_launch(const char* what) {
   const hipError_t e = hipGetLastError();
@@ -192,10 +206,13 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const bool flash = dt == S2D2_BF16 && d.head_dim == 128 && kv->page_size % 8 == 0 && !c->force_generic_attention;
   const int q_tiles = (3 * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
   int Z = 1;
-  if (flash) {  // enough workgroups to fill the chip, but at least ~8 key tiles (256 keys) per workgroup
+  if (flash) {
+    // One split (no merge kernel) while that leaves <= 4 key tiles per wavefront or the batch alone
+    // fills the chip; else enough splits for ~512 workgroups with >= 2 tiles per wavefront.
     const int cap_tiles = (kv->max_pages_per_seq * kv->page_size + 31) / 32;
-    const int want = (512 + N * d.n_kv_heads * q_tiles - 1) / (N * d.n_kv_heads * q_tiles);
-    Z = std::max(1, std::min(std::min(want, (cap_tiles + 7) / 8), c->attn_zmax));
+    const int groups = N * d.n_kv_heads * q_tiles;
+    const int want = (512 + groups - 1) / groups;
+    if (cap_tiles > 32 && groups < 512) Z = std::max(1, std::min(std::min(want, (cap_tiles + 15) / 16), c->attn_zmax));
     if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, want));
   }
   const size_t lds = flash ? 0 : attention_generic_lds_bytes(g, 3 * B);
@@ -204,13 +221,26 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const size_t page_layer = (size_t)kv->n_pages * d.n_kv_heads * kv->page_size * d.head_dim * es;
   const int32_t* n_rows = c->plan.counts;
   { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
+  const bool fused = c->pk != nullptr;
+  if (fused) { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
   for (int l = 0; l < d.n_layers; ++l) {
     const s2d2_layer_weights& L = c->layers[l];
     void* kw = k_stage ? (uint8_t*)k_stage + l * stage_layer : c->kwin;
     void* vw = v_stage ? (uint8_t*)v_stage + l * stage_layer : c->vwin;
-    { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
-    { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
-    { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw, flash ? c->vT_win : nullptr, c->wpad); }
+    if (fused) {
+      GemmStreamArgs a{};
+      a.Wp = c->pk[l].wqkv; a.NT = qkv_n / 16; a.KT = d.d_model / 32; a.N = qkv_n; a.K = d.d_model;
+      a.m_count = n_rows; a.H = c->h; a.gain = L.norm1; a.eps = d.rms_eps;
+      a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
+      a.q_out = (bf16_t*)c->qbuf; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
+      a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
+      ProfScope ps(c, 0, (double)qkv_n * d.d_model * es);
+      launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
+    } else {
+      { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
+      { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
+      { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw, flash ? c->vT_win : nullptr, c->wpad); }
+    }
     const void* kp = (const uint8_t*)kv->k_pages + l * page_layer;
     const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
     if (flash) {
@@ -220,14 +250,41 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
     }
-    { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
-    { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
-    { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
-    { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model); }
+    if (fused) {
+      GemmStreamArgs a{};
+      a.m_count = n_rows;
+      a.Wp = c->pk[l].wo; a.NT = d.d_model / 16; a.KT = HqD / 32; a.N = d.d_model; a.K = HqD;
+      a.X = (const bf16_t*)c->obuf; a.ldx = HqD; a.out = c->h; a.ldo = d.d_model;
+      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
+      GemmStreamArgs b{};
+      b.m_count = n_rows;
+      b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
+      b.H = c->h; b.gain = L.norm2; b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
+      { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
+      GemmStreamArgs e{};
+      e.m_count = n_rows;
+      e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
+      e.X = (const bf16_t*)c->ffn; e.ldx = d.d_ffn; e.out = c->h; e.ldo = d.d_model;
+      { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
+    } else {
+      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
+      { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
+      { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
+      { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model); }
+    }
   }
   const int32_t* n_logit = c->plan.counts + 1;
-  { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af); }
-  { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
+  if (fused) {
+    GemmStreamArgs a{};
+    a.Wp = c->pk_unembed; a.NT = (d.vocab + 15) / 16; a.KT = d.d_model / 32; a.N = d.vocab; a.K = d.d_model;
+    a.m_count = n_logit; a.H = c->h; a.gain = c->w.norm_f; a.gather = c->plan.logit_src; a.eps = d.rms_eps;
+    a.out = logits; a.ldo = d.vocab;
+    ProfScope ps(c, 0, (double)d.vocab * d.d_model * es);
+    launch_gemm_stream(st, SEPI_STORE_F32, a, LR);
+  } else {
+    { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af); }
+    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
+  }
   return check_launch("forward");
 }
 
@@ -265,8 +322,15 @@ int64_t s2d2_workspace_bytes(const s2d2_model_desc* desc, int32_t max_batch, int
   return (int64_t)carve(&tmp, nullptr);
 }
 
+int64_t s2d2_packed_bytes(const s2d2_model_desc* desc) {
+  const int32_t rc = check_desc(desc);
+  if (rc) return rc;
+  return (int64_t)packed_total_bytes(*desc);
+}
+
 int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, int32_t max_batch,
-                    int32_t max_block, void* stream, void* workspace, size_t workspace_bytes, s2d2_ctx** out) {
+                    int32_t max_block, void* stream, void* workspace, size_t workspace_bytes, void* packed,
+                    size_t packed_bytes, s2d2_ctx** out) {
   if (!out) return fail(S2D2_EINVAL, "out is NULL");
   *out = nullptr;
   int32_t rc = check_desc(desc);
@@ -286,6 +350,9 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   const int64_t need = s2d2_workspace_bytes(desc, max_batch, max_block);
   if (need < 0) return (int32_t)need;
   if (workspace_bytes < (size_t)need) return fail(S2D2_ENOSPC, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)need);
+  const bool use_packed = packed != nullptr && packed_total_bytes(*desc) > 0 && gemm_stream_norm_fits(desc->d_model);
+  if (packed && ((uintptr_t)packed & 255)) return fail(S2D2_EINVAL, "packed buffer is not 256-byte aligned");
+  if (use_packed && packed_bytes < packed_total_bytes(*desc)) return fail(S2D2_ENOSPC, "packed buffer has %zu bytes, %zu needed", packed_bytes, packed_total_bytes(*desc));
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -313,6 +380,28 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   carve(c, c->ws);
   if (const char* e = getenv("S2D2_ATTN_Z")) c->attn_z_override = atoi(e);
   if (const char* e = getenv("S2D2_GENERIC_ATTENTION")) c->force_generic_attention = atoi(e) != 0;
+  if (use_packed) {  // re-lay the projection weights out for the streaming GEMM (enqueued on the stream)
+    const s2d2_model_desc& d = c->desc;
+    const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    c->pk = (s2d2_ctx::PackedLayer*)malloc(sizeof(s2d2_ctx::PackedLayer) * d.n_layers);
+    uint8_t* p = (uint8_t*)packed;
+    auto put = [&](const void* W, int N, int K, int rope) {
+      const uint4* at = (const uint4*)p;
+      launch_pack_weight(c->stream, W, N, K, rope, d.head_dim, p);
+      p += packed_weight_bytes(N, K);
+      return at;
+    };
+    for (int l = 0; l < d.n_layers; ++l) {
+      const s2d2_layer_weights& L = c->layers[l];
+      c->pk[l].wqkv = put(L.wqkv, qkv_n, d.d_model, 1);
+      c->pk[l].wo = put(L.wo, d.d_model, HqD, 0);
+      c->pk[l].wg = put(L.wgu, d.d_ffn, d.d_model, 0);
+      c->pk[l].wu = put((const uint8_t*)L.wgu + (size_t)d.d_ffn * d.d_model * 2, d.d_ffn, d.d_model, 0);
+      c->pk[l].wdown = put(L.wdown, d.d_model, d.d_ffn, 0);
+    }
+    c->pk_unembed = put(c->w.unembed, d.vocab, d.d_model, 0);
+    if (hipGetLastError() != hipSuccess) { free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "weight packing failed to launch"); }
+  }
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;
@@ -325,6 +414,7 @@ int32_t s2d2_destroy(s2d2_ctx* ctx) {
     delete ctx->prof_pool;
     delete ctx->prof;
   }
+  free(ctx->pk);
   free(ctx->layers);
   free(ctx);
   return S2D2_OK;

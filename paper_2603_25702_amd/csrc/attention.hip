@@ -167,16 +167,27 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
   const int Hkv = g.n_kv_heads, ps = g.page_size;
   const int n = blockIdx.z / Hkv, kvh = blockIdx.z % Hkv;
   const int grp = Hq / Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, h = lane >> 5;
+  const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
+  // Tile t of the cached keys belongs to wavefront (t mod GW) of the GW = Z * NW wavefronts that
+  // share this (sequence, KV head, query tile): the assignment does not depend on seq_len, so the
+  // page-table entries of a wavefront's first tile are requested together with seq_len and the
+  // plan entries (one round trip), and K / V follow in the second.
+  const int gw = z * NW + wave, GW = Z * NW;
+  const int kperm = fa_perm(c);
+  const int cap = g.max_pages_per_seq * ps;
+  int page_k = pt[min(gw * 32 + kperm, cap - 1) / ps];
+  int page_v[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) page_v[j] = pt[min(gw * 32 + 16 * j + 8 * h, cap - 1) / ps];
+  const int S = max(0, min(g.seq_len[n], cap));
   const int row0 = p.seq_row0[n], nw = p.seq_rows[n];
   const int nq = nw * grp, q0 = qt * 32;
   if (q0 >= nq) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = lane & 31, h = lane >> 5;
   const int qi = min(q0 + c, nq - 1);
   const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
   const int lo = p.row_lo[r], hi = p.row_hi[r];
-  const int S = max(0, min(g.seq_len[n], g.max_pages_per_seq * ps));
-  const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
 
   uint4 qf[8];
   {
@@ -192,15 +203,14 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
 
-  // tiles of this split: cached tiles [t0, t1) then, for the last split, the window tiles
   const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
-  const int t0 = (int)((long long)z * Tc / Z), t1 = (int)((long long)(z + 1) * Tc / Z);
-  const int n_tiles = (t1 - t0) + (z == Z - 1 ? Tw : 0);
-  const int kperm = fa_perm(c);
+  const int n_c = Tc > gw ? (Tc - gw + GW - 1) / GW : 0;           // cached tiles gw, gw + GW, ...
+  const int w_first = (GW - 1 - gw) % GW;                          // window tiles go to the last wavefronts
+  const int n_w = Tw > w_first ? (Tw - w_first + GW - 1) / GW : 0;
 
-  for (int it = wave; it < n_tiles; it += NW) {
-    const bool win = it >= (t1 - t0);
-    const int tile = win ? it - (t1 - t0) : t0 + it;
+  for (int it = 0; it < n_c + n_w; ++it) {
+    const bool win = it >= n_c;
+    const int tile = win ? w_first + (it - n_c) * GW : gw + it * GW;
     const int limit = win ? nw : S;             // keys of this region
     const int kbase = tile * 32;
     // ---- S^T = K Q^T ----
@@ -210,8 +220,9 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
       if (win) {
         kp = k_win + ((size_t)(row0 + key) * Hkv + kvh) * D;
       } else {
-        const int page = min(max(pt[key / ps], 0), g.n_pages - 1);
-        kp = k_pages + (((size_t)page * Hkv + kvh) * ps + key % ps) * D;
+        // a lane whose key lies beyond seq_len reads some valid row; its score is replaced below
+        const int page = min(max(page_k, 0), g.n_pages - 1);
+        kp = k_pages + (((size_t)page * Hkv + kvh) * ps + (kbase + kperm) % ps) * D;
       }
     }
     uint4 kf[8];
@@ -229,13 +240,18 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
         vp = vT_win + ((size_t)(n * Hkv + kvh) * D + c) * wpad + min(key0, wpad - 8);
         dstride = (size_t)32 * wpad;
       } else {
-        const int kc = min(key0, max(S - 1, 0));
-        const int page = min(max(pt[kc / ps], 0), g.n_pages - 1);
-        vp = v_pages + (((size_t)page * Hkv + kvh) * D + c) * ps + (kc % ps & ~7);
+        const int page = min(max(page_v[j], 0), g.n_pages - 1);
+        vp = v_pages + (((size_t)page * Hkv + kvh) * D + c) * ps + (key0 % ps);
         dstride = (size_t)32 * ps;
       }
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) vf[dt][j] = mask_keys(*(const uint4*)(vp + dt * dstride), nv);
+    }
+    if (it + 1 < n_c) {  // page-table entries of the next cached tile, in flight during this tile's math
+      const int nb = (tile + GW) * 32;
+      page_k = pt[min(nb + kperm, cap - 1) / ps];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) page_v[j] = pt[min(nb + 16 * j + 8 * h, cap - 1) / ps];
     }
     f32x16_t sacc;
 #pragma unroll
@@ -378,13 +394,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
   }
 }
 
-static constexpr int FA_NW = 8;
-static constexpr size_t FA_LDS = (size_t)(FA_NW / 2) * 66 * 64 * sizeof(float);
+static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * sizeof(float); }
 
 // Floats needed for `entries` split partials (one per (sequence, KV head, query tile, split)).
 size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * FA_D + 64); }
 
-// q_tiles = ceil(3 B grp / 32); Z key splits.  part must hold attention_flash_partial_floats().
+// q_tiles = ceil(3 B grp / 32); Z key splits of 8 wavefronts each.  One split writes the output
+// directly; Z > 1 merges the splits in a second kernel.
 void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part) {
@@ -392,7 +408,7 @@ void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, co
   const int items = N * g.n_kv_heads;
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
-  hipLaunchKernelGGL(attn_flash_kernel<FA_NW>, dim3(Z, q_tiles, items), dim3(FA_NW * 64), FA_LDS, st,
+  hipLaunchKernelGGL(attn_flash_kernel<8>, dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
                      (const bf16_t*)q, (const bf16_t*)k_win, (const bf16_t*)vT_win, (const bf16_t*)k_pages_layer,
                      (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, part_o, part_ml);
   if (Z > 1)
@@ -404,7 +420,7 @@ void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, co
 int attention_init() {
   hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_generic_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<FA_NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FA_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_lds(8));
   return e == hipSuccess ? 0 : -1;
 }
 

@@ -11,6 +11,8 @@ typedef uint16_t bf16_t;  // raw bfloat16 bits
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even
@@ -84,6 +86,38 @@ void launch_rope_split(hipStream_t st, int dtype, const float* qkv, const Plan& 
 // gemm.hip : Y[m, n] = sum_k X[m, k] * W[n, k], X and W in `dtype`, fp32 accumulation.
 void launch_gemm(hipStream_t st, int dtype, GemmEpilogue epi, const void* X, int ldx, const void* W, int K,
                  int N, const int32_t* m_count, int m_cap, void* out, int ldo);
+
+// gemm_stream.hip : packed-weight streaming GEMM with fused prologue / epilogue (bf16)
+enum StreamEpilogue { SEPI_STORE_F32 = 0, SEPI_ADD_F32 = 1, SEPI_SWIGLU = 2, SEPI_QKV_ROPE = 3 };
+enum StreamPrologue { SPRO_BF16 = 0, SPRO_NORM = 1 };
+struct GemmStreamArgs {
+  const uint4* Wp;          // packed weights [NT][KT][64] x 16 bytes
+  const uint4* Wp2;         // second matrix (up projection) for SEPI_SWIGLU
+  int32_t NT, KT, N, K;
+  const int32_t* m_count;   // device: number of valid rows
+  const bf16_t* X;          // SPRO_BF16: activations [M, ldx]
+  int32_t ldx;
+  const float* H;           // SPRO_NORM: fp32 residual rows [*, K]
+  const float* gain;        // [K]
+  const int32_t* gather;    // optional row indices into H
+  float eps;
+  void* out;
+  int32_t ldo;
+  // SEPI_QKV_ROPE
+  const float2* rope_cs;    // [rows, D/2] (cos, sin)
+  int32_t Hq, Hkv, D, wpad;
+  bf16_t* q_out;
+  bf16_t* k_out;
+  bf16_t* v_out;
+  bf16_t* vT_out;
+  const int32_t* row_seq;
+  const int32_t* seq_row0;
+};
+size_t packed_weight_bytes(int N, int K);
+void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
+void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs);
+bool gemm_stream_norm_fits(int K);
+void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
 
 // attention.hip
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,

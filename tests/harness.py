@@ -98,14 +98,14 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
 class GpuRun:
     """Device-side mirror of a Case plus output buffers; methods call the C ABI."""
 
-    def __init__(self, case: Case, device: str = "cuda:0", session=None):
+    def __init__(self, case: Case, device: str = "cuda:0", session=None, packed: bool = True):
         cfg, N, B = case.cfg, case.N, case.B
         self.case, self.dev = case, torch.device(device)
         if session is not None:  # wrap the buffers of a runner.Session (cache already on the device)
             self.eng, self.kv, self.st = session.eng, session.kv, session.st
             self.d, self.v, self.a = session.d, session.v, session.a
             return
-        self.eng = Engine(cfg, case.W, N, B, device)
+        self.eng = Engine(cfg, case.W, N, B, device, packed=packed)
         i32 = torch.int32
         self.kv = KvCache(torch.stack(case.k_pages).to(self.dev), torch.stack(case.v_pages).to(self.dev),
                           torch.as_tensor(case.page_table, dtype=i32, device=self.dev),

@@ -54,6 +54,9 @@ def test_workspace_bytes_and_limits(lib):
     assert b"max_block" in lib.s2d2_last_error()
     assert lib.s2d2_stage_rows(2, 8) == 48
     assert lib.s2d2_workspace_bytes(None, 1, 4) == Bd.S2D2_EINVAL
+    d2 = Bd.model_desc(CONFIGS[2].cfg)
+    assert lib.s2d2_packed_bytes(C.byref(d2)) == 2 * (CONFIGS[2].cfg.n_params())  # every tile is full
+    assert lib.s2d2_packed_bytes(C.byref(Bd.model_desc(CONFIGS[1].cfg))) == 0    # fp32: canonical layouts
 
 
 @pytest.mark.parametrize("field,value", [("dtype", 7), ("head_dim", 48), ("n_kv_heads", 3), ("mask_id", -1),
@@ -68,16 +71,16 @@ def test_bad_descriptions_are_rejected(lib, field, value):
 def test_create_rejects_null_and_misaligned_arguments_without_a_device(lib):
     d = Bd.model_desc(CONFIGS[1].cfg)
     ctx = C.c_void_p()
-    assert lib.s2d2_create(C.byref(d), None, 1, 4, None, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL
+    assert lib.s2d2_create(C.byref(d), None, 1, 4, None, None, 0, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL
     layers = (Bd.LayerWeights * d.n_layers)()
     for l in range(d.n_layers):
         layers[l] = Bd.LayerWeights(*([0x1000] * 6), None, None, None)
     w = Bd.Weights(0x1000, 0x1000, 0x1000, layers)
-    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL  # no workspace
-    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1010, 1 << 30, C.byref(ctx)) == Bd.S2D2_EINVAL  # misaligned
-    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1000, 16, C.byref(ctx)) == Bd.S2D2_ENOSPC
+    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, None, 0, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL  # no workspace
+    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1010, 1 << 30, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL  # misaligned
+    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1000, 16, None, 0, C.byref(ctx)) == Bd.S2D2_ENOSPC
     layers[1].wo = 0x1004
-    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1000, 1 << 30, C.byref(ctx)) == Bd.S2D2_EINVAL
+    assert lib.s2d2_create(C.byref(d), C.byref(w), 1, 4, None, 0x1000, 1 << 30, None, 0, C.byref(ctx)) == Bd.S2D2_EINVAL
     assert b"layer 1" in lib.s2d2_last_error()
     assert ctx.value is None
 

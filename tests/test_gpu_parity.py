@@ -13,8 +13,8 @@ TINY = I.CONFIGS[1].cfg
 SMALL_BF16 = I.ModelCfg("small-bf16", 2, 512, 8, 4, 128, 1536, 32000)
 
 
-def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True):
-    run = H.GpuRun(case)
+def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True, packed=True):
+    run = H.GpuRun(case, packed=packed)
     rep = H.Report()
     for s in range(steps):
         prm = Params(step=s, seed=1234, **(prm_kw or {}))
@@ -51,6 +51,19 @@ def test_small_bf16_ragged_batch_paged():
     run, rep = run_steps(case, 3)
     print("small bf16:", rep)
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
+
+
+def test_small_bf16_canonical_weight_layout_path():
+    """Same model without the packed weight copy: the plain (unfused) kernels."""
+    case = H.make_case(SMALL_BF16, 2, 4, [70, 33], seed=6, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 2, packed=False)
+    print("small bf16 unpacked:", rep)
+
+
+def test_small_bf16_jittered_norm_gains_fused_path():
+    case = H.make_case(SMALL_BF16, 2, 8, [40, 90], seed=9, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.2)
+    run, rep = run_steps(case, 3)
+    print("small bf16 jitter:", rep)
 
 
 def test_small_bf16_real_prefill_b4():
