@@ -44,10 +44,13 @@ struct s2d2_ctx {
   void* vwin;
   void* vT_win;      // [max_batch, Hkv, D, wpad] key-minor V of the window (MFMA attention)
   float* attn_part;  // split-key partial outputs
+  int32_t* attn_counters;  // arrival counters of the split-key merge, zero between launches
+  int32_t attn_groups;
   int32_t wpad, attn_zmax, attn_z_override;
   bool force_generic_attention;
   VocabWs vws;
   float2* rope_cs;   // [rows_cap, D/2] cos / sin of the window rows
+  float* ss;         // [rows_cap, d/16] partial sums of squares of the residual rows (split RMSNorm)
   // packed bf16 weights (streaming GEMM); null when the caller gave no packed buffer
   struct PackedLayer { const uint4 *wqkv, *wo, *wg, *wu, *wdown; };
   PackedLayer* pk;
@@ -140,8 +143,11 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     const int q_tiles = (3 * c->max_block * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
     // Z * items * q_tiles < 512 + items * q_tiles by the choice of Z in forward()
     c->attn_part = cv.take<float>(attention_flash_partial_floats(512 + NB * d.n_kv_heads * q_tiles));
+    c->attn_groups = (int32_t)(NB * d.n_kv_heads * q_tiles);
+    c->attn_counters = cv.take<int32_t>(c->attn_groups);
   }
   c->rope_cs = cv.take<float2>(R * (size_t)(d.head_dim / 2));
+  c->ss = cv.take<float>(R * (size_t)((d.d_model + 15) / 16));
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   return (cv.off + 255) & ~(size_t)255;
@@ -198,7 +204,7 @@ KvGeom geom(const s2d2_ctx* c, const s2d2_kv_view* kv) {
 // ([n_layers, rows_cap, Hkv, D]) if given, else to a one-layer scratch.
 int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void* k_stage, void* v_stage, float* logits) {
   const s2d2_model_desc& d = c->desc;
-  const int dt = d.dtype, R = 3 * N * B, LR = N * B, es = elt_size(dt);  // grid bounds of this call
+  const int dt = d.dtype, R = (k_stage ? 3 : 2) * N * B, LR = N * B, es = elt_size(dt);  // row bounds of this call (draft: carry + block)
   const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
   hipStream_t st = c->stream;
   const KvGeom g = geom(c, kv);
@@ -207,12 +213,12 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int q_tiles = (3 * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
   int Z = 1;
   if (flash) {
-    // One split (no merge kernel) while that leaves <= 4 key tiles per wavefront or the batch alone
-    // fills the chip; else enough splits for ~512 workgroups with >= 2 tiles per wavefront.
+    // Splits until there are ~512 workgroups or a wavefront is down to one 32-key tile; the last
+    // split to finish merges, so extra splits cost one atomic, not a launch.
     const int cap_tiles = (kv->max_pages_per_seq * kv->page_size + 31) / 32;
     const int groups = N * d.n_kv_heads * q_tiles;
     const int want = (512 + groups - 1) / groups;
-    if (cap_tiles > 32 && groups < 512) Z = std::max(1, std::min(std::min(want, (cap_tiles + 15) / 16), c->attn_zmax));
+    Z = std::max(1, std::min(std::min(want, (cap_tiles + 7) / 8), c->attn_zmax));
     if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, want));
   }
   const size_t lds = flash ? 0 : attention_generic_lds_bytes(g, 3 * B);
@@ -220,8 +226,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const size_t stage_layer = (size_t)c->rows_cap * d.n_kv_heads * d.head_dim * es;
   const size_t page_layer = (size_t)kv->n_pages * d.n_kv_heads * kv->page_size * d.head_dim * es;
   const int32_t* n_rows = c->plan.counts;
-  { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   const bool fused = c->pk != nullptr;
+  const int ss_stride = (d.d_model + 15) / 16;
+  if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, c->ss, ss_stride); }
+  else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
   for (int l = 0; l < d.n_layers; ++l) {
     const s2d2_layer_weights& L = c->layers[l];
@@ -230,7 +238,8 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     if (fused) {
       GemmStreamArgs a{};
       a.Wp = c->pk[l].wqkv; a.NT = qkv_n / 16; a.KT = d.d_model / 32; a.N = qkv_n; a.K = d.d_model;
-      a.m_count = n_rows; a.H = c->h; a.gain = L.norm1; a.eps = d.rms_eps;
+      a.m_count = n_rows; a.X = (const bf16_t*)c->a; a.ldx = d.d_model; a.ss_part = c->ss; a.ss_stride = ss_stride;
+      a.ss_count = l == 0 ? 1 : ss_stride; a.eps = d.rms_eps;
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
       a.q_out = (bf16_t*)c->qbuf; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
@@ -245,7 +254,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
     if (flash) {
       ProfScope ps(c, 1, 0.0);
-      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, c->attn_part);
+      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, c->attn_part, c->attn_counters);
     } else {
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
@@ -255,16 +264,19 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.m_count = n_rows;
       a.Wp = c->pk[l].wo; a.NT = d.d_model / 16; a.KT = HqD / 32; a.N = d.d_model; a.K = HqD;
       a.X = (const bf16_t*)c->obuf; a.ldx = HqD; a.out = c->h; a.ldo = d.d_model;
+      a.xg_out = (bf16_t*)c->a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
       GemmStreamArgs b{};
       b.m_count = n_rows;
       b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
-      b.H = c->h; b.gain = L.norm2; b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
+      b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
+      b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
       { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
       GemmStreamArgs e{};
       e.m_count = n_rows;
       e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
       e.X = (const bf16_t*)c->ffn; e.ldx = d.d_ffn; e.out = c->h; e.ldo = d.d_model;
+      e.xg_out = (bf16_t*)c->a; e.gain_next = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f; e.ss_out = c->ss; e.ss_stride = ss_stride;
       { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
     } else {
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
@@ -277,7 +289,8 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   if (fused) {
     GemmStreamArgs a{};
     a.Wp = c->pk_unembed; a.NT = (d.vocab + 15) / 16; a.KT = d.d_model / 32; a.N = d.vocab; a.K = d.d_model;
-    a.m_count = n_logit; a.H = c->h; a.gain = c->w.norm_f; a.gather = c->plan.logit_src; a.eps = d.rms_eps;
+    a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = d.d_model; a.gather = c->plan.logit_src;
+    a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
     a.out = logits; a.ldo = d.vocab;
     ProfScope ps(c, 0, (double)d.vocab * d.d_model * es);
     launch_gemm_stream(st, SEPI_STORE_F32, a, LR);
@@ -350,7 +363,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   const int64_t need = s2d2_workspace_bytes(desc, max_batch, max_block);
   if (need < 0) return (int32_t)need;
   if (workspace_bytes < (size_t)need) return fail(S2D2_ENOSPC, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)need);
-  const bool use_packed = packed != nullptr && packed_total_bytes(*desc) > 0 && gemm_stream_norm_fits(desc->d_model);
+  const bool use_packed = packed != nullptr && packed_total_bytes(*desc) > 0;
   if (packed && ((uintptr_t)packed & 255)) return fail(S2D2_EINVAL, "packed buffer is not 256-byte aligned");
   if (use_packed && packed_bytes < packed_total_bytes(*desc)) return fail(S2D2_ENOSPC, "packed buffer has %zu bytes, %zu needed", packed_bytes, packed_total_bytes(*desc));
 
@@ -402,6 +415,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     c->pk_unembed = put(c->w.unembed, d.vocab, d.d_model, 0);
     if (hipGetLastError() != hipSuccess) { free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "weight packing failed to launch"); }
   }
+  launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;

@@ -156,11 +156,45 @@ __device__ __forceinline__ void fa_merge(FaState& a, float m2, float l2, const f
     for (int i = 0; i < 16; ++i) a.o[t][i] = a.o[t][i] * f1 + o2[t][i] * f2;
 }
 
+// Merges the Z split partials of one (sequence, KV head, query tile) in split order.
+__device__ __forceinline__ void fa_combine(const float* part_o, const float* part_ml, size_t item0, int Z, int tid,
+                                           int nthreads, int qt, int nq, int grp, int row0, int kvh, int Hq,
+                                           bf16_t* __restrict__ o) {
+  constexpr int D = FA_D;
+  for (int e = tid; e < 32 * (D / 4); e += nthreads) {
+    const int c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+    const int qi = qt * 32 + c;
+    if (qi >= nq) continue;
+    float M = -INFINITY;
+    for (int z = 0; z < Z; ++z) M = fmaxf(M, __builtin_nontemporal_load(&part_ml[(item0 + z) * 64 + c]));
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < Z; ++z) {
+      const float m = __builtin_nontemporal_load(&part_ml[(item0 + z) * 64 + c]);
+      if (m == -INFINITY) continue;
+      const float f = __builtin_amdgcn_exp2f(m - M);
+      l += f * __builtin_nontemporal_load(&part_ml[(item0 + z) * 64 + 32 + c]);
+      const float* pv = part_o + ((item0 + z) * 32 + c) * D + d0;
+      acc.x += f * __builtin_nontemporal_load(pv);
+      acc.y += f * __builtin_nontemporal_load(pv + 1);
+      acc.z += f * __builtin_nontemporal_load(pv + 2);
+      acc.w += f * __builtin_nontemporal_load(pv + 3);
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+    uint2 pk;
+    pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
+    pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
+    *(uint2*)(o + ((size_t)r * Hq + head) * D + d0) = pk;
+  }
+}
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
     const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
-    int wpad, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    int wpad, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ part_o, float* __restrict__ part_ml,
+    int32_t* __restrict__ counters) {
   extern __shared__ float smem[];
   constexpr int D = FA_D;
   const int z = blockIdx.x, qt = blockIdx.y;
@@ -323,11 +357,10 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
     }
     __syncthreads();
   }
-  if (wave != 0) return;
   // st.o[dt][i]: d = dt*32 + 8 (i/4) + 4 h + (i%4), query row c
   const bool q_ok = (q0 + c) < nq;
   if (Z == 1) {
-    if (!q_ok) return;
+    if (wave != 0 || !q_ok) return;
     const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
     bf16_t* op = o + ((size_t)r * Hq + head) * D;
 #pragma unroll
@@ -340,8 +373,14 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
         pk.y = (uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 2] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 3] * inv) << 16);
         *(uint2*)(op + d0) = pk;
       }
-  } else {
-    const size_t item = ((size_t)blockIdx.z * gridDim.y + qt) * Z + z;
+    return;
+  }
+  // Z > 1: write this split's partial; the workgroup that arrives last merges all splits in split
+  // order (so the result does not depend on which one it is) and re-arms the counter.
+  const int group = blockIdx.z * gridDim.y + qt;
+  const size_t item0 = (size_t)group * Z;
+  if (wave == 0) {
+    const size_t item = item0 + z;
     float* po = part_o + item * 32 * D + (size_t)c * D;
     if (h == 0) {
       part_ml[item * 64 + c] = st.m;
@@ -354,44 +393,19 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
         const int d0 = dt * 32 + 8 * i4 + 4 * h;
         *(float4*)(po + d0) = make_float4(st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
       }
+    __threadfence();  // partial visible device-wide before the arrival is counted
   }
-}
-
-// Merges the Z split partials of one (sequence, KV head, query tile) in split order.
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o,
-                                                           const float* __restrict__ part_ml, KvGeom g, Plan p,
-                                                           int Hq, int Z, bf16_t* __restrict__ o) {
-  constexpr int D = FA_D;
-  const int qt = blockIdx.x;
-  const int Hkv = g.n_kv_heads;
-  const int n = blockIdx.y / Hkv, kvh = blockIdx.y % Hkv;
-  const int grp = Hq / Hkv;
-  const int row0 = p.seq_row0[n], nq = p.seq_rows[n] * grp;
-  if (qt * 32 >= nq) return;
-  const size_t item0 = ((size_t)blockIdx.y * gridDim.x + qt) * Z;
-  for (int e = threadIdx.x; e < 32 * (D / 4); e += 256) {
-    const int c = e / (D / 4), d0 = (e % (D / 4)) * 4;
-    const int qi = qt * 32 + c;
-    if (qi >= nq) continue;
-    float M = -INFINITY;
-    for (int z = 0; z < Z; ++z) M = fmaxf(M, part_ml[(item0 + z) * 64 + c]);
-    float l = 0.f;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int z = 0; z < Z; ++z) {
-      const float m = part_ml[(item0 + z) * 64 + c];
-      if (m == -INFINITY) continue;
-      const float f = __builtin_amdgcn_exp2f(m - M);
-      l += f * part_ml[(item0 + z) * 64 + 32 + c];
-      const float4 v = *(const float4*)(part_o + ((item0 + z) * 32 + c) * D + d0);
-      acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
-    }
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-    const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
-    uint2 pk;
-    pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
-    pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
-    *(uint2*)(o + ((size_t)r * Hq + head) * D + d0) = pk;
+  __syncthreads();
+  int* s_last = (int*)smem;
+  if (threadIdx.x == 0) {
+    const int prev = atomicAdd(&counters[group], 1);
+    *s_last = prev == Z - 1;
+    if (prev == Z - 1) counters[group] = 0;
   }
+  __syncthreads();
+  if (!*s_last) return;
+  __threadfence();  // acquire the other splits' partials
+  fa_combine(part_o, part_ml, item0, Z, threadIdx.x, NW * 64, qt, nq, grp, row0, kvh, Hq, o);
 }
 
 static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * sizeof(float); }
@@ -399,21 +413,27 @@ static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * siz
 // Floats needed for `entries` split partials (one per (sequence, KV head, query tile, split)).
 size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * FA_D + 64); }
 
-// q_tiles = ceil(3 B grp / 32); Z key splits of 8 wavefronts each.  One split writes the output
-// directly; Z > 1 merges the splits in a second kernel.
+// q_tiles = ceil(3 B grp / 32); Z key splits of 8 wavefronts each.  `counters` holds one zeroed
+// arrival counter per (sequence, KV head, query tile); the last split to arrive merges.
 void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
-                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part) {
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part, int32_t* counters) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.head_dim);
   const int items = N * g.n_kv_heads;
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
   hipLaunchKernelGGL(attn_flash_kernel<8>, dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
                      (const bf16_t*)q, (const bf16_t*)k_win, (const bf16_t*)vT_win, (const bf16_t*)k_pages_layer,
-                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, part_o, part_ml);
-  if (Z > 1)
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(q_tiles, items), dim3(256), 0, st, part_o, part_ml, g, p, Hq, Z,
-                       (bf16_t*)o);
+                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, part_o, part_ml,
+                     counters);
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
 }
 
 // Raises the dynamic-LDS limit of the kernels once (160 KB per workgroup on gfx950).

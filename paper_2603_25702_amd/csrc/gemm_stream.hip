@@ -68,10 +68,15 @@ void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float
 
 // ---------------------------------------------------------------------------------------------
 // Latency matters as much as bandwidth here (a layer's matrices are 8-50 MB, a few microseconds
-// of HBM time each), so the kernel is arranged to have every global load in flight at once:
-// the wavefront's weight fragments are requested first (they depend on nothing), then the row
-// count, then all residual rows of the fused RMSNorm (one column group per thread, all rows
-// unrolled), and only then does anything wait.
+// of HBM time each), so every global load of a wavefront is in flight at once: its weight
+// fragments first (they depend on nothing), then the row count, the activation fragments and
+// the partial sums of squares.
+//
+// RMSNorm is split across the producer / consumer pair so that no workgroup has to see a whole
+// residual row twice: the residual-add epilogue (SEPI_ADD_F32) of the producing GEMM also writes
+// xg = bf16(h * gain_of_the_next_norm) and, per (row, 16-feature tile), the sum of squares of
+// its h values; the consuming GEMM (SPRO_BF16S) multiplies xg as it is and scales its fp32 result
+// by 1/rms, which it gets by adding the row's partial sums in tile order (deterministic).
 template <int NW, int TA>
 __device__ __forceinline__ float tile_total(const float* s_red, int t, int fe, int row) {
   const int src = (fe & 3) * 64 + (fe >> 2) * 16 + row;
@@ -85,7 +90,6 @@ template <int EPI, int PRO, int NW, int TPW, int U>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
-  constexpr int T = NW * 64;
   extern __shared__ __align__(16) uint8_t smem_raw[];
   const int m0 = blockIdx.y * 16;
   int M = 0;
@@ -96,12 +100,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   const int nt0 = blockIdx.x * TPW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, f = lane & 15;
-  const int K = a.K, KT = a.KT;
-  const int xs_stride = K + 8;  // bf16 elements; 16-byte skew between rows avoids LDS bank conflicts
+  const int KT = a.KT;
 
-  float* s_part = (float*)smem_raw;                                 // [NW][16] partial sums of squares
-  float* s_red = s_part + NW * 16;                                  // [NW][TA][256]
-  bf16_t* xs = (bf16_t*)(s_red + (size_t)NW * TA * 256);            // [16][K + 8] (SPRO_NORM only)
+  float* s_rs = (float*)smem_raw;                                   // [16] 1/rms per row (SPRO_BF16S)
+  float* s_red = s_rs + 16;                                         // [NW][TA][256]
 
   const u32x4_t zero = {0u, 0u, 0u, 0u};
   const int kt_begin = (int)((long long)wave * KT / NW), kt_end = (int)((long long)(wave + 1) * KT / NW);
@@ -122,61 +124,33 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   const int Mloc = min(16, M - m0);
   if (Mloc <= 0) return;  // whole workgroup (M is uniform)
 
-  if (PRO == SPRO_NORM) {
-    // thread -> group of 4 columns, all rows: Mloc + 1 independent 16-byte loads per group
-    const int C4 = K >> 2;
-    float ss[16];
+  const bool row_ok = f < Mloc;
+  const int xrow = row_ok ? (a.gather ? a.gather[m0 + f] : m0 + f) : 0;
+  const bf16_t* xg = a.X + (size_t)xrow * a.ldx + g * 8;
+  u32x4_t xb[U];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) ss[r] = 0.f;
-    for (int c = threadIdx.x; c < C4; c += T) {
-      const f32x4_t gn = ((const f32x4_t*)a.gain)[c];
-      f32x4_t hv[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (r < Mloc) {
-          const int src = a.gather ? a.gather[m0 + r] : m0 + r;
-          hv[r] = ((const f32x4_t*)a.H)[(size_t)src * C4 + c];
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        u32x2_t pk = {0u, 0u};
-        if (r < Mloc) {
-          const f32x4_t h = hv[r];
-          ss[r] += h.x * h.x + h.y * h.y + h.z * h.z + h.w * h.w;
-          pk.x = (uint32_t)f32_to_bf16(h.x * gn.x) | ((uint32_t)f32_to_bf16(h.y * gn.y) << 16);
-          pk.y = (uint32_t)f32_to_bf16(h.z * gn.z) | ((uint32_t)f32_to_bf16(h.w * gn.w) << 16);
-        }
-        *(u32x2_t*)(xs + (size_t)r * xs_stride + 4 * c) = pk;
-      }
+  for (int u = 0; u < U; ++u)
+    xb[u] = (row_ok && kt_begin + u < kt_end) ? *(const u32x4_t*)(xg + (kt_begin + u) * 32) : zero;
+
+  if (PRO == SPRO_BF16S && threadIdx.x < 256) {  // 1/rms of the 16 rows from the producer's partial sums
+    const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
+    float v = 0.f;
+    if (row < Mloc) {
+      const float* pp = a.ss_part + (size_t)(a.gather ? a.gather[m0 + row] : m0 + row) * a.ss_stride;
+      for (int i = sub; i < a.ss_count; i += 16) v += pp[i];
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      if (r < Mloc) {
-        float v = ss[r];
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        if (lane == 0) s_part[wave * 16 + r] = v;
-      }
-    }
-    __syncthreads();
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 8, 64);
+    if (sub == 0) s_rs[row] = 1.0f / sqrtf(v / (float)a.K + a.eps);
   }
 
   f32x4_t acc[TA];
 #pragma unroll
   for (int t = 0; t < TA; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  const bool row_ok = f < Mloc;
-  const bf16_t* xg = PRO == SPRO_BF16 ? a.X + (size_t)(row_ok ? m0 + f : m0) * a.ldx + g * 8 : nullptr;
-  const bf16_t* xl = xs + (size_t)f * xs_stride + g * 8;
 
   for (int kt0 = kt_begin; kt0 < kt_end;) {
-    u32x4_t xb[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u;
-      const bool ok = kt < kt_end;
-      if (PRO == SPRO_NORM) xb[u] = ok ? *(const u32x4_t*)(xl + kt * 32) : zero;
-      else xb[u] = (ok && row_ok) ? *(const u32x4_t*)(xg + kt * 32) : zero;
-    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -186,9 +160,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     kt0 += U;
     if (kt0 < kt_end) {  // next batch (the layer matrices are sized so that one batch covers a wavefront's share)
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u) {
 #pragma unroll
         for (int t = 0; t < TA; ++t) w[t][u] = (kt0 + u < kt_end) ? wp[t][(size_t)(kt0 + u) * 64] : zero;
+        xb[u] = (row_ok && kt0 + u < kt_end) ? *(const u32x4_t*)(xg + (kt0 + u) * 32) : zero;
+      }
     }
   }
   // acc[t][i] = Y[m0 + f][tile t, feature 4 g + i]
@@ -200,14 +176,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   if (threadIdx.x >= 256) return;
   const int row = threadIdx.x >> 4, fe = threadIdx.x & 15;
   const int m = m0 + row;
-  if (row >= Mloc) return;
-  float rs = 1.0f;
-  if (PRO == SPRO_NORM) {
-    float v = 0.f;
-#pragma unroll
-    for (int w_ = 0; w_ < NW; ++w_) v += s_part[w_ * 16 + row];
-    rs = 1.0f / sqrtf(v / (float)K + a.eps);
-  }
+  const bool live = row < Mloc;
+  const float rs = PRO == SPRO_BF16S ? s_rs[row] : 1.0f;
 #define S2D2_TOTAL(t_, fe_) (tile_total<NW, TA>(s_red, (t_), (fe_), row) * rs)
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -215,15 +185,30 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     if (nt < a.NT) {
       if (EPI == SEPI_STORE_F32) {
         const int n = nt * 16 + fe;
-        if (n < a.N) ((float*)a.out)[(size_t)m * a.ldo + n] = S2D2_TOTAL(t, fe);
+        if (live && n < a.N) ((float*)a.out)[(size_t)m * a.ldo + n] = S2D2_TOTAL(t, fe);
       } else if (EPI == SEPI_ADD_F32) {
+        // residual add; also emits the next norm's operand and this tile's share of the row's sum of squares
         const int n = nt * 16 + fe;
-        if (n < a.N) ((float*)a.out)[(size_t)m * a.ldo + n] += S2D2_TOTAL(t, fe);
+        float hv = 0.f;
+        if (live && n < a.N) {
+          float* hp = (float*)a.out + (size_t)m * a.ldo + n;
+          hv = *hp + S2D2_TOTAL(t, fe);
+          *hp = hv;
+          if (a.xg_out) a.xg_out[(size_t)m * a.ldo + n] = f32_to_bf16(hv * a.gain_next[n]);
+        }
+        if (a.ss_out) {
+          float sq = hv * hv;
+          sq += __shfl_xor(sq, 1, 64);
+          sq += __shfl_xor(sq, 2, 64);
+          sq += __shfl_xor(sq, 4, 64);
+          sq += __shfl_xor(sq, 8, 64);
+          if (live && fe == 0) a.ss_out[(size_t)m * a.ss_stride + nt] = sq;
+        }
       } else if (EPI == SEPI_SWIGLU) {
         const int n = nt * 16 + fe;
         const float gate = S2D2_TOTAL(2 * t, fe), up = S2D2_TOTAL(2 * t + 1, fe);
-        if (n < a.N) ((bf16_t*)a.out)[(size_t)m * a.ldo + n] = f32_to_bf16(gate / (1.0f + __expf(-gate)) * up);
-      } else if (fe < 8) {  // SEPI_QKV_ROPE: lanes fe < 8 own the pair (i, i + D/2) of one head
+        if (live && n < a.N) ((bf16_t*)a.out)[(size_t)m * a.ldo + n] = f32_to_bf16(gate / (1.0f + __expf(-gate)) * up);
+      } else if (live && fe < 8) {  // SEPI_QKV_ROPE: lanes fe < 8 own the pair (i, i + D/2) of one head
         const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
         const int head = nt / tiles_per_head, i = 8 * (nt % tiles_per_head) + fe;
         const float x1 = S2D2_TOTAL(t, fe), x2 = S2D2_TOTAL(t, fe + 8);
@@ -250,43 +235,63 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
       }
     }
   }
+#undef S2D2_TOTAL
 }
 
 template <int EPI, int PRO, int NW, int TPW, int U>
 static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   constexpr int TA = TPW * (EPI == SEPI_SWIGLU ? 2 : 1);
-  size_t lds = (size_t)NW * 16 * sizeof(float) + (size_t)NW * TA * 256 * sizeof(float);
-  if (PRO == SPRO_NORM) lds += (size_t)16 * (a.K + 8) * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_stream_kernel<EPI, PRO, NW, TPW, U>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    attr_set = true;
-  }
+  const size_t lds = 16 * sizeof(float) + (size_t)NW * TA * 256 * sizeof(float);
   dim3 grid((a.NT + TPW - 1) / TPW, (m_cap + 15) / 16), block(NW * 64);
   hipLaunchKernelGGL((gemm_stream_kernel<EPI, PRO, NW, TPW, U>), grid, block, lds, st, a);
 }
-
-bool gemm_stream_norm_fits(int K) { return 16 * 16 * sizeof(float) + 16 * 4 * 256 * sizeof(float) + (size_t)16 * (K + 8) * 2 <= 160 * 1024; }
 
 // Launch shapes: the layer matrices want >= 256 workgroups / >= 2000 wavefronts with the whole
 // share of a wavefront in one batch of loads; the unembedding is long enough to batch.
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
   switch (kind) {
     case SEPI_QKV_ROPE:
-      if (a.NT >= 1024) launch_cfg<SEPI_QKV_ROPE, SPRO_NORM, 4, 2, 4>(st, a, m_cap);
-      else launch_cfg<SEPI_QKV_ROPE, SPRO_NORM, 8, 1, 8>(st, a, m_cap);
+      if (a.NT >= 1024) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4>(st, a, m_cap);
+      else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8>(st, a, m_cap);
       break;
     case SEPI_ADD_F32:
       if (a.KT >= 128) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 12>(st, a, m_cap);
       else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4>(st, a, m_cap);
       break;
     case SEPI_SWIGLU:
-      launch_cfg<SEPI_SWIGLU, SPRO_NORM, 8, 1, 8>(st, a, m_cap);
+      launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8>(st, a, m_cap);
       break;
     case SEPI_STORE_F32:
-      launch_cfg<SEPI_STORE_F32, SPRO_NORM, 4, 4, 4>(st, a, m_cap);
+      launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8>(st, a, m_cap);
       break;
   }
+}
+
+// First norm of the forward: xg = bf16(h * gain), one partial sum of squares per row.
+__global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restrict__ embed, int d, Plan p,
+                                                         const float* __restrict__ gain, float* __restrict__ h,
+                                                         bf16_t* __restrict__ xg, float* __restrict__ ss, int ss_stride) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  if (r >= p.counts[0]) return;
+  const bf16_t* src = embed + (size_t)p.row_token[r] * d;
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float v = bf16_to_f32(src[i]);
+    h[(size_t)r * d + i] = v;
+    xg[(size_t)r * d + i] = f32_to_bf16(v * gain[i]);
+    acc += v * v;
+  }
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) ss[(size_t)r * ss_stride] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
+                       float* h, void* xg, float* ss, int ss_stride) {
+  hipLaunchKernelGGL(embed_norm_kernel, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, gain, h,
+                     (bf16_t*)xg, ss, ss_stride);
 }
 
 }  // namespace s2d2

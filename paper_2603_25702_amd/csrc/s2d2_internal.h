@@ -89,20 +89,24 @@ void launch_gemm(hipStream_t st, int dtype, GemmEpilogue epi, const void* X, int
 
 // gemm_stream.hip : packed-weight streaming GEMM with fused prologue / epilogue (bf16)
 enum StreamEpilogue { SEPI_STORE_F32 = 0, SEPI_ADD_F32 = 1, SEPI_SWIGLU = 2, SEPI_QKV_ROPE = 3 };
-enum StreamPrologue { SPRO_BF16 = 0, SPRO_NORM = 1 };
+enum StreamPrologue { SPRO_BF16 = 0, SPRO_BF16S = 1 };  // S: scale the result by 1/rms from partial sums
 struct GemmStreamArgs {
   const uint4* Wp;          // packed weights [NT][KT][64] x 16 bytes
   const uint4* Wp2;         // second matrix (up projection) for SEPI_SWIGLU
   int32_t NT, KT, N, K;
   const int32_t* m_count;   // device: number of valid rows
-  const bf16_t* X;          // SPRO_BF16: activations [M, ldx]
+  const bf16_t* X;          // activations [*, ldx] (for SPRO_BF16S: h * gain, not yet divided by the rms)
   int32_t ldx;
-  const float* H;           // SPRO_NORM: fp32 residual rows [*, K]
-  const float* gain;        // [K]
-  const int32_t* gather;    // optional row indices into H
+  const int32_t* gather;    // optional row indices into X / ss_part
+  const float* ss_part;     // SPRO_BF16S: [*, ss_stride] partial sums of squares of the residual rows
+  int32_t ss_stride, ss_count;
   float eps;
   void* out;
   int32_t ldo;
+  // SEPI_ADD_F32 extras (all optional): operand of the next norm and its partial sums of squares
+  bf16_t* xg_out;           // [*, ldo]
+  const float* gain_next;   // [N]
+  float* ss_out;            // [*, ss_stride], entry nt of a row = this tile's share
   // SEPI_QKV_ROPE
   const float2* rope_cs;    // [rows, D/2] (cos, sin)
   int32_t Hq, Hkv, D, wpad;
@@ -116,7 +120,8 @@ struct GemmStreamArgs {
 size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
 void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs);
-bool gemm_stream_norm_fits(int K);
+void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
+                       float* h, void* xg, float* ss, int ss_stride);
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
 
 // attention.hip
@@ -127,7 +132,8 @@ int attention_init();
 size_t attention_flash_partial_floats(size_t entries);
 void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
-                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part);
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part, int32_t* counters);
+void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
 
 // vocab.hip
