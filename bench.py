@@ -97,7 +97,7 @@ def main():
         prof = ses.eng.s2d2_profile_stop()
         g = prof["gemm"]
         ach = g["bytes"] / (g["ms"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gemm_rows16_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+        roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
                     "avg_launch_us": round(g["ms"] * 1e3 / g["launches"], 3),
                     "bytes_per_launch": round(g["bytes"] / g["launches"])}

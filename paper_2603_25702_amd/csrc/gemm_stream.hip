@@ -8,9 +8,9 @@
 // MFMA operand: no LDS and no shuffles on the weight path, fully coalesced HBM reads.
 //
 // A workgroup owns TPW feature tiles; its NW wavefronts split K into contiguous ranges and are
-// combined through LDS in a fixed order (deterministic).  Fused prologue: RMSNorm of the fp32
-// residual rows (gain applied before the bf16 rounding, 1/rms applied to the fp32 result).
-// Fused epilogues: fp32 store (logits), residual add, SwiGLU, and RoPE + q/k/v split.
+// combined through LDS in a fixed order (deterministic).  RMSNorm is folded into the GEMMs on
+// both sides of it (see below).  Fused epilogues: fp32 store (logits), residual add (+ operand and
+// partial sums of squares of the next norm), SwiGLU, and RoPE + q/k/v split.
 #include "s2d2_internal.h"
 #include "../../include/s2d2.h"
 
