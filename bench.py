@@ -35,6 +35,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="counter calibration: first run a plain elementwise copy kernel over this many MiB "
+                         "(read once, written once) so that a rocprofv3 --pmc run of this command holds a kernel of "
+                         "known HBM traffic next to the library's kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs would be plain "
@@ -46,6 +50,15 @@ def main():
     import s2d2_inputs as I
     from paper_2603_25702_amd import Params
     from paper_2603_25702_amd.runner import Session
+
+    if args.calibrate_copy_mib > 0:
+        n = args.calibrate_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)  # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = I.CONFIGS[args.config]
     cfg = wl.cfg if not args.layers else I.shrink(wl.cfg, n_layers=args.layers)
