@@ -64,7 +64,9 @@ extern "C" {
 typedef struct s2d2_ctx s2d2_ctx;
 
 /* Decoder shape.  Pre-norm blocks: RMSNorm, GQA attention with half-split RoPE, SwiGLU FFN
- * (n_experts == 0) or softmax-top-k MoE of SwiGLU experts (n_experts > 0). */
+ * (n_experts == 0) or softmax-top-k MoE of SwiGLU experts (n_experts > 0: bf16 only, n_experts <= 256,
+ * top_k <= 64; router = softmax over all experts, top-k by value with ties to the lower index, weights
+ * renormalised to sum 1, no shared expert, no capacity limit). */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t n_experts, top_k, d_expert;   /* all 0 for a dense model */
@@ -201,8 +203,8 @@ int64_t s2d2_stage_rows(int32_t max_batch, int32_t max_block);
 /* Bytes of device workspace needed for these limits; negative S2D2_E* on a bad description. */
 int64_t s2d2_workspace_bytes(const s2d2_model_desc* desc, int32_t max_batch, int32_t max_block);
 
-/* Bytes of the packed copy of the projection weights that the streaming GEMM reads (bf16 dense
- * models; 0 for other models).  The library does not allocate it: the caller passes a device buffer
+/* Bytes of the packed copy of the projection weights that the MFMA GEMMs read (bf16 models; 0 for
+ * fp32 models).  MoE models require it.  The library does not allocate it: the caller passes a device buffer
  * of this size to s2d2_create. */
 int64_t s2d2_packed_bytes(const s2d2_model_desc* desc);
 
@@ -247,6 +249,12 @@ int32_t s2d2_block_advance(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_blo
 /* Alg. 2 commit: x^b_i <- x_hat_i for every i in the draft's threshold set. */
 int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_t B,
                               const s2d2_draft_out* draft);
+
+/* MoE models: the experts chosen by the router in the most recent forward (draft or verifier),
+ * out = device [n_layers, rows, top_k] int32 for the first `rows` window rows (window rows are packed
+ * sequence after sequence: leading causal rows, drafted rows, then [MASK] copies).  The parity
+ * tests use it to hold the oracle to the same routing where a router score is tied to rounding. */
+int32_t s2d2_moe_choices(s2d2_ctx* ctx, int32_t rows, int32_t* out /* device */);
 
 /* Vocabulary stage alone on caller-provided logits (same kernels the calls above use):
  * draft statistics for `rows` fp32 logit rows of width V.  Outputs are [rows]. */

@@ -22,7 +22,7 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
-    "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
+    "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
 PROFILE_CLASSES = ("gemm", "attention", "vocab", "other")
 
@@ -120,12 +120,14 @@ def load_library():
     lib.s2d2_block_advance.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
                                        C.c_void_p]
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
+    lib.s2d2_moe_choices.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    lib.s2d2_moe_choices.restype = C.c_int32
     lib.s2d2_vocab_draft_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 5
     lib.s2d2_vocab_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.s2d2_profile_start.argtypes = [C.c_void_p, C.c_int32]
     lib.s2d2_profile_stop.argtypes = [C.c_void_p, C.POINTER(ProfileC)]
     for name in ("s2d2_profile_start", "s2d2_profile_stop", "s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
-                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
+                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
     return lib
@@ -338,6 +340,12 @@ class Engine:
 
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
+
+    def s2d2_moe_choices(self, rows: int) -> torch.Tensor:
+        """[n_layers, rows, top_k] experts chosen in the most recent forward (device int32)."""
+        out = torch.empty((self.cfg.n_layers, rows, self.cfg.top_k), dtype=torch.int32, device=self.device)
+        _check(self.lib, self.lib.s2d2_moe_choices(self.ctx, rows, out.data_ptr()))
+        return out
 
     def s2d2_profile_start(self, max_launches: int):
         _check(self.lib, self.lib.s2d2_profile_start(self.ctx, max_launches))

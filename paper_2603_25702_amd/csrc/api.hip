@@ -52,7 +52,18 @@ struct s2d2_ctx {
   float2* rope_cs;   // [rows_cap, D/2] cos / sin of the window rows
   float* ss;         // [rows_cap, d/16] partial sums of squares of the residual rows (split RMSNorm)
   // packed bf16 weights (streaming GEMM); null when the caller gave no packed buffer
-  struct PackedLayer { const uint4 *wqkv, *wo, *wg, *wu, *wdown; };
+  struct PackedLayer { const uint4 *wqkv, *wo, *wg, *wu, *wdown, *router, *eg, *eu, *ed; };
+  // MoE scratch
+  float* router_logits;   // [rows_cap, E]
+  int32_t* moe_choice;    // [n_layers, rows_cap * top_k] experts chosen in the last forward
+  int32_t* moe_pos;       // [rows_cap * top_k] place of the slot inside its expert's group
+  float* moe_w;           // [rows_cap * top_k] renormalised routing weights
+  int32_t* moe_cnt;       // [E] group counters, zero between launches
+  int32_t* moe_sorted;    // [rows_cap * top_k]
+  int32_t *moe_tile_expert, *moe_tile_row0, *moe_tile_rows, *moe_n_tiles;
+  int32_t moe_tile_cap;
+  void* moe_act;          // [rows_cap * top_k, d_expert]
+  float* moe_y;           // [rows_cap * top_k, d_model]
   PackedLayer* pk;
   const uint4* pk_unembed;
   // profiling (measurement aid)
@@ -90,9 +101,11 @@ int32_t check_desc(const s2d2_model_desc* d) {
     if (d->d_ffn < kq || d->d_ffn % kq) return fail(S2D2_EINVAL, "d_ffn must be a positive multiple of %d", kq);
     if (d->top_k || d->d_expert) return fail(S2D2_EINVAL, "top_k and d_expert must be 0 for a dense model");
   } else {
-    if (d->n_experts < 0 || d->top_k < 1 || d->top_k > d->n_experts || d->d_expert < kq || d->d_expert % kq)
-      return fail(S2D2_EINVAL, "MoE shape out of range");
-    return fail(S2D2_EINVAL, "MoE models are not supported by this build yet");
+    if (d->n_experts < 0 || d->n_experts > 256 || d->top_k < 1 || d->top_k > d->n_experts || d->top_k > 64 ||
+        d->d_expert < kq || d->d_expert % kq)
+      return fail(S2D2_EINVAL, "MoE shape out of range (n_experts <= 256, top_k <= min(64, n_experts), d_expert a multiple of %d)", kq);
+    if (d->dtype != S2D2_BF16) return fail(S2D2_EINVAL, "MoE models must be bf16");
+    if (d->d_ffn) return fail(S2D2_EINVAL, "d_ffn must be 0 for a MoE model");
   }
   if (d->mask_id < 0 || d->mask_id >= d->vocab) return fail(S2D2_EINVAL, "mask_id outside the vocabulary");
   if (d->vocab > 8192 * 256) return fail(S2D2_EINVAL, "vocab above 2097152 is not supported");
@@ -148,6 +161,22 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   }
   c->rope_cs = cv.take<float2>(R * (size_t)(d.head_dim / 2));
   c->ss = cv.take<float>(R * (size_t)((d.d_model + 15) / 16));
+  if (d.n_experts > 0) {
+    const size_t RK = R * (size_t)d.top_k;
+    c->router_logits = cv.take<float>(R * (size_t)d.n_experts);
+    c->moe_choice = cv.take<int32_t>((size_t)d.n_layers * RK);
+    c->moe_pos = cv.take<int32_t>(RK);
+    c->moe_w = cv.take<float>(RK);
+    c->moe_cnt = cv.take<int32_t>(d.n_experts);
+    c->moe_sorted = cv.take<int32_t>(RK);
+    c->moe_tile_cap = (int32_t)(RK / 128 + d.n_experts + 1);
+    c->moe_tile_expert = cv.take<int32_t>(c->moe_tile_cap);
+    c->moe_tile_row0 = cv.take<int32_t>(c->moe_tile_cap);
+    c->moe_tile_rows = cv.take<int32_t>(c->moe_tile_cap);
+    c->moe_n_tiles = cv.take<int32_t>(8);
+    c->moe_act = cv.take<uint8_t>(RK * (size_t)d.d_expert * es);
+    c->moe_y = cv.take<float>(RK * (size_t)d.d_model);
+  }
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   return (cv.off + 255) & ~(size_t)255;
@@ -167,10 +196,14 @@ struct ProfScope {
 };
 
 size_t packed_total_bytes(const s2d2_model_desc& d) {
-  if (d.dtype != S2D2_BF16 || d.n_experts > 0) return 0;
+  if (d.dtype != S2D2_BF16) return 0;
   const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
-  size_t per = packed_weight_bytes(qkv_n, d.d_model) + packed_weight_bytes(d.d_model, HqD) +
-               2 * packed_weight_bytes(d.d_ffn, d.d_model) + packed_weight_bytes(d.d_model, d.d_ffn);
+  size_t per = packed_weight_bytes(qkv_n, d.d_model) + packed_weight_bytes(d.d_model, HqD);
+  if (d.n_experts > 0)
+    per += packed_weight_bytes(d.n_experts, d.d_model) +
+           (size_t)d.n_experts * (2 * packed_weight_bytes(d.d_expert, d.d_model) + packed_weight_bytes(d.d_model, d.d_expert));
+  else
+    per += 2 * packed_weight_bytes(d.d_ffn, d.d_model) + packed_weight_bytes(d.d_model, d.d_ffn);
   return per * d.n_layers + packed_weight_bytes(d.vocab, d.d_model);
 }
 
@@ -266,18 +299,51 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.X = (const bf16_t*)c->obuf; a.ldx = HqD; a.out = c->h; a.ldo = d.d_model;
       a.xg_out = (bf16_t*)c->a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
-      GemmStreamArgs b{};
-      b.m_count = n_rows;
-      b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
-      b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
-      b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
-      { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
-      GemmStreamArgs e{};
-      e.m_count = n_rows;
-      e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
-      e.X = (const bf16_t*)c->ffn; e.ldx = d.d_ffn; e.out = c->h; e.ldo = d.d_model;
-      e.xg_out = (bf16_t*)c->a; e.gain_next = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f; e.ss_out = c->ss; e.ss_stride = ss_stride;
-      { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
+      const float* gain_after = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f;
+      if (d.n_experts == 0) {
+        GemmStreamArgs b{};
+        b.m_count = n_rows;
+        b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
+        b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
+        b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
+        { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
+        GemmStreamArgs e{};
+        e.m_count = n_rows;
+        e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
+        e.X = (const bf16_t*)c->ffn; e.ldx = d.d_ffn; e.out = c->h; e.ldo = d.d_model;
+        e.xg_out = (bf16_t*)c->a; e.gain_next = gain_after; e.ss_out = c->ss; e.ss_stride = ss_stride;
+        { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
+      } else {
+        // MoE FFN: router -> top-k -> group by expert -> grouped gate/up + SwiGLU -> grouped down -> combine
+        const int E = d.n_experts, Fe = d.d_expert, tk = d.top_k;
+        int32_t* choice = c->moe_choice + (size_t)l * c->rows_cap * tk;
+        GemmStreamArgs r{};
+        r.m_count = n_rows;
+        r.Wp = c->pk[l].router; r.NT = (E + 15) / 16; r.KT = d.d_model / 32; r.N = E; r.K = d.d_model;
+        r.X = (const bf16_t*)c->a; r.ldx = d.d_model; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
+        r.eps = d.rms_eps; r.out = c->router_logits; r.ldo = E;
+        { ProfScope ps(c, 0, (double)E * d.d_model * es); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
+        { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w, c->moe_pos, c->moe_cnt); }
+        { ProfScope ps(c, 3, 0.0); launch_moe_group(st, E, tk, n_rows, choice, c->moe_pos, c->moe_cnt, c->moe_sorted, c->moe_tile_expert,
+                                                     c->moe_tile_row0, c->moe_tile_rows, c->moe_n_tiles, c->moe_tile_cap); }
+        const int tile_cap = std::min(c->moe_tile_cap, R * tk / 128 + E + 1);
+        GemmStreamArgs b{};
+        b.grouped = GROUP_GATHER; b.top_k = tk; b.n_tiles = c->moe_n_tiles; b.tile_expert = c->moe_tile_expert;
+        b.tile_row0 = c->moe_tile_row0; b.tile_rows = c->moe_tile_rows; b.sorted = c->moe_sorted; b.route_w = c->moe_w;
+        b.expert_stride = packed_weight_bytes(Fe, d.d_model) / 16;
+        b.Wp = c->pk[l].eg; b.Wp2 = c->pk[l].eu; b.NT = Fe / 16; b.KT = d.d_model / 32; b.N = Fe; b.K = d.d_model;
+        b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
+        b.eps = d.rms_eps; b.out = c->moe_act; b.ldo = Fe;
+        { ProfScope ps(c, 0, 2.0 * E * (double)Fe * d.d_model * es); launch_gemm_tile(st, SEPI_SWIGLU, SPRO_BF16S, b, tile_cap); }
+        GemmStreamArgs e{};
+        e.grouped = GROUP_SCATTER; e.top_k = tk; e.n_tiles = c->moe_n_tiles; e.tile_expert = c->moe_tile_expert;
+        e.tile_row0 = c->moe_tile_row0; e.tile_rows = c->moe_tile_rows; e.sorted = c->moe_sorted; e.route_w = c->moe_w;
+        e.expert_stride = packed_weight_bytes(d.d_model, Fe) / 16;
+        e.Wp = c->pk[l].ed; e.NT = d.d_model / 16; e.KT = Fe / 32; e.N = d.d_model; e.K = Fe;
+        e.X = (const bf16_t*)c->moe_act; e.ldx = Fe; e.out = c->moe_y; e.ldo = d.d_model;
+        { ProfScope ps(c, 0, (double)E * d.d_model * Fe * es); launch_gemm_tile(st, SEPI_STORE_F32, SPRO_BF16, e, tile_cap); }
+        { ProfScope ps(c, 3, 0.0); launch_moe_combine(st, c->moe_y, d.d_model, tk, n_rows, R, c->h, c->a, gain_after, c->ss, ss_stride); }
+      }
     } else {
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
       { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
@@ -356,7 +422,8 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     if (!L.norm1 || !L.wqkv || !L.wo || !L.norm2) return fail(S2D2_EINVAL, "layer %d: attention weights missing", l);
     if (desc->n_experts == 0 && (!L.wgu || !L.wdown)) return fail(S2D2_EINVAL, "layer %d: FFN weights missing", l);
     if (desc->n_experts > 0 && (!L.router || !L.e_wgu || !L.e_wdown)) return fail(S2D2_EINVAL, "layer %d: MoE weights missing", l);
-    if (((uintptr_t)L.wqkv | (uintptr_t)L.wo | (uintptr_t)L.wgu | (uintptr_t)L.wdown) & 15) return fail(S2D2_EINVAL, "layer %d: weights must be 16-byte aligned", l);
+    if (((uintptr_t)L.wqkv | (uintptr_t)L.wo | (uintptr_t)L.wgu | (uintptr_t)L.wdown | (uintptr_t)L.router |
+         (uintptr_t)L.e_wgu | (uintptr_t)L.e_wdown) & 15) return fail(S2D2_EINVAL, "layer %d: weights must be 16-byte aligned", l);
   }
   if (((uintptr_t)weights->embed | (uintptr_t)weights->unembed) & 15) return fail(S2D2_EINVAL, "embed/unembed must be 16-byte aligned");
   if (!workspace || ((uintptr_t)workspace & 255)) return fail(S2D2_EINVAL, "workspace is NULL or not 256-byte aligned");
@@ -364,6 +431,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   if (need < 0) return (int32_t)need;
   if (workspace_bytes < (size_t)need) return fail(S2D2_ENOSPC, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)need);
   const bool use_packed = packed != nullptr && packed_total_bytes(*desc) > 0;
+  if (desc->n_experts > 0 && !use_packed) return fail(S2D2_EINVAL, "MoE models need the packed weight buffer (s2d2_packed_bytes)");
   if (packed && ((uintptr_t)packed & 255)) return fail(S2D2_EINVAL, "packed buffer is not 256-byte aligned");
   if (use_packed && packed_bytes < packed_total_bytes(*desc)) return fail(S2D2_ENOSPC, "packed buffer has %zu bytes, %zu needed", packed_bytes, packed_total_bytes(*desc));
 
@@ -408,14 +476,32 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
       const s2d2_layer_weights& L = c->layers[l];
       c->pk[l].wqkv = put(L.wqkv, qkv_n, d.d_model, 1);
       c->pk[l].wo = put(L.wo, d.d_model, HqD, 0);
-      c->pk[l].wg = put(L.wgu, d.d_ffn, d.d_model, 0);
-      c->pk[l].wu = put((const uint8_t*)L.wgu + (size_t)d.d_ffn * d.d_model * 2, d.d_ffn, d.d_model, 0);
-      c->pk[l].wdown = put(L.wdown, d.d_model, d.d_ffn, 0);
+      if (d.n_experts == 0) {
+        c->pk[l].wg = put(L.wgu, d.d_ffn, d.d_model, 0);
+        c->pk[l].wu = put((const uint8_t*)L.wgu + (size_t)d.d_ffn * d.d_model * 2, d.d_ffn, d.d_model, 0);
+        c->pk[l].wdown = put(L.wdown, d.d_model, d.d_ffn, 0);
+      } else {  // experts: all gate matrices, then all up matrices, then all down matrices, each [E] packed copies
+        const size_t mat = (size_t)d.d_expert * d.d_model * 2;
+        c->pk[l].router = put(L.router, d.n_experts, d.d_model, 0);
+        for (int e = 0; e < d.n_experts; ++e) {
+          const uint4* at = put((const uint8_t*)L.e_wgu + (size_t)(2 * e) * mat, d.d_expert, d.d_model, 0);
+          if (e == 0) c->pk[l].eg = at;
+        }
+        for (int e = 0; e < d.n_experts; ++e) {
+          const uint4* at = put((const uint8_t*)L.e_wgu + (size_t)(2 * e + 1) * mat, d.d_expert, d.d_model, 0);
+          if (e == 0) c->pk[l].eu = at;
+        }
+        for (int e = 0; e < d.n_experts; ++e) {
+          const uint4* at = put((const uint8_t*)L.e_wdown + (size_t)e * mat, d.d_model, d.d_expert, 0);
+          if (e == 0) c->pk[l].ed = at;
+        }
+      }
     }
     c->pk_unembed = put(c->w.unembed, d.vocab, d.d_model, 0);
     if (hipGetLastError() != hipSuccess) { free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "weight packing failed to launch"); }
   }
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
+  if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;
@@ -570,6 +656,14 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
     out[r.cls].bytes += r.bytes;
   }
   return S2D2_OK;
+}
+
+int32_t s2d2_moe_choices(s2d2_ctx* c, int32_t rows, int32_t* out) {
+  if (!c || !out) return fail(S2D2_EINVAL, "NULL argument");
+  if (c->desc.n_experts == 0) return fail(S2D2_EINVAL, "not a MoE model");
+  if (rows < 1 || rows > c->rows_cap) return fail(S2D2_EINVAL, "rows=%d outside [1, %d]", rows, c->rows_cap);
+  launch_moe_copy_choices(c->stream, c->moe_choice, out, c->desc.n_layers, c->rows_cap * c->desc.top_k, rows * c->desc.top_k);
+  return check_launch("s2d2_moe_choices");
 }
 
 int32_t s2d2_vocab_draft_stats(s2d2_ctx* c, const float* logits, int32_t rows, int32_t* xhat, float* p, float* lse,

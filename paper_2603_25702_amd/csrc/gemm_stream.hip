@@ -249,6 +249,10 @@ static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
 // Launch shapes: the layer matrices want >= 256 workgroups / >= 2000 wavefronts with the whole
 // share of a wavefront in one batch of loads; the unembedding is long enough to batch.
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
+  if (m_cap > 32) {  // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16
+    launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
+    return;
+  }
   switch (kind) {
     case SEPI_QKV_ROPE:
       if (a.NT >= 1024) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4>(st, a, m_cap);

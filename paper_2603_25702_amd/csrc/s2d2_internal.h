@@ -90,6 +90,7 @@ void launch_gemm(hipStream_t st, int dtype, GemmEpilogue epi, const void* X, int
 // gemm_stream.hip : packed-weight streaming GEMM with fused prologue / epilogue (bf16)
 enum StreamEpilogue { SEPI_STORE_F32 = 0, SEPI_ADD_F32 = 1, SEPI_SWIGLU = 2, SEPI_QKV_ROPE = 3 };
 enum StreamPrologue { SPRO_BF16 = 0, SPRO_BF16S = 1 };  // S: scale the result by 1/rms from partial sums
+enum GemmGrouping { GROUP_NONE = 0, GROUP_GATHER = 1, GROUP_SCATTER = 2 };  // expert-grouped rows (tile kernel only)
 struct GemmStreamArgs {
   const uint4* Wp;          // packed weights [NT][KT][64] x 16 bytes
   const uint4* Wp2;         // second matrix (up projection) for SEPI_SWIGLU
@@ -116,6 +117,17 @@ struct GemmStreamArgs {
   bf16_t* vT_out;
   const int32_t* row_seq;
   const int32_t* seq_row0;
+  // expert-grouped rows (tile kernel): row tile t covers sorted slots [tile_row0[t], +tile_rows[t]) of expert
+  // tile_expert[t]; sorted[s] = token * top_k + slot.  GROUP_GATHER reads X row sorted[s] / top_k and writes
+  // row s; GROUP_SCATTER reads X row s and writes row sorted[s], scaled by route_w[sorted[s]].
+  int32_t grouped, top_k;
+  const int32_t* n_tiles;
+  const int32_t* tile_expert;
+  const int32_t* tile_row0;
+  const int32_t* tile_rows;
+  const int32_t* sorted;
+  const float* route_w;
+  size_t expert_stride;     // uint4 elements between the packed matrices of consecutive experts
 };
 size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
@@ -123,6 +135,19 @@ void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
                        float* h, void* xg, float* ss, int ss_stride);
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
+// gemm_tile.hip : 128 x 128 LDS-tiled kernel on the same packed weights and argument block
+void launch_gemm_tile(hipStream_t st, int kind, int pro, const GemmStreamArgs& a, int row_tiles);
+
+// moe.hip
+void launch_moe_route(hipStream_t st, const float* logits, int E, int top_k, const int32_t* m_count, int rows_cap,
+                      int32_t* choice, float* route_w, int32_t* slot_pos, int32_t* cnt);
+void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, const int32_t* choice,
+                      const int32_t* slot_pos, int32_t* cnt, int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0,
+                      int32_t* tile_rows, int32_t* n_tiles, int tile_cap);
+void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const int32_t* m_count, int rows_cap,
+                        float* h, void* xg, const float* gain_next, float* ss, int ss_stride);
+void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
+                             int per_layer_dst);
 
 // attention.hip
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,

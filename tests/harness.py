@@ -131,8 +131,13 @@ class GpuRun:
 
     def step(self, prm: Params, advance: bool = True):
         N, B, e = self.case.N, self.case.B, self.eng
+        moe = self.case.cfg.is_moe
         e.s2d2_draft(self.kv, self.st, N, B, prm, self.d)
+        if moe:
+            self.choices_draft = e.s2d2_moe_choices(2 * N * B)
         e.s2d2_verify(self.kv, self.st, N, B, prm, self.d, self.v)
+        if moe:
+            self.choices_verify = e.s2d2_moe_choices(3 * N * B)
         e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
         e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
         if advance:
@@ -178,11 +183,13 @@ class Report:
     n_commit: List[int] = field(default_factory=list)
     n_accept: List[int] = field(default_factory=list)
     rows_checked: int = 0
+    router_rows: int = 0                  # MoE: (layer, row) pairs compared with the oracle's own routing
+    router_agree: int = 0
 
 
 def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, seqs=None,
                rep: Optional[Report] = None, check_logits: bool = True, check_kv_layers=None,
-               pre_seq_len: Optional[np.ndarray] = None) -> Report:
+               pre_seq_len: Optional[np.ndarray] = None, free_router: bool = False) -> Report:
     """Compares one GPU step (outputs `g`, taken after the step with advance=False) with the oracle.
     case.states must still hold the state from BEFORE the step; on return they hold the oracle's
     state after accept + append (not advanced)."""
@@ -190,6 +197,17 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
     rep = rep or Report()
     seqs = range(case.N) if seqs is None else seqs
     tau = float(np.float32(prm.tau))
+    # MoE: window rows are packed sequence after sequence; the oracle is held to the GPU's expert choices
+    moe = cfg.is_moe
+    if moe:
+        ch_d, ch_v = run.choices_draft.cpu().numpy(), run.choices_verify.cpu().numpy()
+        row0_d, row0_v, rd, rv = [], [], 0, 0
+        for n in range(case.N):
+            wd = O.draft_window(case.states[n], cfg.mask_id, bool(prm.ar_mask))
+            row0_d.append(rd)
+            row0_v.append(rv)
+            rd += len(wd.tokens)
+            rv += len(O.verify_window(case.states[n], np.zeros(B, dtype=np.int64), cfg.mask_id).tokens)
     for n in seqs:
         st = case.states[n]
         ck, cv = case.oracle_cache(n)
@@ -200,7 +218,15 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
         assert [(rows_d[i] >= 0) for i in range(B)] == [i in set(win.logit_index) for i in range(B)]
         gl = np.stack([g["logits"][rows_d[i]] for i in win.logit_index]).astype(np.float64)
         if check_logits:
-            od = O.draft(cfg, case.W, st, ck, cv, tau, bool(prm.ar_mask))
+            forced = None
+            if moe:
+                forced = [ch_d[l, row0_d[n]:row0_d[n] + len(win.tokens)] for l in range(cfg.n_layers)]
+                if free_router:
+                    free = O.draft(cfg, case.W, st, ck, cv, tau, bool(prm.ar_mask))
+                    for l in range(cfg.n_layers):
+                        rep.router_rows += len(win.tokens)
+                        rep.router_agree += int((np.sort(free.fwd.experts[l], axis=1) == np.sort(forced[l], axis=1)).all(axis=1).sum())
+            od = O.draft(cfg, case.W, st, ck, cv, tau, bool(prm.ar_mask), forced_experts=forced)
             scale = np.abs(od.logits).max()
             err = np.abs(gl - od.logits).max() / scale
             rep.max_logit_err_draft = max(rep.max_logit_err_draft, err)
@@ -236,7 +262,10 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
         assert g["stage_lead"][n] == vwin.n_causal - vwin.L
         ov = None
         if check_logits:
-            ov = O.verify(cfg, case.W, st, ck, cv, xhat)
+            forced = None
+            if moe:
+                forced = [ch_v[l, row0_v[n]:row0_v[n] + len(vwin.tokens)] for l in range(cfg.n_layers)]
+            ov = O.verify(cfg, case.W, st, ck, cv, xhat, forced_experts=forced)
             err = np.abs(gv - ov.logits).max() / np.abs(ov.logits).max()
             rep.max_logit_err_verify = max(rep.max_logit_err_verify, err)
             assert err <= LOGIT_RTOL, f"seq {n}: verifier logits off by {err:.3e} of max|logit|"

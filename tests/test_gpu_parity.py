@@ -158,3 +158,30 @@ def test_config2_full_size_step_in_the_benchmark_launch_configuration():
     g = run.fetch()
     rep = H.check_step(case, run, g, prm, check_kv_layers=(0, 13, 27))
     print("config2 full:", rep)
+
+
+SMALL_MOE = I.ModelCfg("small-moe", 2, 512, 8, 4, 128, 0, 32000, n_experts=8, top_k=2, d_expert=256)
+
+
+def test_small_bf16_wide_windows_run_the_tiled_gemm():
+    """Windows of up to 3*3*16 = 144 rows: the LDS-tiled GEMM with every fused epilogue, ragged row tiles."""
+    case = H.make_case(SMALL_BF16, 3, 16, [100, 257, 31], seed=11, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
+    run, rep = run_steps(case, 3)
+    print("small bf16 wide:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL
+
+
+def test_small_moe_routing_grouped_gemm_and_combine():
+    """MoE FFN: the oracle is held to the GPU's expert choices; the free-running router agreement is reported."""
+    case = H.make_case(SMALL_MOE, 3, 8, [40, 90, 65], seed=12, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run = H.GpuRun(case)
+    rep = H.Report()
+    for s in range(2):
+        prm = Params(step=s, seed=99)
+        run.step(prm, advance=False)
+        g = run.fetch()
+        H.check_step(case, run, g, prm, rep=rep, free_router=(s == 0))
+        run.eng.s2d2_block_advance(run.kv, run.st, case.N, case.B, None)
+        H.sync_case_from_gpu(case, run)
+    print("small moe:", rep)
+    assert rep.router_rows > 0 and rep.router_agree >= 0.9 * rep.router_rows
