@@ -72,6 +72,10 @@ typedef struct {
   int32_t n_experts, top_k, d_expert;   /* all 0 for a dense model */
   int32_t dtype;                        /* S2D2_F32 or S2D2_BF16: weights, KV cache, activations */
   int32_t mask_id;                      /* token id of [MASK] */
+  int32_t act_planes;                   /* bf16 models with packed weights: how the inputs of the GEMMs are carried.
+                                           2 (also chosen by 0): as a high- and a low-order bf16 plane, 16 significant
+                                           bits, every weight operand multiplied with both (keeps 36-layer models inside
+                                           the logit tolerance); 1: one bf16 plane, half the MFMA work */
   float rope_theta, rms_eps;
 } s2d2_model_desc;
 

@@ -35,7 +35,7 @@ class S2D2Error(RuntimeError):
 
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn",
-                                         "vocab", "n_experts", "top_k", "d_expert", "dtype", "mask_id")] + \
+                                         "vocab", "n_experts", "top_k", "d_expert", "dtype", "mask_id", "act_planes")] + \
                [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
 
 
@@ -142,10 +142,10 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
-def model_desc(cfg) -> ModelDesc:
+def model_desc(cfg, act_planes: int = 0) -> ModelDesc:
     return ModelDesc(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab,
                      cfg.n_experts, cfg.top_k, cfg.d_expert, S2D2_BF16 if cfg.dtype == "bf16" else S2D2_F32,
-                     cfg.mask_id, cfg.rope_theta, cfg.rms_eps)
+                     cfg.mask_id, act_planes, cfg.rope_theta, cfg.rms_eps)
 
 
 @dataclass
@@ -262,11 +262,12 @@ class Engine:
     """Owns a library context: weights on the device, workspace, stream.  Methods = C calls."""
 
     def __init__(self, cfg, weights: Dict[str, torch.Tensor], max_batch: int, max_block: int,
-                 device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None, packed: bool = True):
+                 device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None, packed: bool = True,
+                 act_planes: int = 0):
         self.lib = load_library()
         self.cfg, self.max_batch, self.max_block = cfg, max_batch, max_block
         self.device = torch.device(device)
-        self.desc = model_desc(cfg)
+        self.desc = model_desc(cfg, act_planes)
         self.w = {k: v.to(self.device).contiguous() for k, v in weights.items() if not k.startswith("__")}
         layers = (LayerWeights * cfg.n_layers)()
         for l in range(cfg.n_layers):

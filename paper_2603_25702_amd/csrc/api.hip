@@ -88,6 +88,8 @@ struct Carver {
 };
 
 int elt_size(int dtype) { return dtype == S2D2_BF16 ? 2 : 4; }
+// bf16 planes in which GEMM inputs are carried (the workspace is sized for this; the plain kernels use one)
+int act_planes(const s2d2_model_desc& d) { return d.dtype == S2D2_BF16 && d.act_planes != 1 ? 2 : 1; }
 
 int32_t check_desc(const s2d2_model_desc* d) {
   if (!d) return fail(S2D2_EINVAL, "model description is NULL");
@@ -108,6 +110,7 @@ int32_t check_desc(const s2d2_model_desc* d) {
     if (d->d_ffn) return fail(S2D2_EINVAL, "d_ffn must be 0 for a MoE model");
   }
   if (d->mask_id < 0 || d->mask_id >= d->vocab) return fail(S2D2_EINVAL, "mask_id outside the vocabulary");
+  if (d->act_planes < 0 || d->act_planes > 2) return fail(S2D2_EINVAL, "act_planes must be 0, 1 or 2");
   if (d->vocab > 8192 * 256) return fail(S2D2_EINVAL, "vocab above 2097152 is not supported");
   if (!(d->rope_theta > 1.0f) || !(d->rms_eps >= 0.0f)) return fail(S2D2_EINVAL, "rope_theta must exceed 1 and rms_eps be non-negative");
   return S2D2_OK;
@@ -141,11 +144,12 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   c->plan.seq_j = cv.take<int32_t>(NB);
   c->plan.seq_L = cv.take<int32_t>(NB);
   c->h = cv.take<float>(R * d.d_model);
-  c->a = cv.take<uint8_t>(R * d.d_model * es);
+  const size_t P = act_planes(d);
+  c->a = cv.take<uint8_t>(R * d.d_model * es * P);
   c->qkv = cv.take<float>(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim);
   c->qbuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es);
-  c->obuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es);
-  c->ffn = cv.take<uint8_t>(R * (size_t)d.d_ffn * es);
+  c->obuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es * P);
+  c->ffn = cv.take<uint8_t>(R * (size_t)d.d_ffn * es * P);
   c->af = cv.take<uint8_t>(LR * (size_t)d.d_model * es);
   c->kwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
   c->vwin = cv.take<uint8_t>(R * (size_t)d.n_kv_heads * d.head_dim * es);
@@ -174,7 +178,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     c->moe_tile_row0 = cv.take<int32_t>(c->moe_tile_cap);
     c->moe_tile_rows = cv.take<int32_t>(c->moe_tile_cap);
     c->moe_n_tiles = cv.take<int32_t>(8);
-    c->moe_act = cv.take<uint8_t>(RK * (size_t)d.d_expert * es);
+    c->moe_act = cv.take<uint8_t>(RK * (size_t)d.d_expert * es * P);
     c->moe_y = cv.take<float>(RK * (size_t)d.d_model);
   }
   c->vws.chunks = vocab_chunks(d.vocab);
@@ -261,7 +265,13 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int32_t* n_rows = c->plan.counts;
   const bool fused = c->pk != nullptr;
   const int ss_stride = (d.d_model + 15) / 16;
-  if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, c->ss, ss_stride); }
+  // GEMM inputs as P bf16 planes per row: [hi | lo]; lo offsets are 0 with a single plane
+  const int P = fused && flash ? act_planes(d) : 1;  // the generic attention kernel writes one plane
+  const int ld_a = P * d.d_model, lo_a = P == 2 ? d.d_model : 0;
+  const int ld_o = P * HqD, lo_o = P == 2 ? HqD : 0;
+  const int ld_f = P * d.d_ffn, lo_f = P == 2 ? d.d_ffn : 0;
+  const int ld_e = P * d.d_expert, lo_e = P == 2 ? d.d_expert : 0;
+  if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
   for (int l = 0; l < d.n_layers; ++l) {
@@ -271,7 +281,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     if (fused) {
       GemmStreamArgs a{};
       a.Wp = c->pk[l].wqkv; a.NT = qkv_n / 16; a.KT = d.d_model / 32; a.N = qkv_n; a.K = d.d_model;
-      a.m_count = n_rows; a.X = (const bf16_t*)c->a; a.ldx = d.d_model; a.ss_part = c->ss; a.ss_stride = ss_stride;
+      a.m_count = n_rows; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.ss_part = c->ss; a.ss_stride = ss_stride;
       a.ss_count = l == 0 ? 1 : ss_stride; a.eps = d.rms_eps;
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
       a.q_out = (bf16_t*)c->qbuf; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
@@ -287,7 +297,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
     if (flash) {
       ProfScope ps(c, 1, 0.0);
-      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, c->attn_part, c->attn_counters);
+      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
     } else {
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
@@ -296,22 +306,22 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       GemmStreamArgs a{};
       a.m_count = n_rows;
       a.Wp = c->pk[l].wo; a.NT = d.d_model / 16; a.KT = HqD / 32; a.N = d.d_model; a.K = HqD;
-      a.X = (const bf16_t*)c->obuf; a.ldx = HqD; a.out = c->h; a.ldo = d.d_model;
-      a.xg_out = (bf16_t*)c->a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
+      a.X = (const bf16_t*)c->obuf; a.ldx = ld_o; a.x_lo = lo_o; a.out = c->h; a.ldo = d.d_model;
+      a.xg_out = (bf16_t*)c->a; a.xg_ld = ld_a; a.xg_lo = lo_a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
       const float* gain_after = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f;
       if (d.n_experts == 0) {
         GemmStreamArgs b{};
         b.m_count = n_rows;
         b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
-        b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
-        b.eps = d.rms_eps; b.out = c->ffn; b.ldo = d.d_ffn;
+        b.X = (const bf16_t*)c->a; b.ldx = ld_a; b.x_lo = lo_a; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
+        b.eps = d.rms_eps; b.out = c->ffn; b.ldo = ld_f; b.out_lo = lo_f;
         { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
         GemmStreamArgs e{};
         e.m_count = n_rows;
         e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
-        e.X = (const bf16_t*)c->ffn; e.ldx = d.d_ffn; e.out = c->h; e.ldo = d.d_model;
-        e.xg_out = (bf16_t*)c->a; e.gain_next = gain_after; e.ss_out = c->ss; e.ss_stride = ss_stride;
+        e.X = (const bf16_t*)c->ffn; e.ldx = ld_f; e.x_lo = lo_f; e.out = c->h; e.ldo = d.d_model;
+        e.xg_out = (bf16_t*)c->a; e.xg_ld = ld_a; e.xg_lo = lo_a; e.gain_next = gain_after; e.ss_out = c->ss; e.ss_stride = ss_stride;
         { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
       } else {
         // MoE FFN: router -> top-k -> group by expert -> grouped gate/up + SwiGLU -> grouped down -> combine
@@ -320,7 +330,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         GemmStreamArgs r{};
         r.m_count = n_rows;
         r.Wp = c->pk[l].router; r.NT = (E + 15) / 16; r.KT = d.d_model / 32; r.N = E; r.K = d.d_model;
-        r.X = (const bf16_t*)c->a; r.ldx = d.d_model; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
+        r.X = (const bf16_t*)c->a; r.ldx = ld_a; r.x_lo = lo_a; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
         r.eps = d.rms_eps; r.out = c->router_logits; r.ldo = E;
         { ProfScope ps(c, 0, (double)E * d.d_model * es); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
         { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w, c->moe_pos, c->moe_cnt); }
@@ -332,17 +342,17 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         b.tile_row0 = c->moe_tile_row0; b.tile_rows = c->moe_tile_rows; b.sorted = c->moe_sorted; b.route_w = c->moe_w;
         b.expert_stride = packed_weight_bytes(Fe, d.d_model) / 16;
         b.Wp = c->pk[l].eg; b.Wp2 = c->pk[l].eu; b.NT = Fe / 16; b.KT = d.d_model / 32; b.N = Fe; b.K = d.d_model;
-        b.X = (const bf16_t*)c->a; b.ldx = d.d_model; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
-        b.eps = d.rms_eps; b.out = c->moe_act; b.ldo = Fe;
+        b.X = (const bf16_t*)c->a; b.ldx = ld_a; b.x_lo = lo_a; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
+        b.eps = d.rms_eps; b.out = c->moe_act; b.ldo = ld_e; b.out_lo = lo_e;
         { ProfScope ps(c, 0, 2.0 * E * (double)Fe * d.d_model * es); launch_gemm_tile(st, SEPI_SWIGLU, SPRO_BF16S, b, tile_cap); }
         GemmStreamArgs e{};
         e.grouped = GROUP_SCATTER; e.top_k = tk; e.n_tiles = c->moe_n_tiles; e.tile_expert = c->moe_tile_expert;
         e.tile_row0 = c->moe_tile_row0; e.tile_rows = c->moe_tile_rows; e.sorted = c->moe_sorted; e.route_w = c->moe_w;
         e.expert_stride = packed_weight_bytes(d.d_model, Fe) / 16;
         e.Wp = c->pk[l].ed; e.NT = d.d_model / 16; e.KT = Fe / 32; e.N = d.d_model; e.K = Fe;
-        e.X = (const bf16_t*)c->moe_act; e.ldx = Fe; e.out = c->moe_y; e.ldo = d.d_model;
+        e.X = (const bf16_t*)c->moe_act; e.ldx = ld_e; e.x_lo = lo_e; e.out = c->moe_y; e.ldo = d.d_model;
         { ProfScope ps(c, 0, (double)E * d.d_model * Fe * es); launch_gemm_tile(st, SEPI_STORE_F32, SPRO_BF16, e, tile_cap); }
-        { ProfScope ps(c, 3, 0.0); launch_moe_combine(st, c->moe_y, d.d_model, tk, n_rows, R, c->h, c->a, gain_after, c->ss, ss_stride); }
+        { ProfScope ps(c, 3, 0.0); launch_moe_combine(st, c->moe_y, d.d_model, tk, n_rows, R, c->h, c->a, ld_a, lo_a, gain_after, c->ss, ss_stride); }
       }
     } else {
       { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
@@ -355,7 +365,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   if (fused) {
     GemmStreamArgs a{};
     a.Wp = c->pk_unembed; a.NT = (d.vocab + 15) / 16; a.KT = d.d_model / 32; a.N = d.vocab; a.K = d.d_model;
-    a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = d.d_model; a.gather = c->plan.logit_src;
+    a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.gather = c->plan.logit_src;
     a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
     a.out = logits; a.ldo = d.vocab;
     ProfScope ps(c, 0, (double)d.vocab * d.d_model * es);

@@ -156,10 +156,28 @@ __device__ __forceinline__ void fa_merge(FaState& a, float m2, float l2, const f
     for (int i = 0; i < 16; ++i) a.o[t][i] = a.o[t][i] * f1 + o2[t][i] * f2;
 }
 
+// Four consecutive output elements as bf16, plus their low-order plane o_lo elements further on if o_lo != 0.
+__device__ __forceinline__ void fa_store4(bf16_t* p, int o_lo, float a, float b, float c, float d) {
+  bf16_t hi[4], lo[4];
+  split_bf16(a, hi[0], lo[0]);
+  split_bf16(b, hi[1], lo[1]);
+  split_bf16(c, hi[2], lo[2]);
+  split_bf16(d, hi[3], lo[3]);
+  uint2 pk;
+  pk.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16);
+  pk.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+  *(uint2*)p = pk;
+  if (o_lo) {
+    pk.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16);
+    pk.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+    *(uint2*)(p + o_lo) = pk;
+  }
+}
+
 // Merges the Z split partials of one (sequence, KV head, query tile) in split order.
 __device__ __forceinline__ void fa_combine(const float* part_o, const float* part_ml, size_t item0, int Z, int tid,
                                            int nthreads, int qt, int nq, int grp, int row0, int kvh, int Hq,
-                                           bf16_t* __restrict__ o) {
+                                           bf16_t* __restrict__ o, int o_ld, int o_lo) {
   constexpr int D = FA_D;
   for (int e = tid; e < 32 * (D / 4); e += nthreads) {
     const int c = e / (D / 4), d0 = (e % (D / 4)) * 4;
@@ -182,10 +200,7 @@ __device__ __forceinline__ void fa_combine(const float* part_o, const float* par
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
-    uint2 pk;
-    pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
-    pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
-    *(uint2*)(o + ((size_t)r * Hq + head) * D + d0) = pk;
+    fa_store4(o + (size_t)r * o_ld + head * D + d0, o_lo, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
   }
 }
 
@@ -193,8 +208,8 @@ template <int NW>
 __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
     const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
-    int wpad, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ part_o, float* __restrict__ part_ml,
-    int32_t* __restrict__ counters) {
+    int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int32_t* __restrict__ counters) {
   extern __shared__ float smem[];
   constexpr int D = FA_D;
   const int z = blockIdx.x, qt = blockIdx.y;
@@ -362,16 +377,14 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
   if (Z == 1) {
     if (wave != 0 || !q_ok) return;
     const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
-    bf16_t* op = o + ((size_t)r * Hq + head) * D;
+    bf16_t* op = o + (size_t)r * o_ld + head * D;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int d0 = dt * 32 + 8 * i4 + 4 * h;
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(st.o[dt][4 * i4] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 1] * inv) << 16);
-        pk.y = (uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 2] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][4 * i4 + 3] * inv) << 16);
-        *(uint2*)(op + d0) = pk;
+        fa_store4(op + d0, o_lo, st.o[dt][4 * i4] * inv, st.o[dt][4 * i4 + 1] * inv, st.o[dt][4 * i4 + 2] * inv,
+                  st.o[dt][4 * i4 + 3] * inv);
       }
     return;
   }
@@ -405,7 +418,7 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
   __syncthreads();
   if (!*s_last) return;
   __threadfence();  // acquire the other splits' partials
-  fa_combine(part_o, part_ml, item0, Z, threadIdx.x, NW * 64, qt, nq, grp, row0, kvh, Hq, o);
+  fa_combine(part_o, part_ml, item0, Z, threadIdx.x, NW * 64, qt, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
 }
 
 static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * sizeof(float); }
@@ -417,15 +430,16 @@ size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * F
 // arrival counter per (sequence, KV head, query tile); the last split to arrive merges.
 void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
-                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part, int32_t* counters) {
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
+                            int32_t* counters) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.head_dim);
   const int items = N * g.n_kv_heads;
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
   hipLaunchKernelGGL(attn_flash_kernel<8>, dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
                      (const bf16_t*)q, (const bf16_t*)k_win, (const bf16_t*)vT_win, (const bf16_t*)k_pages_layer,
-                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, part_o, part_ml,
-                     counters);
+                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, o_ld, o_lo, part_o,
+                     part_ml, counters);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {

@@ -86,7 +86,7 @@ __device__ __forceinline__ float tile_total(const float* s_red, int t, int fe, i
   return v;
 }
 
-template <int EPI, int PRO, int NW, int TPW, int U>
+template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
@@ -127,10 +127,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   const bool row_ok = f < Mloc;
   const int xrow = row_ok ? (a.gather ? a.gather[m0 + f] : m0 + f) : 0;
   const bf16_t* xg = a.X + (size_t)xrow * a.ldx + g * 8;
-  u32x4_t xb[U];
+  u32x4_t xb[U], xl[SPLIT ? U : 1];
 #pragma unroll
-  for (int u = 0; u < U; ++u)
+  for (int u = 0; u < U; ++u) {
     xb[u] = (row_ok && kt_begin + u < kt_end) ? *(const u32x4_t*)(xg + (kt_begin + u) * 32) : zero;
+    if (SPLIT) xl[u] = (row_ok && kt_begin + u < kt_end) ? *(const u32x4_t*)(xg + a.x_lo + (kt_begin + u) * 32) : zero;
+  }
 
   if (PRO == SPRO_BF16S && threadIdx.x < 256) {  // 1/rms of the 16 rows from the producer's partial sums
     const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
@@ -154,9 +156,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int t = 0; t < TA; ++t)
+      for (int t = 0; t < TA; ++t) {
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
                                                          __builtin_bit_cast(bf16x8_t, xb[u]), acc[t], 0, 0, 0);
+        if (SPLIT)  // low-order plane of the activations: same weights, second product
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
+                                                           __builtin_bit_cast(bf16x8_t, xl[u]), acc[t], 0, 0, 0);
+      }
     kt0 += U;
     if (kt0 < kt_end) {  // next batch (the layer matrices are sized so that one batch covers a wavefront's share)
 #pragma unroll
@@ -164,6 +170,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #pragma unroll
         for (int t = 0; t < TA; ++t) w[t][u] = (kt0 + u < kt_end) ? wp[t][(size_t)(kt0 + u) * 64] : zero;
         xb[u] = (row_ok && kt0 + u < kt_end) ? *(const u32x4_t*)(xg + (kt0 + u) * 32) : zero;
+        if (SPLIT) xl[u] = (row_ok && kt0 + u < kt_end) ? *(const u32x4_t*)(xg + a.x_lo + (kt0 + u) * 32) : zero;
       }
     }
   }
@@ -194,7 +201,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
           float* hp = (float*)a.out + (size_t)m * a.ldo + n;
           hv = *hp + S2D2_TOTAL(t, fe);
           *hp = hv;
-          if (a.xg_out) a.xg_out[(size_t)m * a.ldo + n] = f32_to_bf16(hv * a.gain_next[n]);
+          if (a.xg_out) {
+            bf16_t hi, lo;
+            split_bf16(hv * a.gain_next[n], hi, lo);
+            a.xg_out[(size_t)m * a.xg_ld + n] = hi;
+            if (a.xg_lo) a.xg_out[(size_t)m * a.xg_ld + a.xg_lo + n] = lo;
+          }
         }
         if (a.ss_out) {
           float sq = hv * hv;
@@ -207,7 +219,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
       } else if (EPI == SEPI_SWIGLU) {
         const int n = nt * 16 + fe;
         const float gate = S2D2_TOTAL(2 * t, fe), up = S2D2_TOTAL(2 * t + 1, fe);
-        if (live && n < a.N) ((bf16_t*)a.out)[(size_t)m * a.ldo + n] = f32_to_bf16(gate / (1.0f + __expf(-gate)) * up);
+        if (live && n < a.N) {
+          bf16_t hi, lo;
+          split_bf16(gate / (1.0f + __expf(-gate)) * up, hi, lo);
+          ((bf16_t*)a.out)[(size_t)m * a.ldo + n] = hi;
+          if (a.out_lo) ((bf16_t*)a.out)[(size_t)m * a.ldo + a.out_lo + n] = lo;
+        }
       } else if (live && fe < 8) {  // SEPI_QKV_ROPE: lanes fe < 8 own the pair (i, i + D/2) of one head
         const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
         const int head = nt / tiles_per_head, i = 8 * (nt % tiles_per_head) + fe;
@@ -238,35 +255,37 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #undef S2D2_TOTAL
 }
 
-template <int EPI, int PRO, int NW, int TPW, int U>
+template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
 static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   constexpr int TA = TPW * (EPI == SEPI_SWIGLU ? 2 : 1);
   const size_t lds = 16 * sizeof(float) + (size_t)NW * TA * 256 * sizeof(float);
   dim3 grid((a.NT + TPW - 1) / TPW, (m_cap + 15) / 16), block(NW * 64);
-  hipLaunchKernelGGL((gemm_stream_kernel<EPI, PRO, NW, TPW, U>), grid, block, lds, st, a);
+  hipLaunchKernelGGL((gemm_stream_kernel<EPI, PRO, NW, TPW, U, SPLIT>), grid, block, lds, st, a);
 }
 
 // Launch shapes: the layer matrices want >= 256 workgroups / >= 2000 wavefronts with the whole
-// share of a wavefront in one batch of loads; the unembedding is long enough to batch.
+// share of a wavefront in one batch of loads (two batches where a second activation plane would
+// not fit the registers of a 1024-thread workgroup); the unembedding is long enough to batch.
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
   if (m_cap > 32) {  // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16
     launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
     return;
   }
+  const bool sp = a.x_lo != 0;
   switch (kind) {
     case SEPI_QKV_ROPE:
-      if (a.NT >= 1024) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4>(st, a, m_cap);
-      else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8>(st, a, m_cap);
+      if (a.NT >= 1024) { if (sp) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4, true>(st, a, m_cap); else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4, false>(st, a, m_cap); }
+      else { if (sp) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8, true>(st, a, m_cap); else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8, false>(st, a, m_cap); }
       break;
     case SEPI_ADD_F32:
-      if (a.KT >= 128) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 12>(st, a, m_cap);
-      else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4>(st, a, m_cap);
+      if (a.KT >= 128) { if (sp) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 6, true>(st, a, m_cap); else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 12, false>(st, a, m_cap); }
+      else { if (sp) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4, true>(st, a, m_cap); else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4, false>(st, a, m_cap); }
       break;
     case SEPI_SWIGLU:
-      launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8>(st, a, m_cap);
+      if (sp) launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8, true>(st, a, m_cap); else launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8, false>(st, a, m_cap);
       break;
     case SEPI_STORE_F32:
-      launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8>(st, a, m_cap);
+      if (sp) launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8, true>(st, a, m_cap); else launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8, false>(st, a, m_cap);
       break;
   }
 }
@@ -274,7 +293,8 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
 // First norm of the forward: xg = bf16(h * gain), one partial sum of squares per row.
 __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restrict__ embed, int d, Plan p,
                                                          const float* __restrict__ gain, float* __restrict__ h,
-                                                         bf16_t* __restrict__ xg, float* __restrict__ ss, int ss_stride) {
+                                                         bf16_t* __restrict__ xg, int xg_ld, int xg_lo,
+                                                         float* __restrict__ ss, int ss_stride) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   if (r >= p.counts[0]) return;
@@ -283,7 +303,10 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restric
   for (int i = threadIdx.x; i < d; i += 256) {
     const float v = bf16_to_f32(src[i]);
     h[(size_t)r * d + i] = v;
-    xg[(size_t)r * d + i] = f32_to_bf16(v * gain[i]);
+    bf16_t hi, lo;
+    split_bf16(v * gain[i], hi, lo);
+    xg[(size_t)r * xg_ld + i] = hi;
+    if (xg_lo) xg[(size_t)r * xg_ld + xg_lo + i] = lo;
     acc += v * v;
   }
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
@@ -293,9 +316,9 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restric
 }
 
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
-                       float* h, void* xg, float* ss, int ss_stride) {
+                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride) {
   hipLaunchKernelGGL(embed_norm_kernel, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, gain, h,
-                     (bf16_t*)xg, ss, ss_stride);
+                     (bf16_t*)xg, xg_ld, xg_lo, ss, ss_stride);
 }
 
 }  // namespace s2d2

@@ -21,11 +21,13 @@
 namespace s2d2 {
 
 static constexpr int TM = 128, TN = 128, TK = 64;
-static constexpr int XROW = 144;  // bytes per LDS row: 64 bf16 + 16 bytes of padding
 
-template <int EPI, int PRO>
+// SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
+// of a row sit side by side in LDS and every weight operand is multiplied with both.
+template <int EPI, int PRO, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) {
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
+  constexpr int XROW = (SPLIT ? 256 : 128) + 16;  // bytes per LDS row: 64 bf16 per plane + 16 bytes of padding
   __shared__ __align__(16) uint8_t s_x[2][TM * XROW];
   __shared__ int s_xrow[TM], s_orow[TM];
   __shared__ float s_rs[TM];
@@ -101,12 +103,13 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
     for (int t = 0; t < 4 * NACC; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int nk = (a.K + TK - 1) / TK;
-  u32x4_t xr[4], wn[2][4 * NACC], wcur[2][4 * NACC];
+  u32x4_t xr[4], xl[SPLIT ? 4 : 1], wn[2][4 * NACC], wcur[2][4 * NACC];
   auto load_x = [&](int kb) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int k = kb * TK + c16 * 8;
       xr[i] = (xsrc[i] && k < a.K) ? *(const u32x4_t*)(xsrc[i] + kb * TK) : zero;
+      if (SPLIT) xl[i] = (xsrc[i] && k < a.K) ? *(const u32x4_t*)(xsrc[i] + a.x_lo + kb * TK) : zero;
     }
   };
   auto load_w = [&](int kb) {
@@ -119,7 +122,10 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
   };
   auto store_x = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + c16 * 16) = xr[i];
+    for (int i = 0; i < 4; ++i) {
+      *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + c16 * 16) = xr[i];
+      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + 128 + c16 * 16) = xl[i];
+    }
   };
 
   load_x(0);
@@ -145,6 +151,13 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
         for (int t = 0; t < 4 * NACC; ++t)
           acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wcur[k2][t]),
                                                                __builtin_bit_cast(bf16x8_t, b), acc[rb][t], 0, 0, 0);
+        if (SPLIT) {
+          const u32x4_t bl = *(const u32x4_t*)(xb + rb * 16 * XROW + 128 + k2 * 64);
+#pragma unroll
+          for (int t = 0; t < 4 * NACC; ++t)
+            acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wcur[k2][t]),
+                                                                 __builtin_bit_cast(bf16x8_t, bl), acc[rb][t], 0, 0, 0);
+        }
       }
     }
     if (kb + 1 < nk) store_x((kb + 1) & 1);
@@ -182,7 +195,12 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
           if (a.xg_out) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (n + i < a.N) a.xg_out[(size_t)orow * a.ldo + n + i] = f32_to_bf16(hv[i] * a.gain_next[n + i]);
+              if (n + i < a.N) {
+                bf16_t hi, lo;
+                split_bf16(hv[i] * a.gain_next[n + i], hi, lo);
+                a.xg_out[(size_t)orow * a.xg_ld + n + i] = hi;
+                if (a.xg_lo) a.xg_out[(size_t)orow * a.xg_ld + a.xg_lo + n + i] = lo;
+              }
           }
         }
         if (a.ss_out) {
@@ -197,7 +215,12 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gate = acc[rb][2 * t][i] * rs, up = acc[rb][2 * t + 1][i] * rs;
-            if (n + i < a.N) op[i] = f32_to_bf16(gate / (1.0f + __expf(-gate)) * up);
+            if (n + i < a.N) {
+              bf16_t hi, lo;
+              split_bf16(gate / (1.0f + __expf(-gate)) * up, hi, lo);
+              op[i] = hi;
+              if (a.out_lo) op[a.out_lo + i] = lo;
+            }
           }
         }
       } else {  // SEPI_QKV_ROPE: features 0-7 of a tile pair with features 8-15 (lanes 32 apart)
@@ -241,7 +264,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
 template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
   dim3 grid((a.NT + TN / 16 - 1) / (TN / 16), row_tiles), block(256);
-  hipLaunchKernelGGL((gemm_tile_kernel<EPI, PRO>), grid, block, 0, st, a);
+  if (a.x_lo) hipLaunchKernelGGL((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((gemm_tile_kernel<EPI, PRO, false>), grid, block, 0, st, a);
 }
 
 // row_tiles: upper bound of 128-row tiles (ungrouped: ceil(m_cap / 128); grouped: capacity of the tile list)

@@ -101,7 +101,8 @@ __global__ __launch_bounds__(1024) void moe_group_kernel(int E, int top_k, const
 // of squares of the next norm (one partial per 16 features, like the GEMM epilogue writes them).
 __global__ __launch_bounds__(256) void moe_combine_kernel(const float* __restrict__ y, int d, int top_k,
                                                           const int32_t* __restrict__ m_count, float* __restrict__ h,
-                                                          bf16_t* __restrict__ xg, const float* __restrict__ gain_next,
+                                                          bf16_t* __restrict__ xg, int xg_ld, int xg_lo,
+                                                          const float* __restrict__ gain_next,
                                                           float* __restrict__ ss, int ss_stride) {
   const int row = blockIdx.x;
   if (row >= *m_count) return;
@@ -113,10 +114,19 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const float* __restric
     }
     *(float4*)(h + (size_t)row * d + c) = acc;
     const float4 gn = *(const float4*)(gain_next + c);
+    const float xv[4] = {acc.x * gn.x, acc.y * gn.y, acc.z * gn.z, acc.w * gn.w};
+    bf16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split_bf16(xv[i], hi[i], lo[i]);
     uint2 pk;
-    pk.x = (uint32_t)f32_to_bf16(acc.x * gn.x) | ((uint32_t)f32_to_bf16(acc.y * gn.y) << 16);
-    pk.y = (uint32_t)f32_to_bf16(acc.z * gn.z) | ((uint32_t)f32_to_bf16(acc.w * gn.w) << 16);
-    *(uint2*)(xg + (size_t)row * d + c) = pk;
+    pk.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16);
+    pk.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+    *(uint2*)(xg + (size_t)row * xg_ld + c) = pk;
+    if (xg_lo) {
+      pk.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16);
+      pk.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+      *(uint2*)(xg + (size_t)row * xg_ld + xg_lo + c) = pk;
+    }
     float sq = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
     sq += __shfl_xor(sq, 1, 64);
     sq += __shfl_xor(sq, 2, 64);
@@ -145,9 +155,9 @@ void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, 
 }
 
 void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const int32_t* m_count, int rows_cap,
-                        float* h, void* xg, const float* gain_next, float* ss, int ss_stride) {
+                        float* h, void* xg, int xg_ld, int xg_lo, const float* gain_next, float* ss, int ss_stride) {
   hipLaunchKernelGGL(moe_combine_kernel, dim3(rows_cap), dim3(256), 0, st, y, d, top_k, m_count, h, (bf16_t*)xg,
-                     gain_next, ss, ss_stride);
+                     xg_ld, xg_lo, gain_next, ss, ss_stride);
 }
 
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,

@@ -21,6 +21,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest ev
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+// High- and low-order bf16 planes of a float: v ~= hi + lo with 16 significant bits.
+__device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
+  hi = f32_to_bf16(v);
+  lo = f32_to_bf16(v - bf16_to_f32(hi));
+}
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
@@ -98,14 +103,17 @@ struct GemmStreamArgs {
   const int32_t* m_count;   // device: number of valid rows
   const bf16_t* X;          // activations [*, ldx] (for SPRO_BF16S: h * gain, not yet divided by the rms)
   int32_t ldx;
+  int32_t x_lo;             // element offset, inside a row of X, of the low-order bf16 plane (0: single plane)
   const int32_t* gather;    // optional row indices into X / ss_part
   const float* ss_part;     // SPRO_BF16S: [*, ss_stride] partial sums of squares of the residual rows
   int32_t ss_stride, ss_count;
   float eps;
   void* out;
   int32_t ldo;
+  int32_t out_lo;           // SEPI_SWIGLU: element offset of the low-order plane inside an output row (0: none)
   // SEPI_ADD_F32 extras (all optional): operand of the next norm and its partial sums of squares
-  bf16_t* xg_out;           // [*, ldo]
+  bf16_t* xg_out;           // [*, xg_ld]
+  int32_t xg_ld, xg_lo;     // row stride and low-order plane offset of xg_out
   const float* gain_next;   // [N]
   float* ss_out;            // [*, ss_stride], entry nt of a row = this tile's share
   // SEPI_QKV_ROPE
@@ -133,7 +141,7 @@ size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
 void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs);
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
-                       float* h, void* xg, float* ss, int ss_stride);
+                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride);
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
 // gemm_tile.hip : 128 x 128 LDS-tiled kernel on the same packed weights and argument block
 void launch_gemm_tile(hipStream_t st, int kind, int pro, const GemmStreamArgs& a, int row_tiles);
@@ -145,7 +153,7 @@ void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, 
                       const int32_t* slot_pos, int32_t* cnt, int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0,
                       int32_t* tile_rows, int32_t* n_tiles, int tile_cap);
 void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const int32_t* m_count, int rows_cap,
-                        float* h, void* xg, const float* gain_next, float* ss, int ss_stride);
+                        float* h, void* xg, int xg_ld, int xg_lo, const float* gain_next, float* ss, int ss_stride);
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
                              int per_layer_dst);
 
@@ -157,7 +165,8 @@ int attention_init();
 size_t attention_flash_partial_floats(size_t entries);
 void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
-                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, float* part, int32_t* counters);
+                            int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
+                            int32_t* counters);
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
 

@@ -14,7 +14,9 @@ those same bits.
 """
 from __future__ import annotations
 
+import os
 import zlib
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field, replace
 from typing import Dict, Optional, Tuple
 
@@ -101,6 +103,10 @@ CONFIGS: Dict[int, Workload] = {
 def shrink(cfg: ModelCfg, **kw) -> ModelCfg:
     """Same architecture with some dimensions replaced (used for fast parity cases)."""
     return replace(cfg, **kw)
+
+
+def _workers() -> int:
+    return max(1, min(16, os.cpu_count() or 1))
 
 
 def _rng(seed: int, name: str) -> np.random.Generator:
@@ -202,7 +208,10 @@ def gen_weights(cfg: ModelCfg, seed: int = 0, unembed_gain: Optional[float] = No
                 norm_jitter: float = 0.0) -> Dict[str, torch.Tensor]:
     if unembed_gain is None:
         unembed_gain = calibrate_unembed_gain(cfg, seed)
-    w = {n: gen_tensor(cfg, seed, n, unembed_gain, norm_jitter) for n in tensor_names(cfg)}
+    names = tensor_names(cfg)
+    # every tensor has its own keyed generator, so the tensors can be drawn concurrently
+    with ThreadPoolExecutor(max_workers=_workers()) as ex:
+        w = dict(zip(names, ex.map(lambda n: gen_tensor(cfg, seed, n, unembed_gain, norm_jitter), names)))
     w["__unembed_gain__"] = torch.tensor(unembed_gain, dtype=torch.float64)
     return w
 

@@ -75,9 +75,11 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
     table = I.gen_page_table(N, max_pages, seed)
     n_pages = N * max_pages
     if synthetic_kv:
-        k_pages = [I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "k") for l in range(cfg.n_layers)]
-        v_pages = [I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "v").permute(0, 1, 3, 2).contiguous()
-                   for l in range(cfg.n_layers)]
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:  # independent keyed generators per (layer, k/v)
+            k_pages = list(ex.map(lambda l: I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "k"), range(cfg.n_layers)))
+            v_pages = list(ex.map(lambda l: I.gen_synth_kv_pages(cfg, n_pages, page_size, seed, l, "v").permute(0, 1, 3, 2).contiguous(),
+                                  range(cfg.n_layers)))
     else:
         shape = (n_pages, cfg.n_kv_heads, page_size, cfg.head_dim)
         k_pages = [torch.zeros(shape, dtype=cfg.torch_dtype) for _ in range(cfg.n_layers)]
@@ -95,6 +97,23 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
     return case
 
 
+class LazyF64Weights(dict):
+    """The same stored weights, with the expert tensors of the most recently used layer kept up-cast to
+    fp64 so that the oracle's per-(row, expert) up-casts become no-ops.  Values are unchanged."""
+
+    def __init__(self, W):
+        super().__init__(W)
+        self._key, self._val = {}, {}
+
+    def __getitem__(self, k):
+        base = k.split(".")[-1]
+        if base in ("e_wgu", "e_wdown"):
+            if self._key.get(base) != k:
+                self._key[base], self._val[base] = k, super().__getitem__(k).to(torch.float64).numpy()
+            return self._val[base]
+        return super().__getitem__(k)
+
+
 class GpuRun:
     """Device-side mirror of a Case plus output buffers; methods call the C ABI."""
 
@@ -107,7 +126,12 @@ class GpuRun:
             return
         self.eng = Engine(cfg, case.W, N, B, device, packed=packed)
         i32 = torch.int32
-        self.kv = KvCache(torch.stack(case.k_pages).to(self.dev), torch.stack(case.v_pages).to(self.dev),
+        kdev = torch.empty((cfg.n_layers,) + tuple(case.k_pages[0].shape), dtype=cfg.torch_dtype, device=self.dev)
+        vdev = torch.empty((cfg.n_layers,) + tuple(case.v_pages[0].shape), dtype=cfg.torch_dtype, device=self.dev)
+        for l in range(cfg.n_layers):  # layer by layer: no second host copy of a multi-GB cache
+            kdev[l].copy_(case.k_pages[l])
+            vdev[l].copy_(case.v_pages[l])
+        self.kv = KvCache(kdev, vdev,
                           torch.as_tensor(case.page_table, dtype=i32, device=self.dev),
                           torch.as_tensor(case.seq_len, dtype=i32, device=self.dev),
                           torch.zeros(N, dtype=i32, device=self.dev))
