@@ -260,6 +260,11 @@ int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t
  * tests use it to hold the oracle to the same routing where a router score is tied to rounding. */
 int32_t s2d2_moe_choices(s2d2_ctx* ctx, int32_t rows, int32_t* out /* device */);
 
+/* Debugging aid: device address of an internal activation buffer of the most recent forward
+ * ("h" fp32 residual rows [rows, d]; "a" operand of the next norm; "q", "o", "ffn", "kwin", "vwin", "ss").
+ * Contents are those of the last layer that ran; layouts are internal and may change. */
+int32_t s2d2_debug_buffer(s2d2_ctx* ctx, const char* name, void** ptr);
+
 /* Vocabulary stage alone on caller-provided logits (same kernels the calls above use):
  * draft statistics for `rows` fp32 logit rows of width V.  Outputs are [rows]. */
 int32_t s2d2_vocab_draft_stats(s2d2_ctx* ctx, const float* logits, int32_t rows, int32_t* xhat,

@@ -147,7 +147,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   const size_t P = act_planes(d);
   c->a = cv.take<uint8_t>(R * d.d_model * es * P);
   c->qkv = cv.take<float>(R * (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim);
-  c->qbuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es);
+  c->qbuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es * act_planes(d));
   c->obuf = cv.take<uint8_t>(R * (size_t)d.n_q_heads * d.head_dim * es * P);
   c->ffn = cv.take<uint8_t>(R * (size_t)d.d_ffn * es * P);
   c->af = cv.take<uint8_t>(LR * (size_t)d.d_model * es);
@@ -284,7 +284,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.m_count = n_rows; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.ss_part = c->ss; a.ss_stride = ss_stride;
       a.ss_count = l == 0 ? 1 : ss_stride; a.eps = d.rms_eps;
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
-      a.q_out = (bf16_t*)c->qbuf; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
+      a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_o; a.q_lo = lo_o; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
       ProfScope ps(c, 0, (double)qkv_n * d.d_model * es);
       launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
@@ -297,7 +297,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
     if (flash) {
       ProfScope ps(c, 1, 0.0);
-      launch_attention_flash(st, c->qbuf, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
+      launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
     } else {
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
@@ -666,6 +666,15 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
     out[r.cls].bytes += r.bytes;
   }
   return S2D2_OK;
+}
+
+int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
+  if (!c || !name || !ptr) return fail(S2D2_EINVAL, "NULL argument");
+  const struct { const char* n; void* p; } tab[] = {{"h", c->h}, {"a", c->a}, {"q", c->qbuf}, {"o", c->obuf}, {"ffn", c->ffn},
+                                                    {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}};
+  for (const auto& t : tab)
+    if (!strcmp(t.n, name)) { *ptr = t.p; return S2D2_OK; }
+  return fail(S2D2_EINVAL, "unknown buffer %s", name);
 }
 
 int32_t s2d2_moe_choices(s2d2_ctx* c, int32_t rows, int32_t* out) {

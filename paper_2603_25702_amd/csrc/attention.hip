@@ -204,9 +204,11 @@ __device__ __forceinline__ void fa_combine(const float* part_o, const float* par
   }
 }
 
-template <int NW>
+// SPLIT: queries and softmax weights are used as high + low bf16 planes (16 significant bits): the
+// score and the P*V products are each issued twice against the same K / V operands.
+template <int NW, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
+    const bf16_t* __restrict__ q, int q_ld, int q_lo, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
     const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
     int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
     float* __restrict__ part_ml, int32_t* __restrict__ counters) {
@@ -238,11 +240,14 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
   const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
   const int lo = p.row_lo[r], hi = p.row_hi[r];
 
-  uint4 qf[8];
+  uint4 qf[8], ql[SPLIT ? 8 : 1];
   {
-    const bf16_t* qp = q + ((size_t)r * Hq + head) * D + 8 * h;
+    const bf16_t* qp = q + (size_t)r * q_ld + head * D + 8 * h;
 #pragma unroll
-    for (int ds = 0; ds < 8; ++ds) qf[ds] = *(const uint4*)(qp + ds * 16);
+    for (int ds = 0; ds < 8; ++ds) {
+      qf[ds] = *(const uint4*)(qp + ds * 16);
+      if (SPLIT) ql[ds] = *(const uint4*)(qp + q_lo + ds * 16);
+    }
   }
   FaState st;
   st.m = -INFINITY;
@@ -306,8 +311,10 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-    for (int ds = 0; ds < 8; ++ds)
+    for (int ds = 0; ds < 8; ++ds) {
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ds]), __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
+      if (SPLIT) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ds]), __builtin_bit_cast(bf16x8_t, ql[ds]), sacc, 0, 0, 0);
+    }
     // sacc[i]: key kbase + 16 (i / 8) + 8 h + (i % 8), query row c
     float sv[16];
     float mx = -INFINITY;
@@ -329,12 +336,14 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
     const float m_ref = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
     float ls = 0.f;
-    bf16x8_t pb[2];
+    bf16x8_t pb[2], pl[SPLIT ? 2 : 1];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float pv = __builtin_amdgcn_exp2f(sv[i] - m_ref);
       ls += pv;
-      pb[i >> 3][i & 7] = (__bf16)pv;
+      const __bf16 ph = (__bf16)pv;
+      pb[i >> 3][i & 7] = ph;
+      if (SPLIT) pl[i >> 3][i & 7] = (__bf16)(pv - (float)ph);
     }
     ls += __shfl_xor(ls, 32, 64);
     st.l = st.l * alpha + ls;
@@ -344,8 +353,10 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) st.o[dt][i] *= alpha;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 2; ++j) {
         st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[dt][j]), pb[j], st.o[dt], 0, 0, 0);
+        if (SPLIT) st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[dt][j]), pl[j], st.o[dt], 0, 0, 0);
+      }
     }
   }
   // ---- merge the wavefronts of the workgroup: fixed tree, through LDS ----
@@ -428,7 +439,7 @@ size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * F
 
 // q_tiles = ceil(3 B grp / 32); Z key splits of 8 wavefronts each.  `counters` holds one zeroed
 // arrival counter per (sequence, KV head, query tile); the last split to arrive merges.
-void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
+void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
                             int32_t* counters) {
@@ -436,10 +447,16 @@ void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, co
   const int items = N * g.n_kv_heads;
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
-  hipLaunchKernelGGL(attn_flash_kernel<8>, dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
-                     (const bf16_t*)q, (const bf16_t*)k_win, (const bf16_t*)vT_win, (const bf16_t*)k_pages_layer,
-                     (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e, (bf16_t*)o, o_ld, o_lo, part_o,
-                     part_ml, counters);
+  if (q_lo)
+    hipLaunchKernelGGL((attn_flash_kernel<8, true>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+                       (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
+                       (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
+                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
+  else
+    hipLaunchKernelGGL((attn_flash_kernel<8, false>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+                       (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
+                       (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
+                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
@@ -454,7 +471,8 @@ void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v) {
 int attention_init() {
   hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_generic_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_lds(8));
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_lds(8));
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_lds(8));
   return e == hipSuccess ? 0 : -1;
 }
 

@@ -232,10 +232,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
         if (head < a.Hq + a.Hkv) {
           const float2 cs = a.rope_cs[(size_t)m * half + i];
           const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
-          bf16_t* dst = head < a.Hq ? a.q_out + ((size_t)m * a.Hq + head) * D
-                                    : a.k_out + ((size_t)m * a.Hkv + (head - a.Hq)) * D;
-          dst[i] = f32_to_bf16(y1);
-          dst[i + half] = f32_to_bf16(y2);
+          if (head < a.Hq) {  // queries: both planes when the attention kernel multiplies with both
+            bf16_t* dst = a.q_out + (size_t)m * a.q_ld + head * D;
+            bf16_t h1, l1, h2, l2;
+            split_bf16(y1, h1, l1);
+            split_bf16(y2, h2, l2);
+            dst[i] = h1;
+            dst[i + half] = h2;
+            if (a.q_lo) { dst[a.q_lo + i] = l1; dst[a.q_lo + i + half] = l2; }
+          } else {
+            bf16_t* dst = a.k_out + ((size_t)m * a.Hkv + (head - a.Hq)) * D;
+            dst[i] = f32_to_bf16(y1);
+            dst[i + half] = f32_to_bf16(y2);
+          }
         } else {
           const int vh = head - a.Hq - a.Hkv;
           const bf16_t b1 = f32_to_bf16(x1), b2 = f32_to_bf16(x2);

@@ -235,13 +235,17 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
         if (live) {
           const bool second = g >= 2;   // this lane holds x2 (element i + D/2) of the pair
           if (head < a.Hq + a.Hkv) {
-            bf16_t* dst = head < a.Hq ? a.q_out + ((size_t)orow * a.Hq + head) * D
-                                      : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
+            const bool is_q = head < a.Hq;
+            bf16_t* dst = is_q ? a.q_out + (size_t)orow * a.q_ld + head * D
+                               : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const float2 cs = a.rope_cs[(size_t)orow * half + i0 + i];
               const float y = second ? own[i] * cs.x + oth[i] * cs.y : own[i] * cs.x - oth[i] * cs.y;
-              dst[i0 + i + (second ? half : 0)] = f32_to_bf16(y);
+              bf16_t hi, lo;
+              split_bf16(y, hi, lo);
+              dst[i0 + i + (second ? half : 0)] = hi;
+              if (is_q && a.q_lo) dst[a.q_lo + i0 + i + (second ? half : 0)] = lo;
             }
           } else {
             const int vh = head - a.Hq - a.Hkv;

@@ -119,6 +119,7 @@ struct GemmStreamArgs {
   // SEPI_QKV_ROPE
   const float2* rope_cs;    // [rows, D/2] (cos, sin)
   int32_t Hq, Hkv, D, wpad;
+  int32_t q_ld, q_lo;       // row stride of q_out and offset of its low-order plane (0: single plane)
   bf16_t* q_out;
   bf16_t* k_out;
   bf16_t* v_out;
@@ -163,7 +164,7 @@ void launch_attention_generic(hipStream_t st, int dtype, const void* q, const vo
                               const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes);
 int attention_init();
 size_t attention_flash_partial_floats(size_t entries);
-void launch_attention_flash(hipStream_t st, const void* q, const void* k_win, const void* vT_win,
+void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
                             int32_t* counters);
