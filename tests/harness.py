@@ -362,12 +362,19 @@ def _accept_forced(st, d, vo, prm, n, n_acc):
     return O.AcceptOut(n_acc, n_commit, resampled, block, u)
 
 
-def sync_case_from_gpu(case: Case, run: GpuRun):
-    """Adopts the GPU's cache contents and state as the stored inputs of the next step."""
+def sync_case_from_gpu(case: Case, run: GpuRun, seqs=None):
+    """Adopts the GPU's cache contents and state as the stored inputs of the next step.  With `seqs`, only
+    the pages of those sequences are copied back (full-size caches are tens of GB)."""
     torch.cuda.synchronize(run.dev)
-    k, v = run.kv.k.cpu(), run.kv.v.cpu()
-    case.k_pages = [k[l] for l in range(case.cfg.n_layers)]
-    case.v_pages = [v[l] for l in range(case.cfg.n_layers)]
+    if seqs is None:
+        k, v = run.kv.k.cpu(), run.kv.v.cpu()
+        case.k_pages = [k[l] for l in range(case.cfg.n_layers)]
+        case.v_pages = [v[l] for l in range(case.cfg.n_layers)]
+    else:
+        pages = torch.as_tensor(np.unique(case.page_table[list(seqs)].reshape(-1)).astype(np.int64))
+        for l in range(case.cfg.n_layers):
+            case.k_pages[l][pages] = run.kv.k[l][pages.to(run.dev)].cpu()
+            case.v_pages[l][pages] = run.kv.v[l][pages.to(run.dev)].cpu()
     case.seq_len = run.kv.seq_len.cpu().numpy().copy()
     blk, pos0, car = run.st.block_tokens.cpu().numpy(), run.st.block_pos0.cpu().numpy(), run.st.carry_tokens.cpu().numpy()
     for n, s in enumerate(case.states):

@@ -185,3 +185,76 @@ def test_small_moe_routing_grouped_gemm_and_combine():
         H.sync_case_from_gpu(case, run)
     print("small moe:", rep)
     assert rep.router_rows > 0 and rep.router_agree >= 0.9 * rep.router_rows
+
+
+def test_vocab_and_accept_kernels_on_synthetic_logit_pairs_at_full_vocabulary():
+    """The vocabulary stage alone on draft / verifier logit pairs shaped like the paper's confidence-by-ratio
+    table (about three quarters agreeing rows, the rest independent), at V = 151936: statistics, scores, the
+    accept scan with accepted runs of every length, and the residual draw, against the oracle on the same rows."""
+    from oracle import s2d2_oracle as O
+    from paper_2603_25702_amd import BlockState
+    cfg = I.shrink(I.CONFIGS[2].cfg, n_layers=1, d_model=64, n_q_heads=1, n_kv_heads=1, head_dim=64, d_ffn=64)  # only V matters here
+    N, B, V = 6, 8, cfg.vocab
+    W = I.gen_weights(cfg, 0, unembed_gain=1.0)
+    from paper_2603_25702_amd import Engine
+    eng = Engine(cfg, W, N, B)
+    dev = eng.device
+    ld, lv, agree = I.gen_logit_pairs(N * B, V, seed=5)
+    d, v, a = eng.alloc_draft_out(N, B), eng.alloc_verify_out(N, B), eng.alloc_accept_out(N, B)
+    d.logits.copy_(torch.from_numpy(ld))
+    v.logits_ver.copy_(torch.from_numpy(lv))
+    ident = torch.arange(N * B, dtype=torch.int32, device=dev).view(N, B)
+    d.logit_row_of.copy_(ident)
+    v.logit_row_of.copy_(ident)
+    st_d = eng.s2d2_vocab_draft_stats(d.logits)
+    for k in ("xhat", "p", "lse", "margin", "entropy_n"):
+        d.t[k].copy_(st_d[k].view(N, B))
+    q, lse_v = eng.s2d2_vocab_score(v.logits_ver, d.xhat.view(-1))
+    v.q.copy_(q.view(N, B))
+    v.lse_ver.copy_(lse_v.view(N, B))
+    starts = np.array([0, 1, 0, 2, 0, 3], dtype=np.int32)
+    lens = np.array([8, 7, 8, 5, 8, 1], dtype=np.int32)
+    d.span_start.copy_(torch.from_numpy(starts))
+    d.span_len.copy_(torch.from_numpy(lens))
+    blk = torch.full((N, B), cfg.mask_id, dtype=torch.int32, device=dev)
+    st = BlockState(blk, torch.zeros(N, dtype=torch.int32, device=dev), torch.zeros((N, B), dtype=torch.int32, device=dev))
+    hist = []
+    for step in range(6):
+        blk.fill_(cfg.mask_id)
+        prm = Params(seed=31, step=step)
+        eng.s2d2_accept(st, N, B, prm, d, v, a)
+        torch.cuda.synchronize()
+        g = {k: t.cpu().numpy() for k, t in list(d.t.items()) + list(a.t.items()) if k != "logits"}
+        gq = v.q.cpu().numpy()
+        for n in range(N):
+            j, L = int(starts[n]), int(lens[n])
+            rows = range(n * B + j, n * B + j + L)
+            # oracle statistics on the same fp32 rows
+            for r, i in zip(rows, range(j, j + L)):
+                s = O.sample_from_logits(ld[r].astype(np.float64))
+                assert s["xhat"] == g["xhat"][n, i] and abs(s["p"] - g["p"][n, i]) < 1e-3
+                assert abs(s["margin"] - g["margin"][n, i]) < 2e-3 and abs(s["entropy_n"] - g["entropy_n"][n, i]) < 1e-3
+                qq, _ = O.score_from_logits(lv[r].astype(np.float64), s["xhat"])
+                assert abs(qq - gq[n, i]) < 1e-3
+            u = np.array([O.uniform(31, step, n, j + r, O.STREAM_ACCEPT) for r in range(L)])
+            p64, q64 = g["p"][n, j:j + L].astype(np.float64), gq[n, j:j + L].astype(np.float64)
+            n_acc = O.accept_scan(p64, q64, u)
+            if n_acc != g["n_accept"][n]:
+                upto = min(L, max(n_acc, int(g["n_accept"][n])) + 1)
+                assert (np.abs(q64[:upto] / p64[:upto] - u[:upto]) < H.TIE).any()
+                n_acc = int(g["n_accept"][n])
+            hist.append(n_acc)
+            if n_acc < L:
+                r = n * B + j + n_acc
+                u2 = O.uniform(31, step, n, j + n_acc, O.STREAM_RESAMPLE)
+                tok = O.residual_resample(ld[r].astype(np.float64), lv[r].astype(np.float64), u2)
+                got = int(g["resampled"][n])
+                if tok != got:
+                    res = O.residual_distribution(ld[r].astype(np.float64), lv[r].astype(np.float64))
+                    cdf = np.cumsum(res) / res.sum()
+                    assert abs(cdf[min(tok, got)] - u2) < H.TIE, (n, step, tok, got)
+                assert g["n_commit"][n] == n_acc + 1
+            else:
+                assert g["resampled"][n] == -1 and g["n_commit"][n] == L
+    print("accepted-run histogram:", np.bincount(hist, minlength=9).tolist(), "agreeing rows:", int(agree.sum()), "of", N * B)
+    assert max(hist) >= 2 and min(hist) == 0   # both long accepted runs and immediate rejections occurred

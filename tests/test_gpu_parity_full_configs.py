@@ -28,7 +28,11 @@ def full_case(cfg_id, seed=0):
     return wl, case, lens
 
 
-def run_and_check(case, prm, seqs, kv_layers, free_router=False):
+def run_and_check(case, prm, seqs, kv_layers, free_router=False, second_step=True):
+    """One step on the whole batch, checked on `seqs`.  With random weights the verifier rejects the first
+    drafted token almost surely, so nothing but the length is appended in step one; a second step then carries
+    the resampled token as a leading causal row, whose K/V it appends: that exercises the cache write at
+    full size (page arithmetic, key-minor V) against the oracle's causal rows."""
     t0 = time.time()
     run = H.GpuRun(case)
     run.step(prm, advance=False)
@@ -39,6 +43,16 @@ def run_and_check(case, prm, seqs, kv_layers, free_router=False):
         case.W = H.LazyF64Weights(case.W)
     rep = H.check_step(case, run, g, prm, seqs=seqs, check_kv_layers=kv_layers, free_router=free_router)
     print(f"oracle check of sequences {list(seqs)} took {time.time() - t0:.0f}s: {rep}", flush=True)
+    if second_step:
+        t0 = time.time()
+        run.eng.s2d2_block_advance(run.kv, run.st, case.N, case.B, None)
+        H.sync_case_from_gpu(case, run, seqs=seqs)
+        prm2 = Params(tau=prm.tau, seed=prm.seed, step=prm.step + 1)
+        run.step(prm2, advance=False)
+        g2 = run.fetch()
+        rep = H.check_step(case, run, g2, prm2, seqs=seqs, check_kv_layers=kv_layers, rep=rep)
+        print(f"second step, oracle check took {time.time() - t0:.0f}s: {rep}", flush=True)
+        assert rep.max_kv_err > 0.0   # some K/V rows were appended and compared
     return run, g, rep
 
 
