@@ -254,6 +254,11 @@ int32_t s2d2_block_advance(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_blo
 int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_t B,
                               const s2d2_draft_out* draft);
 
+/* Synchronises the context's stream and reports a sticky device-side failure: S2D2_ELAUNCH if a
+ * device-wide barrier of the fused forward ran out of its bounded spin (a workgroup was not resident),
+ * after which every later fused forward returns at once without computing; S2D2_OK otherwise. */
+int32_t s2d2_status(s2d2_ctx* ctx);
+
 /* MoE models: the experts chosen by the router in the most recent forward (draft or verifier),
  * out = device [n_layers, rows, top_k] int32 for the first `rows` window rows (window rows are packed
  * sequence after sequence: leading causal rows, drafted rows, then [MASK] copies).  The parity
@@ -281,8 +286,10 @@ int32_t s2d2_vocab_score(s2d2_ctx* ctx, const float* logits_ver, int32_t rows,
  *   bytes       algorithmic HBM bytes of those launches: weight matrix once for a GEMM, K and V
  *               of the cached prefix once for attention, the fp32 logit rows once for the
  *               vocabulary kernels (window rows and tiny outputs are not counted)
- * Classes: 0 GEMM (weight streaming), 1 attention, 2 vocabulary, 3 everything else. */
-#define S2D2_PROFILE_CLASSES 4
+ * Classes: 0 GEMM (weight streaming), 1 attention, 2 vocabulary, 3 everything else, 4 the fused
+ * forward (one persistent launch that holds all layers of a narrow window: its bytes are the layer
+ * weights once). */
+#define S2D2_PROFILE_CLASSES 5
 typedef struct {
   int64_t launches;
   double ms;

@@ -22,9 +22,9 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
-    "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
+    "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
-PROFILE_CLASSES = ("gemm", "attention", "vocab", "other")
+PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "forward")
 
 
 class S2D2Error(RuntimeError):
@@ -120,6 +120,8 @@ def load_library():
     lib.s2d2_block_advance.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
                                        C.c_void_p]
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
+    lib.s2d2_status.argtypes = [C.c_void_p]
+    lib.s2d2_status.restype = C.c_int32
     lib.s2d2_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p)]
     lib.s2d2_debug_buffer.restype = C.c_int32
     lib.s2d2_moe_choices.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
@@ -129,7 +131,7 @@ def load_library():
     lib.s2d2_profile_start.argtypes = [C.c_void_p, C.c_int32]
     lib.s2d2_profile_stop.argtypes = [C.c_void_p, C.POINTER(ProfileC)]
     for name in ("s2d2_profile_start", "s2d2_profile_stop", "s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
-                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
+                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
     return lib
@@ -343,6 +345,9 @@ class Engine:
 
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
+
+    def s2d2_status(self):
+        _check(self.lib, self.lib.s2d2_status(self.ctx))
 
     def s2d2_debug_buffer(self, name: str) -> int:
         p = C.c_void_p()

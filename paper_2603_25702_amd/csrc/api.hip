@@ -66,6 +66,15 @@ struct s2d2_ctx {
   float* moe_y;           // [rows_cap * top_k, d_model]
   PackedLayer* pk;
   const uint4* pk_unembed;
+  // fused forward (one persistent launch) for windows of at most 16 rows
+  FusedLayer* fused_layers;  // device
+  uint32_t* fused_bar;       // 9 x 64 words
+  int32_t* fused_err;
+  uint64_t* moe_y_or_scratch; // clock stamps of the timing build
+  uint8_t* fused_act;        // per-layer exchange buffers of the fused forward
+  size_t fused_act_stride;
+  int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
+  bool no_fused;
   // profiling (measurement aid)
   bool prof_on;
   int32_t prof_cap;
@@ -181,6 +190,13 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     c->moe_act = cv.take<uint8_t>(RK * (size_t)d.d_expert * es * P);
     c->moe_y = cv.take<float>(RK * (size_t)d.d_model);
   }
+  c->fused_layers = cv.take<FusedLayer>(d.n_layers);
+  c->fused_bar = cv.take<uint32_t>(9 * 64);
+  c->fused_err = cv.take<int32_t>(64);
+  c->fused_act_stride = d.n_experts == 0 && d.dtype == S2D2_BF16 && d.d_model <= 4096
+                            ? forward_fused_act_bytes(d.d_model, d.n_q_heads * d.head_dim, d.d_ffn) : 0;
+  c->fused_act = cv.take<uint8_t>(c->fused_act_stride * (size_t)(d.n_layers + 1));
+  c->moe_y_or_scratch = cv.take<uint64_t>(832);
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   return (cv.off + 255) & ~(size_t)255;
@@ -271,6 +287,37 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int ld_o = P * HqD, lo_o = P == 2 ? HqD : 0;
   const int ld_f = P * d.d_ffn, lo_f = P == 2 ? d.d_ffn : 0;
   const int ld_e = P * d.d_expert, lo_e = P == 2 ? d.d_expert : 0;
+  // ---- one persistent launch for narrow windows ----
+  const int grp = d.n_q_heads / d.n_kv_heads;
+  if (fused && flash && P == 2 && c->fused_G > 0 && c->fused_act_stride > 0 && !c->no_fused && R <= 16 && R * grp <= 32 && d.d_model / 16 <= c->fused_G &&
+      N * d.n_kv_heads * Z <= c->fused_G - d.d_model / 16) {
+    { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
+    { ProfScope ps(c, 3, 0.0); launch_fill_i32(st, (int32_t*)c->fused_bar, 9 * 64, 0); }
+    FusedArgs fa{};
+    fa.n_layers = d.n_layers; fa.d = d.d_model; fa.Hq = d.n_q_heads; fa.Hkv = d.n_kv_heads; fa.D = d.head_dim; fa.F = d.d_ffn; fa.n_seq = N;
+    fa.layers = c->fused_layers; fa.norm_f = c->w.norm_f; fa.embed = (const bf16_t*)c->w.embed; fa.plan = c->plan;
+    fa.rope_cs = c->rope_cs; fa.g = g; fa.k_pages = (const bf16_t*)kv->k_pages; fa.v_pages = (const bf16_t*)kv->v_pages;
+    fa.page_layer = page_layer / es;
+    fa.k_stage = (bf16_t*)(k_stage ? k_stage : c->kwin); fa.v_stage = (bf16_t*)(v_stage ? v_stage : c->vwin);
+    fa.stage_layer = k_stage ? stage_layer / es : 0;
+    fa.vT_win = (bf16_t*)c->vT_win; fa.wpad = c->wpad;
+    fa.xg = (bf16_t*)c->a; fa.q = (bf16_t*)c->qbuf; fa.ss = c->ss; fa.h_out = c->h;
+    fa.act = (char*)c->fused_act; fa.act_stride = c->fused_act_stride;
+    fa.part = c->attn_part; fa.attn_counters = c->attn_counters; fa.Z = Z;
+    fa.eps = d.rms_eps; fa.scale_log2e = 1.4426950408889634f / sqrtf((float)d.head_dim);
+    fa.bar = c->fused_bar; fa.err = c->fused_err; fa.spin_limit = 1 << 20;
+    fa.tstamp = (unsigned long long*)c->moe_y_or_scratch;
+    const double wbytes = (double)d.n_layers * ((double)qkv_n * d.d_model + (double)d.d_model * HqD + 3.0 * d.d_ffn * d.d_model) * es;
+    { ProfScope ps(c, 4, wbytes); launch_forward_fused(st, fa, c->fused_G); }
+    const int32_t* n_logit = c->plan.counts + 1;
+    GemmStreamArgs a{};
+    a.Wp = c->pk_unembed; a.NT = (d.vocab + 15) / 16; a.KT = d.d_model / 32; a.N = d.vocab; a.K = d.d_model;
+    a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.gather = c->plan.logit_src;
+    a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
+    a.out = logits; a.ldo = d.vocab;
+    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm_stream(st, SEPI_STORE_F32, a, LR); }
+    return check_launch("forward (fused)");
+  }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
@@ -510,6 +557,18 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     c->pk_unembed = put(c->w.unembed, d.vocab, d.d_model, 0);
     if (hipGetLastError() != hipSuccess) { free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "weight packing failed to launch"); }
   }
+  c->no_fused = true;   // the fused forward is opt-in: on this hardware its device-wide barriers cost what kernel boundaries cost
+  if (const char* e = getenv("S2D2_FUSED")) c->no_fused = atoi(e) == 0;
+  launch_fill_i32(c->stream, c->fused_err, 64, 0);
+  if (use_packed && c->desc.n_experts == 0 && act_planes(c->desc) == 2 && c->desc.head_dim == 128) {
+    // one workgroup per compute unit must be resident at the same time for the device-wide barriers
+    if (forward_fused_init() == 0 && forward_fused_occupancy() >= 1 && prop.multiProcessorCount >= 8) c->fused_G = prop.multiProcessorCount;
+    (void)hipGetLastError();
+    for (int l = 0; l < c->desc.n_layers && c->fused_G; ++l) {
+      FusedLayer fl{c->pk[l].wqkv, c->pk[l].wo, c->pk[l].wg, c->pk[l].wu, c->pk[l].wdown, c->layers[l].norm1, c->layers[l].norm2};
+      launch_fused_set_layer(c->stream, c->fused_layers + l, fl);
+    }
+  }
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
@@ -668,10 +727,19 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
   return S2D2_OK;
 }
 
+int32_t s2d2_status(s2d2_ctx* c) {
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  int32_t flag = 0;
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipMemcpy(&flag, c->fused_err, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(S2D2_ELAUNCH, "could not read the device status: %s", hipGetErrorString(hipGetLastError()));
+  if (flag) return fail(S2D2_ELAUNCH, "a device-wide barrier of the fused forward timed out (workgroups not co-resident)");
+  return S2D2_OK;
+}
+
 int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
   if (!c || !name || !ptr) return fail(S2D2_EINVAL, "NULL argument");
   const struct { const char* n; void* p; } tab[] = {{"h", c->h}, {"a", c->a}, {"q", c->qbuf}, {"o", c->obuf}, {"ffn", c->ffn},
-                                                    {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}};
+                                                    {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->moe_y_or_scratch}};
   for (const auto& t : tab)
     if (!strcmp(t.n, name)) { *ptr = t.p; return S2D2_OK; }
   return fail(S2D2_EINVAL, "unknown buffer %s", name);

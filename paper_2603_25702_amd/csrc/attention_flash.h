@@ -1,0 +1,365 @@
+// MFMA flash attention over the paged prefix cache plus the window: device-side body, shared by the
+// stand-alone kernel (attention.hip) and the fused forward (forward_fused.hip).
+#pragma once
+#include "s2d2_internal.h"
+
+namespace s2d2 {
+
+// ---------------------------------------------------------------------------------------------
+// attn_flash_kernel (bf16, head_dim 128): split-key flash attention on 32x32x16 MFMA.
+//
+// Work item = (sequence, KV head, tile of 32 query rows, key split).  A "query row" is a
+// (window row, query head of the group) pair, so GQA groups share every K/V byte.  Each of the
+// NW wavefronts of a workgroup takes every NW-th tile of 32 keys of its split, streams K and V
+// straight from global memory into MFMA operands (no LDS on the K/V path), and keeps an online
+// softmax state.  Scores are computed transposed, S^T = K Q^T, so that one lane owns one query
+// row: its running max / sum and the rescaling of its output column need no cross-lane traffic
+// beyond one exchange between the two half-waves.  The rows of the K tile are fed in a permuted
+// order chosen so that the fp32 S^T accumulators of a lane, packed to bf16, are exactly the B
+// operand (8 consecutive keys) of O^T = V^T P^T; the cache stores V key-minor ([D, page_size])
+// so that the matching A operand is one 16-byte load.  Wavefronts merge through LDS in a fixed
+// tree; splits merge in attn_combine_kernel (fixed order) unless there is only one split.
+// ---------------------------------------------------------------------------------------------
+static constexpr int FA_D = 128;
+
+__device__ __forceinline__ int fa_perm(int rr) {  // MFMA row -> key offset inside the 32-key tile
+  const int a = rr >> 3, hh = (rr >> 2) & 1, b = rr & 3;
+  return (a >> 1) * 16 + hh * 8 + (a & 1) * 4 + b;
+}
+
+__device__ __forceinline__ uint4 mask_keys(uint4 v, int nv) {  // keep the first nv of 8 bf16, zero the rest
+  if (nv >= 8) return v;
+  if (nv <= 0) return make_uint4(0, 0, 0, 0);
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int k = nv - 2 * e;  // valid halves in this dword
+    w[e] = k >= 2 ? w[e] : (k == 1 ? (w[e] & 0xffffu) : 0u);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+struct FaState {
+  float m, l;
+  f32x16_t o[4];
+};
+
+__device__ __forceinline__ void fa_merge(FaState& a, float m2, float l2, const f32x16_t* o2) {
+  const float M = fmaxf(a.m, m2);
+  const float f1 = a.m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(a.m - M);
+  const float f2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - M);
+  a.l = a.l * f1 + l2 * f2;
+  a.m = M;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a.o[t][i] = a.o[t][i] * f1 + o2[t][i] * f2;
+}
+
+// Four consecutive output elements as bf16, plus their low-order plane o_lo elements further on if o_lo != 0.
+template <bool COH>
+__device__ __forceinline__ void fa_store4(bf16_t* p, int o_lo, float a, float b, float c, float d) {
+  bf16_t hi[4], lo[4];
+  split_bf16(a, hi[0], lo[0]);
+  split_bf16(b, hi[1], lo[1]);
+  split_bf16(c, hi[2], lo[2]);
+  split_bf16(d, hi[3], lo[3]);
+  uint2 pk;
+  pk.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16);
+  pk.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+  if (COH) st8_coh(p, pk); else *(uint2*)p = pk;
+  if (o_lo) {
+    pk.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16);
+    pk.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+    if (COH) st8_coh(p + o_lo, pk); else *(uint2*)(p + o_lo) = pk;
+  }
+}
+
+// Merges the Z split partials of one (sequence, KV head, query tile) in split order.  All loads of a thread's
+// items are issued before any of them is used (one memory round trip for up to ZMAX splits); more splits
+// take further rounds of ZMAX.
+template <bool COH, int NTHREADS>
+__device__ __forceinline__ void fa_combine(const float* part_o, const float* part_ml, size_t item0, int Z, int tid,
+                                           int qt, int nq, int grp, int row0, int kvh, int Hq,
+                                           bf16_t* __restrict__ o, int o_ld, int o_lo) {
+  constexpr int D = FA_D, ITEMS = 32 * (D / 4) / NTHREADS, ZMAX = 4;
+  static_assert(ITEMS >= 1 && ITEMS * NTHREADS == 32 * (D / 4), "thread count must divide the 1024 output chunks");
+  float M[ITEMS], l[ITEMS];
+  float4 acc[ITEMS];
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) { M[it] = -INFINITY; l[it] = 0.f; acc[it] = make_float4(0.f, 0.f, 0.f, 0.f); }
+  for (int z0 = 0; z0 < Z; z0 += ZMAX) {
+    float m[ITEMS][ZMAX], lz[ITEMS][ZMAX];
+    uint4 pq[ITEMS][ZMAX];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int e = tid + it * NTHREADS, c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+#pragma unroll
+      for (int k = 0; k < ZMAX; ++k) {
+        const int z = min(z0 + k, Z - 1);   // clamped duplicates are skipped below
+        m[it][k] = ld4f_coh(&part_ml[(item0 + z) * 64 + c]);
+        lz[it][k] = ld4f_coh(&part_ml[(item0 + z) * 64 + 32 + c]);
+        pq[it][k] = ld16_coh(part_o + ((item0 + z) * 32 + c) * D + d0);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+#pragma unroll
+      for (int k = 0; k < ZMAX; ++k) {   // in split order: running rescale
+        if (z0 + k >= Z || m[it][k] == -INFINITY) continue;
+        const float Mn = fmaxf(M[it], m[it][k]);
+        const float fo = M[it] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M[it] - Mn);
+        const float fn = __builtin_amdgcn_exp2f(m[it][k] - Mn);
+        l[it] = l[it] * fo + fn * lz[it][k];
+        acc[it].x = acc[it].x * fo + fn * __uint_as_float(pq[it][k].x);
+        acc[it].y = acc[it].y * fo + fn * __uint_as_float(pq[it][k].y);
+        acc[it].z = acc[it].z * fo + fn * __uint_as_float(pq[it][k].z);
+        acc[it].w = acc[it].w * fo + fn * __uint_as_float(pq[it][k].w);
+        M[it] = Mn;
+      }
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int e = tid + it * NTHREADS, c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+    const int qi = qt * 32 + c;
+    if (qi >= nq) continue;
+    const float inv = l[it] > 0.f ? 1.0f / l[it] : 0.f;
+    const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+    fa_store4<COH>(o + (size_t)r * o_ld + head * D + d0, o_lo, acc[it].x * inv, acc[it].y * inv, acc[it].z * inv, acc[it].w * inv);
+  }
+}
+
+// SPLIT: queries and softmax weights are used as high + low bf16 planes (16 significant bits): the
+// score and the P*V products are each issued twice against the same K / V operands.
+// COH: q, the window K / V and o are exchanged with other workgroups of the SAME launch (fused forward), so
+// they are read and written with device-coherent accesses.  The split partials always are.
+// (z, qt, item) = (key split, query tile, sequence * Hkv + KV head); q_tiles = query tiles per item.
+template <int NW, bool SPLIT, bool COH>
+__device__ __forceinline__ void attn_flash_body(
+    const bf16_t* __restrict__ q, int q_ld, int q_lo, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
+    const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, const KvGeom& g, const Plan& p, int Hq, int Z,
+    int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int32_t* __restrict__ counters, int z, int qt, int item_zy, int q_tiles, float* smem) {
+  constexpr int D = FA_D;
+  const int Hkv = g.n_kv_heads, ps = g.page_size;
+  const int n = item_zy / Hkv, kvh = item_zy % Hkv;
+  const int grp = Hq / Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, h = lane >> 5;
+  const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
+  // Tile t of the cached keys belongs to wavefront (t mod GW) of the GW = Z * NW wavefronts that
+  // share this (sequence, KV head, query tile): the assignment does not depend on seq_len, so the
+  // page-table entries of a wavefront's first tile are requested together with seq_len and the
+  // plan entries (one round trip), and K / V follow in the second.
+  const int gw = z * NW + wave, GW = Z * NW;
+  const int kperm = fa_perm(c);
+  const int cap = g.max_pages_per_seq * ps;
+  int page_k = pt[min(gw * 32 + kperm, cap - 1) / ps];
+  int page_v[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) page_v[j] = pt[min(gw * 32 + 16 * j + 8 * h, cap - 1) / ps];
+  const int S = max(0, min(g.seq_len[n], cap));
+  const int row0 = p.seq_row0[n], nw = p.seq_rows[n];
+  const int nq = nw * grp, q0 = qt * 32;
+  if (q0 >= nq) return;
+  const int qi = min(q0 + c, nq - 1);
+  const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+  const int lo = p.row_lo[r], hi = p.row_hi[r];
+
+  uint4 qf[8], ql[SPLIT ? 8 : 1];
+  {
+    const bf16_t* qp = q + (size_t)r * q_ld + head * D + 8 * h;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) {
+      qf[ds] = COH ? ld16_coh(qp + ds * 16) : *(const uint4*)(qp + ds * 16);
+      if (SPLIT) ql[ds] = COH ? ld16_coh(qp + q_lo + ds * 16) : *(const uint4*)(qp + q_lo + ds * 16);
+    }
+  }
+  FaState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
+
+  const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
+  const int n_c = Tc > gw ? (Tc - gw + GW - 1) / GW : 0;           // cached tiles gw, gw + GW, ...
+  const int w_first = (GW - 1 - gw) % GW;                          // window tiles go to the last wavefronts
+  const int n_w = Tw > w_first ? (Tw - w_first + GW - 1) / GW : 0;
+
+  for (int it = 0; it < n_c + n_w; ++it) {
+    const bool win = it >= n_c;
+    const int tile = win ? w_first + (it - n_c) * GW : gw + it * GW;
+    const int limit = win ? nw : S;             // keys of this region
+    const int kbase = tile * 32;
+    // ---- S^T = K Q^T ----
+    const bf16_t* kp;
+    {
+      const int key = min(kbase + kperm, limit - 1);
+      if (win) {
+        kp = k_win + ((size_t)(row0 + key) * Hkv + kvh) * D;
+      } else {
+        // a lane whose key lies beyond seq_len reads some valid row; its score is replaced below
+        const int page = min(max(page_k, 0), g.n_pages - 1);
+        kp = k_pages + (((size_t)page * Hkv + kvh) * ps + (kbase + kperm) % ps) * D;
+      }
+    }
+    uint4 kf[8];
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) kf[ds] = (COH && win) ? ld16_coh(kp + ds * 16 + 8 * h) : *(const uint4*)(kp + ds * 16 + 8 * h);
+    // ---- V^T fragments: [dt][j]: d = dt*32 + c, keys kbase + 16 j + 8 h .. +8 ----
+    uint4 vf[4][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int key0 = kbase + 16 * j + 8 * h;
+      const int nv = limit - key0;
+      const bf16_t* vp;
+      size_t dstride;
+      if (win) {
+        vp = vT_win + ((size_t)(n * Hkv + kvh) * D + c) * wpad + min(key0, wpad - 8);
+        dstride = (size_t)32 * wpad;
+      } else {
+        const int page = min(max(page_v[j], 0), g.n_pages - 1);
+        vp = v_pages + (((size_t)page * Hkv + kvh) * D + c) * ps + (key0 % ps);
+        dstride = (size_t)32 * ps;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+        vf[dt][j] = mask_keys((COH && win) ? ld16_coh(vp + dt * dstride) : *(const uint4*)(vp + dt * dstride), nv);
+    }
+    if (it + 1 < n_c) {  // page-table entries of the next cached tile, in flight during this tile's math
+      const int nb = (tile + GW) * 32;
+      page_k = pt[min(nb + kperm, cap - 1) / ps];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) page_v[j] = pt[min(nb + 16 * j + 8 * h, cap - 1) / ps];
+    }
+    f32x16_t sacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ds]), __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
+      if (SPLIT) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[ds]), __builtin_bit_cast(bf16x8_t, ql[ds]), sacc, 0, 0, 0);
+    }
+    // sacc[i]: key kbase + 16 (i / 8) + 8 h + (i % 8), query row c
+    float sv[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = kbase + 16 * (i >> 3) + 8 * h + (i & 7);
+      bool ok = key < limit;
+      if (win) {
+        const int w = row0 + key;
+        ok = ok && ((w >= lo && w < hi) || w == r);
+      }
+      sv[i] = ok ? sacc[i] * scale_log2e : -INFINITY;
+      mx = fmaxf(mx, sv[i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // no divergent control flow around the MFMAs: a query row that sees nothing yet keeps m = -inf
+    // and uses 0 as the reference, which makes every p below exp2(-inf) = 0
+    const float m_new = fmaxf(st.m, mx);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
+    float ls = 0.f;
+    bf16x8_t pb[2], pl[SPLIT ? 2 : 1];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pv = __builtin_amdgcn_exp2f(sv[i] - m_ref);
+      ls += pv;
+      const __bf16 ph = (__bf16)pv;
+      pb[i >> 3][i & 7] = ph;
+      if (SPLIT) pl[i >> 3][i & 7] = (__bf16)(pv - (float)ph);
+    }
+    ls += __shfl_xor(ls, 32, 64);
+    st.l = st.l * alpha + ls;
+    st.m = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.o[dt][i] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[dt][j]), pb[j], st.o[dt], 0, 0, 0);
+        if (SPLIT) st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[dt][j]), pl[j], st.o[dt], 0, 0, 0);
+      }
+    }
+  }
+  // ---- merge the wavefronts of the workgroup: fixed tree, through LDS ----
+  // slot layout: [slot][66][64]: 64 accumulator registers + m + l per lane
+  for (int s = NW / 2; s >= 1; s >>= 1) {
+    if (wave >= s && wave < 2 * s) {
+      float* dst = smem + (size_t)(wave - s) * 66 * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dst[(t * 16 + i) * 64] = st.o[t][i];
+      dst[64 * 64] = st.m;
+      dst[65 * 64] = st.l;
+    }
+    __syncthreads();
+    if (wave < s) {
+      const float* src = smem + (size_t)wave * 66 * 64 + lane;
+      f32x16_t o2[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o2[t][i] = src[(t * 16 + i) * 64];
+      fa_merge(st, src[64 * 64], src[65 * 64], o2);
+    }
+    __syncthreads();
+  }
+  // st.o[dt][i]: d = dt*32 + 8 (i/4) + 4 h + (i%4), query row c
+  const bool q_ok = (q0 + c) < nq;
+  if (Z == 1) {
+    if (wave != 0 || !q_ok) return;
+    const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
+    bf16_t* op = o + (size_t)r * o_ld + head * D;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d0 = dt * 32 + 8 * i4 + 4 * h;
+        fa_store4<COH>(op + d0, o_lo, st.o[dt][4 * i4] * inv, st.o[dt][4 * i4 + 1] * inv, st.o[dt][4 * i4 + 2] * inv,
+                  st.o[dt][4 * i4 + 3] * inv);
+      }
+    return;
+  }
+  // Z > 1: write this split's partial; the workgroup that arrives last merges all splits in split
+  // order (so the result does not depend on which one it is) and re-arms the counter.
+  const int group = item_zy * q_tiles + qt;
+  const size_t item0 = (size_t)group * Z;
+  if (wave == 0) {
+    const size_t item = item0 + z;
+    float* po = part_o + item * 32 * D + (size_t)c * D;
+    if (h == 0) {
+      st4f_coh(&part_ml[item * 64 + c], st.m);
+      st4f_coh(&part_ml[item * 64 + 32 + c], st.l);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d0 = dt * 32 + 8 * i4 + 4 * h;
+        st16f_coh(po + d0, st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
+      }
+    __builtin_amdgcn_s_waitcnt(0);  // the write-through stores of the partial have completed before the arrival is counted
+  }
+  __syncthreads();
+  int* s_last = (int*)smem;
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(&counters[group], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = prev == Z - 1;
+    if (prev == Z - 1) __hip_atomic_store(&counters[group], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!*s_last) return;
+  fa_combine<COH, NW * 64>(part_o, part_ml, item0, Z, threadIdx.x, qt, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
+}
+
+
+static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * sizeof(float); }
+
+}  // namespace s2d2

@@ -26,6 +26,26 @@ __device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
   hi = f32_to_bf16(v);
   lo = f32_to_bf16(v - bf16_to_f32(hi));
 }
+// Device-coherent accesses (agent scope, relaxed: write-through stores, loads that bypass the non-coherent
+// caches) for data that workgroups of one launch hand to each other.  The producer waits for its stores
+// (s_waitcnt) before it signals; no cache-wide fence is involved.
+__device__ __forceinline__ uint4 ld16_coh(const void* p) {
+  const uint64_t* q = (const uint64_t*)p;
+  const uint64_t a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+}
+__device__ __forceinline__ void st8_coh(void* p, uint2 v) {
+  __hip_atomic_store((uint64_t*)p, (uint64_t)v.x | ((uint64_t)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st2_coh(bf16_t* p, bf16_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st4f_coh(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld4f_coh(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st16f_coh(float* p, float a, float b, float c, float d) {
+  uint64_t* q = (uint64_t*)p;
+  __hip_atomic_store(q, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, (uint64_t)__float_as_uint(c) | ((uint64_t)__float_as_uint(d) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
@@ -157,6 +177,49 @@ void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const 
                         float* h, void* xg, int xg_ld, int xg_lo, const float* gain_next, float* ss, int ss_stride);
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
                              int per_layer_dst);
+
+// forward_fused.hip : the whole forward of a window of at most 16 rows in one persistent launch
+struct FusedLayer {            // device-resident, one per layer
+  const uint4 *wqkv, *wo, *wg, *wu, *wdown;   // packed weights
+  const float *norm1, *norm2;
+};
+struct FusedArgs {
+  int32_t n_layers, d, Hq, Hkv, D, F, n_seq;
+  const FusedLayer* layers;    // device [n_layers]
+  const float* norm_f;
+  const bf16_t* embed;
+  Plan plan;
+  const float2* rope_cs;
+  KvGeom g;
+  const bf16_t* k_pages;
+  const bf16_t* v_pages;
+  size_t page_layer;           // elements per layer of the page arrays
+  bf16_t* k_stage;             // window K / V of every layer ([layer, rows_cap, Hkv, D]) or a one-layer scratch
+  bf16_t* v_stage;
+  size_t stage_layer;          // elements per layer (0 for the scratch)
+  bf16_t* vT_win;
+  int32_t wpad;
+  bf16_t* xg;                  // [16, 2, d]   operand of the FINAL norm, row-major (read by the unembedding GEMM)
+  bf16_t* q;                   // [16, 2, Hq D]
+  float* ss;                   // [16, d / 16] partial sums of squares of the final residual rows
+  char* act;                   // per-layer exchange buffers, act_stride bytes per layer (forward_fused_act_bytes)
+  size_t act_stride;
+  float* h_out;                // [16, d] final residual rows (inspection only)
+  float* part;                 // split-key partials of the attention
+  int32_t* attn_counters;
+  int32_t Z;
+  float eps, scale_log2e;
+  uint32_t* bar;               // 9 counters at 64-word spacing, zero at launch
+  int32_t* err;                // sticky: set when a barrier wait ran out of spins
+  int32_t spin_limit;
+  unsigned long long* tstamp;  // timing build only: 2 x 400 clock stamps
+};
+size_t forward_fused_act_bytes(int d, int HqD, int F);   // per layer
+size_t forward_fused_lds();
+int forward_fused_init();
+int forward_fused_occupancy();
+void launch_fused_set_layer(hipStream_t st, FusedLayer* dst, const FusedLayer& v);
+void launch_forward_fused(hipStream_t st, const FusedArgs& a, int G);
 
 // attention.hip
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,

@@ -169,6 +169,7 @@ class GpuRun:
 
     def fetch(self) -> Dict[str, np.ndarray]:
         torch.cuda.synchronize(self.dev)
+        self.eng.s2d2_status()   # raises if a device-side barrier of the fused forward timed out
         out = {}
         for src in (self.d.t, self.v.t, self.a.t):
             for k, t in src.items():

@@ -258,3 +258,20 @@ def test_vocab_and_accept_kernels_on_synthetic_logit_pairs_at_full_vocabulary():
                 assert g["resampled"][n] == -1 and g["n_commit"][n] == L
     print("accepted-run histogram:", np.bincount(hist, minlength=9).tolist(), "agreeing rows:", int(agree.sum()), "of", N * B)
     assert max(hist) >= 2 and min(hist) == 0   # both long accepted runs and immediate rejections occurred
+
+
+def test_fused_single_launch_forward_matches_the_oracle_and_the_multi_kernel_path(monkeypatch):
+    """The opt-in persistent forward (one launch per forward, device-wide barriers between phases) on a window
+    of at most 16 rows: same parity protocol, several consecutive steps, and no barrier time-out reported."""
+    monkeypatch.setenv("S2D2_FUSED", "1")
+    cfg = I.ModelCfg("small-bf16-4l", 4, 512, 8, 4, 128, 1536, 32000)
+    case = H.make_case(cfg, 1, 4, [150], seed=21, synthetic_kv=False, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 4)
+    run.eng.s2d2_status()
+    print("fused forward:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL
+    prof_run = H.GpuRun(case)
+    prof_run.eng.s2d2_profile_start(64)
+    prof_run.eng.s2d2_draft(prof_run.kv, prof_run.st, 1, 4, Params(), prof_run.d)
+    prof = prof_run.eng.s2d2_profile_stop()
+    assert prof["forward"]["launches"] == 1   # the forward really was one launch
