@@ -282,7 +282,8 @@ int32_t s2d2_vocab_score(s2d2_ctx* ctx, const float* logits_ver, int32_t rows,
  * forward is bracketed by HIP events on the context's stream and attributed to a class.
  * s2d2_profile_stop synchronises the stream, sums the event times and turns profiling off.
  *   launches    kernel launches of the class
- *   ms          summed event-to-event time
+ *   ms          summed event-to-event time, each launch's reading reduced by what an empty event pair reads on
+ *               this stream (median of 33 pairs taken by s2d2_profile_start), so that it is the kernel's own time
  *   bytes       algorithmic HBM bytes of those launches: weight matrix once for a GEMM, K and V
  *               of the cached prefix once for attention, the fp32 logit rows once for the
  *               vocabulary kernels (window rows and tiny outputs are not counted)

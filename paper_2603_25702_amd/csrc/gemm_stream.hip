@@ -14,6 +14,9 @@
 #include "s2d2_internal.h"
 #include "../../include/s2d2.h"
 
+#include <stdlib.h>
+#include <string.h>
+
 namespace s2d2 {
 
 // ---------------------------------------------------------------------------------------------
@@ -281,22 +284,51 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
     return;
   }
   const bool sp = a.x_lo != 0;
+  // launch shape variant per kind, digits of S2D2_GEMM_CFG in the order qkv, add (long K), swiglu, store (tuning aid)
+  static int variant[4] = {-1, -1, -1, -1};
+  if (variant[0] < 0) {
+    const char* e = getenv("S2D2_GEMM_CFG");
+    for (int i = 0; i < 4; ++i) variant[i] = (e && strlen(e) == 4 && e[i] >= '0' && e[i] <= '9') ? e[i] - '0' : 0;
+  }
+#define S2D2_CFG(EPI, PRO, NW, TPW, U)                                         \
+  do {                                                                         \
+    if (sp) launch_cfg<EPI, PRO, NW, TPW, U, true>(st, a, m_cap);              \
+    else launch_cfg<EPI, PRO, NW, TPW, U, false>(st, a, m_cap);                \
+  } while (0)
   switch (kind) {
     case SEPI_QKV_ROPE:
-      if (a.NT >= 1024) { if (sp) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4, true>(st, a, m_cap); else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4, false>(st, a, m_cap); }
-      else { if (sp) launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8, true>(st, a, m_cap); else launch_cfg<SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8, false>(st, a, m_cap); }
+      if (a.NT >= 1024) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4);
+      else if (variant[0] == 1) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8);
+      else if (variant[0] == 2) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 16, 1, 4);
+      else if (variant[0] == 3) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 2, 1, 8);
+      else S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 8);
       break;
     case SEPI_ADD_F32:
-      if (a.KT >= 128) { if (sp) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 6, true>(st, a, m_cap); else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 12, false>(st, a, m_cap); }
-      else { if (sp) launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4, true>(st, a, m_cap); else launch_cfg<SEPI_ADD_F32, SPRO_BF16, 16, 1, 4, false>(st, a, m_cap); }
+      if (a.KT >= 128) {
+        if (variant[1] == 1) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
+        else if (variant[1] == 2) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 6);
+        else if (variant[1] == 4) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 4, 1, 8);
+        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
+      } else {
+        if (variant[1] == 3) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
+        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
+      }
       break;
     case SEPI_SWIGLU:
-      if (sp) launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8, true>(st, a, m_cap); else launch_cfg<SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8, false>(st, a, m_cap);
+      if (variant[2] == 1) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8);
+      else if (variant[2] == 2) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 8);
+      else if (variant[2] == 3) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 4);
+      else if (variant[2] == 4) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 4);
+      else S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 8);
       break;
     case SEPI_STORE_F32:
-      if (sp) launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8, true>(st, a, m_cap); else launch_cfg<SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8, false>(st, a, m_cap);
+      if (variant[3] == 1) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8);
+      else if (variant[3] == 2) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 2, 2, 4);
+      else if (variant[3] == 3) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 1, 8);
+      else S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 4);
       break;
   }
+#undef S2D2_CFG
 }
 
 // First norm of the forward: xg = bf16(h * gain), one partial sum of squares per row.
