@@ -34,6 +34,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; result is labelled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every call of a step from the host instead of replaying a HIP graph of one step")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="counter calibration: first run a plain elementwise copy kernel over this many MiB "
@@ -87,14 +88,27 @@ def main():
 
     run(Wm)
     torch.cuda.synchronize()
-    ses.reset_blocks(lens)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(K)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    committed = int(com_buf[:K].sum().item())
-    accepted = int(acc_buf[:K].sum().item())
+    if args.no_graph:
+        ses.reset_blocks(lens)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(K)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        committed = int(com_buf[:K].sum().item())
+        accepted = int(acc_buf[:K].sum().item())
+    else:
+        # one step = one HIP graph (every kernel of draft, verify, accept, append, advance); K replays are timed
+        graph = ses.capture_step(prm)
+        ses.reset_blocks(lens)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        committed = int(ses.tot_commit.sum().item())
+        accepted = int(ses.tot_accept.sum().item())
     assert int(ses.kv.status.abs().sum().item()) == 0, "a sequence ran out of cache pages"
     value = committed / elapsed
     log(f"[bench] {K} steps in {elapsed * 1e3:.2f} ms: {committed} tokens committed ({accepted} accepted drafts)")
@@ -162,6 +176,7 @@ def main():
         "metric": "accepted tokens/s per draft+verify step", "value": round(value, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(elapsed * 1e3 / K, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
         "config": {"workload": f"config {args.config}: {cfg.name} {cfg.n_layers}L d{cfg.d_model} V{cfg.vocab}, batch {N}, "
                                f"prefix {int(lens.min())}-{int(lens.max())}, block {B}, tau {prm.tau}, {K} consecutive steps",
                    "tokens_committed": committed, "drafts_accepted": accepted},

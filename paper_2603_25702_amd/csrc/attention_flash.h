@@ -5,6 +5,15 @@
 
 namespace s2d2 {
 
+#ifdef S2D2_FUSED_TIMING
+__device__ unsigned long long g_attn_ts[64];
+#define S2D2_ATS(k) do { if (threadIdx.x == 0 && z == 0 && item_zy == 0) g_attn_ts[k] = wall_clock64(); } while (0)
+#define S2D2_ATS_ANY(k) do { if (threadIdx.x == 0 && item_zy == 0) g_attn_ts[k] = wall_clock64(); } while (0)
+#else
+#define S2D2_ATS(k) do {} while (0)
+#define S2D2_ATS_ANY(k) do {} while (0)
+#endif
+
 // ---------------------------------------------------------------------------------------------
 // attn_flash_kernel (bf16, head_dim 128): split-key flash attention on 32x32x16 MFMA.
 //
@@ -93,13 +102,13 @@ __device__ __forceinline__ void fa_combine(const float* part_o, const float* par
     uint4 pq[ITEMS][ZMAX];
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int e = tid + it * NTHREADS, c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+      const int e = tid + it * NTHREADS, c = e & 31;   // element e: lane e % 64 = 32 h + c, group e / 64 = dt*4 + i4
 #pragma unroll
       for (int k = 0; k < ZMAX; ++k) {
         const int z = min(z0 + k, Z - 1);   // clamped duplicates are skipped below
         m[it][k] = ld4f_coh(&part_ml[(item0 + z) * 64 + c]);
         lz[it][k] = ld4f_coh(&part_ml[(item0 + z) * 64 + 32 + c]);
-        pq[it][k] = ld16_coh(part_o + ((item0 + z) * 32 + c) * D + d0);
+        pq[it][k] = ld16_coh(part_o + (item0 + z) * 32 * D + (size_t)e * 4);
       }
     }
 #pragma unroll
@@ -121,7 +130,8 @@ __device__ __forceinline__ void fa_combine(const float* part_o, const float* par
   }
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
-    const int e = tid + it * NTHREADS, c = e / (D / 4), d0 = (e % (D / 4)) * 4;
+    const int e = tid + it * NTHREADS, c = e & 31, g16 = e >> 6;
+    const int d0 = (g16 >> 2) * 32 + 8 * (g16 & 3) + 4 * ((e >> 5) & 1);
     const int qi = qt * 32 + c;
     if (qi >= nq) continue;
     const float inv = l[it] > 0.f ? 1.0f / l[it] : 0.f;
@@ -142,6 +152,7 @@ __device__ __forceinline__ void attn_flash_body(
     int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
     float* __restrict__ part_ml, int32_t* __restrict__ counters, int z, int qt, int item_zy, int q_tiles, float* smem) {
   constexpr int D = FA_D;
+  S2D2_ATS(0);
   const int Hkv = g.n_kv_heads, ps = g.page_size;
   const int n = item_zy / Hkv, kvh = item_zy % Hkv;
   const int grp = Hq / Hkv;
@@ -176,6 +187,8 @@ __device__ __forceinline__ void attn_flash_body(
       if (SPLIT) ql[ds] = COH ? ld16_coh(qp + q_lo + ds * 16) : *(const uint4*)(qp + q_lo + ds * 16);
     }
   }
+  if (qf[0].x == 0x12345678u && S < 0) return;   // (timing aid: forces the header and q loads to complete)
+  S2D2_ATS(1);
   FaState st;
   st.m = -INFINITY;
   st.l = 0.f;
@@ -287,79 +300,99 @@ __device__ __forceinline__ void attn_flash_body(
       }
     }
   }
-  // ---- merge the wavefronts of the workgroup: fixed tree, through LDS ----
-  // slot layout: [slot][66][64]: 64 accumulator registers + m + l per lane
-  for (int s = NW / 2; s >= 1; s >>= 1) {
-    if (wave >= s && wave < 2 * s) {
-      float* dst = smem + (size_t)(wave - s) * 66 * 64 + lane;
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dst[(t * 16 + i) * 64] = st.o[t][i];
-      dst[64 * 64] = st.m;
-      dst[65 * 64] = st.l;
-    }
-    __syncthreads();
-    if (wave < s) {
-      const float* src = smem + (size_t)wave * 66 * 64 + lane;
-      f32x16_t o2[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o2[t][i] = src[(t * 16 + i) * 64];
-      fa_merge(st, src[64 * 64], src[65 * 64], o2);
-    }
-    __syncthreads();
-  }
-  // st.o[dt][i]: d = dt*32 + 8 (i/4) + 4 h + (i%4), query row c
-  const bool q_ok = (q0 + c) < nq;
-  if (Z == 1) {
-    if (wave != 0 || !q_ok) return;
-    const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
-    bf16_t* op = o + (size_t)r * o_ld + head * D;
+  if (st.l == 12345.678f) return;
+  S2D2_ATS(2);
+  // ---- merge the wavefronts of the workgroup through LDS, in wavefront order, with all threads ----
+  // Every wavefront deposits its state; thread (w, c) of the first NW*32 threads turns the running maxima
+  // into per-(wavefront, query row) scale factors; then every thread merges 8 output elements over the NW
+  // states.  Element index idx = (dt*4 + i4)*64 + lane holds the 4 consecutive head-dim positions
+  // d0 = dt*32 + 8*i4 + 4*h of query row c (lane = 32*h + c): the same order as the MFMA accumulators.
+  float* s_o = smem;                              // [NW][16][64] float4
+  float* s_m = smem + (size_t)NW * 4096;          // [NW][32]
+  float* s_l = s_m + NW * 32;                     // [NW][32]
+  float* s_f = s_l + NW * 32;                     // [NW][32] scale of wavefront w for row c
+  float* s_ML = s_f + NW * 32;                    // [2][32]  merged max and sum
+  {
+    float4* dst = (float4*)(s_o + (size_t)wave * 4096) + lane;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int d0 = dt * 32 + 8 * i4 + 4 * h;
-        fa_store4<COH>(op + d0, o_lo, st.o[dt][4 * i4] * inv, st.o[dt][4 * i4 + 1] * inv, st.o[dt][4 * i4 + 2] * inv,
-                  st.o[dt][4 * i4 + 3] * inv);
-      }
-    return;
-  }
-  // Z > 1: write this split's partial; the workgroup that arrives last merges all splits in split
-  // order (so the result does not depend on which one it is) and re-arms the counter.
-  const int group = item_zy * q_tiles + qt;
-  const size_t item0 = (size_t)group * Z;
-  if (wave == 0) {
-    const size_t item = item0 + z;
-    float* po = part_o + item * 32 * D + (size_t)c * D;
-    if (h == 0) {
-      st4f_coh(&part_ml[item * 64 + c], st.m);
-      st4f_coh(&part_ml[item * 64 + 32 + c], st.l);
-    }
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int d0 = dt * 32 + 8 * i4 + 4 * h;
-        st16f_coh(po + d0, st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
-      }
-    __builtin_amdgcn_s_waitcnt(0);  // the write-through stores of the partial have completed before the arrival is counted
+      for (int i4 = 0; i4 < 4; ++i4)
+        dst[(dt * 4 + i4) * 64] = make_float4(st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
+    if (h == 0) { s_m[wave * 32 + c] = st.m; s_l[wave * 32 + c] = st.l; }
   }
   __syncthreads();
-  int* s_last = (int*)smem;
+  if (threadIdx.x < NW * 32) {
+    const int w = threadIdx.x >> 5, cc = threadIdx.x & 31;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < NW; ++w2) M = fmaxf(M, s_m[w2 * 32 + cc]);
+    const float mw = s_m[w * 32 + cc];
+    s_f[w * 32 + cc] = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+    if (w == 0) {
+      float L = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < NW; ++w2) {   // wavefront order
+        const float m2 = s_m[w2 * 32 + cc];
+        L += m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - M) * s_l[w2 * 32 + cc];
+      }
+      s_ML[cc] = M;
+      s_ML[32 + cc] = L;
+    }
+  }
+  __syncthreads();
+  S2D2_ATS(3);
+  const int group = item_zy * q_tiles + qt;
+  const size_t item0 = (size_t)group * Z;
+  constexpr int PER = 16 * 64 / (NW * 64);        // output elements (float4) per thread
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int idx = threadIdx.x + k * NW * 64, ln = idx & 63, g16 = idx >> 6, cc = ln & 31, hh = ln >> 5;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int w2 = 0; w2 < NW; ++w2) {
+      const float f = s_f[w2 * 32 + cc];
+      const float4 v = ((const float4*)(s_o + (size_t)w2 * 4096))[g16 * 64 + ln];
+      acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
+    }
+    if (Z == 1) {
+      const int qi2 = q0 + cc;
+      if (qi2 < nq) {
+        const float L = s_ML[32 + cc], inv = L > 0.f ? 1.0f / L : 0.f;
+        const int r2 = row0 + qi2 / grp, head2 = kvh * grp + qi2 % grp;
+        const int d0 = (g16 >> 2) * 32 + 8 * (g16 & 3) + 4 * hh;
+        fa_store4<COH>(o + (size_t)r2 * o_ld + head2 * D + d0, o_lo, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+      }
+    } else {
+      st16f_coh(part_o + (item0 + z) * 32 * D + (size_t)idx * 4, acc.x, acc.y, acc.z, acc.w);
+    }
+  }
+  if (Z == 1) return;
+  // Z > 1: this split's partial is written; the workgroup that arrives last merges all splits in split
+  // order (so the result does not depend on which one it is) and re-arms the counter.
+  if (threadIdx.x < 32) {
+    st4f_coh(&part_ml[(item0 + z) * 64 + threadIdx.x], s_ML[threadIdx.x]);
+    st4f_coh(&part_ml[(item0 + z) * 64 + 32 + threadIdx.x], s_ML[32 + threadIdx.x]);
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // the write-through stores of the partial have completed before the arrival is counted
+  __syncthreads();
+  S2D2_ATS(4);
+  int* s_last = (int*)(s_ML + 64);
   if (threadIdx.x == 0) {
     const int prev = __hip_atomic_fetch_add(&counters[group], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *s_last = prev == Z - 1;
     if (prev == Z - 1) __hip_atomic_store(&counters[group], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
+  S2D2_ATS(5);
   if (!*s_last) return;
+  S2D2_ATS_ANY(6);
   fa_combine<COH, NW * 64>(part_o, part_ml, item0, Z, threadIdx.x, qt, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
+  __builtin_amdgcn_s_waitcnt(0);
+  S2D2_ATS_ANY(7);
 }
 
 
-static constexpr size_t fa_lds(int nw) { return (size_t)(nw / 2) * 66 * 64 * sizeof(float); }
+static constexpr size_t fa_lds(int nw) { return ((size_t)nw * (4096 + 96) + 64 + 4) * sizeof(float); }
 
 }  // namespace s2d2

@@ -232,6 +232,7 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
                             int32_t* counters);
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
+void launch_attn_ts_copy(hipStream_t st, void* out);   // timing build only
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
 
 // vocab.hip

@@ -94,3 +94,23 @@ class Session:
         e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
         e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
         e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
+
+    def capture_step(self, prm: Params):
+        """Records one step (plus the on-device running totals of accepted and committed tokens) into a HIP graph
+        and returns it; `graph.replay()` then enqueues the whole step with one host call.  The RNG step word advances
+        on the device (prm.step_dev), so every replay is a new step of the same session."""
+        assert prm.step_dev is not None, "a captured step needs the device-resident step counter"
+        self.tot_accept = torch.zeros(self.N, dtype=torch.int32, device=self.dev)
+        self.tot_commit = torch.zeros(self.N, dtype=torch.int32, device=self.dev)
+        side = torch.cuda.Stream(self.dev)
+        side.wait_stream(torch.cuda.current_stream(self.dev))
+        graph = torch.cuda.CUDAGraph()
+        self.eng.set_stream(side)
+        try:
+            with torch.cuda.graph(graph, stream=side):
+                self.step(prm)
+                self.tot_accept += self.a.n_accept
+                self.tot_commit += self.a.n_commit
+        finally:
+            self.eng.set_stream(torch.cuda.current_stream(self.dev))
+        return graph

@@ -275,3 +275,38 @@ def test_fused_single_launch_forward_matches_the_oracle_and_the_multi_kernel_pat
     prof_run.eng.s2d2_draft(prof_run.kv, prof_run.st, 1, 4, Params(), prof_run.d)
     prof = prof_run.eng.s2d2_profile_stop()
     assert prof["forward"]["launches"] == 1   # the forward really was one launch
+
+
+def test_captured_step_graph_replays_match_eager_steps():
+    """A HIP graph of one step, replayed with eager work and synchronisations between the replays: every replay
+    must leave exactly the state the same steps leave when enqueued call by call."""
+    from paper_2603_25702_amd.runner import Session
+    cfg = SMALL_BF16
+    W = I.gen_weights(cfg, 3)
+    ids = [I.gen_prefix_ids(cfg, 90, 3, 0), I.gen_prefix_ids(cfg, 41, 3, 1)]
+
+    def session():
+        ses = Session(cfg, W, 2, 4, 512, 16, "cuda:0", max_block=16)
+        ses.prefill(ids)
+        return ses
+
+    eager, states = session(), []
+    prm_e = Params(seed=5, step=0, step_dev=eager.step_dev)
+    for _ in range(4):
+        eager.step(prm_e)
+        torch.cuda.synchronize()
+        states.append((eager.st.block_tokens.clone(), eager.kv.seq_len.clone(), eager.a.n_commit.clone(), eager.d.p.clone()))
+    cap = session()
+    prm_c = Params(seed=5, step=0, step_dev=cap.step_dev)
+    graph = cap.capture_step(prm_c)
+    cap.reset_blocks([90, 41])
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    for k in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        cap.eng.s2d2_status()
+        scratch.add_(1.0).sum().item()       # eager work between replays
+        blk, sl, nc, p = states[k]
+        assert torch.equal(cap.st.block_tokens, blk) and torch.equal(cap.kv.seq_len, sl), f"replay {k}"
+        assert torch.equal(cap.a.n_commit, nc) and torch.equal(cap.d.p, p), f"replay {k}"
+    assert int(cap.tot_commit.sum()) == sum(int(s[2].sum()) for s in states)
