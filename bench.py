@@ -19,6 +19,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the streaming GEMM on this workload, from the FETCH_SIZE / WRITE_SIZE counter runs
+# recorded in profiles/gemm_stream_kernel_config2.md (31.07 MB fetched + 0.13 MB written; 30.45 MB algorithmic)
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 31.2e6
 
 
 def log(*a):
@@ -129,7 +132,8 @@ def main():
         ach = g["bytes"] / (g["ms"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "forward_fused_kernel" if fused else "gemm_stream_kernel",
                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                    "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.config == 2 and not fused and not args.layers) else None,
                     "avg_launch_us": round(g["ms"] * 1e3 / g["launches"], 3),
                     "bytes_per_launch": round(g["bytes"] / g["launches"])}
         tot = sum(c["ms"] for c in prof.values())

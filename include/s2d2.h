@@ -278,12 +278,12 @@ int32_t s2d2_vocab_draft_stats(s2d2_ctx* ctx, const float* logits, int32_t rows,
 int32_t s2d2_vocab_score(s2d2_ctx* ctx, const float* logits_ver, int32_t rows,
                          const int32_t* token, float* q, float* lse);
 
-/* Measurement aid (not part of the method): while profiling is on, every kernel launch of a
- * forward is bracketed by HIP events on the context's stream and attributed to a class.
+/* Measurement aid (not part of the method): while profiling is on, the kernel launches of a step are
+ * timed with HIP events on the context's stream and attributed to a class.
  * s2d2_profile_stop synchronises the stream, sums the event times and turns profiling off.
  *   launches    kernel launches of the class
- *   ms          summed event-to-event time, each launch's reading reduced by what an empty event pair reads on
- *               this stream (median of 33 pairs taken by s2d2_profile_start), so that it is the kernel's own time
+ *   ms          summed kernel durations: the two events of a launch are stamped by the dispatch itself
+ *               (hipExtLaunchKernelGGL), i.e. they read what a kernel trace reads for that launch
  *   bytes       algorithmic HBM bytes of those launches: weight matrix once for a GEMM, K and V
  *               of the cached prefix once for attention, the fp32 logit rows once for the
  *               vocabulary kernels (window rows and tiny outputs are not counted)

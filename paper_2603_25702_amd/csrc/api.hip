@@ -13,6 +13,7 @@
 using namespace s2d2;
 
 static thread_local char g_err[512] = "";
+namespace s2d2 { thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr; }
 
 static int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -78,7 +79,6 @@ struct s2d2_ctx {
   // profiling (measurement aid)
   bool prof_on;
   int32_t prof_cap;
-  double prof_pair_ms;       // event-to-event time of an empty pair, subtracted from every measured launch
   struct ProfRec { int cls; double bytes; hipEvent_t a, b; };
   std::vector<ProfRec>* prof;
   std::vector<hipEvent_t>* prof_pool;
@@ -203,17 +203,17 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   return (cv.off + 255) & ~(size_t)255;
 }
 
+// Arms the event pair of the next kernel launch (S2D2_LAUNCH) and books it under a class.  A scope that holds
+// several launches times the first one.
 struct ProfScope {
-  s2d2_ctx* c;
-  hipEvent_t stop = nullptr;
-  ProfScope(s2d2_ctx* ctx, int cls, double bytes) : c(ctx) {
+  ProfScope(s2d2_ctx* c, int cls, double bytes) {
     if (!c->prof_on || (int32_t)c->prof->size() >= c->prof_cap) return;
     hipEvent_t a = (*c->prof_pool)[2 * c->prof->size()], b = (*c->prof_pool)[2 * c->prof->size() + 1];
-    (void)hipEventRecord(a, c->stream);
     c->prof->push_back({cls, bytes, a, b});
-    stop = b;
+    g_prof_start = a;
+    g_prof_stop = b;
   }
-  ~ProfScope() { if (stop) (void)hipEventRecord(stop, c->stream); }
+  ~ProfScope() { g_prof_start = nullptr; }
 };
 
 size_t packed_total_bytes(const s2d2_model_desc& d) {
@@ -645,7 +645,7 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
   { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
               draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
-  hipLaunchKernelGGL(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
+  S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
                      out->logit_row_of, out->q, out->lse_ver);
   { ProfScope ps(c, 2, 0.0); launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
                      c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver); }
@@ -708,22 +708,6 @@ int32_t s2d2_profile_start(s2d2_ctx* c, int32_t max_launches) {
   }
   c->prof->clear();
   c->prof_cap = max_launches;
-  // what an event pair measures with nothing between its records: median of 33 pairs on this stream
-  {
-    const int n = std::min<int>(33, max_launches);
-    for (int i = 0; i < n; ++i) {
-      (void)hipEventRecord((*c->prof_pool)[2 * i], c->stream);
-      (void)hipEventRecord((*c->prof_pool)[2 * i + 1], c->stream);
-    }
-    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(S2D2_ELAUNCH, "stream synchronize failed");
-    std::vector<float> t;
-    for (int i = 0; i < n; ++i) {
-      float ms = 0.f;
-      if (hipEventElapsedTime(&ms, (*c->prof_pool)[2 * i], (*c->prof_pool)[2 * i + 1]) == hipSuccess) t.push_back(ms);
-    }
-    std::sort(t.begin(), t.end());
-    c->prof_pair_ms = t.empty() ? 0.0 : t[t.size() / 2];
-  }
   c->prof_on = true;
   return S2D2_OK;
 }
@@ -736,9 +720,9 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
   for (int k = 0; k < S2D2_PROFILE_CLASSES; ++k) out[k] = s2d2_profile{0, 0.0, 0.0};
   for (const auto& r : *c->prof) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return fail(S2D2_ELAUNCH, "hipEventElapsedTime failed");
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { (void)hipGetLastError(); continue; }   // scope without a launch
     out[r.cls].launches += 1;
-    out[r.cls].ms += std::max(0.0, (double)ms - c->prof_pair_ms);
+    out[r.cls].ms += ms;
     out[r.cls].bytes += r.bytes;
   }
   return S2D2_OK;
@@ -778,7 +762,7 @@ int32_t s2d2_vocab_draft_stats(s2d2_ctx* c, const float* logits, int32_t rows, i
   if (!logits || !xhat || !p || !lse || !margin || !entropy_n) return fail(S2D2_EINVAL, "NULL argument");
   if ((uintptr_t)logits & 15) return fail(S2D2_EINVAL, "logits must be 16-byte aligned");
   if (rows == 0) return S2D2_OK;
-  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
+  S2D2_LAUNCH(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
   launch_vocab_draft(c->stream, logits, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, xhat, p, lse,
                      margin, entropy_n);
   return check_launch("s2d2_vocab_draft_stats");
@@ -790,7 +774,7 @@ int32_t s2d2_vocab_score(s2d2_ctx* c, const float* logits_ver, int32_t rows, con
   if (!logits_ver || !token || !q || !lse) return fail(S2D2_EINVAL, "NULL argument");
   if ((uintptr_t)logits_ver & 15) return fail(S2D2_EINVAL, "logits must be 16-byte aligned");
   if (rows == 0) return S2D2_OK;
-  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
+  S2D2_LAUNCH(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
   launch_vocab_score(c->stream, logits_ver, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, token, q, lse);
   return check_launch("s2d2_vocab_score");
 }

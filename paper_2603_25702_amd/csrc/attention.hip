@@ -132,12 +132,12 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
   if (q_lo)
-    hipLaunchKernelGGL((attn_flash_kernel<8, true>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+    S2D2_LAUNCH((attn_flash_kernel<8, true>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
                        (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
                        (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
                        (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
   else
-    hipLaunchKernelGGL((attn_flash_kernel<8, false>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+    S2D2_LAUNCH((attn_flash_kernel<8, false>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
                        (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
                        (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
                        (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
@@ -145,7 +145,7 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
 
 #ifdef S2D2_FUSED_TIMING
 __global__ void attn_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_attn_ts[threadIdx.x]; }
-void launch_attn_ts_copy(hipStream_t st, void* out) { hipLaunchKernelGGL(attn_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
+void launch_attn_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(attn_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
 #else
 void launch_attn_ts_copy(hipStream_t, void*) {}
 #endif
@@ -155,7 +155,7 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
   if (i < n) p[i] = v;
 }
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v) {
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
+  S2D2_LAUNCH(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
 }
 
 // Raises the dynamic-LDS limit of the kernels once (160 KB per workgroup on gfx950).
@@ -178,11 +178,11 @@ void launch_attention_generic(hipStream_t st, int dtype, const void* q, const vo
   const float scale = 1.0f / sqrtf((float)g.head_dim);
   dim3 grid(rows_cap, Hq), block(256);
   if (dtype == S2D2_BF16) {
-    hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds_bytes, st, (const bf16_t*)q,
+    S2D2_LAUNCH(attn_generic_kernel<bf16_t>, grid, block, lds_bytes, st, (const bf16_t*)q,
                        (const bf16_t*)k_win, (const bf16_t*)v_win, (const bf16_t*)k_pages_layer,
                        (const bf16_t*)v_pages_layer, g, p, Hq, (bf16_t*)o, scale);
   } else {
-    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds_bytes, st, (const float*)q,
+    S2D2_LAUNCH(attn_generic_kernel<float>, grid, block, lds_bytes, st, (const float*)q,
                        (const float*)k_win, (const float*)v_win, (const float*)k_pages_layer,
                        (const float*)v_pages_layer, g, p, Hq, (float*)o, scale);
   }

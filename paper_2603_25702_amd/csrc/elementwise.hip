@@ -17,9 +17,9 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ embed,
 
 void launch_embed(hipStream_t st, int dtype, const void* embed, int d, const Plan& p, int rows_cap, float* h) {
   if (dtype == S2D2_BF16)
-    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, h);
+    S2D2_LAUNCH(embed_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, h);
   else
-    hipLaunchKernelGGL(embed_kernel<float>, dim3(rows_cap), dim3(256), 0, st, (const float*)embed, d, p, h);
+    S2D2_LAUNCH(embed_kernel<float>, dim3(rows_cap), dim3(256), 0, st, (const float*)embed, d, p, h);
 }
 
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
@@ -52,10 +52,10 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 void launch_rmsnorm(hipStream_t st, int dtype, const float* h, const float* gain, int d, float eps,
                     const int32_t* count, const int32_t* gather, int rows_cap, void* out) {
   if (dtype == S2D2_BF16)
-    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, h, gain, d, eps, count, gather,
+    S2D2_LAUNCH(rmsnorm_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, h, gain, d, eps, count, gather,
                        (bf16_t*)out);
   else
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows_cap), dim3(256), 0, st, h, gain, d, eps, count, gather,
+    S2D2_LAUNCH(rmsnorm_kernel<float>, dim3(rows_cap), dim3(256), 0, st, h, gain, d, eps, count, gather,
                        (float*)out);
 }
 
@@ -104,10 +104,10 @@ __global__ __launch_bounds__(256) void rope_split_kernel(const float* __restrict
 void launch_rope_split(hipStream_t st, int dtype, const float* qkv, const Plan& p, int rows_cap, int Hq,
                        int Hkv, int D, float theta, void* q_out, void* k_out, void* v_out, void* vT_out, int wpad) {
   if (dtype == S2D2_BF16)
-    hipLaunchKernelGGL(rope_split_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
+    S2D2_LAUNCH(rope_split_kernel<bf16_t>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
                        (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out, (bf16_t*)vT_out, wpad);
   else
-    hipLaunchKernelGGL(rope_split_kernel<float>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
+    S2D2_LAUNCH(rope_split_kernel<float>, dim3(rows_cap), dim3(256), 0, st, qkv, p, Hq, Hkv, D, theta,
                        (float*)q_out, (float*)k_out, (float*)v_out, (float*)vT_out, wpad);
 }
 

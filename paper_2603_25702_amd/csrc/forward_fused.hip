@@ -450,7 +450,7 @@ size_t forward_fused_lds() {
 __global__ void fused_set_layer_kernel(FusedLayer* dst, FusedLayer v) { *dst = v; }
 
 void launch_fused_set_layer(hipStream_t st, FusedLayer* dst, const FusedLayer& v) {
-  hipLaunchKernelGGL(fused_set_layer_kernel, dim3(1), dim3(1), 0, st, dst, v);
+  S2D2_LAUNCH(fused_set_layer_kernel, dim3(1), dim3(1), 0, st, dst, v);
 }
 
 int forward_fused_init() {
@@ -469,7 +469,7 @@ int forward_fused_occupancy() {
 }
 
 void launch_forward_fused(hipStream_t st, const FusedArgs& a, int G) {
-  hipLaunchKernelGGL(forward_fused_kernel, dim3(G), dim3(FW * 64), forward_fused_lds(), st, a);
+  S2D2_LAUNCH(forward_fused_kernel, dim3(G), dim3(FW * 64), forward_fused_lds(), st, a);
 }
 
 }  // namespace s2d2

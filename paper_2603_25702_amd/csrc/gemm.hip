@@ -103,13 +103,13 @@ static void launch_t(hipStream_t st, GemmEpilogue epi, const T* X, int ldx, cons
   dim3 grid((N + 15) / 16, (m_cap + 15) / 16), block(256);
   switch (epi) {
     case EPI_STORE_F32:
-      hipLaunchKernelGGL((gemm_rows16_kernel<T, EPI_STORE_F32>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
+      S2D2_LAUNCH((gemm_rows16_kernel<T, EPI_STORE_F32>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
       break;
     case EPI_ADD_F32:
-      hipLaunchKernelGGL((gemm_rows16_kernel<T, EPI_ADD_F32>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
+      S2D2_LAUNCH((gemm_rows16_kernel<T, EPI_ADD_F32>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_rows16_kernel<T, EPI_SWIGLU>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
+      S2D2_LAUNCH((gemm_rows16_kernel<T, EPI_SWIGLU>), grid, block, 0, st, X, ldx, W, K, N, m_count, out, ldo);
       break;
   }
 }

@@ -48,7 +48,7 @@ size_t packed_weight_bytes(int N, int K) { return (size_t)((N + 15) / 16) * (K /
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out) {
   const int NT = (N + 15) / 16, KT = K / 32;
   const size_t total = (size_t)NT * KT * 64;
-  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)W, N,
+  S2D2_LAUNCH(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)W, N,
                      K, NT, KT, rope_pairs, D, (uint4*)out);
 }
 
@@ -66,7 +66,7 @@ __global__ void rope_table_kernel(Plan p, int half, int D, float theta, float2* 
 }
 
 void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs) {
-  hipLaunchKernelGGL(rope_table_kernel, dim3(rows_cap), dim3(64), 0, st, p, D / 2, D, theta, (float2*)cs);
+  S2D2_LAUNCH(rope_table_kernel, dim3(rows_cap), dim3(64), 0, st, p, D / 2, D, theta, (float2*)cs);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -272,7 +272,7 @@ static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   constexpr int TA = TPW * (EPI == SEPI_SWIGLU ? 2 : 1);
   const size_t lds = 16 * sizeof(float) + (size_t)NW * TA * 256 * sizeof(float);
   dim3 grid((a.NT + TPW - 1) / TPW, (m_cap + 15) / 16), block(NW * 64);
-  hipLaunchKernelGGL((gemm_stream_kernel<EPI, PRO, NW, TPW, U, SPLIT>), grid, block, lds, st, a);
+  S2D2_LAUNCH((gemm_stream_kernel<EPI, PRO, NW, TPW, U, SPLIT>), grid, block, lds, st, a);
 }
 
 // Launch shapes: the layer matrices want >= 256 workgroups / >= 2000 wavefronts with the whole
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restric
 
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
                        float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride) {
-  hipLaunchKernelGGL(embed_norm_kernel, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, gain, h,
+  S2D2_LAUNCH(embed_norm_kernel, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, gain, h,
                      (bf16_t*)xg, xg_ld, xg_lo, ss, ss_stride);
 }
 

@@ -268,8 +268,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
 template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
   dim3 grid((a.NT + TN / 16 - 1) / (TN / 16), row_tiles), block(256);
-  if (a.x_lo) hipLaunchKernelGGL((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((gemm_tile_kernel<EPI, PRO, false>), grid, block, 0, st, a);
+  if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);
+  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, false>), grid, block, 0, st, a);
 }
 
 // row_tiles: upper bound of 128-row tiles (ungrouped: ceil(m_cap / 128); grouped: capacity of the tile list)

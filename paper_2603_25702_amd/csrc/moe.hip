@@ -143,27 +143,27 @@ __global__ void moe_copy_choices_kernel(const int32_t* __restrict__ src, int32_t
 
 void launch_moe_route(hipStream_t st, const float* logits, int E, int top_k, const int32_t* m_count, int rows_cap,
                       int32_t* choice, float* route_w, int32_t* slot_pos, int32_t* cnt) {
-  hipLaunchKernelGGL(moe_route_kernel, dim3((rows_cap + 3) / 4), dim3(256), 0, st, logits, E, top_k, m_count, choice,
+  S2D2_LAUNCH(moe_route_kernel, dim3((rows_cap + 3) / 4), dim3(256), 0, st, logits, E, top_k, m_count, choice,
                      route_w, slot_pos, cnt);
 }
 
 void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, const int32_t* choice,
                       const int32_t* slot_pos, int32_t* cnt, int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0,
                       int32_t* tile_rows, int32_t* n_tiles, int tile_cap) {
-  hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(1024), 0, st, E, top_k, m_count, choice, slot_pos, cnt, sorted,
+  S2D2_LAUNCH(moe_group_kernel, dim3(1), dim3(1024), 0, st, E, top_k, m_count, choice, slot_pos, cnt, sorted,
                      tile_expert, tile_row0, tile_rows, n_tiles, tile_cap);
 }
 
 void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const int32_t* m_count, int rows_cap,
                         float* h, void* xg, int xg_ld, int xg_lo, const float* gain_next, float* ss, int ss_stride) {
-  hipLaunchKernelGGL(moe_combine_kernel, dim3(rows_cap), dim3(256), 0, st, y, d, top_k, m_count, h, (bf16_t*)xg,
+  S2D2_LAUNCH(moe_combine_kernel, dim3(rows_cap), dim3(256), 0, st, y, d, top_k, m_count, h, (bf16_t*)xg,
                      xg_ld, xg_lo, gain_next, ss, ss_stride);
 }
 
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
                              int per_layer_dst) {
   const int n = layers * per_layer_dst;
-  hipLaunchKernelGGL(moe_copy_choices_kernel, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, layers, per_layer_src,
+  S2D2_LAUNCH(moe_copy_choices_kernel, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, layers, per_layer_src,
                      per_layer_dst);
 }
 

@@ -125,7 +125,7 @@ void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, verify ? 1 : 0, N, B, mask_id, ar_mask,
+  S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify ? 1 : 0, N, B, mask_id, ar_mask,
                      seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
                      stage_row0, stage_lead);
 }
@@ -191,10 +191,10 @@ void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_c
                       const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B) {
   const int elt = dtype == S2D2_BF16 ? 2 : 4;
   const int per_seq = 2 * B;  // upper bound of staged causal rows per sequence (carry + block)
-  hipLaunchKernelGGL(kv_append_copy_kernel, dim3(N * per_seq, n_layers), dim3(256), 0, st, elt, per_seq,
+  S2D2_LAUNCH(kv_append_copy_kernel, dim3(N * per_seq, n_layers), dim3(256), 0, st, elt, per_seq,
                      rows_cap, g, (uint8_t*)k_pages, (uint8_t*)v_pages, (const uint8_t*)k_stage,
                      (const uint8_t*)v_stage, stage_row0, stage_lead, n_accept, span_len);
-  hipLaunchKernelGGL(kv_append_commit_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, g, stage_lead,
+  S2D2_LAUNCH(kv_append_commit_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, g, stage_lead,
                      n_accept, span_len, seq_len, status);
 }
 
@@ -223,7 +223,7 @@ __global__ void block_advance_kernel(int N, int B, int mask_id, const int32_t* _
 
 void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
                           int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev) {
-  hipLaunchKernelGGL(block_advance_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, B, mask_id, seq_len,
+  S2D2_LAUNCH(block_advance_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, B, mask_id, seq_len,
                      pos0, block, carry, step_dev);
 }
 
@@ -237,7 +237,7 @@ __global__ void commit_threshold_kernel(int N, int B, int32_t* __restrict__ bloc
 
 void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const int32_t* xhat,
                              const uint64_t* unmask) {
-  hipLaunchKernelGGL(commit_threshold_kernel, dim3((N * B + 255) / 256), dim3(256), 0, st, N, B, block, xhat,
+  S2D2_LAUNCH(commit_threshold_kernel, dim3((N * B + 255) / 256), dim3(256), 0, st, N, B, block, xhat,
                      unmask);
 }
 

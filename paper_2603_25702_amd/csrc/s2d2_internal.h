@@ -1,10 +1,25 @@
 // Internal declarations shared by the HIP translation units of libs2d2.  Not part of the ABI.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
 namespace s2d2 {
+
+// Measurement aid: when the profiling scope has armed an event pair, the next kernel launch is made with
+// hipExtLaunchKernelGGL, which stamps the two events with the dispatch's own start and end times (what a
+// kernel trace reports); otherwise an ordinary launch.
+extern thread_local hipEvent_t g_prof_start, g_prof_stop;
+#define S2D2_LAUNCH(kernel, grid, block, lds, st, ...)                                                          \
+  do {                                                                                                         \
+    if (s2d2::g_prof_start) {                                                                                  \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, st, s2d2::g_prof_start, s2d2::g_prof_stop, 0, __VA_ARGS__); \
+      s2d2::g_prof_start = nullptr;                                                                            \
+    } else {                                                                                                   \
+      hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                                           \
+    }                                                                                                          \
+  } while (0)
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 

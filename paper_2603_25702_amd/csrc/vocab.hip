@@ -148,18 +148,18 @@ __global__ void vocab_score_final_kernel(const float* __restrict__ part, int chu
 void launch_vocab_draft(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
                         int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n) {
-  hipLaunchKernelGGL(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
+  S2D2_LAUNCH(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
                      ws.chunks, ws.part);
-  hipLaunchKernelGGL(vocab_draft_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
+  S2D2_LAUNCH(vocab_draft_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
                      count, logit_seq, logit_idx, B, xhat, p, lse, margin, entropy_n);
 }
 
 void launch_vocab_score(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
                         const int32_t* token, float* q, float* lse) {
-  hipLaunchKernelGGL(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
+  S2D2_LAUNCH(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
                      ws.chunks, ws.part);
-  hipLaunchKernelGGL(vocab_score_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
+  S2D2_LAUNCH(vocab_score_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
                      logits, count, logit_seq, logit_idx, B, token, q, lse);
 }
 
@@ -191,7 +191,7 @@ __global__ void draft_finish_kernel(int N, int B, int mask_id, float tau, const 
 void launch_draft_finish(hipStream_t st, int N, int B, int mask_id, float tau, const int32_t* block,
                          int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n,
                          uint64_t* unmask, int32_t* n_hi) {
-  hipLaunchKernelGGL(draft_finish_kernel, dim3((N + 63) / 64), dim3(64), 0, st, N, B, mask_id, tau, block, xhat, p,
+  S2D2_LAUNCH(draft_finish_kernel, dim3((N + 63) / 64), dim3(64), 0, st, N, B, mask_id, tau, block, xhat, p,
                      lse, margin, entropy_n, unmask, n_hi);
 }
 
@@ -386,7 +386,7 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
                    int32_t* resampled, float* u_used) {
-  hipLaunchKernelGGL(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample,
+  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample,
                      span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
                      n_accept, n_commit, resampled, u_used);
 }
