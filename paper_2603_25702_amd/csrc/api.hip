@@ -72,6 +72,8 @@ struct s2d2_ctx {
   uint32_t* fused_bar;       // 9 x 64 words
   int32_t* fused_err;
   uint64_t* moe_y_or_scratch; // clock stamps of the timing build
+  float* tile_partials;      // split-K partials of the tiled GEMM, TILE_PARTIAL_CAP x 64 KB
+  int32_t* tile_counters;    // TILE_COUNTER_CAP arrival counters, zero between launches
   uint8_t* fused_act;        // per-layer exchange buffers of the fused forward
   size_t fused_act_stride;
   int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
@@ -85,6 +87,8 @@ struct s2d2_ctx {
 };
 
 namespace {
+
+constexpr int TILE_PARTIAL_CAP = 1280, TILE_COUNTER_CAP = 4096;
 
 struct Carver {
   uint8_t* base;
@@ -191,6 +195,10 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     c->moe_act = cv.take<uint8_t>(RK * (size_t)d.d_expert * es * P);
     c->moe_y = cv.take<float>(RK * (size_t)d.d_model);
   }
+  if (d.dtype == S2D2_BF16) {
+    c->tile_partials = cv.take<float>((size_t)TILE_PARTIAL_CAP * 16384);
+    c->tile_counters = cv.take<int32_t>(TILE_COUNTER_CAP);
+  }
   c->fused_layers = cv.take<FusedLayer>(d.n_layers);
   c->fused_bar = cv.take<uint32_t>(9 * 64);
   c->fused_err = cv.take<int32_t>(64);
@@ -282,6 +290,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int32_t* n_rows = c->plan.counts;
   const bool fused = c->pk != nullptr;
   const int ss_stride = (d.d_model + 15) / 16;
+  auto sk = [&](GemmStreamArgs& x) {   // split-K buffers of the tiled GEMM
+    x.tile_partials = c->tile_partials; x.tile_counters = c->tile_counters;
+    x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
+  };
   // GEMM inputs as P bf16 planes per row: [hi | lo]; lo offsets are 0 with a single plane
   const int P = fused && flash ? act_planes(d) : 1;  // the generic attention kernel writes one plane
   const int ld_a = P * d.d_model, lo_a = P == 2 ? d.d_model : 0;
@@ -316,7 +328,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.gather = c->plan.logit_src;
     a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
     a.out = logits; a.ldo = d.vocab;
-    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm_stream(st, SEPI_STORE_F32, a, LR); }
+    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); sk(a); launch_gemm_stream(st, SEPI_STORE_F32, a, LR); }
     return check_launch("forward (fused)");
   }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride); }
@@ -335,7 +347,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_o; a.q_lo = lo_o; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
       ProfScope ps(c, 0, (double)qkv_n * d.d_model * es);
-      launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
+      sk(a); launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
     } else {
       { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
       { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
@@ -356,7 +368,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.Wp = c->pk[l].wo; a.NT = d.d_model / 16; a.KT = HqD / 32; a.N = d.d_model; a.K = HqD;
       a.X = (const bf16_t*)c->obuf; a.ldx = ld_o; a.x_lo = lo_o; a.out = c->h; a.ldo = d.d_model;
       a.xg_out = (bf16_t*)c->a; a.xg_ld = ld_a; a.xg_lo = lo_a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
-      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
+      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); sk(a); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
       const float* gain_after = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f;
       if (d.n_experts == 0) {
         GemmStreamArgs b{};
@@ -364,13 +376,13 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
         b.X = (const bf16_t*)c->a; b.ldx = ld_a; b.x_lo = lo_a; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
         b.eps = d.rms_eps; b.out = c->ffn; b.ldo = ld_f; b.out_lo = lo_f;
-        { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
+        { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); sk(b); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
         GemmStreamArgs e{};
         e.m_count = n_rows;
         e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
         e.X = (const bf16_t*)c->ffn; e.ldx = ld_f; e.x_lo = lo_f; e.out = c->h; e.ldo = d.d_model;
         e.xg_out = (bf16_t*)c->a; e.xg_ld = ld_a; e.xg_lo = lo_a; e.gain_next = gain_after; e.ss_out = c->ss; e.ss_stride = ss_stride;
-        { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
+        { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); sk(e); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
       } else {
         // MoE FFN: router -> top-k -> group by expert -> grouped gate/up + SwiGLU -> grouped down -> combine
         const int E = d.n_experts, Fe = d.d_expert, tk = d.top_k;
@@ -380,7 +392,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         r.Wp = c->pk[l].router; r.NT = (E + 15) / 16; r.KT = d.d_model / 32; r.N = E; r.K = d.d_model;
         r.X = (const bf16_t*)c->a; r.ldx = ld_a; r.x_lo = lo_a; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
         r.eps = d.rms_eps; r.out = c->router_logits; r.ldo = E;
-        { ProfScope ps(c, 0, (double)E * d.d_model * es); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
+        { ProfScope ps(c, 0, (double)E * d.d_model * es); sk(r); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
         { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w, c->moe_pos, c->moe_cnt); }
         { ProfScope ps(c, 3, 0.0); launch_moe_group(st, E, tk, n_rows, choice, c->moe_pos, c->moe_cnt, c->moe_sorted, c->moe_tile_expert,
                                                      c->moe_tile_row0, c->moe_tile_rows, c->moe_n_tiles, c->moe_tile_cap); }
@@ -417,7 +429,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
     a.out = logits; a.ldo = d.vocab;
     ProfScope ps(c, 0, (double)d.vocab * d.d_model * es);
-    launch_gemm_stream(st, SEPI_STORE_F32, a, LR);
+    sk(a); launch_gemm_stream(st, SEPI_STORE_F32, a, LR);
   } else {
     { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af); }
     { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
@@ -571,6 +583,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     }
   }
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
+  if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
@@ -741,6 +754,7 @@ int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
   if (!c || !name || !ptr) return fail(S2D2_EINVAL, "NULL argument");
   const struct { const char* n; void* p; } tab[] = {{"h", c->h}, {"a", c->a}, {"q", c->qbuf}, {"o", c->obuf}, {"ffn", c->ffn},
                                                     {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->moe_y_or_scratch}};
+  if (!strcmp(name, "tile_ts")) { launch_tile_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
   if (!strcmp(name, "attn_ts")) { launch_attn_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
   for (const auto& t : tab)
     if (!strcmp(t.n, name)) { *ptr = t.p; return S2D2_OK; }

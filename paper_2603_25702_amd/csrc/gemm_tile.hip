@@ -7,8 +7,15 @@
 // steps of 64.  The activation tile goes through LDS (double-buffered, rows padded to 144 bytes so
 // that the 16-byte operand reads of a wavefront hit 64 distinct banks); the weight operands are
 // read straight from the packed copy, where one wavefront-wide 16-byte load is a complete A
-// operand of v_mfma_f32_16x16x32_bf16, one step ahead of their use.  Each wavefront computes
-// 64 rows x 64 features (4 x 4 MFMA tiles, 8 x 4 for the gate/up pair of SwiGLU).
+// operand of v_mfma_f32_16x16x32_bf16, through a ring of register stages that keeps them up to three
+// K steps (HBM latency is several steps of MFMA work) ahead of their use.  Each wavefront computes
+// 64 rows x 64 features (4 x 4 MFMA tiles); for the gate/up pair of SwiGLU 64 rows x 32 features of
+// each matrix, so a workgroup tile is 128 x 64 there.
+//
+// K can be split over blockIdx.z when the tiles alone would leave compute units idle (few rows, narrow
+// outputs): every split writes its accumulators as an fp32 partial in register order (write-through
+// stores), the workgroup that arrives last at the tile's counter adds all partials in split order and
+// runs the epilogue, so the result does not depend on which workgroup that is.
 //
 // The prologue / epilogues are the ones of the streaming kernel (same argument block): 1/rms from
 // the producer's partial sums of squares, fp32 store, residual add with the operand and partial
@@ -18,15 +25,25 @@
 #include "s2d2_internal.h"
 #include "../../include/s2d2.h"
 
+#include <algorithm>
+
 namespace s2d2 {
 
-static constexpr int TM = 128, TN = 128, TK = 64;
+static constexpr int TM = 128, TK = 64;
+#ifdef S2D2_FUSED_TIMING
+__device__ unsigned long long g_tile_ts[64];
+#define S2D2_TTS(k) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && (blockIdx.z == 0 || (k) >= 4)) g_tile_ts[(k)] = wall_clock64(); } while (0)
+#else
+#define S2D2_TTS(k) do {} while (0)
+#endif
 
 // SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
 // of a row sit side by side in LDS and every weight operand is multiplied with both.
 template <int EPI, int PRO, bool SPLIT>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) {
+__global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
+  constexpr int FT = 4 / NACC;                    // feature tiles per wavefront and matrix; FT * NACC = 4 accumulator columns
+  constexpr int WS = 3;                           // weight stages in flight
   constexpr int XROW = (SPLIT ? 256 : 128) + 16;  // bytes per LDS row: 64 bf16 per plane + 16 bytes of padding
   __shared__ __align__(16) uint8_t s_x[2][TM * XROW];
   __shared__ int s_xrow[TM], s_orow[TM];
@@ -35,6 +52,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, f = lane & 15;
   const int wr = wave >> 1, wc = wave & 1;
+  S2D2_TTS(0);
   int m0, Mloc, expert = 0;
   if (a.grouped != GROUP_NONE) {
     if ((int)blockIdx.y >= *a.n_tiles) return;
@@ -48,7 +66,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
     Mloc = min(TM, M - m0);
   }
   const int KT = a.KT;
-  const int nt0 = blockIdx.x * (TN / 16) + wc * 4;
+  const int nt0 = blockIdx.x * (2 * FT) + wc * FT;
 
   // ---- row maps: source row of X, row of the partial sums of squares, destination row, scale ----
   {
@@ -68,9 +86,20 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
     float rs = ow;
     if (PRO == SPRO_BF16S) {
       float v = 0.f;
-      if (r < Mloc) {
+      if (r < Mloc) {   // independent 16-byte loads, all in flight at once per round (not a chain of L2 round trips)
         const float* pp = a.ss_part + (size_t)ssrow * a.ss_stride;
-        for (int i = hf; i < a.ss_count; i += 2) v += pp[i];
+        if ((a.ss_count & 3) == 0 && (a.ss_stride & 3) == 0) {
+          const int n4 = a.ss_count >> 2;
+          for (int i0 = hf; i0 < n4; i0 += 32) {
+            float4 t[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) t[j] = (i0 + 2 * j < n4) ? ((const float4*)pp)[i0 + 2 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v += (t[j].x + t[j].y) + (t[j].z + t[j].w);
+          }
+        } else {
+          for (int i = hf; i < a.ss_count; i += 2) v += pp[i];
+        }
       }
       v += __shfl_xor(v, 1, 64);
       rs *= 1.0f / sqrtf(v / (float)a.K + a.eps);
@@ -79,91 +108,160 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
   }
   __syncthreads();
 
+  S2D2_TTS(1);
   // ---- operand addressing ----
   const int c16 = tid & 7, rbase = tid >> 3;   // this thread stages rows rbase + 32 i, bytes [16 c16, +16) of the 128
+  // Loads in the K loop are unconditional (clamped addresses, values of invalid rows / columns replaced when
+  // they are stored to LDS): a load under a branch would make the compiler wait for every outstanding load
+  // before the MFMA block and so undo the weight pipeline.
   const bf16_t* xsrc[4];
+  bool xok[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int xr = s_xrow[rbase + 32 * i];
-    xsrc[i] = xr >= 0 ? a.X + (size_t)xr * a.ldx + c16 * 8 : nullptr;
+    const int xr_ = s_xrow[rbase + 32 * i];
+    xok[i] = xr_ >= 0;
+    xsrc[i] = a.X + (size_t)(xok[i] ? xr_ : 0) * a.ldx + c16 * 8;
   }
-  const u32x4_t* wp[4 * NACC];
+  const u32x4_t* wp[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < FT; ++t) {
     const int nt = min(nt0 + t, a.NT - 1);
     wp[t * NACC] = (const u32x4_t*)a.Wp + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
     if (NACC == 2) wp[t * NACC + 1] = (const u32x4_t*)a.Wp2 + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
   }
   const u32x4_t zero = {0u, 0u, 0u, 0u};
 
-  f32x4_t acc[4][4 * NACC];
+  f32x4_t acc[4][4];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-    for (int t = 0; t < 4 * NACC; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (a.K + TK - 1) / TK;
-  u32x4_t xr[4], xl[SPLIT ? 4 : 1], wn[2][4 * NACC], wcur[2][4 * NACC];
+  const int nk = (a.K + TK - 1) / TK, KS = gridDim.z, z = blockIdx.z;
+  const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
+  u32x4_t xr[4], xl[SPLIT ? 4 : 1], wst[WS][2][4];
   auto load_x = [&](int kb) {
+    const int ko = min(kb * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int k = kb * TK + c16 * 8;
-      xr[i] = (xsrc[i] && k < a.K) ? *(const u32x4_t*)(xsrc[i] + kb * TK) : zero;
-      if (SPLIT) xl[i] = (xsrc[i] && k < a.K) ? *(const u32x4_t*)(xsrc[i] + a.x_lo + kb * TK) : zero;
+      xr[i] = *(const u32x4_t*)(xsrc[i] + ko);
+      if (SPLIT) xl[i] = *(const u32x4_t*)(xsrc[i] + a.x_lo + ko);
     }
   };
-  auto load_w = [&](int kb) {
+  auto load_w = [&](u32x4_t (&w)[2][4], int kb) {
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
-      const int kt = kb * 2 + k2;
+      const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
 #pragma unroll
-      for (int t = 0; t < 4 * NACC; ++t) wn[k2][t] = kt < KT ? wp[t][(size_t)kt * 64] : zero;
+      for (int t = 0; t < 4; ++t) w[k2][t] = wp[t][(size_t)kt * 64];
     }
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](int buf, int kb) {
+    const bool kok = kb * TK + c16 * 8 < a.K;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + c16 * 16) = xr[i];
-      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + 128 + c16 * 16) = xl[i];
+      const bool ok = xok[i] && kok;
+      *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + c16 * 16) = ok ? xr[i] : zero;
+      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + 128 + c16 * 16) = ok ? xl[i] : zero;
     }
   };
 
-  load_x(0);
-  load_w(0);
-  store_x(0);
+#pragma unroll
+  for (int st_ = 0; st_ < WS; ++st_) load_w(wst[st_], kb0 + st_);
+  load_x(kb0);
+  store_x(0, kb0);
   __syncthreads();
-  for (int kb = 0; kb < nk; ++kb) {
+  for (int kbase = kb0; kbase < kb1; kbase += WS) {
 #pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2)
+    for (int st_ = 0; st_ < WS; ++st_) {   // stage st_ holds the weights of step kbase + st_
+      const int kb = kbase + st_;
+      if (kb >= kb1) break;
+      if (kb + 1 < kb1) load_x(kb + 1);
+      const uint8_t* xb = s_x[(kb - kb0) & 1] + (wr * 64 + f) * XROW + g * 16;
 #pragma unroll
-      for (int t = 0; t < 4 * NACC; ++t) wcur[k2][t] = wn[k2][t];
-    if (kb + 1 < nk) {
-      load_x(kb + 1);
-      load_w(kb + 1);
+      for (int k2 = 0; k2 < 2; ++k2) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          if (wr * 64 + rb * 16 >= Mloc) continue;   // 16-row block past the tile's rows (uniform over the wavefront)
+          const u32x4_t b = *(const u32x4_t*)(xb + rb * 16 * XROW + k2 * 64);
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wst[st_][k2][t]),
+                                                                 __builtin_bit_cast(bf16x8_t, b), acc[rb][t], 0, 0, 0);
+          if (SPLIT) {
+            const u32x4_t bl = *(const u32x4_t*)(xb + rb * 16 * XROW + 128 + k2 * 64);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wst[st_][k2][t]),
+                                                                   __builtin_bit_cast(bf16x8_t, bl), acc[rb][t], 0, 0, 0);
+          }
+        }
+      }
+      load_w(wst[st_], kb + WS);   // refill this stage: WS - 1 steps of MFMA work cover the latency
+      if (kb + 1 < kb1) store_x((kb + 1 - kb0) & 1, kb + 1);
+      __syncthreads();
     }
-    const uint8_t* xb = s_x[kb & 1] + (wr * 64 + f) * XROW + g * 16;
+  }
+
+  if (acc[0][0][0] == 12345.678f) return;
+  S2D2_TTS(2);
+  // ---- split K: partials in register order, the last arrival adds them in split order ----
+  // Device-coherent write-through stores and loads around the arrival counter (a __threadfence pair per
+  // workgroup instead made the launches 60 % slower: the fences are cache-wide); words are laid out
+  // [accumulator][half][thread] so that every wavefront instruction covers 512 contiguous bytes; 16-row blocks
+  // past the tile's rows are neither written nor read.
+  if (KS > 1) {
+    const size_t tile_id = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+    uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * 8192 + tid;
 #pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
+    for (int rb = 0; rb < 4; ++rb) {
+      if (wr * 64 + rb * 16 >= Mloc) continue;   // uniform over the wavefront
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const f32x4_t v = acc[rb][t];
+        __hip_atomic_store(mine + ((rb * 4 + t) * 2) * 256, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + ((rb * 4 + t) * 2 + 1) * 256, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);   // write-through stores completed before the arrival is counted
+    __syncthreads();
+    __shared__ int s_last;
+    if (tid == 0) {
+      const int prev = __hip_atomic_fetch_add(&a.tile_counters[tile_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last = prev == KS - 1;
+      if (prev == KS - 1) __hip_atomic_store(&a.tile_counters[tile_id], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    S2D2_TTS(3);
+    if (!s_last) return;
+    S2D2_TTS(4);
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int zz = 0; zz < KS; ++zz) {
+      const uint64_t* src = (const uint64_t*)a.tile_partials + (tile_id * KS + zz) * 8192 + tid;
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
-        const u32x4_t b = *(const u32x4_t*)(xb + rb * 16 * XROW + k2 * 64);
+        if (wr * 64 + rb * 16 >= Mloc) continue;
+        uint64_t v[8];
 #pragma unroll
-        for (int t = 0; t < 4 * NACC; ++t)
-          acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wcur[k2][t]),
-                                                               __builtin_bit_cast(bf16x8_t, b), acc[rb][t], 0, 0, 0);
-        if (SPLIT) {
-          const u32x4_t bl = *(const u32x4_t*)(xb + rb * 16 * XROW + 128 + k2 * 64);
+        for (int e = 0; e < 8; ++e) v[e] = __hip_atomic_load(src + (rb * 8 + e) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-          for (int t = 0; t < 4 * NACC; ++t)
-            acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wcur[k2][t]),
-                                                                 __builtin_bit_cast(bf16x8_t, bl), acc[rb][t], 0, 0, 0);
+        for (int t = 0; t < 4; ++t) {
+          acc[rb][t][0] += __uint_as_float((uint32_t)v[2 * t]);
+          acc[rb][t][1] += __uint_as_float((uint32_t)(v[2 * t] >> 32));
+          acc[rb][t][2] += __uint_as_float((uint32_t)v[2 * t + 1]);
+          acc[rb][t][3] += __uint_as_float((uint32_t)(v[2 * t + 1] >> 32));
         }
       }
     }
-    if (kb + 1 < nk) store_x((kb + 1) & 1);
-    __syncthreads();
   }
 
+  if (acc[0][0][0] == 12345.678f) return;
+  S2D2_TTS(5);
   // ---- epilogue: acc[rb][t][i] = Y[row wr*64 + rb*16 + f][feature (nt0 + t)*16 + 4 g + i] ----
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
@@ -172,7 +270,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
     const int orow = live ? s_orow[r] : 0;
     const float rs = s_rs[r];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < FT; ++t) {
       const int nt = nt0 + t;
       if (nt >= a.NT) continue;   // uniform over the wavefront
       const int n = nt * 16 + 4 * g;
@@ -185,22 +283,25 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
             for (int i = 0; i < 4; ++i)
               if (n + i < a.N) op[i] = v[i];
         }
-      } else if (EPI == SEPI_ADD_F32) {
+      } else if (EPI == SEPI_ADD_F32) {   // N is a multiple of 16 here: four features per lane as one 16-byte access
         float hv[4] = {0.f, 0.f, 0.f, 0.f};
         if (live) {
-          float* hp = (float*)a.out + (size_t)orow * a.ldo + n;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (n + i < a.N) { hv[i] = hp[i] + acc[rb][t][i] * rs; hp[i] = hv[i]; }
+          float4* hp = (float4*)((float*)a.out + (size_t)orow * a.ldo + n);
+          const float4 h0 = *hp;
+          hv[0] = h0.x + acc[rb][t][0] * rs;
+          hv[1] = h0.y + acc[rb][t][1] * rs;
+          hv[2] = h0.z + acc[rb][t][2] * rs;
+          hv[3] = h0.w + acc[rb][t][3] * rs;
+          *hp = make_float4(hv[0], hv[1], hv[2], hv[3]);
           if (a.xg_out) {
+            const float4 gn = *(const float4*)(a.gain_next + n);
+            const float xv[4] = {hv[0] * gn.x, hv[1] * gn.y, hv[2] * gn.z, hv[3] * gn.w};
+            bf16_t hi[4], lo[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (n + i < a.N) {
-                bf16_t hi, lo;
-                split_bf16(hv[i] * a.gain_next[n + i], hi, lo);
-                a.xg_out[(size_t)orow * a.xg_ld + n + i] = hi;
-                if (a.xg_lo) a.xg_out[(size_t)orow * a.xg_ld + a.xg_lo + n + i] = lo;
-              }
+            for (int i = 0; i < 4; ++i) split_bf16(xv[i], hi[i], lo[i]);
+            bf16_t* xp = a.xg_out + (size_t)orow * a.xg_ld + n;
+            *(uint2*)xp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+            if (a.xg_lo) *(uint2*)(xp + a.xg_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
           }
         }
         if (a.ss_out) {
@@ -212,16 +313,14 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
       } else if (EPI == SEPI_SWIGLU) {
         if (live) {
           bf16_t* op = (bf16_t*)a.out + (size_t)orow * a.ldo + n;
+          bf16_t hi[4], lo[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float gate = acc[rb][2 * t][i] * rs, up = acc[rb][2 * t + 1][i] * rs;
-            if (n + i < a.N) {
-              bf16_t hi, lo;
-              split_bf16(gate / (1.0f + __expf(-gate)) * up, hi, lo);
-              op[i] = hi;
-              if (a.out_lo) op[a.out_lo + i] = lo;
-            }
+            const float gate = acc[rb][NACC == 2 ? 2 * t : 0][i] * rs, up = acc[rb][NACC == 2 ? 2 * t + 1 : 0][i] * rs;
+            split_bf16(gate / (1.0f + __expf(-gate)) * up, hi[i], lo[i]);
           }
+          *(uint2*)op = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+          if (a.out_lo) *(uint2*)(op + a.out_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
         }
       } else {  // SEPI_QKV_ROPE: features 0-7 of a tile pair with features 8-15 (lanes 32 apart)
         const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
@@ -238,36 +337,59 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const GemmStreamArgs a) 
             const bool is_q = head < a.Hq;
             bf16_t* dst = is_q ? a.q_out + (size_t)orow * a.q_ld + head * D
                                : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
+            const float4 c01 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0), c23 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0 + 2);
+            const float cs_c[4] = {c01.x, c01.z, c23.x, c23.z}, cs_s[4] = {c01.y, c01.w, c23.y, c23.w};
+            bf16_t hi[4], lo[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float2 cs = a.rope_cs[(size_t)orow * half + i0 + i];
-              const float y = second ? own[i] * cs.x + oth[i] * cs.y : own[i] * cs.x - oth[i] * cs.y;
-              bf16_t hi, lo;
-              split_bf16(y, hi, lo);
-              dst[i0 + i + (second ? half : 0)] = hi;
-              if (is_q && a.q_lo) dst[a.q_lo + i0 + i + (second ? half : 0)] = lo;
+              const float y = second ? own[i] * cs_c[i] + oth[i] * cs_s[i] : own[i] * cs_c[i] - oth[i] * cs_s[i];
+              split_bf16(y, hi[i], lo[i]);
             }
+            bf16_t* dp = dst + i0 + (second ? half : 0);
+            *(uint2*)dp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+            if (is_q && a.q_lo) *(uint2*)(dp + a.q_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
           } else {
             const int vh = head - a.Hq - a.Hkv;
             bf16_t* dst = a.v_out + ((size_t)orow * a.Hkv + vh) * D + (second ? half : 0);
             const int sq = a.row_seq[orow], tw = orow - a.seq_row0[sq];
+            bf16_t b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const bf16_t b = f32_to_bf16(own[i]);
-              dst[i0 + i] = b;
-              if (a.vT_out)
-                a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = b;
+            for (int i = 0; i < 4; ++i) b[i] = f32_to_bf16(own[i]);
+            *(uint2*)(dst + i0) = make_uint2((uint32_t)b[0] | ((uint32_t)b[1] << 16), (uint32_t)b[2] | ((uint32_t)b[3] << 16));
+            if (a.vT_out) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = b[i];
             }
           }
         }
       }
     }
   }
+  __builtin_amdgcn_s_waitcnt(0);
+  S2D2_TTS(6);
 }
+
+#ifdef S2D2_FUSED_TIMING
+__global__ void tile_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_tile_ts[threadIdx.x]; }
+void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
+#else
+void launch_tile_ts_copy(hipStream_t, void*) {}
+#endif
 
 template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
-  dim3 grid((a.NT + TN / 16 - 1) / (TN / 16), row_tiles), block(256);
+  constexpr int COLS = EPI == SEPI_SWIGLU ? 4 : 8;   // 16-feature tiles per workgroup
+  const int col_tiles = (a.NT + COLS - 1) / COLS;
+  // split K until about 768 workgroups exist (two are resident per compute unit), within the partial buffer
+  int KS = 1;
+  const long long tiles = (long long)col_tiles * row_tiles;
+  const int nk = (a.K + TK - 1) / TK;
+  if (a.tile_partials && a.grouped == GROUP_NONE && tiles < 384) {
+    KS = (int)std::min<long long>(std::min<long long>(8, (512 + tiles - 1) / tiles), std::max(1, nk / 4));
+    while (KS > 1 && (tiles * KS > a.tile_partial_cap || tiles > a.tile_counter_cap)) --KS;
+  }
+  dim3 grid(col_tiles, row_tiles, KS), block(256);
   if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);
   else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, false>), grid, block, 0, st, a);
 }

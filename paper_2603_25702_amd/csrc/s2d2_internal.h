@@ -172,6 +172,10 @@ struct GemmStreamArgs {
   const int32_t* sorted;
   const float* route_w;
   size_t expert_stride;     // uint4 elements between the packed matrices of consecutive experts
+  // split K of the tile kernel: fp32 partials (64 KB per workgroup) and one arrival counter per tile
+  float* tile_partials;
+  int32_t* tile_counters;
+  int32_t tile_partial_cap, tile_counter_cap;
 };
 size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
@@ -248,6 +252,7 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
                             int32_t* counters);
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
 void launch_attn_ts_copy(hipStream_t st, void* out);   // timing build only
+void launch_tile_ts_copy(hipStream_t st, void* out);   // timing build only
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
 
 // vocab.hip
