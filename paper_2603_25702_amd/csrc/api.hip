@@ -45,6 +45,7 @@ struct s2d2_ctx {
   void* vwin;
   void* vT_win;      // [max_batch, Hkv, D, wpad] key-minor V of the window (MFMA attention)
   float* attn_part;  // split-key partial outputs
+  size_t attn_part_entries;
   int32_t* attn_counters;  // arrival counters of the split-key merge, zero between launches
   int32_t attn_groups;
   int32_t wpad, attn_zmax, attn_z_override;
@@ -78,6 +79,8 @@ struct s2d2_ctx {
   size_t fused_act_stride;
   int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
   bool no_fused;
+  bool no_wide_attention;   // S2D2_ATTN_WIDE=0: one workgroup per query tile even for wide windows
+  int wide_wgs;             // workgroups the split choice of the wide attention kernel aims for
   // profiling (measurement aid)
   bool prof_on;
   int32_t prof_cap;
@@ -172,8 +175,9 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   c->vT_win = cv.take<uint8_t>(NB * (size_t)d.n_kv_heads * d.head_dim * c->wpad * es);
   {
     const int q_tiles = (3 * c->max_block * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
-    // Z * items * q_tiles < 512 + items * q_tiles by the choice of Z in forward()
-    c->attn_part = cv.take<float>(attention_flash_partial_floats(512 + NB * d.n_kv_heads * q_tiles));
+    // Z * items * q_tiles < 512 * 8 + items * q_tiles by the choice of Z in forward()
+    c->attn_part_entries = 4096 + NB * d.n_kv_heads * q_tiles;
+    c->attn_part = cv.take<float>(attention_flash_partial_floats(c->attn_part_entries));
     c->attn_groups = (int32_t)(NB * d.n_kv_heads * q_tiles);
     c->attn_counters = cv.take<int32_t>(c->attn_groups);
   }
@@ -272,8 +276,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const KvGeom g = geom(c, kv);
   // MFMA flash attention for bf16 / head_dim 128 / pages that hold whole 8-key groups; else the generic kernel
   const bool flash = dt == S2D2_BF16 && d.head_dim == 128 && kv->page_size % 8 == 0 && !c->force_generic_attention;
-  const int q_tiles = (3 * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
+  const int q_tiles = ((k_stage ? 3 : 2) * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;   // 32-row query tiles of this call's windows
   int Z = 1;
+  // several query tiles per (sequence, KV head): the kernel that shares K / V tiles among them
+  bool wide = flash && q_tiles >= 2 && !c->no_wide_attention && (kv->page_size & (kv->page_size - 1)) == 0;
   if (flash) {
     // Splits until there are ~512 workgroups or a wavefront is down to one 32-key tile; the last
     // split to finish merges, so extra splits cost one atomic, not a launch.
@@ -282,6 +288,15 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const int want = (512 + groups - 1) / groups;
     Z = std::max(1, std::min(std::min(want, (cap_tiles + 7) / 8), c->attn_zmax));
     if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, want));
+    if (wide) {
+      // one workgroup per (sequence, KV head, group of query tiles, split); a split keeps at least 4 key tiles
+      const int wg = N * d.n_kv_heads * ((q_tiles + 7) / 8);
+      Z = std::max(1, std::min((c->wide_wgs + wg - 1) / wg, std::min((cap_tiles + 3) / 4, c->attn_zmax)));
+      if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, cap_tiles));
+      while (Z > 1 && ((size_t)Z * N * d.n_kv_heads * q_tiles > c->attn_part_entries ||
+                       attention_wide_lds_bytes(attention_wide_pt_cap(g, Z)) > 160 * 1024)) --Z;
+      if (attention_wide_lds_bytes(attention_wide_pt_cap(g, Z)) > 160 * 1024) wide = false, Z = 1;
+    }
   }
   const size_t lds = flash ? 0 : attention_generic_lds_bytes(g, 3 * B);
   if (lds > 160 * 1024) return fail(S2D2_ENOSPC, "attention needs %zu bytes of LDS for max_pages_per_seq*page_size=%d keys (limit 163840)", lds, kv->max_pages_per_seq * kv->page_size);
@@ -357,7 +372,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const void* vp = (const uint8_t*)kv->v_pages + l * page_layer;
     if (flash) {
       ProfScope ps(c, 1, 0.0);
-      launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
+      if (wide)
+        launch_attention_wide(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
+      else
+        launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
     } else {
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
@@ -530,6 +548,10 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   c->ws_bytes = workspace_bytes;
   carve(c, c->ws);
   if (const char* e = getenv("S2D2_ATTN_Z")) c->attn_z_override = atoi(e);
+  c->no_wide_attention = false;
+  if (const char* e = getenv("S2D2_ATTN_WIDE")) c->no_wide_attention = atoi(e) == 0;
+  c->wide_wgs = 512;
+  if (const char* e = getenv("S2D2_ATTN_WIDE_WGS")) c->wide_wgs = std::max(1, atoi(e));
   if (const char* e = getenv("S2D2_GENERIC_ATTENTION")) c->force_generic_attention = atoi(e) != 0;
   if (use_packed) {  // re-lay the projection weights out for the streaming GEMM (enqueued on the stream)
     const s2d2_model_desc& d = c->desc;
@@ -585,7 +607,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
-  if (attention_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
+  if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;
 }

@@ -1,0 +1,363 @@
+// Flash attention for windows with several 32-row query tiles (batched verification, large blocks).
+//
+// attn_flash_kernel gives every query tile a workgroup of its own, so a (sequence, KV head) pair with
+// q_tiles query tiles reads its cached K / V q_tiles times.  Here the NW wavefronts of a workgroup each own
+// ONE query tile of the same (sequence, KV head, key split) and walk the keys together: a 32-key tile of K
+// and of V^T is fetched from global memory once per workgroup (every thread one or a few 16-byte pieces),
+// parked in LDS, and read from there as MFMA operands by all wavefronts.  A wavefront never shares its
+// softmax state, so there is no merge inside the workgroup; key splits merge through the same
+// last-arriver scheme as the narrow kernel, in split order.
+//
+// Pipeline: two tiles are in flight in registers (sets R0 / R1) while a third is being consumed from one of two
+// LDS buffers; a wavefront parks tile i + 1 in the other buffer after its own math on tile i, and one barrier
+// per tile separates that from the reads of tile i + 1.  The page-table entries of the split's key range are copied to LDS
+// once, so address generation never waits on a dependent global load.
+#include "attention_flash.h"
+
+namespace s2d2 {
+
+static constexpr int FW_KROW = 272;               // bytes per K row in LDS: 128 bf16 + 16 bytes (bank spread)
+static constexpr int FW_VROW = 80;                // bytes per V^T row in LDS: 32 keys bf16 + 16 bytes
+static constexpr int FW_KBUF = 32 * FW_KROW;
+static constexpr int FW_BUF = FW_KBUF + 128 * FW_VROW;
+static constexpr int FW_RING = 2;
+
+size_t attention_wide_lds_bytes(int pt_cap) { return (size_t)FW_RING * FW_BUF + (size_t)pt_cap * 4 + 16; }
+
+struct FwTile { bool win; int kbase, limit; };
+
+// Keeps the first nv of 8 bf16 and zeroes the rest, without branches.
+__device__ __forceinline__ uint4 fw_mask(uint4 v, int nv) {
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int k = nv - 2 * e;   // valid halves of this dword
+    const uint32_t m = k >= 2 ? 0xffffffffu : (k == 1 ? 0xffffu : 0u);
+    w[e] &= m;
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int NW, bool SPLIT>
+__global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
+    const bf16_t* __restrict__ q, int q_ld, int q_lo, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
+    const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
+    int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int32_t* __restrict__ counters, int q_tiles, int per, int pt_cap, int ps_shift) {
+  constexpr int D = FA_D, T = NW * 64, U = 512 / T;
+  static_assert(U == 1 || U == 2 || U == 4, "8, 4 or 2 wavefronts");
+  extern __shared__ __align__(16) unsigned char lds[];
+  int32_t* s_pt = (int32_t*)(lds + FW_RING * FW_BUF);
+  int* s_last = (int*)(s_pt + pt_cap);
+  const int z = blockIdx.x, qgrp = blockIdx.y, item = blockIdx.z;
+  const int Hkv = g.n_kv_heads, ps = g.page_size;
+  const int n = item / Hkv, kvh = item % Hkv;
+  const int grp = Hq / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, h = lane >> 5;
+  const int cap = g.max_pages_per_seq * ps;
+  const int S = max(0, min(g.seq_len[n], cap));
+  const int row0 = p.seq_row0[n], nw = p.seq_rows[n];
+  const int nq = nw * grp;
+  // query tiles qgrp * per .. + per of this (sequence, KV head) belong to this workgroup, one per wavefront (per <= NW)
+  if (qgrp * per * 32 >= nq) return;            // the whole workgroup: nothing to do (before any barrier)
+  const int qt = qgrp * per + wave, q0 = qt * 32;
+  const bool active = wave < per && q0 < nq;
+  const int qi = min(q0 + c, nq - 1);
+  const int r = row0 + qi / grp, head = kvh * grp + qi % grp;
+  const int lo = p.row_lo[r], hi = p.row_hi[r];
+
+  const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
+  const int t0 = (int)((long long)Tc * z / Z), t1 = (int)((long long)Tc * (z + 1) / Z);
+  const int n_c = t1 - t0, n_w = z == Z - 1 ? Tw : 0, n_it = n_c + n_w;
+
+  // page-table slice of this split's keys
+  const int pb0 = (t0 * 32) >> ps_shift;   // page_size = 1 << ps_shift
+  {
+    const int pe = (min(t1 * 32, cap) + ps - 1) >> ps_shift;
+    const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
+    for (int i = tid; i < min(pe - pb0, pt_cap); i += T) s_pt[i] = min(max(pt[pb0 + i], 0), g.n_pages - 1);
+  }
+
+  uint4 qf[8], ql[SPLIT ? 8 : 1];
+  {
+    const bf16_t* qp = q + (size_t)r * q_ld + head * D + 8 * h;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) {
+      qf[ds] = *(const uint4*)(qp + ds * 16);
+      if (SPLIT) ql[ds] = *(const uint4*)(qp + q_lo + ds * 16);
+    }
+  }
+  FaState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
+  __syncthreads();   // s_pt
+
+  // (closures capture scalars by value: captured references would pin the locals to memory)
+  auto tile_of = [=](int i) {
+    FwTile t;
+    i = min(i, n_it - 1);
+    t.win = i >= n_c;
+    t.kbase = (t.win ? i - n_c : t0 + i) * 32;
+    t.limit = t.win ? nw : S;
+    return t;
+  };
+  // piece idx of a tile: K row idx / 16, 16-byte piece idx % 16;  V^T row idx / 4, keys 8 (idx % 4) .. + 8.
+  // Thread tid handles pieces tid + u T, u < U (each piece in a named register set, never an indexed array).
+  auto fetch1 = [=](int u, int i, uint4& kr, uint4& vr) {
+    const FwTile t = tile_of(i);
+    const int idx = min(tid + u * T, 511);
+    const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
+    const int key = min(t.kbase + kk, t.limit - 1);   // rows beyond the region read a valid row; their scores are masked
+    const int key0 = t.kbase + vko;
+    // both address forms are computed and one is selected: no control flow around the loads
+    const int kv0 = min(key0, cap - 8);
+    const int pk = s_pt[max(0, min((key >> ps_shift) - pb0, pt_cap - 1))];
+    const int pv = s_pt[max(0, min((kv0 >> ps_shift) - pb0, pt_cap - 1))];
+    const size_t k_off_c = (((size_t)pk * Hkv + kvh) * ps + (key & (ps - 1))) * D + kch * 8;
+    const size_t v_off_c = (((size_t)pv * Hkv + kvh) * D + vd) * ps + (kv0 & (ps - 1));
+    const size_t k_off_w = ((size_t)(row0 + key) * Hkv + kvh) * D + kch * 8;
+    const size_t v_off_w = ((size_t)(n * Hkv + kvh) * D + vd) * wpad + min(key0, wpad - 8);
+    const bf16_t* kp = t.win ? k_win + k_off_w : k_pages + k_off_c;
+    const bf16_t* vp = t.win ? vT_win + v_off_w : v_pages + v_off_c;
+    kr = *(const uint4*)kp;
+    vr = *(const uint4*)vp;
+  };
+  auto stash1 = [=](int u, int i, int b, uint4 kr, uint4 vr) {
+    const FwTile t = tile_of(i);
+    unsigned char* base = lds + b * FW_BUF;
+    const int idx = min(tid + u * T, 511);   // clamped duplicates rewrite the same bytes
+    const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
+    *(uint4*)(base + kk * FW_KROW + kch * 16) = kr;
+    *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = fw_mask(vr, t.limit - (t.kbase + vko));
+  };
+  const int kperm = fa_perm(c);
+  auto compute = [=](FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) {
+    const FwTile t = tile_of(i);
+    const unsigned char* kb = lds + b * FW_BUF + kperm * FW_KROW + 16 * h;
+    const unsigned char* vb = lds + b * FW_BUF + FW_KBUF + c * FW_VROW + 16 * h;
+    f32x16_t sacc;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) sacc[j] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < 8; ++ds) {
+      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(kb + ds * 32));
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
+      if (SPLIT) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, ql[ds]), sacc, 0, 0, 0);
+    }
+    // sacc[j]: key kbase + 16 (j / 8) + 8 h + (j % 8), query row c.  Scores stay unscaled until the exponent:
+    // the running maximum is kept in scaled units, exp2(s * scale - m) is one fused multiply-add per element.
+    float mx = -INFINITY;
+    if (!t.win && t.kbase + 32 <= t.limit) {   // a full tile of cached keys: every key is visible
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sacc[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int key = t.kbase + 16 * (j >> 3) + 8 * h + (j & 7);
+        const int w = row0 + key;
+        const int vis = (int)!t.win | ((int)(w >= lo) & (int)(w < hi)) | (int)(w == r);
+        sacc[j] = ((int)(key < t.limit) & vis) ? sacc[j] : -INFINITY;
+        mx = fmaxf(mx, sacc[j]);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;
+    // no divergent control flow around the MFMAs: a query row that sees nothing yet keeps m = -inf
+    // and uses 0 as the reference, which makes every p below exp2(-inf) = 0
+    const float m_new = fmaxf(st.m, mx);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
+    float ls = 0.f;
+    bf16x8_t pb[2], pl[SPLIT ? 2 : 1];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j], scale_log2e, -m_ref));
+      ls += pv;
+      const __bf16 ph = (__bf16)pv;
+      pb[j >> 3][j & 7] = ph;
+      if (SPLIT) pl[j >> 3][j & 7] = (__bf16)(pv - (float)ph);
+    }
+    ls += __shfl_xor(ls, 32, 64);
+    st.l = st.l * alpha + ls;
+    st.m = m_new;
+    // the accumulators are rescaled only when some row's maximum moved (alpha = 1 leaves them as they are)
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.o[dt][j] *= alpha;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(vb + dt * 32 * FW_VROW + j * 32));
+        st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[j], st.o[dt], 0, 0, 0);
+        if (SPLIT) st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[j], st.o[dt], 0, 0, 0);
+      }
+    }
+  };
+
+  if (n_it > 0) {
+    if constexpr (U == 1) {
+      // two tiles in flight in registers: set B holds tile i + 1 and set A tile i + 2 at the top of an (even) iteration
+      uint4 ak, av, bk, bv;
+      fetch1(0, 0, ak, av);
+      fetch1(0, 1, bk, bv);
+      stash1(0, 0, 0, ak, av);
+      fetch1(0, 2, ak, av);
+      __syncthreads();
+      for (int i = 0; i < n_it; i += 2) {
+        if (active) compute(st, qf, ql, i, 0);
+        stash1(0, i + 1, 1, bk, bv);
+        fetch1(0, i + 3, bk, bv);
+        __syncthreads();
+        if (i + 1 < n_it) {
+          if (active) compute(st, qf, ql, i + 1, 1);
+          stash1(0, i + 2, 0, ak, av);
+          fetch1(0, i + 4, ak, av);
+          __syncthreads();
+        }
+      }
+    } else {
+      // smaller workgroups hold several pieces per thread: one tile in flight (two workgroups share a CU)
+      uint4 k0, v0, k1, v1, k2, v2, k3, v3;
+      auto fetch_all = [&](int i) {
+        fetch1(0, i, k0, v0);
+        fetch1(1, i, k1, v1);
+        if constexpr (U > 2) { fetch1(2, i, k2, v2); fetch1(3, i, k3, v3); }
+      };
+      auto stash_all = [&](int i, int b) {
+        stash1(0, i, b, k0, v0);
+        stash1(1, i, b, k1, v1);
+        if constexpr (U > 2) { stash1(2, i, b, k2, v2); stash1(3, i, b, k3, v3); }
+      };
+      fetch_all(0);
+      stash_all(0, 0);
+      fetch_all(1);
+      __syncthreads();
+      for (int i = 0; i < n_it; ++i) {
+        if (active) compute(st, qf, ql, i, i & 1);
+        stash_all(i + 1, (i + 1) & 1);
+        fetch_all(i + 2);
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- output: lane (c, h) holds head-dim positions dt*32 + 8*i4 + 4*h .. + 4 of query row c ----
+  const size_t item0 = ((size_t)item * q_tiles + qt) * Z;
+  if (Z == 1) {
+    if (active && q0 + c < nq) {
+      const float inv = st.l > 0.f ? 1.0f / st.l : 0.f;
+      bf16_t* op = o + (size_t)r * o_ld + head * D + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          fa_store4<false>(op + dt * 32 + 8 * i4, o_lo, st.o[dt][4 * i4] * inv, st.o[dt][4 * i4 + 1] * inv,
+                           st.o[dt][4 * i4 + 2] * inv, st.o[dt][4 * i4 + 3] * inv);
+    }
+    return;
+  }
+  if (active) {
+    float* po = part_o + (item0 + z) * 32 * D + (size_t)lane * 4;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4)
+        st16f_coh(po + (dt * 4 + i4) * 256, st.o[dt][4 * i4], st.o[dt][4 * i4 + 1], st.o[dt][4 * i4 + 2], st.o[dt][4 * i4 + 3]);
+    if (h == 0) {
+      st4f_coh(&part_ml[(item0 + z) * 64 + c], st.m);
+      st4f_coh(&part_ml[(item0 + z) * 64 + 32 + c], st.l);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // the write-through stores of the partials have completed before the arrival is counted
+  __syncthreads();
+  const int cidx = item * q_tiles + qgrp * per;
+  if (tid == 0) {
+    const int prev = __hip_atomic_fetch_add(&counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = prev == Z - 1;
+    if (prev == Z - 1) __hip_atomic_store(&counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!*s_last) return;
+  // the last split to arrive merges every query tile of the workgroup, all threads on one tile at a time
+  for (int w = 0; w < per; ++w) {
+    const int qt2 = qgrp * per + w;
+    if (qt2 * 32 >= nq) break;
+    // in passes of 512 pieces, so that a thread never holds more than two pieces per split in registers
+#pragma unroll 1
+    for (int pass = 0; pass < 512 / T; ++pass)
+      fa_combine<false, 512>(part_o, part_ml, ((size_t)item * q_tiles + qt2) * Z, Z, tid + pass * T, qt2, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
+  }
+}
+
+template <int NW>
+static void launch_wide(hipStream_t st, bool split, dim3 grid, size_t lds, const bf16_t* q, int q_ld, int q_lo,
+                        const bf16_t* k_win, const bf16_t* vT_win, const bf16_t* kp, const bf16_t* vp, const KvGeom& g,
+                        const Plan& p, int Hq, int Z, int wpad, float scale_log2e, bf16_t* o, int o_ld, int o_lo,
+                        float* part_o, float* part_ml, int32_t* counters, int q_tiles, int per, int pt_cap, int ps_shift) {
+  if (split)
+    S2D2_LAUNCH((attn_flash_wide_kernel<NW, true>), grid, dim3(NW * 64), lds, st, q, q_ld, q_lo, k_win, vT_win, kp, vp, g, p,
+                Hq, Z, wpad, scale_log2e, o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift);
+  else
+    S2D2_LAUNCH((attn_flash_wide_kernel<NW, false>), grid, dim3(NW * 64), lds, st, q, q_ld, q_lo, k_win, vT_win, kp, vp, g, p,
+                Hq, Z, wpad, scale_log2e, o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift);
+}
+
+// Wavefronts per workgroup for q_tiles query tiles: as few query groups as 8-wavefront workgroups allow,
+// then the smallest supported workgroup that covers a group.
+int attention_wide_nw(int q_tiles) {
+  const int groups = (q_tiles + 7) / 8, need = (q_tiles + groups - 1) / groups;
+  return need <= 2 ? 2 : need <= 4 ? 4 : 8;
+}
+
+// Page-table entries a split can touch (plus slack for the ragged ends).
+int attention_wide_pt_cap(const KvGeom& g, int Z) {
+  const int cap_tiles = (g.max_pages_per_seq * g.page_size + 31) / 32;
+  const int per_split = (cap_tiles + Z - 1) / Z + 1;
+  return std::min(g.max_pages_per_seq, per_split * 32 / g.page_size + 2);
+}
+
+void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
+                           const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p, int N,
+                           int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
+                           size_t part_entries, int32_t* counters) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.head_dim);
+  const int items = N * g.n_kv_heads;
+  const int qgroups = (q_tiles + 7) / 8, per = (q_tiles + qgroups - 1) / qgroups;   // tiles per workgroup, balanced
+  const int nw = attention_wide_nw(q_tiles);
+  const int pt_cap = attention_wide_pt_cap(g, Z);
+  float* part_o = part;
+  float* part_ml = part + part_entries * 32 * FA_D;
+  const dim3 grid(Z, qgroups, items);
+  const size_t lds = attention_wide_lds_bytes(pt_cap);
+  int ps_shift = 0;
+  while ((1 << ps_shift) < g.page_size) ++ps_shift;   // the caller has checked that page_size is a power of two
+#define S2D2_WIDE(NWV)                                                                                                  \
+  launch_wide<NWV>(st, q_lo != 0, grid, lds, (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win, \
+                   (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,          \
+                   (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift)
+  if (nw == 2) S2D2_WIDE(2);
+  else if (nw == 4) S2D2_WIDE(4);
+  else S2D2_WIDE(8);
+#undef S2D2_WIDE
+}
+
+int attention_wide_init() {
+  const int lim = 160 * 1024;
+  hipError_t e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  return e == hipSuccess ? 0 : -1;
+}
+
+}  // namespace s2d2

@@ -250,6 +250,15 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
                             int32_t* counters);
+// Several query tiles per (sequence, KV head): one workgroup shares each K / V tile among them.
+int attention_wide_init();
+int attention_wide_nw(int q_tiles);
+int attention_wide_pt_cap(const KvGeom& g, int Z);
+size_t attention_wide_lds_bytes(int pt_cap);
+void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
+                           const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p, int N,
+                           int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
+                           size_t part_entries, int32_t* counters);
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
 void launch_attn_ts_copy(hipStream_t st, void* out);   // timing build only
 void launch_tile_ts_copy(hipStream_t st, void* out);   // timing build only
