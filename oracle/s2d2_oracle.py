@@ -518,6 +518,79 @@ def commit_threshold(st: SeqState, d: DraftOut) -> int:
     return int(d.unmask.sum())
 
 
+# --------------------------------------------------------------------------------------
+# Verification routing (Section 4.3: Eq. 5 and the score below it; Algorithm "DoVerify").
+# --------------------------------------------------------------------------------------
+ROUTE_MIN_SPAN, ROUTE_SCORE, ROUTE_HYSTERESIS = 0, 1, 2
+EST_MARGIN, EST_ENTROPY = 0, 1
+H_OFF, H_ON = 0, 1
+
+
+@dataclass
+class RouteParams:
+    policy: int = ROUTE_MIN_SPAN
+    estimator: int = EST_ENTROPY
+    dynamic: bool = True          # s = K - c N_hi (dynamic) or s = K - c (static)
+    tau_span: int = 1
+    tau_score: float = 0.0
+    tau_on: float = 1.0
+    tau_off: float = -5.0
+    c: float = 1.0
+    beta: float = 1.0             # entropy proxy alpha = exp(-beta H / ln V)
+    tau_margin: float = 0.5       # margin proxy alpha = 1[m >= tau_margin]
+
+
+def acceptance_proxy(margin: np.ndarray, entropy_n: np.ndarray, estimator: int, tau_margin: float,
+                     beta: float) -> np.ndarray:
+    """alpha_i of Section 4.3 for the positions given: indicator of the top-1 minus top-2 margin, or
+    exp(-beta * normalised entropy)."""
+    if estimator == EST_MARGIN:
+        return (f64(margin) >= tau_margin).astype(np.float64)
+    return np.exp(-beta * f64(entropy_n))
+
+
+def expected_prefix_length(alpha: np.ndarray) -> float:
+    """Eq. 5: K = sum over k = 1..L of the product of alpha_1 .. alpha_k (each product taken anew)."""
+    total = 0.0
+    for k in range(1, len(alpha) + 1):
+        prod = 1.0
+        for i in range(k):
+            prod *= float(alpha[i])
+        total += prod
+    return total
+
+
+def verify_score(khat: float, n_hi: int, c: float, dynamic: bool) -> float:
+    """Static score K - c, dynamic score K - c * N_hi (Section 4.3)."""
+    return khat - c * n_hi if dynamic else khat - c
+
+
+def do_verify(rp: RouteParams, L: int, score: float, h: int) -> Tuple[bool, int]:
+    """Algorithm DoVerify: returns (decision, hysteresis state after the call).  A block without a
+    masked span (L = 0) has nothing to verify under any policy."""
+    if L <= 0:
+        return False, h
+    if rp.policy == ROUTE_MIN_SPAN:
+        return bool(L >= rp.tau_span), h
+    if rp.policy == ROUTE_SCORE:
+        return bool(score >= rp.tau_score), h
+    if h == H_ON and score < rp.tau_off:
+        h = H_OFF
+    elif h == H_OFF and score >= rp.tau_on:
+        h = H_ON
+    return h == H_ON, h
+
+
+def route(st: SeqState, d: DraftOut, mask_id: int, rp: RouteParams, h: int = H_ON):
+    """K, score and decision for one sequence from the draft's statistics over C_t."""
+    j, L = first_span(np.asarray(st.block), mask_id)
+    alpha = acceptance_proxy(d.margin[j:j + L], d.entropy_n[j:j + L], rp.estimator, rp.tau_margin, rp.beta)
+    khat = expected_prefix_length(alpha)
+    score = verify_score(khat, d.n_hi, rp.c, rp.dynamic)
+    decision, h2 = do_verify(rp, L, score, h)
+    return dict(khat=khat, score=score, verify=decision, h=h2, L=L)
+
+
 def block_advance(st: SeqState, mask_id: int) -> bool:
     """Alg. 1: once the block holds no [MASK], start a fresh [MASK]^B block right after it.
     Committed tokens of the finished block that are not cached yet are carried."""
@@ -541,6 +614,24 @@ def step(cfg, W, st: SeqState, cache_k, cache_v, tau: float, seed: int, step_idx
     kv_append(st, cache_k, cache_v, vo, a.n_accept)
     block_advance(st, cfg.mask_id)
     return d, vo, a
+
+
+def step_routed(cfg, W, st: SeqState, cache_k, cache_v, tau: float, seed: int, step_idx: int, rp: RouteParams,
+                h: int = H_ON, seq: int = 0, ar_mask: bool = True, mode: int = GREEDY, temperature: float = 1.0):
+    """Alg. 3 in full: draft; DoVerify; then either verify + accept + append, or the threshold-set
+    commit of Alg. 2.  Returns (draft, route record, verify or None, accept or None)."""
+    d = draft(cfg, W, st, cache_k, cache_v, tau, ar_mask, mode, temperature, seed, step_idx, seq)
+    r = route(st, d, cfg.mask_id, rp, h)
+    vo = a = None
+    if r["verify"]:
+        vo = verify(cfg, W, st, cache_k, cache_v, d.xhat, mode, temperature)
+        a = accept(st, d, vo, seed, step_idx, seq, mode, temperature)
+        st.block = a.block
+        kv_append(st, cache_k, cache_v, vo, a.n_accept)
+    else:
+        commit_threshold(st, d)
+    block_advance(st, cfg.mask_id)
+    return d, r, vo, a
 
 
 def prefill(cfg, W, ids: np.ndarray, chunk: int = 256):
