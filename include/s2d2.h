@@ -144,6 +144,9 @@ typedef struct {
   int32_t ar_mask;      /* 1: Eq. 4 (committed in-block prefix causal); 0: block fully bidirectional */
   int32_t resample;     /* 1: residual resampling at the first rejection; 0: reject only */
   uint32_t* step_dev;   /* device, optional */
+  const int32_t* active; /* device [N] or NULL: sequences with active[n] == 0 are skipped by s2d2_verify (no window
+                          * rows, nothing staged), s2d2_accept (n_accept = n_commit = 0) and hence s2d2_kv_append;
+                          * NULL = all sequences.  s2d2_route writes such a mask (routing of Section 4.3). */
 } s2d2_params;
 
 /* Outputs of s2d2_draft (all device, caller-owned).  Per-position arrays are indexed
@@ -253,6 +256,43 @@ int32_t s2d2_block_advance(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_blo
 /* Alg. 2 commit: x^b_i <- x_hat_i for every i in the draft's threshold set. */
 int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_t B,
                               const s2d2_draft_out* draft);
+
+/* Verification routing (Section 4.3, Eq. 5; algorithm DoVerify): from the draft's statistics over C_t of every
+ * sequence, the expected accepted prefix length K = sum_k prod_{i<=k} alpha_i with alpha_i = 1[margin_i >=
+ * tau_margin] (S2D2_EST_MARGIN) or exp(-beta * entropy_n_i) (S2D2_EST_ENTROPY), the score K - c (static) or
+ * K - c * n_hi (dynamic), and the decision of the chosen policy:
+ *   S2D2_ROUTE_MIN_SPAN     |C_t| >= tau_span
+ *   S2D2_ROUTE_SCORE        score >= tau_score
+ *   S2D2_ROUTE_HYSTERESIS   state ON and score < tau_off -> OFF; state OFF and score >= tau_on -> ON; verify iff ON
+ * A sequence whose block has no [MASK] is never verified.  fp32 arithmetic, products and sum taken left to right.
+ * Outputs (device, caller-owned, [N]):
+ *   do_verify        1 = run the verifier for this sequence, 0 = fall back to the threshold commit of Alg. 2;
+ *                    pass it as s2d2_params.active to s2d2_verify / s2d2_accept
+ *   khat, score      K and the score (score is computed under every policy)
+ *   unmask_fallback  the draft's threshold set where do_verify == 0, else 0: a copy of the draft outputs with
+ *                    `unmask` pointing here makes s2d2_commit_threshold act on exactly the sequences that fell back
+ * hysteresis: device [N], in/out, 1 = ON, 0 = OFF; read and written only under S2D2_ROUTE_HYSTERESIS (may be NULL
+ * otherwise).  Errors: S2D2_EINVAL for a NULL argument, an unknown policy or estimator, tau_span < 0. */
+#define S2D2_ROUTE_MIN_SPAN 0
+#define S2D2_ROUTE_SCORE 1
+#define S2D2_ROUTE_HYSTERESIS 2
+#define S2D2_EST_MARGIN 0
+#define S2D2_EST_ENTROPY 1
+typedef struct {
+  int32_t policy, estimator;
+  int32_t dynamic;      /* 0: score = K - c; 1: score = K - c * n_hi */
+  int32_t tau_span;
+  float tau_score, tau_on, tau_off;
+  float c, beta, tau_margin;
+} s2d2_route_params;
+typedef struct {
+  int32_t* do_verify;
+  float* khat;
+  float* score;
+  uint64_t* unmask_fallback;
+} s2d2_route_out;
+int32_t s2d2_route(s2d2_ctx* ctx, int32_t N, int32_t B, const s2d2_route_params* rp, const s2d2_draft_out* draft,
+                   int32_t* hysteresis, const s2d2_route_out* out);
 
 /* Synchronises the context's stream and reports a sticky device-side failure: S2D2_ELAUNCH if a
  * device-wide barrier of the fused forward ran out of its bounded spin (a workgroup was not resident),

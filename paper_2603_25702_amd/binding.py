@@ -22,7 +22,7 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
-    "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
+    "s2d2_commit_threshold", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
 PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "forward")
 
@@ -59,7 +59,17 @@ class BlockStateC(C.Structure):
 class ParamsC(C.Structure):
     _fields_ = [("tau", C.c_float), ("temperature", C.c_float), ("gamma", C.c_float), ("seed", C.c_uint64),
                 ("step", C.c_uint32), ("mode", C.c_int32), ("ar_mask", C.c_int32), ("resample", C.c_int32),
-                ("step_dev", C.c_void_p)]
+                ("step_dev", C.c_void_p), ("active", C.c_void_p)]
+
+
+class RouteParamsC(C.Structure):
+    _fields_ = [("policy", C.c_int32), ("estimator", C.c_int32), ("dynamic", C.c_int32), ("tau_span", C.c_int32),
+                ("tau_score", C.c_float), ("tau_on", C.c_float), ("tau_off", C.c_float), ("c", C.c_float),
+                ("beta", C.c_float), ("tau_margin", C.c_float)]
+
+
+class RouteOutC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("do_verify", "khat", "score", "unmask_fallback")]
 
 
 class DraftOutC(C.Structure):
@@ -120,6 +130,8 @@ def load_library():
     lib.s2d2_block_advance.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
                                        C.c_void_p]
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
+    lib.s2d2_route.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(RouteParamsC), C.POINTER(DraftOutC), C.c_void_p,
+                               C.POINTER(RouteOutC)]
     lib.s2d2_status.argtypes = [C.c_void_p]
     lib.s2d2_status.restype = C.c_int32
     lib.s2d2_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p)]
@@ -131,7 +143,7 @@ def load_library():
     lib.s2d2_profile_start.argtypes = [C.c_void_p, C.c_int32]
     lib.s2d2_profile_stop.argtypes = [C.c_void_p, C.POINTER(ProfileC)]
     for name in ("s2d2_profile_start", "s2d2_profile_stop", "s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
-                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
+                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
     return lib
@@ -163,10 +175,52 @@ class Params:
     ar_mask: int = 1
     resample: int = 1
     step_dev: Optional[torch.Tensor] = None  # uint32 counter on the device (as int32 storage)
+    active: Optional[torch.Tensor] = None    # int32 [N] on the device: 0 = skipped by verify / accept
 
     def c(self) -> ParamsC:
         return ParamsC(self.tau, self.temperature, self.gamma, self.seed, self.step, self.mode, self.ar_mask,
-                       self.resample, _ptr(self.step_dev))
+                       self.resample, _ptr(self.step_dev), _ptr(self.active))
+
+
+S2D2_ROUTE_MIN_SPAN, S2D2_ROUTE_SCORE, S2D2_ROUTE_HYSTERESIS = 0, 1, 2
+S2D2_EST_MARGIN, S2D2_EST_ENTROPY = 0, 1
+
+
+@dataclass
+class RouteParams:
+    policy: int = S2D2_ROUTE_MIN_SPAN
+    estimator: int = S2D2_EST_ENTROPY
+    dynamic: int = 1
+    tau_span: int = 1
+    tau_score: float = 0.0
+    tau_on: float = 1.0
+    tau_off: float = -5.0
+    c: float = 1.0
+    beta: float = 1.0
+    tau_margin: float = 0.5
+
+    def c_struct(self) -> RouteParamsC:
+        return RouteParamsC(self.policy, self.estimator, int(self.dynamic), self.tau_span, self.tau_score, self.tau_on,
+                            self.tau_off, self.c, self.beta, self.tau_margin)
+
+
+@dataclass
+class RouteOut:
+    t: Dict[str, torch.Tensor]
+
+    @staticmethod
+    def alloc(N: int, device) -> "RouteOut":
+        return RouteOut(_alloc([("do_verify", (N,), torch.int32), ("khat", (N,), torch.float32),
+                                ("score", (N,), torch.float32), ("unmask_fallback", (N,), torch.int64)], device))
+
+    def c(self) -> RouteOutC:
+        return RouteOutC(*[self.t[n].data_ptr() for n, _ in RouteOutC._fields_])
+
+    def __getattr__(self, k):
+        try:
+            return self.__dict__["t"][k]
+        except KeyError:
+            raise AttributeError(k)
 
 
 @dataclass
@@ -345,6 +399,10 @@ class Engine:
 
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
+
+    def s2d2_route(self, N, B, rp: RouteParams, draft: DraftOut, hysteresis: Optional[torch.Tensor], out: RouteOut):
+        _check(self.lib, self.lib.s2d2_route(self.ctx, N, B, C.byref(rp.c_struct()), C.byref(draft.c()), _ptr(hysteresis),
+                                             C.byref(out.c())))
 
     def s2d2_status(self):
         _check(self.lib, self.lib.s2d2_status(self.ctx))

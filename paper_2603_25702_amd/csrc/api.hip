@@ -14,6 +14,12 @@ using namespace s2d2;
 
 static thread_local char g_err[512] = "";
 namespace s2d2 { thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr; }
+namespace s2d2 {   // defined in plan.hip (takes a type of the public header)
+void launch_route(hipStream_t st, int N, int B, const s2d2_route_params& rp, const int32_t* span_start,
+                  const int32_t* span_len, const float* margin, const float* entropy_n, const int32_t* n_hi,
+                  const uint64_t* unmask, int32_t* hysteresis, int32_t* do_verify, float* khat, float* score,
+                  uint64_t* unmask_fallback);
+}
 
 static int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -661,7 +667,7 @@ int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* 
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) || (rc = check_draft_out(out))) return rc;
   const s2d2_model_desc& d = c->desc;
   { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, false, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
-              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr); }
+              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
   { ProfScope ps(c, 2, 0.0); launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
                      c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n); }
@@ -678,7 +684,7 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
     return rc;
   const s2d2_model_desc& d = c->desc;
   { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
-              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead); }
+              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
   S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
                      out->logit_row_of, out->q, out->lse_ver);
@@ -697,7 +703,7 @@ int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t 
   { ProfScope ps(c, 2, 0.0); launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
                 draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
                 ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
-                out->n_accept, out->n_commit, out->resampled, out->u_used); }
+                out->n_accept, out->n_commit, out->resampled, out->u_used, prm->active); }
   return check_launch("s2d2_accept");
 }
 
@@ -730,6 +736,23 @@ int32_t s2d2_commit_threshold(s2d2_ctx* c, const s2d2_block_state* st, int32_t N
   if ((rc = check_state(c, st, N, B)) || (rc = check_draft_out(draft))) return rc;
   launch_commit_threshold(c->stream, N, B, st->block_tokens, draft->xhat, draft->unmask);
   return check_launch("s2d2_commit_threshold");
+}
+
+int32_t s2d2_route(s2d2_ctx* c, int32_t N, int32_t B, const s2d2_route_params* rp, const s2d2_draft_out* draft,
+                   int32_t* hysteresis, const s2d2_route_out* out) {
+  int32_t rc;
+  if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
+  if (N < 1 || N > c->max_batch || B < 1 || B > c->max_block) return fail(S2D2_EINVAL, "N=%d or B=%d outside the limits given to s2d2_create (%d, %d)", N, B, c->max_batch, c->max_block);
+  if ((rc = check_draft_out(draft))) return rc;
+  if (!rp) return fail(S2D2_EINVAL, "route parameters are NULL");
+  if (rp->policy < S2D2_ROUTE_MIN_SPAN || rp->policy > S2D2_ROUTE_HYSTERESIS) return fail(S2D2_EINVAL, "unknown routing policy %d", rp->policy);
+  if (rp->estimator != S2D2_EST_MARGIN && rp->estimator != S2D2_EST_ENTROPY) return fail(S2D2_EINVAL, "unknown acceptance estimator %d", rp->estimator);
+  if (rp->tau_span < 0) return fail(S2D2_EINVAL, "tau_span=%d is negative", rp->tau_span);
+  if (rp->policy == S2D2_ROUTE_HYSTERESIS && !hysteresis) return fail(S2D2_EINVAL, "the hysteresis policy needs the state array");
+  if (!out || !out->do_verify || !out->khat || !out->score || !out->unmask_fallback) return fail(S2D2_EINVAL, "route output or one of its pointers is NULL");
+  { ProfScope ps(c, 3, 0.0); launch_route(c->stream, N, B, *rp, draft->span_start, draft->span_len, draft->margin, draft->entropy_n, draft->n_hi,
+               draft->unmask, hysteresis, out->do_verify, out->khat, out->score, out->unmask_fallback); }
+  return check_launch("s2d2_route");
 }
 
 int32_t s2d2_profile_start(s2d2_ctx* c, int32_t max_launches) {

@@ -15,7 +15,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     const int32_t* __restrict__ pos0, const int32_t* __restrict__ block,
     const int32_t* __restrict__ carry, const int32_t* __restrict__ xhat, Plan p,
     int32_t* __restrict__ logit_row_of, int32_t* __restrict__ span_start,
-    int32_t* __restrict__ span_len, int32_t* __restrict__ stage_row0, int32_t* __restrict__ stage_lead) {
+    int32_t* __restrict__ span_len, int32_t* __restrict__ stage_row0, int32_t* __restrict__ stage_lead,
+    const int32_t* __restrict__ active) {
   __shared__ int32_t s_rows[1024];
   __shared__ int32_t s_lrows[1024];
   const int n = threadIdx.x;
@@ -34,6 +35,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     while (j + L < B && blk[j + L] == mask_id) ++L;
     c = min(c, j);
     lead = nc + (j - c);
+    if (verify && active && active[n] == 0) { L = 0; lead = 0; }   // routed to the fallback: no verifier window
     if (verify) { rows = lead + 2 * L; lrows = L; }
     else        { rows = nc + (B - c); lrows = n_masked; }
   }
@@ -124,10 +126,11 @@ __global__ __launch_bounds__(1024) void plan_kernel(
 void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
-                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead) {
+                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
+                 const int32_t* active) {
   S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify ? 1 : 0, N, B, mask_id, ar_mask,
                      seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
-                     stage_row0, stage_lead);
+                     stage_row0, stage_lead, active);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -239,6 +242,57 @@ void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const
                              const uint64_t* unmask) {
   S2D2_LAUNCH(commit_threshold_kernel, dim3((N * B + 255) / 256), dim3(256), 0, st, N, B, block, xhat,
                      unmask);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Verification routing (Section 4.3): one thread per sequence.  K = sum_k prod_{i<=k} alpha_i over C_t,
+// score, policy decision, hysteresis state update.
+// ---------------------------------------------------------------------------------------------
+__global__ void route_kernel(int N, int B, s2d2_route_params rp, const int32_t* __restrict__ span_start,
+                             const int32_t* __restrict__ span_len, const float* __restrict__ margin,
+                             const float* __restrict__ entropy_n, const int32_t* __restrict__ n_hi,
+                             const uint64_t* __restrict__ unmask, int32_t* __restrict__ hysteresis,
+                             int32_t* __restrict__ do_verify, float* __restrict__ khat, float* __restrict__ score,
+                             uint64_t* __restrict__ unmask_fallback) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  const int j = span_start[n], L = max(0, min(span_len[n], B - j));
+  float prod = 1.f, k = 0.f;
+  for (int i = 0; i < L; ++i) {
+    const int o = n * B + j + i;
+    const float a = rp.estimator == S2D2_EST_MARGIN ? (margin[o] >= rp.tau_margin ? 1.f : 0.f)
+                                                    : expf(-rp.beta * entropy_n[o]);
+    prod *= a;
+    k += prod;
+  }
+  const float s = rp.dynamic ? k - rp.c * (float)n_hi[n] : k - rp.c;
+  bool dec;
+  if (rp.policy == S2D2_ROUTE_MIN_SPAN) {
+    dec = L >= rp.tau_span;
+  } else if (rp.policy == S2D2_ROUTE_SCORE) {
+    dec = s >= rp.tau_score;
+  } else {
+    int h = hysteresis[n] != 0;
+    if (L > 0) {   // a block without a masked span leaves the state as it is
+      if (h && s < rp.tau_off) h = 0;
+      else if (!h && s >= rp.tau_on) h = 1;
+      hysteresis[n] = h;
+    }
+    dec = h != 0;
+  }
+  dec = dec && L > 0;
+  do_verify[n] = dec ? 1 : 0;
+  khat[n] = k;
+  score[n] = s;
+  unmask_fallback[n] = dec ? 0ull : unmask[n];
+}
+
+void launch_route(hipStream_t st, int N, int B, const s2d2_route_params& rp, const int32_t* span_start,
+                  const int32_t* span_len, const float* margin, const float* entropy_n, const int32_t* n_hi,
+                  const uint64_t* unmask, int32_t* hysteresis, int32_t* do_verify, float* khat, float* score,
+                  uint64_t* unmask_fallback) {
+  S2D2_LAUNCH(route_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, B, rp, span_start, span_len, margin,
+              entropy_n, n_hi, unmask, hysteresis, do_verify, khat, score, unmask_fallback);
 }
 
 }  // namespace s2d2

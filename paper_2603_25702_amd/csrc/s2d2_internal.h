@@ -105,7 +105,8 @@ enum GemmEpilogue {
 void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
-                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead);
+                 int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
+                 const int32_t* active);
 void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
                       void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
                       const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
@@ -284,6 +285,6 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
-                   int32_t* resampled, float* u_used);
+                   int32_t* resampled, float* u_used, const int32_t* active);
 
 }  // namespace s2d2

@@ -255,14 +255,14 @@ __global__ __launch_bounds__(256) void accept_kernel(
     const int32_t* __restrict__ xhat, const float* __restrict__ p, const float* __restrict__ lse_d,
     const float* __restrict__ q, const float* __restrict__ lse_v, int32_t* __restrict__ block,
     int32_t* __restrict__ n_accept, int32_t* __restrict__ n_commit, int32_t* __restrict__ resampled,
-    float* __restrict__ u_used) {
+    float* __restrict__ u_used, const int32_t* __restrict__ active) {
   __shared__ float s_tile[RMAX_TILES];
   __shared__ float s_w[4];
   __shared__ int s_nacc;
   __shared__ int s_tile_sel;
   __shared__ float s_before;
   const int n = blockIdx.x, tid = threadIdx.x;
-  const int j = span_start[n], L = span_len[n];
+  const int j = span_start[n], L = (active && active[n] == 0) ? 0 : span_len[n];   // not routed to the verifier: nothing to scan
   const uint32_t stp = step + (step_dev ? *step_dev : 0u);
   for (int i = tid; i < B; i += 256) u_used[(size_t)n * B + i] = 0.f;
   __syncthreads();
@@ -385,10 +385,10 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
-                   int32_t* resampled, float* u_used) {
+                   int32_t* resampled, float* u_used, const int32_t* active) {
   S2D2_LAUNCH(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample,
                      span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
-                     n_accept, n_commit, resampled, u_used);
+                     n_accept, n_commit, resampled, u_used, active);
 }
 
 }  // namespace s2d2

@@ -9,7 +9,9 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 import torch
 
-from .binding import AcceptOut, BlockState, DraftOut, Engine, KvCache, Params, VerifyOut
+import dataclasses
+
+from .binding import AcceptOut, BlockState, DraftOut, Engine, KvCache, Params, RouteOut, RouteParams, VerifyOut
 
 PREFILL_BLOCK = 64  # window used to push prompt tokens through the causal rows of the verifier
 
@@ -93,6 +95,24 @@ class Session:
         e.s2d2_verify(self.kv, self.st, N, B, prm, self.d, self.v)
         e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
         e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
+        e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
+
+    def step_routed(self, prm: Params, rp: RouteParams):
+        """Alg. 3 with its routing: draft -> DoVerify -> (verify -> accept -> kv_append for the sequences routed to the
+        verifier, threshold commit for the others) -> block_advance.  The hysteresis state lives on the device and
+        persists across steps and blocks (initially ON)."""
+        N, B, e = self.N, self.B, self.eng
+        if not hasattr(self, "route"):
+            self.route = RouteOut.alloc(N, self.dev)
+            self.hysteresis = torch.ones(N, dtype=torch.int32, device=self.dev)
+            self._d_fallback = DraftOut({**self.d.t, "unmask": self.route.unmask_fallback})
+        e.s2d2_draft(self.kv, self.st, N, B, prm, self.d)
+        e.s2d2_route(N, B, rp, self.d, self.hysteresis, self.route)
+        prm_r = dataclasses.replace(prm, active=self.route.do_verify)
+        e.s2d2_verify(self.kv, self.st, N, B, prm_r, self.d, self.v)
+        e.s2d2_accept(self.st, N, B, prm_r, self.d, self.v, self.a)
+        e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
+        e.s2d2_commit_threshold(self.st, N, B, self._d_fallback)
         e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
 
     def capture_step(self, prm: Params):

@@ -37,7 +37,8 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(Bd.ModelDesc) == 13 * 4 + 8
     assert C.sizeof(Bd.LayerWeights) == 9 * 8
     assert C.sizeof(Bd.KvView) == 5 * 8 + 3 * 4 + 4
-    assert C.sizeof(Bd.ParamsC) == 48
+    assert C.sizeof(Bd.ParamsC) == 56
+    assert C.sizeof(Bd.RouteParamsC) == 10 * 4 and C.sizeof(Bd.RouteOutC) == 4 * 8
     assert C.sizeof(Bd.DraftOutC) == 11 * 8 and C.sizeof(Bd.VerifyOutC) == 8 * 8 and C.sizeof(Bd.AcceptOutC) == 4 * 8
 
 

@@ -310,3 +310,103 @@ def test_captured_step_graph_replays_match_eager_steps():
         assert torch.equal(cap.st.block_tokens, blk) and torch.equal(cap.kv.seq_len, sl), f"replay {k}"
         assert torch.equal(cap.a.n_commit, nc) and torch.equal(cap.d.p, p), f"replay {k}"
     assert int(cap.tot_commit.sum()) == sum(int(s[2].sum()) for s in states)
+
+
+def test_routing_scores_decisions_and_the_routed_step():
+    """Section 4.3 on the device: K, score and decision of every policy against the oracle's routing applied to the
+    same fp32 draft statistics; then one routed step (some sequences verified, the others committed by the
+    threshold rule) against the oracle's routed step."""
+    from oracle import s2d2_oracle as O
+    from paper_2603_25702_amd.binding import DraftOut, RouteOut, RouteParams
+    N, B = 5, 8
+    case = H.make_case(SMALL_BF16, N, B, [100, 57, 31, 80, 64], seed=4, synthetic_kv=True, page_size=16, room=64)
+    run, rep = run_steps(case, 1, advance=True)             # one verified step leaves blocks with different spans
+    prm = Params(step=1, seed=1234)
+    e = run.eng
+    e.s2d2_draft(run.kv, run.st, N, B, prm, run.d)
+    g = run.fetch()
+    ro = RouteOut.alloc(N, run.dev)
+    spans = [(int(g["span_start"][n]), int(g["span_len"][n])) for n in range(N)]
+    assert len({L for _, L in spans}) > 1, spans
+
+    def oracle_route(rp_or, h0):
+        out = []
+        for n in range(N):
+            j, L = spans[n]
+            al = O.acceptance_proxy(g["margin"][n, j:j + L].astype(np.float64), g["entropy_n"][n, j:j + L].astype(np.float64),
+                                    rp_or.estimator, rp_or.tau_margin, rp_or.beta)
+            k = O.expected_prefix_length(al)
+            s = O.verify_score(k, int(g["n_hi"][n]), rp_or.c, rp_or.dynamic)
+            dec, h = O.do_verify(rp_or, L, s, int(h0[n]))
+            out.append((k, s, dec, h))
+        return out
+
+    policies = [
+        dict(policy=0, tau_span=1), dict(policy=0, tau_span=4), dict(policy=0, tau_span=B + 1),
+        dict(policy=1, estimator=1, dynamic=0, c=1.0, beta=2.0, tau_score=0.5),
+        dict(policy=1, estimator=1, dynamic=1, c=0.5, beta=4.0, tau_score=0.0),
+        dict(policy=1, estimator=0, dynamic=0, c=1.0, tau_margin=0.25, tau_score=1.0),
+        dict(policy=2, estimator=1, dynamic=1, c=1.0, beta=1.0, tau_on=1.0, tau_off=-5.0),
+        dict(policy=2, estimator=0, dynamic=0, c=2.0, tau_margin=0.5, tau_on=2.0, tau_off=0.0),
+    ]
+    near = 0
+    for kw in policies:
+        rp = RouteParams(**kw)
+        rp_or = O.RouteParams(**{**kw, "dynamic": bool(kw.get("dynamic", 1))})
+        h0 = np.array([1, 0, 1, 0, 1], dtype=np.int32)
+        hyst = torch.as_tensor(h0, device=run.dev)
+        e.s2d2_route(N, B, rp, run.d, hyst, ro)
+        torch.cuda.synchronize()
+        want = oracle_route(rp_or, h0)
+        for n in range(N):
+            k, s, dec, h = want[n]
+            assert abs(float(ro.khat[n]) - k) <= 1e-5 * max(1.0, k), (kw, n)
+            assert abs(float(ro.score[n]) - s) <= 1e-5 * max(1.0, abs(s)), (kw, n)
+            thresholds = {1: [rp.tau_score], 2: [rp.tau_on, rp.tau_off]}.get(rp.policy, [])
+            if any(abs(s - t) < 1e-4 for t in thresholds):
+                near += 1
+                continue
+            assert int(ro.do_verify[n]) == int(dec), (kw, n, s)
+            if rp.policy == 2:
+                assert int(hyst[n]) == h, (kw, n)
+            else:
+                assert int(hyst[n]) == h0[n]
+            assert int(ro.unmask_fallback[n]) == (0 if dec else int(g["unmask"][n]))
+    assert near <= 2
+    # error paths are host-side
+    with pytest.raises(Exception):
+        e.s2d2_route(N, B, RouteParams(policy=7), run.d, None, ro)
+    with pytest.raises(Exception):
+        e.s2d2_route(N, B, RouteParams(policy=2), run.d, None, ro)
+
+    # ---- a routed step: a score threshold at the median sends about half of the sequences to the verifier ----
+    rp0 = RouteParams(policy=1, estimator=1, dynamic=0, c=0.0, beta=2.0, tau_score=0.0)
+    e.s2d2_route(N, B, rp0, run.d, None, ro)
+    med = float(np.sort(ro.score.cpu().numpy())[N // 2])
+    rp = RouteParams(policy=1, estimator=1, dynamic=0, c=0.0, beta=2.0, tau_score=med)
+    e.s2d2_route(N, B, rp, run.d, None, ro)
+    dv = ro.do_verify.cpu().numpy().astype(bool)
+    assert dv.any() and (~dv).any(), dv
+    prm_r = Params(step=1, seed=1234, active=ro.do_verify)
+    before = [np.array(s.block, copy=True) for s in case.states]
+    seq_before = [s.seq_len for s in case.states]
+    e.s2d2_verify(run.kv, run.st, N, B, prm_r, run.d, run.v)
+    e.s2d2_accept(run.st, N, B, prm_r, run.d, run.v, run.a)
+    e.s2d2_kv_append(run.kv, N, B, run.d, run.v, run.a.n_accept)
+    e.s2d2_commit_threshold(run.st, N, B, DraftOut({**run.d.t, "unmask": ro.unmask_fallback}))
+    g2 = run.fetch()
+    verified = [n for n in range(N) if dv[n]]
+    H.check_step(case, run, g2, prm, seqs=verified, rep=rep)       # these went through Alg. 3's verify branch
+    for n in range(N):
+        if dv[n]:
+            continue
+        S = np.array([(int(g2["unmask"][n]) >> i) & 1 for i in range(B)], dtype=bool)
+        want = np.where(S, g2["xhat"][n], before[n])
+        np.testing.assert_array_equal(g2["block_tokens"][n], want)   # Alg. 2 commit, nothing else
+        assert S.sum() >= 1 and (before[n][S] == SMALL_BF16.mask_id).all()
+        assert int(g2["seq_len"][n]) == seq_before[n] and int(g2["n_accept"][n]) == 0 and int(g2["n_commit"][n]) == 0
+        assert int(g2["resampled"][n]) == -1 and int(g2["stage_lead"][n]) == 0
+        gp = g2["p"][n].astype(np.float64)
+        S_or, _ = O.threshold_set(gp, before[n] == SMALL_BF16.mask_id, float(np.float32(prm.tau)))
+        assert (S == S_or).all() or (np.abs(gp[before[n] == SMALL_BF16.mask_id] - prm.tau) < H.TIE).any()
+    print("routing: decisions", dv.astype(int).tolist(), "scores", np.round(ro.score.cpu().numpy(), 3).tolist(), "near-threshold skips", near)
