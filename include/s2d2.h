@@ -57,7 +57,8 @@ extern "C" {
 #define S2D2_BF16  1
 
 #define S2D2_GREEDY 0      /* x_hat = arg-max, p = softmax(logits)[x_hat] */
-#define S2D2_SAMPLE 1      /* x_hat ~ softmax(logits / temperature) */
+#define S2D2_SAMPLE 1      /* x_hat ~ softmax(logits / temperature) by inverse CDF in ascending token order (stream 2
+                            * uniform); p, q, margin, entropy and the residual are then all taken at that temperature */
 
 #define S2D2_MAX_BLOCK 64  /* B <= 64: per-sequence sets are returned as 64-bit masks */
 

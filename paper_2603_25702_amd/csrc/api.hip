@@ -639,11 +639,15 @@ int32_t s2d2_set_stream(s2d2_ctx* ctx, void* stream) {
 
 static int32_t check_params(const s2d2_params* p) {
   if (!p) return fail(S2D2_EINVAL, "params is NULL");
-  if (p->mode != S2D2_GREEDY) return fail(S2D2_EINVAL, "only S2D2_GREEDY drafting is supported by this build");
+  if (p->mode != S2D2_GREEDY && p->mode != S2D2_SAMPLE) return fail(S2D2_EINVAL, "unknown drafting mode %d", p->mode);
+  if (p->mode == S2D2_SAMPLE && !(p->temperature > 0.f)) return fail(S2D2_EINVAL, "sampling mode needs a positive temperature");
   if (!(p->gamma > 0.f)) return fail(S2D2_EINVAL, "gamma must be positive");
   if (!(p->tau >= 0.f)) return fail(S2D2_EINVAL, "tau must be non-negative");
   return S2D2_OK;
 }
+
+// 1 / T of the sampling mode; exactly 1 in greedy mode, where all probabilities are taken at temperature 1
+static float inv_temperature(const s2d2_params* p) { return p->mode == S2D2_SAMPLE ? 1.0f / p->temperature : 1.0f; }
 
 static int32_t check_draft_out(const s2d2_draft_out* o) {
   if (!o || !o->logits || !o->logit_row_of || !o->xhat || !o->p || !o->lse || !o->margin || !o->entropy_n ||
@@ -670,7 +674,8 @@ int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* 
               st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
   { ProfScope ps(c, 2, 0.0); launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
-                     c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n); }
+                     c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n,
+                     VocabSample{prm->mode == S2D2_SAMPLE, prm->temperature, prm->seed, prm->step, prm->step_dev}); }
   { ProfScope ps(c, 2, 0.0); launch_draft_finish(c->stream, N, B, d.mask_id, prm->tau, st->block_tokens, out->xhat, out->p, out->lse,
                       out->margin, out->entropy_n, out->unmask, out->n_hi); }
   return check_launch("s2d2_draft");
@@ -689,7 +694,7 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
   S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
                      out->logit_row_of, out->q, out->lse_ver);
   { ProfScope ps(c, 2, 0.0); launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
-                     c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver); }
+                     c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver, inv_temperature(prm)); }
   return check_launch("s2d2_verify");
 }
 
@@ -701,7 +706,7 @@ int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t 
     return rc;
   if (!out || !out->n_accept || !out->n_commit || !out->resampled || !out->u_used) return fail(S2D2_EINVAL, "accept output or one of its pointers is NULL");
   { ProfScope ps(c, 2, 0.0); launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
-                draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
+                inv_temperature(prm), draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
                 ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
                 out->n_accept, out->n_commit, out->resampled, out->u_used, prm->active); }
   return check_launch("s2d2_accept");
@@ -823,7 +828,7 @@ int32_t s2d2_vocab_draft_stats(s2d2_ctx* c, const float* logits, int32_t rows, i
   if (rows == 0) return S2D2_OK;
   S2D2_LAUNCH(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
   launch_vocab_draft(c->stream, logits, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, xhat, p, lse,
-                     margin, entropy_n);
+                     margin, entropy_n, VocabSample{false, 1.0f, 0, 0, nullptr});
   return check_launch("s2d2_vocab_draft_stats");
 }
 
@@ -834,7 +839,7 @@ int32_t s2d2_vocab_score(s2d2_ctx* c, const float* logits_ver, int32_t rows, con
   if ((uintptr_t)logits_ver & 15) return fail(S2D2_EINVAL, "logits must be 16-byte aligned");
   if (rows == 0) return S2D2_OK;
   S2D2_LAUNCH(set_i32_kernel, dim3(1), dim3(1), 0, c->stream, c->tmp_count, rows);
-  launch_vocab_score(c->stream, logits_ver, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, token, q, lse);
+  launch_vocab_score(c->stream, logits_ver, c->desc.vocab, c->tmp_count, rows, c->vws, nullptr, nullptr, 0, token, q, lse, 1.0f);
   return check_launch("s2d2_vocab_score");
 }
 

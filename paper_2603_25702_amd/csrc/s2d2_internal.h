@@ -271,17 +271,24 @@ struct VocabWs {
   int32_t chunks;
 };
 int vocab_chunks(int V);
+struct VocabSample {   // sampling mode of SampleFromLogits: proposals drawn from softmax(logits / temperature)
+  bool sample;
+  float temperature;
+  uint64_t seed;
+  uint32_t step;
+  const uint32_t* step_dev;
+};
 void launch_vocab_draft(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
-                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n);
+                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n, const VocabSample& sm);
 void launch_vocab_score(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
-                        const int32_t* token, float* q, float* lse);
+                        const int32_t* token, float* q, float* lse, float inv_t);
 void launch_draft_finish(hipStream_t st, int N, int B, int mask_id, float tau, const int32_t* block,
                          int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n,
                          uint64_t* unmask, int32_t* n_hi);
 void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t step, const uint32_t* step_dev,
-                   float gamma, int resample, const int32_t* span_start, const int32_t* span_len,
+                   float gamma, int resample, float inv_t, const int32_t* span_start, const int32_t* span_len,
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,

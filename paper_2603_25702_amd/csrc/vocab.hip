@@ -47,9 +47,11 @@ __device__ __forceinline__ Stat stat_shfl_xor(const Stat& s, int off) {
 }
 
 // part[row][chunk][8] = {m, z, e, m2, arg}
+// inv_t: 1 / temperature (1 in greedy mode: the multiplication is then exact); all statistics are those of
+// softmax(logits * inv_t).
 __global__ __launch_bounds__(256) void vocab_partial_kernel(const float* __restrict__ logits, int V,
                                                             const int32_t* __restrict__ count, int chunks,
-                                                            float* __restrict__ part) {
+                                                            float inv_t, float* __restrict__ part) {
   __shared__ Stat s_w[4];
   const int row = blockIdx.y, chunk = blockIdx.x;
   if (row >= *count) return;
@@ -65,10 +67,10 @@ __global__ __launch_bounds__(256) void vocab_partial_kernel(const float* __restr
     idx0[t] = i;
     if (vec_ok && i + 3 < V) {
       const float4 f = *(const float4*)(x + i);
-      v[4 * t] = f.x; v[4 * t + 1] = f.y; v[4 * t + 2] = f.z; v[4 * t + 3] = f.w;
+      v[4 * t] = f.x * inv_t; v[4 * t + 1] = f.y * inv_t; v[4 * t + 2] = f.z * inv_t; v[4 * t + 3] = f.w * inv_t;
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[4 * t + e] = (i + e < V) ? x[i + e] : -INFINITY;
+      for (int e = 0; e < 4; ++e) v[4 * t + e] = (i + e < V) ? x[i + e] * inv_t : -INFINITY;
     }
   }
   Stat s = stat_empty();
@@ -133,7 +135,7 @@ __global__ void vocab_score_final_kernel(const float* __restrict__ part, int chu
                                          const float* __restrict__ logits, const int32_t* __restrict__ count,
                                          const int32_t* __restrict__ logit_seq,
                                          const int32_t* __restrict__ logit_idx, int B,
-                                         const int32_t* __restrict__ token, float* __restrict__ q,
+                                         const int32_t* __restrict__ token, float inv_t, float* __restrict__ q,
                                          float* __restrict__ lse) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= *count) return;
@@ -142,25 +144,34 @@ __global__ void vocab_score_final_kernel(const float* __restrict__ part, int chu
   const float l = s.m + logf(s.z);
   const int tok = token[o];
   lse[o] = l;
-  q[o] = (tok >= 0 && tok < V) ? expf(logits[(size_t)row * V + tok] - l) : 0.f;
+  q[o] = (tok >= 0 && tok < V) ? expf(logits[(size_t)row * V + tok] * inv_t - l) : 0.f;
 }
+
+__global__ void vocab_sample_kernel(const float* __restrict__ logits, int V, const int32_t* __restrict__ count,
+                                    const int32_t* __restrict__ logit_seq, const int32_t* __restrict__ logit_idx, int B,
+                                    uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev, float inv_t,
+                                    const float* __restrict__ lse, int32_t* __restrict__ xhat, float* __restrict__ p);
 
 void launch_vocab_draft(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
-                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n) {
+                        int32_t* xhat, float* p, float* lse, float* margin, float* entropy_n, const VocabSample& sm) {
+  const float inv_t = sm.sample ? 1.0f / sm.temperature : 1.0f;
   S2D2_LAUNCH(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
-                     ws.chunks, ws.part);
+                     ws.chunks, inv_t, ws.part);
   S2D2_LAUNCH(vocab_draft_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
                      count, logit_seq, logit_idx, B, xhat, p, lse, margin, entropy_n);
+  if (sm.sample)
+    S2D2_LAUNCH(vocab_sample_kernel, dim3(rows_cap), dim3(256), 0, st, logits, V, count, logit_seq, logit_idx, B,
+                sm.seed, sm.step, sm.step_dev, inv_t, lse, xhat, p);
 }
 
 void launch_vocab_score(hipStream_t st, const float* logits, int V, const int32_t* count, int rows_cap,
                         const VocabWs& ws, const int32_t* logit_seq, const int32_t* logit_idx, int B,
-                        const int32_t* token, float* q, float* lse) {
+                        const int32_t* token, float* q, float* lse, float inv_t) {
   S2D2_LAUNCH(vocab_partial_kernel, dim3(ws.chunks, rows_cap), dim3(256), 0, st, logits, V, count,
-                     ws.chunks, ws.part);
+                     ws.chunks, inv_t, ws.part);
   S2D2_LAUNCH(vocab_score_final_kernel, dim3((rows_cap + 63) / 64), dim3(64), 0, st, ws.part, ws.chunks, V,
-                     logits, count, logit_seq, logit_idx, B, token, q, lse);
+                     logits, count, logit_seq, logit_idx, B, token, inv_t, q, lse);
 }
 
 // Per sequence: defaults for committed positions, threshold set S = {i in M: p_i > tau} U {argmax p}.
@@ -245,11 +256,128 @@ __device__ __forceinline__ float block_scan_256(float v, float* s_w, float* excl
 static constexpr int RTILE = 256;     // residual tile: one wavefront x float4
 static constexpr int RMAX_TILES = 8192;
 
+// Inverse CDF over V non-negative weights in ascending index order, by the 256 threads of a workgroup:
+// returns (in the lanes of wavefront 0; -1 elsewhere) the smallest index whose inclusive prefix sum exceeds
+// u * total, or -1 if the weights have no mass.  w4(i0, r) yields the weights of indices i0 .. i0+3 (zeros
+// past V).  Two levels with a fixed summation order: tile sums (256 indices per tile: one wavefront x 4),
+// a scan of the tile sums, then a walk of the selected tile; rounding at either level falls back to the
+// nearest index that has mass.  s_tile needs RMAX_TILES floats, s_w four.
+template <typename F>
+__device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, float* s_tile, float* s_w,
+                                                 int* s_tile_sel, float* s_before) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tiles = (V + RTILE - 1) / RTILE;
+  for (int t = w; t < tiles; t += 4) {
+    float r4[4];
+    w4(t * RTILE + lane * 4, r4);
+    float r = ((r4[0] + r4[1]) + r4[2]) + r4[3];
+    for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
+    if (lane == 0) s_tile[t] = r;
+  }
+  __syncthreads();
+  // scan tile sums: thread t owns tiles [t*per, (t+1)*per)
+  const int per = (tiles + 255) / 256;
+  float mine = 0.f;
+  for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) mine += s_tile[t];
+  float total, excl;
+  const float incl = block_scan_256(mine, s_w, &excl, &total);
+  const float target = u * total;
+  if (tid == 0) { *s_tile_sel = -1; *s_before = 0.f; }
+  __syncthreads();
+  if (excl <= target && target < incl) {  // exactly one thread: the intervals tile [0, total)
+    float run = excl, before = excl;
+    int sel = -1, last = -1;
+    for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) {
+      const float ts = s_tile[t];
+      if (ts > 0.f) { last = t; before = run; }
+      if (ts > 0.f && run + ts > target) { sel = t; break; }
+      run += ts;
+    }
+    if (sel < 0) sel = last;          // rounding: take the thread's last tile that has mass
+    *s_tile_sel = sel;
+    *s_before = before;
+  }
+  __syncthreads();
+  int sel = *s_tile_sel;
+  int token = -1;
+  if (total > 0.f && sel < 0) {  // target landed at or beyond the total by rounding: last tile with mass
+    if (tid == 0) {
+      for (int t = tiles - 1; t >= 0; --t)
+        if (s_tile[t] > 0.f) { *s_tile_sel = t; break; }
+      float run = 0.f;
+      for (int t = 0; t < *s_tile_sel; ++t) run += s_tile[t];
+      *s_before = run;
+    }
+    __syncthreads();
+    sel = *s_tile_sel;
+  }
+  if (total > 0.f && sel >= 0 && w == 0) {  // wave 0 walks the selected tile in index order
+    const int i0 = sel * RTILE + lane * 4;
+    float r4[4];
+    w4(i0, r4);
+    const float ls = ((r4[0] + r4[1]) + r4[2]) + r4[3];
+    float inc = ls;
+    for (int off = 1; off < 64; off <<= 1) {
+      const float t = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += t;
+    }
+    float run = *s_before + (inc - ls);
+    int cand = 0x7fffffff, last_pos = -1;
+    for (int e = 0; e < 4; ++e) {
+      if (r4[e] > 0.f) last_pos = i0 + e;
+      run += r4[e];
+      if (cand == 0x7fffffff && r4[e] > 0.f && run > target) cand = i0 + e;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      cand = min(cand, __shfl_xor(cand, off, 64));
+      last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
+    }
+    token = cand != 0x7fffffff ? cand : last_pos;
+  }
+  return token;
+}
+
+// SampleFromLogits in sampling mode: x_hat ~ softmax(logits / T) by inverse CDF in ascending vocabulary order with
+// the uniform of stream 2 at (step, sequence, block index); p = that token's probability.  One workgroup per
+// logit row; runs after the statistics kernels (reads lse, overwrites the arg-max proposal and its probability).
+__global__ __launch_bounds__(256) void vocab_sample_kernel(
+    const float* __restrict__ logits, int V, const int32_t* __restrict__ count, const int32_t* __restrict__ logit_seq,
+    const int32_t* __restrict__ logit_idx, int B, uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev,
+    float inv_t, const float* __restrict__ lse, int32_t* __restrict__ xhat, float* __restrict__ p) {
+  __shared__ float s_tile[RMAX_TILES];
+  __shared__ float s_w[4];
+  __shared__ int s_tile_sel;
+  __shared__ float s_before;
+  const int row = blockIdx.x;
+  if (row >= *count) return;
+  const int n = logit_seq ? logit_seq[row] : row, idx = logit_idx ? logit_idx[row] : 0;
+  const int o = logit_seq ? n * B + idx : row;
+  const float* x = logits + (size_t)row * V;
+  const float z = lse[o];
+  const uint32_t stp = step + (step_dev ? *step_dev : 0u);
+  const float u = uniform01(seed, stp, (uint32_t)n, (uint32_t)idx, 2u);
+  auto prob4 = [&](int i0, float (&r)[4]) {
+    if ((V & 3) == 0 && i0 + 3 < V) {
+      const float4 a = *(const float4*)(x + i0);
+      r[0] = __expf(a.x * inv_t - z); r[1] = __expf(a.y * inv_t - z);
+      r[2] = __expf(a.z * inv_t - z); r[3] = __expf(a.w * inv_t - z);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = (i0 + e < V) ? __expf(x[i0 + e] * inv_t - z) : 0.f;
+    }
+  };
+  const int token = inverse_cdf_block(prob4, V, u, s_tile, s_w, &s_tile_sel, &s_before);
+  if (threadIdx.x == 0 && token >= 0) {   // (no mass cannot happen for a softmax; the arg-max proposal would stay)
+    xhat[o] = token;
+    p[o] = expf(x[token] * inv_t - z);
+  }
+}
+
 // One workgroup per sequence: accept scan over C_t (thread 0), then, if a drafted token failed,
 // draw from the residual (P_ver - P_draft)_+ by inverse CDF in ascending vocabulary order.
 __global__ __launch_bounds__(256) void accept_kernel(
     int B, int V, uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev, float gamma, int resample,
-    const int32_t* __restrict__ span_start, const int32_t* __restrict__ span_len,
+    float inv_t, const int32_t* __restrict__ span_start, const int32_t* __restrict__ span_len,
     const float* __restrict__ logits_d, const int32_t* __restrict__ row_of_d,
     const float* __restrict__ logits_v, const int32_t* __restrict__ row_of_v,
     const int32_t* __restrict__ xhat, const float* __restrict__ p, const float* __restrict__ lse_d,
@@ -285,92 +413,26 @@ __global__ __launch_bounds__(256) void accept_kernel(
     if (tid == 0) { n_accept[n] = acc; n_commit[n] = acc; resampled[n] = -1; }
     return;
   }
-  // ---- residual at block index i: r(v) = max(0, Q(v) - P(v)) ----
+  // ---- residual at block index i: r(v) = max(0, Q(v) - P(v)), both at the sampling temperature ----
   const int o = n * B + j + acc;
   const float* ld = logits_d + (size_t)row_of_d[o] * V;
   const float* lv = logits_v + (size_t)row_of_v[o] * V;
   const float zd = lse_d[o], zv = lse_v[o];
-  const int tiles = (V + RTILE - 1) / RTILE;
-  const int lane = tid & 63, w = tid >> 6;
-  const bool vec_ok = (V & 3) == 0;
-  for (int t = w; t < tiles; t += 4) {
-    const int i0 = t * RTILE + lane * 4;
-    float r = 0.f;
-    if (vec_ok && i0 + 3 < V) {
-      const float4 a = *(const float4*)(ld + i0), b = *(const float4*)(lv + i0);
-      r = ((fmaxf(0.f, __expf(b.x - zv) - __expf(a.x - zd)) + fmaxf(0.f, __expf(b.y - zv) - __expf(a.y - zd))) +
-           fmaxf(0.f, __expf(b.z - zv) - __expf(a.z - zd))) + fmaxf(0.f, __expf(b.w - zv) - __expf(a.w - zd));
-    } else {
-      for (int e = 0; e < 4; ++e)
-        if (i0 + e < V) r += fmaxf(0.f, __expf(lv[i0 + e] - zv) - __expf(ld[i0 + e] - zd));
-    }
-    for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
-    if (lane == 0) s_tile[t] = r;
-  }
-  __syncthreads();
-  // scan tile sums: thread t owns tiles [t*per, (t+1)*per)
-  const int per = (tiles + 255) / 256;
-  float mine = 0.f;
-  for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) mine += s_tile[t];
-  float total, excl;
-  const float incl = block_scan_256(mine, s_w, &excl, &total);
   const float u2 = uniform01(seed, stp, (uint32_t)n, (uint32_t)(j + acc), 1u);
-  const float target = u2 * total;
-  if (tid == 0) { s_tile_sel = -1; s_before = 0.f; }
-  __syncthreads();
-  if (excl <= target && target < incl) {  // exactly one thread: the intervals tile [0, total)
-    float run = excl, before = excl;
-    int sel = -1, last = -1;
-    for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) {
-      const float ts = s_tile[t];
-      if (ts > 0.f) { last = t; before = run; }
-      if (ts > 0.f && run + ts > target) { sel = t; break; }
-      run += ts;
+  auto residual4 = [&](int i0, float (&r)[4]) {
+    if ((V & 3) == 0 && i0 + 3 < V) {
+      const float4 a = *(const float4*)(ld + i0), b = *(const float4*)(lv + i0);
+      r[0] = fmaxf(0.f, __expf(b.x * inv_t - zv) - __expf(a.x * inv_t - zd));
+      r[1] = fmaxf(0.f, __expf(b.y * inv_t - zv) - __expf(a.y * inv_t - zd));
+      r[2] = fmaxf(0.f, __expf(b.z * inv_t - zv) - __expf(a.z * inv_t - zd));
+      r[3] = fmaxf(0.f, __expf(b.w * inv_t - zv) - __expf(a.w * inv_t - zd));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        r[e] = (i0 + e < V) ? fmaxf(0.f, __expf(lv[i0 + e] * inv_t - zv) - __expf(ld[i0 + e] * inv_t - zd)) : 0.f;
     }
-    if (sel < 0) sel = last;          // rounding: take the thread's last tile that has mass
-    s_tile_sel = sel;
-    s_before = before;
-  }
-  __syncthreads();
-  int sel = s_tile_sel;
-  int token = -1;
-  if (total > 0.f && sel < 0) {  // target landed at or beyond the total by rounding: last tile with mass
-    if (tid == 0) {
-      for (int t = tiles - 1; t >= 0; --t)
-        if (s_tile[t] > 0.f) { s_tile_sel = t; break; }
-      float run = 0.f;
-      for (int t = 0; t < s_tile_sel; ++t) run += s_tile[t];
-      s_before = run;
-    }
-    __syncthreads();
-    sel = s_tile_sel;
-  }
-  if (total > 0.f && sel >= 0 && w == 0) {  // wave 0 walks the selected tile in index order
-    const int i0 = sel * RTILE + lane * 4;
-    float r4[4];
-    float ls = 0.f;
-    for (int e = 0; e < 4; ++e) {
-      r4[e] = (i0 + e < V) ? fmaxf(0.f, __expf(lv[i0 + e] - zv) - __expf(ld[i0 + e] - zd)) : 0.f;
-      ls += r4[e];
-    }
-    float inc = ls;
-    for (int off = 1; off < 64; off <<= 1) {
-      const float t = __shfl_up(inc, off, 64);
-      if (lane >= off) inc += t;
-    }
-    float run = s_before + (inc - ls);
-    int cand = 0x7fffffff, last_pos = -1;
-    for (int e = 0; e < 4; ++e) {
-      if (r4[e] > 0.f) last_pos = i0 + e;
-      run += r4[e];
-      if (cand == 0x7fffffff && r4[e] > 0.f && run > target) cand = i0 + e;
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-      cand = min(cand, __shfl_xor(cand, off, 64));
-      last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
-    }
-    token = cand != 0x7fffffff ? cand : last_pos;
-  }
+  };
+  int token = inverse_cdf_block(residual4, V, u2, s_tile, s_w, &s_tile_sel, &s_before);
   if (tid == 0) {
     if (token < 0) token = xhat[o];  // residual without mass in fp32 (p and q equal to rounding): keep the draft
     block[o] = token;
@@ -381,12 +443,12 @@ __global__ __launch_bounds__(256) void accept_kernel(
 }
 
 void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t step, const uint32_t* step_dev,
-                   float gamma, int resample, const int32_t* span_start, const int32_t* span_len,
+                   float gamma, int resample, float inv_t, const int32_t* span_start, const int32_t* span_len,
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
                    int32_t* resampled, float* u_used, const int32_t* active) {
-  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample,
+  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample, inv_t,
                      span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
                      n_accept, n_commit, resampled, u_used, active);
 }

@@ -222,6 +222,7 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
     rep = rep or Report()
     seqs = range(case.N) if seqs is None else seqs
     tau = float(np.float32(prm.tau))
+    mode, T = int(prm.mode), (float(np.float32(prm.temperature)) if int(prm.mode) == O.SAMPLE else 1.0)
     # MoE: window rows are packed sequence after sequence; the oracle is held to the GPU's expert choices
     moe = cfg.is_moe
     if moe:
@@ -256,13 +257,18 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
             err = np.abs(gl - od.logits).max() / scale
             rep.max_logit_err_draft = max(rep.max_logit_err_draft, err)
             assert err <= LOGIT_RTOL, f"seq {n}: draft logits off by {err:.3e} of max|logit|"
-        d = O.draft_from_logits(st, win, gl, cfg.mask_id, tau)
+        d = O.draft_from_logits(st, win, gl, cfg.mask_id, tau, mode, T, prm.seed, prm.step, n)
         xhat = g["xhat"][n].astype(np.int64).copy()
         for r, i in enumerate(win.logit_index):
-            P, _ = O.log_softmax_stats(gl[r])
+            P, _ = O.log_softmax_stats(gl[r], T)
             top2 = np.sort(P)[-2:]
             if xhat[i] != d.xhat[i]:
-                assert top2[1] - top2[0] < TIE and abs(P[xhat[i]] - top2[1]) < TIE, f"seq {n} pos {i}: x_hat {xhat[i]} vs {d.xhat[i]}"
+                if mode == O.SAMPLE:   # the inverse CDF lands within rounding of a boundary between the two tokens
+                    cdf = np.cumsum(P)
+                    ud = O.uniform(prm.seed, prm.step, n, int(i), O.STREAM_DRAFT)
+                    assert abs(cdf[min(xhat[i], d.xhat[i])] - ud) < TIE, f"seq {n} pos {i}: sampled x_hat {xhat[i]} vs {d.xhat[i]}"
+                else:
+                    assert top2[1] - top2[0] < TIE and abs(P[xhat[i]] - top2[1]) < TIE, f"seq {n} pos {i}: x_hat {xhat[i]} vs {d.xhat[i]}"
                 rep.exempt_xhat += 1
                 d.xhat[i] = xhat[i]
                 d.p[i] = P[xhat[i]]
@@ -294,14 +300,14 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
             err = np.abs(gv - ov.logits).max() / np.abs(ov.logits).max()
             rep.max_logit_err_verify = max(rep.max_logit_err_verify, err)
             assert err <= LOGIT_RTOL, f"seq {n}: verifier logits off by {err:.3e} of max|logit|"
-        vo = O.verify_from_logits(vwin, gv, xhat, ov.k if ov else None, ov.v if ov else None)
+        vo = O.verify_from_logits(vwin, gv, xhat, ov.k if ov else None, ov.v if ov else None, mode, T)
         for r, i in enumerate(vwin.logit_index):
             e = abs(float(g["q"][n, i]) - vo.q[r])
             rep.max_prob_err = max(rep.max_prob_err, e)
             assert e <= PROB_ATOL, f"seq {n} pos {i}: q {g['q'][n, i]} vs {vo.q[r]}"
         # ---- stage 4: accept ---------------------------------------------------------------------
         d.xhat, d.logits = xhat, gl
-        a = O.accept(st, d, vo, prm.seed, prm.step, n, gamma=prm.gamma, resample=bool(prm.resample))
+        a = O.accept(st, d, vo, prm.seed, prm.step, n, mode=mode, temperature=T, gamma=prm.gamma, resample=bool(prm.resample))
         j, L = vwin.j, vwin.L
         np.testing.assert_array_equal(g["u_used"][n, j:j + min(L, int(g["n_accept"][n]) + 1)].astype(np.float64),
                                       a.u[:min(L, int(g["n_accept"][n]) + 1)])
@@ -317,7 +323,7 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
         if res_gpu != a.resampled:
             assert a.resampled >= 0 and res_gpu >= 0
             i = j + a.n_accept
-            r = O.residual_distribution(gl[list(win.logit_index).index(i)], gv[a.n_accept])
+            r = O.residual_distribution(gl[list(win.logit_index).index(i)], gv[a.n_accept], T)
             cdf = np.cumsum(r) / r.sum()
             u2 = O.uniform(prm.seed, prm.step, n, i, O.STREAM_RESAMPLE)
             assert abs(cdf[min(res_gpu, a.resampled)] - u2) < TIE, f"seq {n}: resampled {res_gpu} vs {a.resampled}"

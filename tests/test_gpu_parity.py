@@ -410,3 +410,36 @@ def test_routing_scores_decisions_and_the_routed_step():
         S_or, _ = O.threshold_set(gp, before[n] == SMALL_BF16.mask_id, float(np.float32(prm.tau)))
         assert (S == S_or).all() or (np.abs(gp[before[n] == SMALL_BF16.mask_id] - prm.tau) < H.TIE).any()
     print("routing: decisions", dv.astype(int).tolist(), "scores", np.round(ro.score.cpu().numpy(), 3).tolist(), "near-threshold skips", near)
+
+
+def test_accept_variants_ratio_tempering_and_reject_only():
+    """Ablation flags of the accept step (appendix on acceptance variants): u < min(1, (q/p)^gamma) with gamma != 1,
+    and rejection without the residual draw."""
+    for kw in (dict(gamma=0.5), dict(gamma=2.0), dict(resample=0), dict(gamma=0.25, resample=0)):
+        case = H.make_case(SMALL_BF16, 3, 8, [60, 45, 90], seed=8, synthetic_kv=True, page_size=16, room=64)
+        run, rep = run_steps(case, 2, prm_kw=kw, check_logits=False)
+        print("accept variant", kw, "n_accept", rep.n_accept, "n_commit", rep.n_commit)
+        if kw.get("resample", 1) == 0:
+            assert rep.n_commit == rep.n_accept          # nothing is committed at the rejected position
+        else:
+            assert all(c >= 1 for c in rep.n_commit)
+
+
+def test_sampling_mode_drafting_at_temperature_half():
+    """SAMPLE-mode drafting (the paper's T = 0.5 ablation): proposals drawn from softmax(logits / T) with the stream-2
+    uniforms, p, q and the residual all at that temperature."""
+    from paper_2603_25702_amd.binding import S2D2_SAMPLE
+    for T in (0.5, 1.0):
+        case = H.make_case(SMALL_BF16, 3, 8, [60, 45, 90], seed=12, synthetic_kv=True, page_size=16, room=64)
+        run, rep = run_steps(case, 3, prm_kw=dict(mode=S2D2_SAMPLE, temperature=T), check_logits=(T == 0.5))
+        print(f"sampling T={T}:", rep)
+        assert all(c >= 1 for c in rep.n_commit)
+    # the proposals really are samples: at T = 1 on near-uniform rows they differ from the arg-max somewhere
+    case = H.make_case(SMALL_BF16, 2, 8, [40, 41], seed=13, synthetic_kv=True, page_size=16, room=64)
+    run = H.GpuRun(case)
+    run.eng.s2d2_draft(run.kv, run.st, 2, 8, Params(step=0, seed=5), run.d)
+    greedy = run.fetch()["xhat"].copy()
+    run.eng.s2d2_draft(run.kv, run.st, 2, 8, Params(step=0, seed=5, mode=S2D2_SAMPLE, temperature=4.0), run.d)
+    sampled = run.fetch()
+    assert (sampled["xhat"] != greedy).any()
+    assert (sampled["p"] > 0).all() and (sampled["p"] <= 1).all()
