@@ -804,6 +804,7 @@ int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
   if (!c || !name || !ptr) return fail(S2D2_EINVAL, "NULL argument");
   const struct { const char* n; void* p; } tab[] = {{"h", c->h}, {"a", c->a}, {"q", c->qbuf}, {"o", c->obuf}, {"ffn", c->ffn},
                                                     {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->moe_y_or_scratch}};
+  if (!strcmp(name, "stream_ts")) { launch_stream_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
   if (!strcmp(name, "tile_ts")) { launch_tile_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
   if (!strcmp(name, "attn_ts")) { launch_attn_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
   for (const auto& t : tab)

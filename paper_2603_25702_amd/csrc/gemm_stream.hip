@@ -89,11 +89,24 @@ __device__ __forceinline__ float tile_total(const float* s_red, int t, int fe, i
   return v;
 }
 
+#ifdef S2D2_FUSED_TIMING
+__device__ unsigned long long g_stream_ts[4][16];   // [epilogue kind][first workgroup: 0-7, last workgroup: 8-15]
+// stamps are kept in registers and written once at the end: a store in the middle of the kernel would turn the
+// scalar loads after it into vector loads (possible aliasing) and so change what is being timed
+#define S2D2_GTS(k) do { ts_[(k)] = wall_clock64(); } while (0)
+#else
+#define S2D2_GTS(k) do {} while (0)
+#endif
+
 template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
   extern __shared__ __align__(16) uint8_t smem_raw[];
+#ifdef S2D2_FUSED_TIMING
+  unsigned long long ts_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  S2D2_GTS(0);
   const int m0 = blockIdx.y * 16;
   int M = 0;
   if (blockIdx.y != 0) {  // further row tiles exist only for wide windows: do not stream weights for nothing
@@ -117,72 +130,125 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     wp[t * NACC] = (const u32x4_t*)a.Wp + (size_t)nt * KT * 64 + lane;
     if (NACC == 2) wp[t * NACC + 1] = (const u32x4_t*)a.Wp2 + (size_t)nt * KT * 64 + lane;
   }
+  // Loads are unconditional with addresses clamped to the wavefront's share; a slot whose tile lies past the
+  // share is never multiplied (uniform test before its MFMAs), and window rows past the row count read row 0:
+  // their accumulator rows are never stored.  No select ever sits between a load and its use.
   u32x4_t w[TA][U];
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int t = 0; t < TA; ++t) w[t][u] = (kt_begin + u < kt_end) ? wp[t][(size_t)(kt_begin + u) * 64] : zero;
+    for (int t = 0; t < TA; ++t) w[t][u] = wp[t][(size_t)max(0, min(kt_begin + u, kt_end - 1)) * 64];
 
   if (blockIdx.y == 0) M = *a.m_count;
   const int Mloc = min(16, M - m0);
   if (Mloc <= 0) return;  // whole workgroup (M is uniform)
 
   const bool row_ok = f < Mloc;
-  const int xrow = row_ok ? (a.gather ? a.gather[m0 + f] : m0 + f) : 0;
+  // Row gathering exists for the unembedding only (its rows are the window's logit rows).  Compiled out of the
+  // layer GEMMs: the index load would put a wait for ALL earlier loads (the weight stream) in front of the
+  // activation loads, also on launches that do not gather.
+  constexpr bool CAN_GATHER = EPI == SEPI_STORE_F32;
+  const int32_t* gather = CAN_GATHER ? a.gather : nullptr;
+  const int xrow_i = m0 + (row_ok ? f : 0);
+  const int xrow = gather ? gather[xrow_i] : xrow_i;
   const bf16_t* xg = a.X + (size_t)xrow * a.ldx + g * 8;
   u32x4_t xb[U], xl[SPLIT ? U : 1];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    xb[u] = (row_ok && kt_begin + u < kt_end) ? *(const u32x4_t*)(xg + (kt_begin + u) * 32) : zero;
-    if (SPLIT) xl[u] = (row_ok && kt_begin + u < kt_end) ? *(const u32x4_t*)(xg + a.x_lo + (kt_begin + u) * 32) : zero;
+    const int kc = max(0, min(kt_begin + u, kt_end - 1));   // (an empty share reads tile 0 and multiplies nothing)
+    xb[u] = *(const u32x4_t*)(xg + kc * 32);
+    if (SPLIT) xl[u] = *(const u32x4_t*)(xg + a.x_lo + kc * 32);
   }
 
-  if (PRO == SPRO_BF16S && threadIdx.x < 256) {  // 1/rms of the 16 rows from the producer's partial sums
-    const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
-    float v = 0.f;
-    if (row < Mloc) {
-      const float* pp = a.ss_part + (size_t)(a.gather ? a.gather[m0 + row] : m0 + row) * a.ss_stride;
-      for (int i = sub; i < a.ss_count; i += 16) v += pp[i];
+  // 1/rms of the 16 rows from the producer's partial sums of squares: 16 threads per row.  The partials are only
+  // REQUESTED here, as independent 16-byte loads (up to four per thread, in flight together with the operand
+  // stream); they are added up after the K loop, where the result is first needed.  Reading them one after the
+  // other at this point cost eight dependent cache round trips before the first MFMA (5-9 us per launch).
+  constexpr int SSV = 4;   // float4 per thread: covers ss_count <= 256, i.e. K <= 4096 (wider: the loop below)
+  float4 ssv[SSV];
+  const bool ss_vec = PRO == SPRO_BF16S && a.ss_count <= 64 * SSV && (a.ss_count & 3) == 0 && (a.ss_stride & 3) == 0;
+  const int ss_row = threadIdx.x >> 4, ss_sub = threadIdx.x & 15;
+  const float* ss_pp = nullptr;
+  if (PRO == SPRO_BF16S && threadIdx.x < 256) {
+    const int rr = m0 + min(ss_row, Mloc - 1);   // rows past the count read a valid row; their 1/rms is never used
+    ss_pp = a.ss_part + (size_t)(gather ? gather[rr] : rr) * a.ss_stride;
+    if (ss_vec) {
+      const int n4 = a.ss_count >> 2;
+#pragma unroll
+      for (int j = 0; j < SSV; ++j) {
+        ssv[j] = ((const float4*)ss_pp)[min(ss_sub + 16 * j, n4 - 1)];   // clamped duplicates are skipped when summing
+      }
     }
-    v += __shfl_xor(v, 1, 64);
-    v += __shfl_xor(v, 2, 64);
-    v += __shfl_xor(v, 4, 64);
-    v += __shfl_xor(v, 8, 64);
-    if (sub == 0) s_rs[row] = 1.0f / sqrtf(v / (float)a.K + a.eps);
   }
 
   f32x4_t acc[TA];
 #pragma unroll
   for (int t = 0; t < TA; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  S2D2_GTS(1);
+#ifdef S2D2_FUSED_TIMING
+  if (w[0][0][0] == 0x12345678u && Mloc < 0) return;   // (timing aid: the first weight tile has arrived)
+  S2D2_GTS(2);
+#endif
 
-  for (int kt0 = kt_begin; kt0 < kt_end;) {
+  // The K loop is a sliding window: register slot u is refilled (weights and activations of the tile U steps on)
+  // right after the MFMAs that consumed it have been issued, so a wavefront keeps U tiles in flight continuously
+  // instead of loading a batch, draining it, and paying the memory latency again for the next batch.  Whether
+  // a batch refills at all is one uniform branch per batch (the last batch of a wavefront's share does not);
+  // inside a refilling batch every load is unconditional (addresses clamped to the share), because a load under
+  // a per-tile branch, or a select on its result, would make the compiler drain the window first.
+  auto mac = [&](int u) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int t = 0; t < TA; ++t) {
+    for (int t = 0; t < TA; ++t) {
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
+                                                       __builtin_bit_cast(bf16x8_t, xb[u]), acc[t], 0, 0, 0);
+      if (SPLIT)  // low-order plane of the activations: same weights, second product
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
-                                                         __builtin_bit_cast(bf16x8_t, xb[u]), acc[t], 0, 0, 0);
-        if (SPLIT)  // low-order plane of the activations: same weights, second product
-          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
-                                                           __builtin_bit_cast(bf16x8_t, xl[u]), acc[t], 0, 0, 0);
-      }
-    kt0 += U;
-    if (kt0 < kt_end) {  // next batch (the layer matrices are sized so that one batch covers a wavefront's share)
+                                                         __builtin_bit_cast(bf16x8_t, xl[u]), acc[t], 0, 0, 0);
+    }
+  };
+  for (int kt0 = kt_begin; kt0 < kt_end; kt0 += U) {
+    if (kt0 + U < kt_end) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
+        mac(u);   // a refilling batch is complete: kt0 + U - 1 < kt_end
+        const int kc = max(0, min(kt0 + U + u, kt_end - 1));
 #pragma unroll
-        for (int t = 0; t < TA; ++t) w[t][u] = (kt0 + u < kt_end) ? wp[t][(size_t)(kt0 + u) * 64] : zero;
-        xb[u] = (row_ok && kt0 + u < kt_end) ? *(const u32x4_t*)(xg + (kt0 + u) * 32) : zero;
-        if (SPLIT) xl[u] = (row_ok && kt0 + u < kt_end) ? *(const u32x4_t*)(xg + a.x_lo + (kt0 + u) * 32) : zero;
+        for (int t = 0; t < TA; ++t) w[t][u] = wp[t][(size_t)kc * 64];
+        xb[u] = *(const u32x4_t*)(xg + kc * 32);
+        if (SPLIT) xl[u] = *(const u32x4_t*)(xg + a.x_lo + kc * 32);
       }
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (kt0 + u < kt_end) mac(u);
     }
   }
   // acc[t][i] = Y[m0 + f][tile t, feature 4 g + i]
+#ifdef S2D2_FUSED_TIMING
+  if (acc[0][0] == 12345.678f && Mloc < 0) return;
+#endif
+  S2D2_GTS(3);
+  if (PRO == SPRO_BF16S && threadIdx.x < 256) {
+    float v = 0.f;
+    if (ss_vec) {
+#pragma unroll
+      for (int j = 0; j < SSV; ++j)
+        if (ss_sub + 16 * j < (a.ss_count >> 2)) v += (ssv[j].x + ssv[j].y) + (ssv[j].z + ssv[j].w);
+    } else {
+      for (int i = ss_sub; i < a.ss_count; i += 16) v += ss_pp[i];
+    }
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 8, 64);
+    if (ss_sub == 0) s_rs[ss_row] = 1.0f / sqrtf(v / (float)a.K + a.eps);
+  }
 #pragma unroll
   for (int t = 0; t < TA; ++t)
 #pragma unroll
     for (int i = 0; i < 4; ++i) s_red[((size_t)wave * TA + t) * 256 + i * 64 + lane] = acc[t][i];
   __syncthreads();
+  S2D2_GTS(4);
   if (threadIdx.x >= 256) return;
   const int row = threadIdx.x >> 4, fe = threadIdx.x & 15;
   const int m = m0 + row;
@@ -265,7 +331,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     }
   }
 #undef S2D2_TOTAL
+#ifdef S2D2_FUSED_TIMING
+  __builtin_amdgcn_s_waitcnt(0);
+  S2D2_GTS(5);
+  if (threadIdx.x == 0 && blockIdx.y == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1))
+    for (int k = 0; k < 6; ++k) g_stream_ts[EPI][(blockIdx.x == 0 ? 0 : 8) + k] = ts_[k];
+#endif
 }
+
+#ifdef S2D2_FUSED_TIMING
+__global__ void stream_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = (&g_stream_ts[0][0])[threadIdx.x]; }
+void launch_stream_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(stream_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
+#else
+void launch_stream_ts_copy(hipStream_t, void*) {}
+#endif
 
 template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
 static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
@@ -301,6 +380,10 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
       else if (variant[0] == 1) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8);
       else if (variant[0] == 2) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 16, 1, 4);
       else if (variant[0] == 3) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 2, 1, 8);
+      else if (variant[0] == 4) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 4);
+      else if (variant[0] == 5) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 4);
+      else if (variant[0] == 6) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 2);
+      else if (variant[0] == 7) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 2);
       else S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 8);
       break;
     case SEPI_ADD_F32:
@@ -308,9 +391,15 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
         if (variant[1] == 1) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
         else if (variant[1] == 2) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 6);
         else if (variant[1] == 4) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 4, 1, 8);
+        else if (variant[1] == 5) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 2);
+        else if (variant[1] == 6) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 4);
+        else if (variant[1] == 7) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 3);
         else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
       } else {
         if (variant[1] == 3) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
+        else if (variant[1] == 5) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 2);
+        else if (variant[1] == 6) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 4);
+        else if (variant[1] == 8) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 2);
         else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
       }
       break;
@@ -319,12 +408,19 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
       else if (variant[2] == 2) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 8);
       else if (variant[2] == 3) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 4);
       else if (variant[2] == 4) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 4);
+      else if (variant[2] == 5) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 4);
+      else if (variant[2] == 6) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 2);
+      else if (variant[2] == 7) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 2);
+      else if (variant[2] == 8) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 16, 1, 2);
       else S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 8);
       break;
     case SEPI_STORE_F32:
       if (variant[3] == 1) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8);
       else if (variant[3] == 2) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 2, 2, 4);
       else if (variant[3] == 3) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 1, 8);
+      else if (variant[3] == 4) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 2);
+      else if (variant[3] == 5) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 8, 2, 2);
+      else if (variant[3] == 6) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 8, 1, 4);
       else S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 4);
       break;
   }
