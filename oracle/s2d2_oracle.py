@@ -634,6 +634,81 @@ def step_routed(cfg, W, st: SeqState, cache_k, cache_v, tau: float, seed: int, s
     return d, r, vo, a
 
 
+# --------------------------------------------------------------------------------------
+# Alg. 1, lines after SampleBlock: forward over the finished block, whole-block cache append.
+# --------------------------------------------------------------------------------------
+def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: List[np.ndarray]) -> int:
+    """Once the block holds no [MASK]: one forward over its tokens that are not cached yet (and over
+    carried tokens of earlier blocks, which stay causal), with the block's rows attending to the whole
+    block (block-diffusion attention), and append of all their K/V.  Returns the rows appended (0 if the
+    block is unfinished).  This is the cache update of the variant that does not cache causally inside a
+    block (Section 4.2 describes the causal alternative the incremental append relies on)."""
+    block = np.asarray(st.block)
+    if (block == cfg.mask_id).any():
+        return 0
+    c = st.n_cached_in_block()
+    carry = np.asarray(st.carry, dtype=np.int64)
+    toks = np.concatenate([carry, block[c:].astype(np.int64)])
+    n, nc = len(toks), len(carry)
+    if n == 0:
+        return 0
+    pos = st.seq_len + np.arange(n)
+    vis = np.zeros((n, n), dtype=bool)
+    for r in range(n):
+        if r < nc:
+            vis[r, :r + 1] = True          # carried tokens: causal
+        else:
+            vis[r, :] = True               # block rows: everything in the window
+    fo = forward(cfg, W, toks, pos, vis, cache_k, cache_v, logit_rows=np.zeros(0, dtype=np.int64))
+    for l in range(cfg.n_layers):
+        cache_k[l] = np.concatenate([f64(cache_k[l]), fo.k[l]], axis=0)
+        cache_v[l] = np.concatenate([f64(cache_v[l]), fo.v[l]], axis=0)
+    st.seq_len += n
+    st.carry = np.zeros(0, dtype=np.int64)
+    return n
+
+
+def generate(cfg, W, st: SeqState, cache_k, cache_v, n_blocks: int, tau: float, seed: int, rp: RouteParams,
+             max_steps_per_block: int, caching: str = "causal", seq: int = 0, mode: int = GREEDY,
+             temperature: float = 1.0):
+    """Alg. 1's outer loop around the block sampler of Alg. 3, for n_blocks blocks, at most max_steps_per_block
+    denoising steps per block (a block that runs out of steps commits the threshold set of a tau = 0 pass, i.e.
+    every remaining proposal).  caching = "causal": the accepted prefix is appended after every verified step
+    (Section 4.2); "block": nothing is appended inside a block (drafting then sees the block fully
+    bidirectionally) and the finished block is appended by block_complete.  Returns the committed tokens and
+    the per-step records."""
+    assert caching in ("causal", "block")
+    out, log, h, step_idx = [], [], H_ON, 0
+    B = len(st.block)
+    for _ in range(n_blocks):
+        for t in range(max_steps_per_block + 1):
+            last = t == max_steps_per_block
+            ar = caching == "causal"
+            d = draft(cfg, W, st, cache_k, cache_v, 0.0 if last else tau, ar, mode, temperature, seed, step_idx, seq)
+            r = route(st, d, cfg.mask_id, rp, h)
+            h = r["h"]
+            if last:
+                r = dict(r, verify=False)
+                d.unmask = np.asarray(st.block) == cfg.mask_id     # out of steps: commit every proposal
+            if r["verify"]:
+                vo = verify(cfg, W, st, cache_k, cache_v, d.xhat, mode, temperature)
+                a = accept(st, d, vo, seed, step_idx, seq, mode, temperature)
+                st.block = a.block
+                if caching == "causal":
+                    kv_append(st, cache_k, cache_v, vo, a.n_accept)
+                log.append(("verify", a.n_accept, a.n_commit))
+            else:
+                log.append(("threshold", 0, commit_threshold(st, d)))
+            step_idx += 1
+            if not (np.asarray(st.block) == cfg.mask_id).any():
+                break
+        out.extend(int(x) for x in st.block)
+        if caching == "block":
+            block_complete(cfg, W, st, cache_k, cache_v)
+        block_advance(st, cfg.mask_id)
+    return out, log
+
+
 def prefill(cfg, W, ids: np.ndarray, chunk: int = 256):
     """Prefix cache by a plain causal forward over the prompt (not on the hot path)."""
     ck = [np.zeros((0, cfg.n_kv_heads, cfg.head_dim)) for _ in range(cfg.n_layers)]

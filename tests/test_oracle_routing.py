@@ -174,3 +174,83 @@ def test_route_record_matches_its_parts(model):
     assert r["L"] == 3 and r["khat"] == pytest.approx(float(np.cumprod(al).sum()), rel=1e-12)
     assert r["score"] == pytest.approx(r["khat"] - 0.25 * d.n_hi, rel=1e-12)
     assert r["verify"] == (r["score"] >= 0.1)
+
+
+# ---------------------------------------------------------------- block completion and the outer loop (Alg. 1)
+def test_block_complete_equals_one_forward_over_prefix_and_block(model):
+    # K/V appended for a finished block = K/V of the same tokens in a single forward over [prefix, block] from an
+    # empty cache whose mask is causal on the prefix and block-bidirectional on the block.
+    W, prefix, ck, cv = model
+    B = 4
+    st = fresh(len(prefix), B)
+    st.block = np.array([3, 17, 29, 5], dtype=np.int64)
+    k, v = list(ck), list(cv)
+    assert O.block_complete(CFG, W, st, k, v) == B and st.seq_len == len(prefix) + B
+    toks = np.concatenate([prefix, [3, 17, 29, 5]])
+    n, P = len(toks), len(prefix)
+    vis = np.tril(np.ones((n, n), dtype=bool))
+    vis[P:, P:] = True
+    empty = [np.zeros((0, CFG.n_kv_heads, CFG.head_dim)) for _ in range(CFG.n_layers)]
+    fo = O.forward(CFG, W, toks, np.arange(n), vis, empty, empty, logit_rows=np.zeros(0, dtype=np.int64))
+    for l in range(CFG.n_layers):
+        np.testing.assert_allclose(k[l][P:], fo.k[l][P:], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(v[l][P:], fo.v[l][P:], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(k[l][:P], ck[l], rtol=0, atol=0)        # the prefix rows are untouched
+    # the first layer's K/V do not depend on the mask; deeper layers do (the block is not cached causally)
+    causal_k, _ = O.prefill(CFG, W, toks)
+    np.testing.assert_allclose(k[0][P:], causal_k[0][P:], rtol=0, atol=1e-12)
+    assert np.abs(k[1][P:P + B - 1] - causal_k[1][P:P + B - 1]).max() > 1e-6
+
+
+def test_block_complete_of_a_one_token_block_is_causal_append_and_unfinished_blocks_are_left(model):
+    W, prefix, ck, cv = model
+    st = fresh(len(prefix), 1)
+    st.block = np.array([33], dtype=np.int64)
+    k, v = list(ck), list(cv)
+    O.block_complete(CFG, W, st, k, v)
+    ref_k, ref_v = O.prefill(CFG, W, np.concatenate([prefix, [33]]))
+    for l in range(CFG.n_layers):
+        np.testing.assert_allclose(k[l], ref_k[l], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(v[l], ref_v[l], rtol=0, atol=1e-12)
+    st2 = fresh(len(prefix), 4)
+    st2.block[1] = 9
+    k2 = list(ck)
+    assert O.block_complete(CFG, W, st2, k2, list(cv)) == 0 and st2.seq_len == len(prefix) and k2[0] is ck[0]
+
+
+def test_generate_commits_whole_blocks_and_both_cachings_end_with_a_full_cache(model):
+    W, prefix, ck, cv = model
+    B, nb = 4, 3
+    rp = O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=2)
+    for caching in ("causal", "block"):
+        st = fresh(len(prefix), B)
+        k, v = list(ck), list(cv)
+        toks, log = O.generate(CFG, W, st, k, v, nb, 0.9, seed=5, rp=rp, max_steps_per_block=6, caching=caching)
+        assert len(toks) == nb * B and all(0 <= t < CFG.vocab and t != MASK for t in toks)
+        assert st.pos0 == len(prefix) + nb * B and (st.block == MASK).all()
+        assert sum(c for _, _, c in log) == nb * B                       # every step's commits add up to the blocks
+        assert all(kind == "threshold" or c >= 1 for kind, _, c in log)   # a verified step always commits something
+        if caching == "block":
+            assert st.seq_len == st.pos0 and k[0].shape[0] == st.pos0     # every finished block is cached whole
+            # cached K/V of the generated blocks = block-diffusion forward over the final text
+            full = np.concatenate([prefix, toks])
+            n, P = len(full), len(prefix)
+            vis = np.tril(np.ones((n, n), dtype=bool))
+            for b in range(nb):
+                vis[P + b * B:P + (b + 1) * B, P + b * B:P + (b + 1) * B] = True
+            empty = [np.zeros((0, CFG.n_kv_heads, CFG.head_dim)) for _ in range(CFG.n_layers)]
+            fo = O.forward(CFG, W, full, np.arange(n), vis, empty, empty, logit_rows=np.zeros(0, dtype=np.int64))
+            np.testing.assert_allclose(k[1], fo.k[1], rtol=0, atol=1e-10)
+        else:
+            assert st.seq_len + len(st.carry) == st.pos0                  # causal caching may trail by carried tokens
+            ref_k, _ = O.prefill(CFG, W, np.concatenate([prefix, toks])[:st.seq_len])
+            np.testing.assert_allclose(k[1], ref_k[1], rtol=0, atol=1e-10)   # AR caching = causal prefill of the text
+
+
+def test_generate_step_cap_forces_completion(model):
+    W, prefix, ck, cv = model
+    st = fresh(len(prefix), 4)
+    rp = O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=99)              # never verify
+    toks, log = O.generate(CFG, W, st, list(ck), list(cv), 1, 2.0, seed=1, rp=rp, max_steps_per_block=1, caching="block")
+    # tau above 1: a threshold step commits only the arg-max position; the cap then commits the rest at once
+    assert [c for _, _, c in log] == [1, 3] and len(toks) == 4
