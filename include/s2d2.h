@@ -254,6 +254,15 @@ int32_t s2d2_kv_append(s2d2_ctx* ctx, const s2d2_kv_view* kv, int32_t N, int32_t
 int32_t s2d2_block_advance(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_block_state* st,
                            int32_t N, int32_t B, uint32_t* step_dev /* device or NULL */);
 
+/* Alg. 1 after the block sampler, for decoding that does not append to the cache inside a block: for every sequence
+ * whose block holds no [MASK], one forward over its tokens that are not cached yet (carried tokens of earlier blocks
+ * stay causal, the block's rows attend to the whole block: block-diffusion attention) and append of their K/V;
+ * seq_len advances by the rows appended, kv->status reports S2D2_ENOSPC as in s2d2_kv_append.  Sequences whose
+ * block still holds a [MASK] are left alone.  `scratch` supplies the staging buffers (a verify output of the same
+ * limits; its contents are overwritten).  Call s2d2_block_advance afterwards. */
+int32_t s2d2_block_complete(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
+                            const s2d2_verify_out* scratch);
+
 /* Alg. 2 commit: x^b_i <- x_hat_i for every i in the draft's threshold set. */
 int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_t B,
                               const s2d2_draft_out* draft);

@@ -22,7 +22,7 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
-    "s2d2_commit_threshold", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
+    "s2d2_commit_threshold", "s2d2_block_complete", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
 PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "forward")
 
@@ -130,6 +130,8 @@ def load_library():
     lib.s2d2_block_advance.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
                                        C.c_void_p]
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
+    lib.s2d2_block_complete.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
+                                        C.POINTER(VerifyOutC)]
     lib.s2d2_route.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(RouteParamsC), C.POINTER(DraftOutC), C.c_void_p,
                                C.POINTER(RouteOutC)]
     lib.s2d2_status.argtypes = [C.c_void_p]
@@ -143,7 +145,7 @@ def load_library():
     lib.s2d2_profile_start.argtypes = [C.c_void_p, C.c_int32]
     lib.s2d2_profile_stop.argtypes = [C.c_void_p, C.POINTER(ProfileC)]
     for name in ("s2d2_profile_start", "s2d2_profile_stop", "s2d2_destroy", "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append",
-                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
+                 "s2d2_block_advance", "s2d2_commit_threshold", "s2d2_block_complete", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score"):
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
     return lib
@@ -399,6 +401,9 @@ class Engine:
 
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
+
+    def s2d2_block_complete(self, kv: KvCache, st: BlockState, N, B, scratch: VerifyOut):
+        _check(self.lib, self.lib.s2d2_block_complete(self.ctx, C.byref(kv.c()), C.byref(st.c()), N, B, C.byref(scratch.c())))
 
     def s2d2_route(self, N, B, rp: RouteParams, draft: DraftOut, hysteresis: Optional[torch.Tensor], out: RouteOut):
         _check(self.lib, self.lib.s2d2_route(self.ctx, N, B, C.byref(rp.c_struct()), C.byref(draft.c()), _ptr(hysteresis),

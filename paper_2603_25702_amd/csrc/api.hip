@@ -58,6 +58,7 @@ struct s2d2_ctx {
   bool force_generic_attention;
   VocabWs vws;
   float2* rope_cs;   // [rows_cap, D/2] cos / sin of the window rows
+  int32_t* zeros_i32;  // [max_batch] zeros (never written)
   float* ss;         // [rows_cap, d/16] partial sums of squares of the residual rows (split RMSNorm)
   // packed bf16 weights (streaming GEMM); null when the caller gave no packed buffer
   struct PackedLayer { const uint4 *wqkv, *wo, *wg, *wu, *wdown, *router, *eg, *eu, *ed; };
@@ -189,6 +190,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   }
   c->rope_cs = cv.take<float2>(R * (size_t)(d.head_dim / 2));
   c->ss = cv.take<float>(R * (size_t)((d.d_model + 15) / 16));
+  c->zeros_i32 = cv.take<int32_t>(NB);
   if (d.n_experts > 0) {
     const size_t RK = R * (size_t)d.top_k;
     c->router_logits = cv.take<float>(R * (size_t)d.n_experts);
@@ -611,6 +613,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     }
   }
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
+  launch_fill_i32(c->stream, c->zeros_i32, c->max_batch, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
@@ -670,7 +673,7 @@ int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* 
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) || (rc = check_draft_out(out))) return rc;
   const s2d2_model_desc& d = c->desc;
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, false, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 0, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
               st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
   { ProfScope ps(c, 2, 0.0); launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
@@ -688,7 +691,7 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
       (rc = check_draft_out(draft)) || (rc = check_verify_out(out)))
     return rc;
   const s2d2_model_desc& d = c->desc;
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, true, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 1, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
               draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
   S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
@@ -724,6 +727,22 @@ int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B
                    ver->k_stage, ver->v_stage, ver->stage_row0, ver->stage_lead, draft->span_len, n_accept,
                    kv->seq_len, kv->status, B); }
   return check_launch("s2d2_kv_append");
+}
+
+int32_t s2d2_block_complete(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
+                            const s2d2_verify_out* scratch) {
+  int32_t rc;
+  if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_verify_out(scratch))) return rc;
+  const s2d2_model_desc& d = c->desc;
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 2, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+              nullptr, c->plan, scratch->logit_row_of, nullptr, nullptr, scratch->stage_row0, scratch->stage_lead, nullptr); }
+  if ((rc = forward(c, kv, N, B, scratch->k_stage, scratch->v_stage, scratch->logits_ver))) return rc;
+  const KvGeom g = geom(c, kv);
+  // every staged row is appended: lead = rows, accepted = 0 (the zero array stands in for n_accept and span_len)
+  { ProfScope ps(c, 3, 0.0); launch_kv_append(c->stream, d.dtype, d.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
+                   scratch->k_stage, scratch->v_stage, scratch->stage_row0, scratch->stage_lead, c->zeros_i32, c->zeros_i32,
+                   kv->seq_len, kv->status, B); }
+  return check_launch("s2d2_block_complete");
 }
 
 int32_t s2d2_block_advance(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,

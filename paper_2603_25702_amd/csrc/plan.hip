@@ -35,8 +35,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     while (j + L < B && blk[j + L] == mask_id) ++L;
     c = min(c, j);
     lead = nc + (j - c);
-    if (verify && active && active[n] == 0) { L = 0; lead = 0; }   // routed to the fallback: no verifier window
-    if (verify) { rows = lead + 2 * L; lrows = L; }
+    if (verify == 1 && active && active[n] == 0) { L = 0; lead = 0; }   // routed to the fallback: no verifier window
+    if (verify == 2) {            // block completion: all uncached tokens of a finished block, no logits
+      rows = n_masked == 0 ? nc + (B - c) : 0;
+      lead = rows;
+      lrows = 0;
+    } else if (verify) { rows = lead + 2 * L; lrows = L; }
     else        { rows = nc + (B - c); lrows = n_masked; }
   }
   s_rows[n] = rows;
@@ -90,6 +94,19 @@ __global__ __launch_bounds__(1024) void plan_kernel(
       p.row_lo[r] = row0;
       p.row_hi[r] = hi;
     }
+  } else if (verify == 2) {
+    // Alg. 1 after the block sampler: carried tokens stay causal, the block's rows attend to the whole window
+    // (block-diffusion attention); every row is staged for the cache
+    stage_row0[n] = row0;
+    stage_lead[n] = rows;
+    for (int t = 0; t < rows; ++t) {
+      const int r = row0 + t;
+      p.row_token[r] = t < nc ? car[t] : blk[c + (t - nc)];
+      p.row_pos[r] = S + t;
+      p.row_seq[r] = n;
+      p.row_lo[r] = row0;
+      p.row_hi[r] = t < nc ? r + 1 : row0 + rows;
+    }
   } else {
     stage_row0[n] = row0;
     stage_lead[n] = lead;
@@ -123,12 +140,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(
   }
 }
 
-void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
+void launch_plan(hipStream_t st, int verify, int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
                  const int32_t* active) {
-  S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify ? 1 : 0, N, B, mask_id, ar_mask,
+  S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify, N, B, mask_id, ar_mask,
                      seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
                      stage_row0, stage_lead, active);
 }

@@ -102,7 +102,7 @@ enum GemmEpilogue {
 };
 
 // plan.hip
-void launch_plan(hipStream_t st, bool verify, int N, int B, int mask_id, int ar_mask,
+void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block completion */, int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,

@@ -115,6 +115,65 @@ class Session:
         e.s2d2_commit_threshold(self.st, N, B, self._d_fallback)
         e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
 
+    def generate(self, prm: Params, rp: RouteParams, n_blocks: int, max_steps_per_block: int, caching: str = "causal"):
+        """Alg. 1's outer loop around the routed block sampler, for n_blocks blocks per sequence.  Host-driven: after
+        every step the block tokens are read back to see which blocks are finished (one small copy per step).
+        caching = "causal": the accepted prefix is appended after every verified step; "block": nothing is appended
+        inside a block, drafting is fully bidirectional, and a finished block is appended by s2d2_block_complete.
+        A block that has used max_steps_per_block steps commits all remaining proposals on its next step.
+        Returns the committed tokens per sequence and the (kind, n_accept, n_commit) record of every step."""
+        assert caching in ("causal", "block")
+        N, B, e, mask = self.N, self.B, self.eng, self.cfg.mask_id
+        if not hasattr(self, "route"):
+            self.route = RouteOut.alloc(N, self.dev)
+            self.hysteresis = torch.ones(N, dtype=torch.int32, device=self.dev)
+            self._d_fallback = DraftOut({**self.d.t, "unmask": self.route.unmask_fallback})
+        steps_in_block, blocks_done = [0] * N, [0] * N
+        out, log = [[] for _ in range(N)], [[] for _ in range(N)]
+        step = prm.step
+        while any(b < n_blocks for b in blocks_done):
+            p = dataclasses.replace(prm, step=step, ar_mask=1 if caching == "causal" else 0)
+            e.s2d2_draft(self.kv, self.st, N, B, p, self.d)
+            e.s2d2_route(N, B, rp, self.d, self.hysteresis, self.route)
+            blk = self.st.block_tokens.cpu().numpy()
+            dv = self.route.do_verify.cpu().numpy().copy()
+            fb = self.route.unmask_fallback.cpu().numpy().copy()
+            forced = False
+            for n in range(N):
+                if blocks_done[n] >= n_blocks:                     # finished sequences idle
+                    dv[n], fb[n], forced = 0, 0, True
+                elif steps_in_block[n] >= max_steps_per_block:     # out of steps: commit every proposal
+                    dv[n], fb[n], forced = 0, sum(1 << i for i in range(B) if blk[n, i] == mask), True
+            if forced:
+                self.route.do_verify.copy_(torch.from_numpy(dv))
+                self.route.unmask_fallback.copy_(torch.from_numpy(fb))
+            pr = dataclasses.replace(p, active=self.route.do_verify)
+            e.s2d2_verify(self.kv, self.st, N, B, pr, self.d, self.v)
+            e.s2d2_accept(self.st, N, B, pr, self.d, self.v, self.a)
+            if caching == "causal":
+                e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
+            e.s2d2_commit_threshold(self.st, N, B, self._d_fallback)
+            if caching == "block":
+                e.s2d2_block_complete(self.kv, self.st, N, B, self.v)
+            after = self.st.block_tokens.cpu().numpy()
+            n_acc, n_com = self.a.n_accept.cpu().numpy(), self.a.n_commit.cpu().numpy()
+            for n in range(N):
+                if blocks_done[n] >= n_blocks:
+                    continue
+                if dv[n]:
+                    log[n].append(("verify", int(n_acc[n]), int(n_com[n])))
+                else:
+                    log[n].append(("threshold", 0, int(bin(int(fb[n]) & ((1 << B) - 1)).count("1"))))
+                if (after[n] != mask).all():
+                    out[n].extend(int(x) for x in after[n])
+                    blocks_done[n] += 1
+                    steps_in_block[n] = 0
+                else:
+                    steps_in_block[n] += 1
+            e.s2d2_block_advance(self.kv, self.st, N, B, None)
+            step += 1
+        return out, log
+
     def capture_step(self, prm: Params):
         """Records one step (plus the on-device running totals of accepted and committed tokens) into a HIP graph
         and returns it; `graph.replay()` then enqueues the whole step with one host call.  The RNG step word advances

@@ -443,3 +443,31 @@ def test_sampling_mode_drafting_at_temperature_half():
     sampled = run.fetch()
     assert (sampled["xhat"] != greedy).any()
     assert (sampled["p"] > 0).all() and (sampled["p"] <= 1).all()
+
+
+def test_generate_loop_routed_with_step_cap_under_both_cachings():
+    """Alg. 1's outer loop on the device (draft, DoVerify, verify+accept or threshold commit, cache append per step or
+    per finished block, block roll-over) against the oracle's generate, free-running on the tiny fp32 model."""
+    from oracle import s2d2_oracle as O
+    from paper_2603_25702_amd.binding import RouteParams
+    from paper_2603_25702_amd.runner import Session
+    cfg, N, B, nb, cap = TINY, 2, 3, 3, 4
+    for caching in ("causal", "block"):
+        W = I.gen_weights(cfg, 15, norm_jitter=0.1)
+        prefixes = [I.gen_prefix_ids(cfg, L, 15, n) for n, L in enumerate([21, 34])]
+        sess = Session(cfg, W, N, B, max_seq=34 + nb * B + 16, page_size=8)
+        sess.prefill(prefixes)
+        rp = RouteParams(policy=0, tau_span=2)
+        toks, log = sess.generate(Params(seed=77), rp, nb, cap, caching)
+        for n in range(N):
+            ck, cv = O.prefill(cfg, W, np.asarray(prefixes[n]))
+            st = O.SeqState(seq_len=len(prefixes[n]), pos0=len(prefixes[n]), block=np.full(B, cfg.mask_id, dtype=np.int64))
+            ot, ol = O.generate(cfg, W, st, ck, cv, nb, float(np.float32(0.9)), seed=77,
+                                rp=O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=2), max_steps_per_block=cap,
+                                caching=caching, seq=n)
+            assert toks[n] == ot, (caching, n, toks[n], ot)
+            assert log[n] == ol, (caching, n, log[n], ol)
+        sl = sess.kv.seq_len.cpu().numpy()
+        if caching == "block":
+            assert [int(x) for x in sl] == [len(p) + nb * B for p in prefixes]
+        print("generate", caching, "tokens", toks, "steps", [len(l) for l in log])
