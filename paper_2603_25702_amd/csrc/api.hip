@@ -98,7 +98,7 @@ struct s2d2_ctx {
 
 namespace {
 
-constexpr int TILE_PARTIAL_CAP = 1280, TILE_COUNTER_CAP = 4096;
+constexpr int TILE_PARTIAL_CAP = 4096, TILE_COUNTER_CAP = 4096;
 
 struct Carver {
   uint8_t* base;
@@ -313,7 +313,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int32_t* n_rows = c->plan.counts;
   const bool fused = c->pk != nullptr;
   const int ss_stride = (d.d_model + 15) / 16;
-  auto sk = [&](GemmStreamArgs& x) {   // split-K buffers of the tiled GEMM
+  // rows a fresh block gives: N*B draft rows, 2*N*B verifier rows (more only with carried or pending committed tokens)
+  const int m_hint = (k_stage ? 2 : 1) * N * B;
+  auto sk = [&](GemmStreamArgs& x) {   // split-K buffers of the tiled GEMM, expected rows
+    x.m_hint = x.m_count == c->plan.counts + 1 ? N * B : m_hint;   // (logit rows: one per masked position)
     x.tile_partials = c->tile_partials; x.tile_counters = c->tile_counters;
     x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
   };

@@ -26,6 +26,7 @@
 #include "../../include/s2d2.h"
 
 #include <algorithm>
+#include <stdlib.h>
 
 namespace s2d2 {
 
@@ -381,13 +382,28 @@ template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
   constexpr int COLS = EPI == SEPI_SWIGLU ? 4 : 8;   // 16-feature tiles per workgroup
   const int col_tiles = (a.NT + COLS - 1) / COLS;
-  // split K until about 768 workgroups exist (two are resident per compute unit), within the partial buffer
+  // Two workgroups are resident per compute unit, so a "round" is 512 workgroups.  K is split when the tiles alone
+  // fill the rounds badly: among 1..8 splits the one with the best fill of whole rounds wins, a split being charged
+  // 20 % for its partial round trip and shorter K loop (measured: flat from 15 to 50 %, worse below; ties: fewer
+  // splits); every split keeps at least 4 K steps and the partials must
+  // fit their buffer.  The fill is judged on the rows the caller expects (m_hint; the grid still covers the row
+  // capacity, workgroups of row tiles past the device-side row count exit at once).
   int KS = 1;
   const long long tiles = (long long)col_tiles * row_tiles;
+  const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
+  const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
-  if (a.tile_partials && a.grouped == GROUP_NONE && tiles < 384) {
-    KS = (int)std::min<long long>(std::min<long long>(8, (512 + tiles - 1) / tiles), std::max(1, nk / 4));
-    while (KS > 1 && (tiles * KS > a.tile_partial_cap || tiles > a.tile_counter_cap)) --KS;
+  static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aids
+  static const double split_cost = getenv("S2D2_TILE_SPLIT_COST") ? atof(getenv("S2D2_TILE_SPLIT_COST")) : 0.2;
+  if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
+    double best = 0.0;
+    for (int ks = 1; ks <= 8; ++ks) {
+      if (ks > 1 && (nk / ks < 4 || tiles * ks > a.tile_partial_cap)) break;
+      const long long wgs = live * ks, rounds = (wgs + 511) / 512;
+      const double fill = (double)wgs / (double)(rounds * 512) / (1.0 + split_cost * (ks - 1));
+      if (fill > best + 1e-9) { best = fill; KS = ks; }
+    }
+    if (ks_override > 0 && nk / ks_override >= 4 && tiles * ks_override <= a.tile_partial_cap) KS = ks_override;
   }
   dim3 grid(col_tiles, row_tiles, KS), block(256);
   if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);

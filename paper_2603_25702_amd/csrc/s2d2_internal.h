@@ -137,6 +137,7 @@ struct GemmStreamArgs {
   const uint4* Wp2;         // second matrix (up projection) for SEPI_SWIGLU
   int32_t NT, KT, N, K;
   const int32_t* m_count;   // device: number of valid rows
+  int32_t m_hint;           // host: rows the caller expects (0 = unknown); only steers the choice of launch shape
   const bf16_t* X;          // activations [*, ldx] (for SPRO_BF16S: h * gain, not yet divided by the rms)
   int32_t ldx;
   int32_t x_lo;             // element offset, inside a row of X, of the low-order bf16 plane (0: single plane)
