@@ -113,7 +113,11 @@ struct Carver {
 
 int elt_size(int dtype) { return dtype == S2D2_BF16 ? 2 : 4; }
 // bf16 planes in which GEMM inputs are carried (the workspace is sized for this; the plain kernels use one)
-int act_planes(const s2d2_model_desc& d) { return d.dtype == S2D2_BF16 && d.act_planes != 1 ? 2 : 1; }
+int act_planes(const s2d2_model_desc& d) {
+  static const int forced = getenv("S2D2_ACT_PLANES") ? atoi(getenv("S2D2_ACT_PLANES")) : 0;   // measurement aid
+  const int want = forced == 1 || forced == 2 ? forced : d.act_planes;
+  return d.dtype == S2D2_BF16 && want != 1 ? 2 : 1;
+}
 
 int32_t check_desc(const s2d2_model_desc* d) {
   if (!d) return fail(S2D2_EINVAL, "model description is NULL");
