@@ -382,26 +382,29 @@ template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
   constexpr int COLS = EPI == SEPI_SWIGLU ? 4 : 8;   // 16-feature tiles per workgroup
   const int col_tiles = (a.NT + COLS - 1) / COLS;
-  // Two workgroups are resident per compute unit, so a "round" is 512 workgroups.  K is split when the tiles alone
-  // fill the rounds badly: among 1..8 splits the one with the best fill of whole rounds wins, a split being charged
-  // 20 % for its partial round trip and shorter K loop (measured: flat from 15 to 50 %, worse below; ties: fewer
-  // splits); every split keeps at least 4 K steps and the partials must
-  // fit their buffer.  The fill is judged on the rows the caller expects (m_hint; the grid still covers the row
-  // capacity, workgroups of row tiles past the device-side row count exit at once).
+  // K is split over blockIdx.z when that shortens the launch.  The choice minimises a small cost model fitted to
+  // kernel traces of the batched configurations (microseconds; two workgroups are resident per compute unit, so a
+  // round is 512 workgroups):
+  //   rounds * (K steps per split * 1.64 + 6)                      K loop (both planes) + prologue / epilogue per round
+  //   + [splits > 1] * (8 + live tiles * splits * 128 KB / 3 TB/s)  partial write + read by the last arrival
+  // It is judged on the rows the caller expects (m_hint; the grid still covers the row capacity, workgroups of
+  // row tiles past the device-side row count exit at once).  Every split keeps at least 4 K steps and the
+  // partials must fit their buffer.  E.g. 512 verifier rows of the 8B shape: gate/up 1 split (222 us; 2 splits
+  // measured 236), QKV 2, O projection 4, down projection 4.
   int KS = 1;
   const long long tiles = (long long)col_tiles * row_tiles;
   const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
   const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
-  static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aids
-  static const double split_cost = getenv("S2D2_TILE_SPLIT_COST") ? atof(getenv("S2D2_TILE_SPLIT_COST")) : 0.2;
+  static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aid
   if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
-    double best = 0.0;
+    double best = 1e30;
     for (int ks = 1; ks <= 8; ++ks) {
       if (ks > 1 && (nk / ks < 4 || tiles * ks > a.tile_partial_cap)) break;
-      const long long wgs = live * ks, rounds = (wgs + 511) / 512;
-      const double fill = (double)wgs / (double)(rounds * 512) / (1.0 + split_cost * (ks - 1));
-      if (fill > best + 1e-9) { best = fill; KS = ks; }
+      const double rounds = (double)((live * ks + 511) / 512), steps = (double)((nk + ks - 1) / ks);
+      double t = rounds * (steps * 1.64 + 6.0);
+      if (ks > 1) t += 8.0 + (double)live * ks * 131072.0 / 3.0e6;
+      if (t < best - 1e-9) { best = t; KS = ks; }
     }
     if (ks_override > 0 && nk / ks_override >= 4 && tiles * ks_override <= a.tile_partial_cap) KS = ks_override;
   }
