@@ -117,14 +117,14 @@ class LazyF64Weights(dict):
 class GpuRun:
     """Device-side mirror of a Case plus output buffers; methods call the C ABI."""
 
-    def __init__(self, case: Case, device: str = "cuda:0", session=None, packed: bool = True):
+    def __init__(self, case: Case, device: str = "cuda:0", session=None, packed: bool = True, act_planes: int = 0):
         cfg, N, B = case.cfg, case.N, case.B
         self.case, self.dev = case, torch.device(device)
         if session is not None:  # wrap the buffers of a runner.Session (cache already on the device)
             self.eng, self.kv, self.st = session.eng, session.kv, session.st
             self.d, self.v, self.a = session.d, session.v, session.a
             return
-        self.eng = Engine(cfg, case.W, N, B, device, packed=packed)
+        self.eng = Engine(cfg, case.W, N, B, device, packed=packed, act_planes=act_planes)
         i32 = torch.int32
         kdev = torch.empty((cfg.n_layers,) + tuple(case.k_pages[0].shape), dtype=cfg.torch_dtype, device=self.dev)
         vdev = torch.empty((cfg.n_layers,) + tuple(case.v_pages[0].shape), dtype=cfg.torch_dtype, device=self.dev)

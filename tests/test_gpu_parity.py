@@ -13,8 +13,8 @@ TINY = I.CONFIGS[1].cfg
 SMALL_BF16 = I.ModelCfg("small-bf16", 2, 512, 8, 4, 128, 1536, 32000)
 
 
-def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True, packed=True):
-    run = H.GpuRun(case, packed=packed)
+def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True, packed=True, act_planes=0):
+    run = H.GpuRun(case, packed=packed, act_planes=act_planes)
     rep = H.Report()
     for s in range(steps):
         prm = Params(step=s, seed=1234, **(prm_kw or {}))
@@ -169,6 +169,19 @@ def test_small_bf16_wide_windows_run_the_tiled_gemm():
     run, rep = run_steps(case, 3)
     print("small bf16 wide:", rep)
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
+
+
+def test_single_activation_plane_narrow_and_wide_windows():
+    """`act_planes = 1` in the model description: activations as one bf16 plane (the single-plane instantiations of
+    the streaming and tiled GEMMs and of both attention kernels).  Two layers keep the rounding well inside the
+    tolerance; the 28- and 36-layer configurations need both planes."""
+    case = H.make_case(SMALL_BF16, 3, 4, [100, 257, 31], seed=21, synthetic_kv=True, page_size=16, room=64)
+    run, rep = run_steps(case, 2, act_planes=1)
+    print("one plane, narrow:", rep)
+    case = H.make_case(SMALL_BF16, 3, 16, [100, 257, 31], seed=22, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
+    run, rep2 = run_steps(case, 2, act_planes=1)
+    print("one plane, wide:", rep2)
+    assert max(rep.max_logit_err_draft, rep2.max_logit_err_draft) <= H.LOGIT_RTOL
 
 
 def test_small_moe_routing_grouped_gemm_and_combine():
