@@ -143,6 +143,25 @@ def main():
         for name in ("gemm", "forward"):
             if prof[name]["launches"]:
                 phases[name]["hbm_GBs"] = round(prof[name]["bytes"] / (prof[name]["ms"] * 1e-3) / 1e9, 1)
+        # Per-phase HBM rate and MFMA use from the workload's shapes (nominal rows of fresh blocks: N*B draft rows,
+        # 2*N*B verifier rows, N*B logit rows per forward; cached lengths = mean of before and after the pass)
+        es = 2 if cfg.dtype == "bf16" else 4
+        S_mean = 0.5 * (float(np.sum(lens)) + float(ses.kv.seq_len.sum().item()))
+        kv_bytes = 2 * cfg.n_layers * S_mean * 2 * cfg.n_kv_heads * cfg.head_dim * es          # both forwards, K and V once
+        attn_flops = cfg.n_layers * (N * B + 2 * N * B) / N * 4.0 * cfg.n_q_heads * cfg.head_dim * S_mean
+        per_layer = cfg.d_model * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim + cfg.n_q_heads * cfg.head_dim * cfg.d_model
+        per_layer += (cfg.top_k * 3 * cfg.d_model * cfg.d_expert + cfg.d_model * cfg.n_experts) if cfg.is_moe else 3 * cfg.d_model * cfg.d_ffn
+        gemm_flops = 2.0 * (3 * N * B * cfg.n_layers * per_layer + 2 * N * B * cfg.d_model * cfg.vocab)
+        vocab_bytes = 2 * N * B * cfg.vocab * 4.0                                                # draft and verifier logits read once
+        MFMA_PEAK = 2.5e15 if cfg.dtype == "bf16" else 157.3e12
+        if prof["attention"]["launches"]:
+            t = prof["attention"]["ms"] * 1e-3 / Kp
+            phases["attention"]["hbm_GBs"] = round(kv_bytes / t / 1e9, 1)
+            phases["attention"]["mfma_pct"] = round(100 * attn_flops / t / MFMA_PEAK, 2)
+        if prof["gemm"]["launches"]:
+            phases["gemm"]["mfma_pct"] = round(100 * gemm_flops / (prof["gemm"]["ms"] * 1e-3 / Kp) / MFMA_PEAK, 2)
+        if prof["vocab"]["launches"]:
+            phases["vocab"]["hbm_GBs"] = round(vocab_bytes / (prof["vocab"]["ms"] * 1e-3 / Kp) / 1e9, 1)
         log(f"[bench] profile pass ({Kp} steps): {json.dumps(phases)}")
 
     # ---- the fp64 oracle on the host cores: one full step of the same workload ---------------------
