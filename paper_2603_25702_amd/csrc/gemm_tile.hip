@@ -26,6 +26,7 @@
 #include "../../include/s2d2.h"
 
 #include <algorithm>
+#include <type_traits>
 #include <stdlib.h>
 
 namespace s2d2 {
@@ -40,8 +41,11 @@ __device__ unsigned long long g_tile_ts[64];
 
 // SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
 // of a row sit side by side in LDS and every weight operand is multiplied with both.
-template <int EPI, int PRO, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
+template <int EPI, int PRO, bool SPLIT, int WC>
+__global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
+  constexpr int NTH = 128 * WC;                   // 2 x WC wavefronts of 64 rows x 64 features each
+  constexpr int XI = 1024 / NTH;                  // 16-byte chunks of an activation plane tile per thread
+  constexpr int XD = WC == 4 ? 2 : 1;             // K steps the activation loads run ahead of their LDS store
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int FT = 4 / NACC;                    // feature tiles per wavefront and matrix; FT * NACC = 4 accumulator columns
   constexpr int WS = 3;                           // weight stages in flight
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, f = lane & 15;
-  const int wr = wave >> 1, wc = wave & 1;
+  const int wr = wave / WC, wc = wave % WC;
   S2D2_TTS(0);
   int m0, Mloc, expert = 0;
   if (a.grouped != GROUP_NONE) {
@@ -67,10 +71,13 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
     Mloc = min(TM, M - m0);
   }
   const int KT = a.KT;
-  const int nt0 = blockIdx.x * (2 * FT) + wc * FT;
+  // live 16-row blocks of this wavefront's 64 rows, as a scalar: the skips in the K loop are then plain scalar
+  // branches and not execution-mask regions
+  const int rb_live = __builtin_amdgcn_readfirstlane(min(4, max(0, (Mloc - wr * 64 + 15) >> 4)));
+  const int nt0 = blockIdx.x * (WC * FT) + wc * FT;
 
   // ---- row maps: source row of X, row of the partial sums of squares, destination row, scale ----
-  {
+  if (tid < 256) {
     const int r = tid >> 1, hf = tid & 1;   // two threads per row
     int xrow = -1, orow = -1, ssrow = 0;
     float ow = 1.f;
@@ -111,15 +118,15 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
 
   S2D2_TTS(1);
   // ---- operand addressing ----
-  const int c16 = tid & 7, rbase = tid >> 3;   // this thread stages rows rbase + 32 i, bytes [16 c16, +16) of the 128
+  const int c16 = tid & 7, rbase = tid >> 3;   // this thread stages rows rbase + (NTH / 8) i, bytes [16 c16, +16) of the 128
   // Loads in the K loop are unconditional (clamped addresses, values of invalid rows / columns replaced when
   // they are stored to LDS): a load under a branch would make the compiler wait for every outstanding load
   // before the MFMA block and so undo the weight pipeline.
-  const bf16_t* xsrc[4];
-  bool xok[4];
+  const bf16_t* xsrc[XI];
+  bool xok[XI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int xr_ = s_xrow[rbase + 32 * i];
+  for (int i = 0; i < XI; ++i) {
+    const int xr_ = s_xrow[rbase + (NTH / 8) * i];
     xok[i] = xr_ >= 0;
     xsrc[i] = a.X + (size_t)(xok[i] ? xr_ : 0) * a.ldx + c16 * 8;
   }
@@ -140,50 +147,63 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
 
   const int nk = (a.K + TK - 1) / TK, KS = gridDim.z, z = blockIdx.z;
   const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
-  u32x4_t xr[4], xl[SPLIT ? 4 : 1], wst[WS][2][4];
-  auto load_x = [&](int kb) {
-    const int ko = min(kb * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      xr[i] = *(const u32x4_t*)(xsrc[i] + ko);
-      if (SPLIT) xl[i] = *(const u32x4_t*)(xsrc[i] + a.x_lo + ko);
-    }
+  u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1], wst[WS][2][4];
+  constexpr int XL = XI * (SPLIT ? 2 : 1);   // activation loads per thread and step
+  // One of the XL activation loads of a step: chunk j % XI of plane j / XI.  Unconditional: past the split's last
+  // step the loads re-read an earlier tile into a register set nobody stores any more.
+  auto load_x1 = [&](u32x4_t (&r)[XI], u32x4_t (&l)[SPLIT ? XI : 1], int kb, int j) {
+    const int ko = min(min(kb, nk - 1) * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
+    if (j < XI) r[j] = *(const u32x4_t*)(xsrc[j] + ko);
+    else l[j - XI] = *(const u32x4_t*)(xsrc[j - XI] + a.x_lo + ko);
   };
-  auto load_w = [&](u32x4_t (&w)[2][4], int kb) {
-#pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-      const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
-#pragma unroll
-      for (int t = 0; t < 4; ++t) w[k2][t] = wp[t][(size_t)kt * 64];
-    }
+  auto load_w1 = [&](u32x4_t& w, int kb, int k2, int t) {
+    const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
+    w = wp[t][(size_t)kt * 64];
   };
-  auto store_x = [&](int buf, int kb) {
+  auto store_x = [&](const u32x4_t (&r)[XI], const u32x4_t (&l)[SPLIT ? XI : 1], int buf, int kb) {
     const bool kok = kb * TK + c16 * 8 < a.K;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < XI; ++i) {
       const bool ok = xok[i] && kok;
-      *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + c16 * 16) = ok ? xr[i] : zero;
-      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + 32 * i) * XROW + 128 + c16 * 16) = ok ? xl[i] : zero;
+      *(u32x4_t*)(s_x[buf] + (rbase + (NTH / 8) * i) * XROW + c16 * 16) = ok ? r[i] : zero;
+      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + (NTH / 8) * i) * XROW + 128 + c16 * 16) = ok ? l[i] : zero;
     }
   };
 
+  // Step j (counted from this split's first step) multiplies out of weight stage j % WS and LDS buffer j & 1.
+  // Its activation tile travels through register set j % XD: requested during step j - XD, stored to LDS at the
+  // end of step j - 1.  The weights of step j + WS - 1 are requested during step j into the stage step j - 1 has
+  // just left.  Both kinds of requests are issued one at a time between the MFMA blocks of the step: a burst of
+  // all of them at the step's end keeps the address unit busy for as long as the MFMAs of the step take, with
+  // every wavefront of the workgroup waiting in it at the same time.
 #pragma unroll
-  for (int st_ = 0; st_ < WS; ++st_) load_w(wst[st_], kb0 + st_);
-  load_x(kb0);
-  store_x(0, kb0);
+  for (int st_ = 0; st_ < WS - 1; ++st_)
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) load_w1(wst[st_][k2][t], kb0 + st_, k2, t);
+#pragma unroll
+  for (int d = 0; d < XD; ++d)
+#pragma unroll
+    for (int j = 0; j < XL; ++j) load_x1(xr[d], xl[d], kb0 + d, j);
+  store_x(xr[0], xl[0], 0, kb0);
   __syncthreads();
-  for (int kbase = kb0; kbase < kb1; kbase += WS) {
+  constexpr int UN = WS * 2;   // unrolled steps: weight stage and register set / LDS buffer are compile-time
+  // FULL: all UN steps exist.  The group that may end early is a second copy of the body: an exit out of the
+  // unrolled body makes the compiler's wait-count bookkeeping drain every outstanding load in the first step of
+  // each group (weights and activations requested for later steps included), and with it the weight pipeline.
+  auto group = [&](auto full_tag, int kbase) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-    for (int st_ = 0; st_ < WS; ++st_) {   // stage st_ holds the weights of step kbase + st_
-      const int kb = kbase + st_;
-      if (kb >= kb1) break;
-      if (kb + 1 < kb1) load_x(kb + 1);
-      const uint8_t* xb = s_x[(kb - kb0) & 1] + (wr * 64 + f) * XROW + g * 16;
+    for (int u_ = 0; u_ < UN; ++u_) {
+      const int st_ = u_ % WS, rs_ = (u_ + WS - 1) % WS;   // stage multiplied from, stage refilled
+      const int kb = kbase + u_;
+      if (!FULL && kb >= kb1) break;
+      const uint8_t* xb = s_x[u_ & 1] + (wr * 64 + f) * XROW + g * 16;
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-          if (wr * 64 + rb * 16 >= Mloc) continue;   // 16-row block past the tile's rows (uniform over the wavefront)
+      for (int blk = 0; blk < 8; ++blk) {
+        const int k2 = blk >> 2, rb = blk & 3;
+        if (rb < rb_live) {   // else: 16-row block past the tile's rows
           const u32x4_t b = *(const u32x4_t*)(xb + rb * 16 * XROW + k2 * 64);
 #pragma unroll
           for (int t = 0; t < 4; ++t)
@@ -197,12 +217,20 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
                                                                    __builtin_bit_cast(bf16x8_t, bl), acc[rb][t], 0, 0, 0);
           }
         }
+        load_w1(wst[rs_][k2][rb], kb + WS - 1, k2, rb);
+        // activation loads: over the first four blocks when they are stored at this step's end, over all eight else
+        constexpr int XB = XD == 1 ? 4 : 8;
+#pragma unroll
+        for (int j = 0; j < XL; ++j)
+          if (j * XB / XL == blk) load_x1(xr[u_ % XD], xl[u_ % XD], kb + XD, j);
       }
-      load_w(wst[st_], kb + WS);   // refill this stage: WS - 1 steps of MFMA work cover the latency
-      if (kb + 1 < kb1) store_x((kb + 1 - kb0) & 1, kb + 1);
+      if (kb + 1 < kb1) store_x(xr[(u_ + 1) % XD], xl[(u_ + 1) % XD], (u_ + 1) & 1, kb + 1);
       __syncthreads();
     }
-  }
+  };
+  int kbase = kb0;
+  for (; kbase + UN <= kb1; kbase += UN) group(std::true_type{}, kbase);
+  if (kbase < kb1) group(std::false_type{}, kbase);
 
   if (acc[0][0][0] == 12345.678f) return;
   S2D2_TTS(2);
@@ -213,16 +241,16 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
   // past the tile's rows are neither written nor read.
   if (KS > 1) {
     const size_t tile_id = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
-    uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * 8192 + tid;
+    uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
       if (wr * 64 + rb * 16 >= Mloc) continue;   // uniform over the wavefront
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const f32x4_t v = acc[rb][t];
-        __hip_atomic_store(mine + ((rb * 4 + t) * 2) * 256, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
+        __hip_atomic_store(mine + ((rb * 4 + t) * 2) * NTH, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mine + ((rb * 4 + t) * 2 + 1) * 256, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
+        __hip_atomic_store(mine + ((rb * 4 + t) * 2 + 1) * NTH, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
@@ -243,13 +271,13 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const GemmStreamArgs 
 #pragma unroll
       for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int zz = 0; zz < KS; ++zz) {
-      const uint64_t* src = (const uint64_t*)a.tile_partials + (tile_id * KS + zz) * 8192 + tid;
+      const uint64_t* src = (const uint64_t*)a.tile_partials + (tile_id * KS + zz) * (32 * NTH) + tid;
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
         if (wr * 64 + rb * 16 >= Mloc) continue;
         uint64_t v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = __hip_atomic_load(src + (rb * 8 + e) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int e = 0; e < 8; ++e) v[e] = __hip_atomic_load(src + (rb * 8 + e) * NTH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           acc[rb][t][0] += __uint_as_float((uint32_t)v[2 * t]);
@@ -378,39 +406,40 @@ void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_k
 void launch_tile_ts_copy(hipStream_t, void*) {}
 #endif
 
-template <int EPI, int PRO>
+template <int EPI, int PRO, int WC>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
-  constexpr int COLS = EPI == SEPI_SWIGLU ? 4 : 8;   // 16-feature tiles per workgroup
+  constexpr int COLS = (EPI == SEPI_SWIGLU ? 2 : 4) * WC;   // 16-feature tiles per workgroup
+  constexpr int RESIDENT = WC == 2 ? 512 : 256;             // workgroups of one round over the chip
+  constexpr double PART_BYTES = 32768.0 * WC;                // fp32 partial of one tile and split
   const int col_tiles = (a.NT + COLS - 1) / COLS;
-  // K is split over blockIdx.z when that shortens the launch.  The choice minimises a small cost model fitted to
-  // kernel traces of the batched configurations (microseconds; two workgroups are resident per compute unit, so a
-  // round is 512 workgroups):
-  //   rounds * (K steps per split * 1.64 + 6)                      K loop (both planes) + prologue / epilogue per round
-  //   + [splits > 1] * (8 + live tiles * splits * 128 KB / 3 TB/s)  partial write + read by the last arrival
-  // It is judged on the rows the caller expects (m_hint; the grid still covers the row capacity, workgroups of
-  // row tiles past the device-side row count exit at once).  Every split keeps at least 4 K steps and the
-  // partials must fit their buffer.  E.g. 512 verifier rows of the 8B shape: gate/up 1 split (222 us; 2 splits
-  // measured 236), QKV 2, O projection 4, down projection 4.
   int KS = 1;
   const long long tiles = (long long)col_tiles * row_tiles;
   const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
   const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
   static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aid
+  static const double step_us = getenv("S2D2_TILE_STEP_US") ? atof(getenv("S2D2_TILE_STEP_US")) : 1.3;
   if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
     double best = 1e30;
     for (int ks = 1; ks <= 8; ++ks) {
-      if (ks > 1 && (nk / ks < 4 || tiles * ks > a.tile_partial_cap)) break;
-      const double rounds = (double)((live * ks + 511) / 512), steps = (double)((nk + ks - 1) / ks);
-      double t = rounds * (steps * 1.64 + 6.0);
-      if (ks > 1) t += 8.0 + (double)live * ks * 131072.0 / 3.0e6;
+      if (ks > 1 && (nk / ks < 4 || tiles * ks * (WC / 2) > a.tile_partial_cap)) break;
+      const double rounds = (double)((live * ks + RESIDENT - 1) / RESIDENT), steps = (double)((nk + ks - 1) / ks);
+      double t = rounds * (steps * step_us + 6.0);
+      if (ks > 1) t += 8.0 + (double)live * ks * PART_BYTES * 2.0 / 3.0e6;
       if (t < best - 1e-9) { best = t; KS = ks; }
     }
-    if (ks_override > 0 && nk / ks_override >= 4 && tiles * ks_override <= a.tile_partial_cap) KS = ks_override;
+    if (ks_override > 0 && nk / ks_override >= 4 && tiles * ks_override * (WC / 2) <= a.tile_partial_cap) KS = ks_override;
   }
-  dim3 grid(col_tiles, row_tiles, KS), block(256);
-  if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true>), grid, block, 0, st, a);
-  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, false>), grid, block, 0, st, a);
+  dim3 grid(col_tiles, row_tiles, KS), block(128 * WC);
+  if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true, WC>), grid, block, 0, st, a);
+  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, false, WC>), grid, block, 0, st, a);
+}
+
+template <int EPI, int PRO>
+static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
+  static const int wc = getenv("S2D2_TILE_WC") ? atoi(getenv("S2D2_TILE_WC")) : 4;   // tuning aid
+  if (wc == 4) launch_tile<EPI, PRO, 4>(st, a, row_tiles);
+  else launch_tile<EPI, PRO, 2>(st, a, row_tiles);
 }
 
 // row_tiles: upper bound of 128-row tiles (ungrouped: ceil(m_cap / 128); grouped: capacity of the tile list)
