@@ -3,14 +3,17 @@
 // (verifier / draft forwards of the batched configurations, the prompt prefill, and the grouped
 // expert GEMMs of the MoE FFN).
 //
-// A workgroup of four wavefronts owns a tile of 128 rows x 128 output features and walks K in
-// steps of 64.  The activation tile goes through LDS (double-buffered, rows padded to 144 bytes so
-// that the 16-byte operand reads of a wavefront hit 64 distinct banks); the weight operands are
-// read straight from the packed copy, where one wavefront-wide 16-byte load is a complete A
-// operand of v_mfma_f32_16x16x32_bf16, through a ring of register stages that keeps them up to three
-// K steps (HBM latency is several steps of MFMA work) ahead of their use.  Each wavefront computes
-// 64 rows x 64 features (4 x 4 MFMA tiles); for the gate/up pair of SwiGLU 64 rows x 32 features of
-// each matrix, so a workgroup tile is 128 x 64 there.
+// A workgroup of eight wavefronts (2 x 4, one workgroup per compute unit) owns a tile of 128 rows x 256 output
+// features and walks K in steps of 64.  The activation tile goes through LDS (double-buffered, rows padded to 144
+// bytes per plane so that the 16-byte operand reads of a wavefront hit 64 distinct banks); it is requested two
+// steps before the step that multiplies it and is loaded once per compute unit.  The weight operands are read
+// straight from the packed copy, where one wavefront-wide 16-byte load is a complete A operand of
+// v_mfma_f32_16x16x32_bf16, through a ring of three register stages: while a step multiplies out of one stage, the
+// stage of the step before is refilled for the step after the next (HBM latency is more than a step of MFMA work).
+// All loads of a step are issued one or two at a time between its eight MFMA blocks.  Each wavefront computes
+// 64 rows x 64 features (4 x 4 MFMA tiles); for the gate/up pair of SwiGLU 64 rows x 32 features of each matrix, so
+// a workgroup tile is 128 x 128 there.  (A four-wavefront variant on 128 x 128 tiles, two workgroups per compute
+// unit, is kept as a tuning aid: it loads every activation tile twice per compute unit and measured 2-10 % slower.)
 //
 // K can be split over blockIdx.z when the tiles alone would leave compute units idle (few rows, narrow
 // outputs): every split writes its accumulators as an fp32 partial in register order (write-through
@@ -412,6 +415,14 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   constexpr int RESIDENT = WC == 2 ? 512 : 256;             // workgroups of one round over the chip
   constexpr double PART_BYTES = 32768.0 * WC;                // fp32 partial of one tile and split
   const int col_tiles = (a.NT + COLS - 1) / COLS;
+  // K is split over blockIdx.z when that shortens the launch.  The choice minimises a small cost model fitted to
+  // kernel traces of the batched configurations (microseconds; a round is as many workgroups as are resident on
+  // the chip at once):
+  //   rounds * (K steps per split * 1.3 + 6)                        K loop (both planes) + prologue / epilogue per round
+  //   + [splits > 1] * (8 + live tiles * splits * partial bytes * 2 / 3 TB/s)   partial write + read by the last arrival
+  // It is judged on the rows the caller expects (m_hint; the grid still covers the row capacity, workgroups of
+  // row tiles past the device-side row count exit at once).  Every split keeps at least 4 K steps and the
+  // partials must fit their buffer.
   int KS = 1;
   const long long tiles = (long long)col_tiles * row_tiles;
   const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
