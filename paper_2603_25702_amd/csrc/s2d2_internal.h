@@ -185,7 +185,7 @@ void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
                        float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride);
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
-// gemm_tile.hip : 128 x 128 LDS-tiled kernel on the same packed weights and argument block
+// gemm_tile.hip : 128 x 256 LDS-tiled kernel on the same packed weights and argument block
 void launch_gemm_tile(hipStream_t st, int kind, int pro, const GemmStreamArgs& a, int row_tiles);
 
 // moe.hip
