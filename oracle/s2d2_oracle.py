@@ -20,6 +20,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
   * ties: lowest index wins (token arg-max, position arg-max, expert top-k).
   * uniforms: Philox-4x32-10, u = (top 23 bits + 0.5) / 2^23 (odd multiples of 2^-24: exact in fp32), accept iff u * p < q.
   * residual draw: inverse CDF in ascending vocabulary order.
+  * right-shifted models (cfg.right_shifted): logits of block index i are read at the row of position i-1 in both
+    forwards; the verifier window is plain causal without [MASK] copies; the cache lags one token behind the
+    committed text so that this row is always a window row.
 """
 from __future__ import annotations
 
@@ -243,6 +246,7 @@ class Window:
     j: int                      # first masked block index (B if none)
     L: int                      # length of the first contiguous masked span C_t
     n_causal: int = 0           # verify window: number of leading causal rows (pending + drafted)
+    n_lead: int = 0             # verify window: uncached committed tokens left of C_t (the first rows)
 
 
 def first_span(block: np.ndarray, mask_id: int) -> Tuple[int, int]:
@@ -279,6 +283,19 @@ def draft_window(st: SeqState, mask_id: int, ar_mask: bool = True) -> Window:
     return Window(tokens, pos, vis, logit_rows=nc + masked_idx - c, logit_index=masked_idx, j=j, L=L)
 
 
+def shifted_draft_window(st: SeqState, mask_id: int, ar_mask: bool = True) -> Window:
+    """Draft window of a right-shifted model (Section 4.2, last sentence before the related-work remark: models
+    whose output at position i-1 is the distribution of token i).  Same rows and visibility as draft_window; the
+    logits of a masked block index are read from the row of the position in front of it.  That row must be in the
+    window: the committed token in front of the first [MASK] is not cached yet (the cache of such a model lags one
+    token behind the committed text; shifted_prefill_state sets a prefilled sequence up that way)."""
+    w = draft_window(st, mask_id, ar_mask)
+    rows = w.logit_rows - 1
+    if len(rows) and rows.min() < 0:
+        raise ValueError("right-shifted drafting needs the token in front of the first [MASK] as a window row")
+    return Window(w.tokens, w.pos, w.vis, logit_rows=rows, logit_index=w.logit_index, j=w.j, L=w.L)
+
+
 def verify_window(st: SeqState, xhat: np.ndarray, mask_id: int) -> Window:
     """Window of the verifier forward (2L trick): all uncached committed tokens left of C_t and
     the drafted tokens of C_t as causal rows, then one [MASK] copy per drafted token at the
@@ -303,7 +320,33 @@ def verify_window(st: SeqState, xhat: np.ndarray, mask_id: int) -> Window:
     vis[na:, n_lead:na] = vm[L:, :L]
     vis[na:, na:] = vm[L:, L:]
     return Window(tokens, pos, vis, logit_rows=na + np.arange(L), logit_index=j + np.arange(L),
-                  j=j, L=L, n_causal=na)
+                  j=j, L=L, n_causal=na, n_lead=n_lead)
+
+
+def shifted_verify_window(st: SeqState, xhat: np.ndarray, mask_id: int) -> Window:
+    """Verifier window of a right-shifted model: the plain causal mask already gives the verifier view (Section 4.2),
+    so there are no [MASK] copies.  Rows: the uncached committed tokens left of C_t, then the first L-1 drafted
+    tokens, all causal; the row at position i-1 yields the verifier distribution of the drafted token at i, i.e.
+    the L logit rows start at the last leading row.  The last drafted token needs no row of its own."""
+    c = st.n_cached_in_block()
+    j, L = first_span(st.block, mask_id)
+    pend = np.asarray(st.block[c:j], dtype=np.int64)
+    lead_tokens = np.concatenate([np.asarray(st.carry, dtype=np.int64), pend])
+    n_lead = len(lead_tokens)
+    if L > 0 and n_lead == 0:
+        raise ValueError("right-shifted verification needs the token in front of C_t as a window row")
+    tokens = np.concatenate([lead_tokens, np.asarray(xhat[j:j + max(L - 1, 0)], dtype=np.int64)])
+    na = len(tokens)
+    pos = st.seq_len + np.arange(na)
+    return Window(tokens, pos, causal_mask(na), logit_rows=n_lead - 1 + np.arange(L), logit_index=j + np.arange(L),
+                  j=j, L=L, n_causal=na, n_lead=n_lead)
+
+
+def shifted_prefill_state(seq_len: int, last_token: int, B: int, mask_id: int) -> SeqState:
+    """State of a right-shifted model after a prompt of seq_len tokens: its last token stays out of the cache and is
+    carried in front of the first block (cache rows at or past seq_len - 1 are not part of the state)."""
+    return SeqState(seq_len=seq_len - 1, pos0=seq_len, block=np.full(B, mask_id, dtype=np.int64),
+                    carry=np.array([last_token], dtype=np.int64))
 
 
 # --------------------------------------------------------------------------------------
@@ -446,7 +489,7 @@ def draft(cfg, W, st: SeqState, cache_k, cache_v, tau: float, ar_mask: bool = Tr
           temperature: float = 1.0, seed: int = 0, step: int = 0, seq: int = 0,
           forced_experts=None) -> DraftOut:
     """Alg. 3, draft forward + SampleFromLogits + M_t, C_t (+ the threshold set of its else-branch)."""
-    win = draft_window(st, cfg.mask_id, ar_mask)
+    win = (shifted_draft_window if getattr(cfg, "right_shifted", False) else draft_window)(st, cfg.mask_id, ar_mask)
     fo = forward(cfg, W, win.tokens, win.pos, win.vis, cache_k, cache_v, win.logit_rows, forced_experts)
     out = draft_from_logits(st, win, fo.logits, cfg.mask_id, tau, mode, temperature, seed, step, seq)
     out.fwd = fo
@@ -464,8 +507,9 @@ def verify_from_logits(win: Window, logits_ver: np.ndarray, xhat: np.ndarray, k,
 
 def verify(cfg, W, st: SeqState, cache_k, cache_v, xhat: np.ndarray, mode: int = GREEDY,
            temperature: float = 1.0, forced_experts=None) -> VerifyOut:
-    """Alg. 3, verifier forward under block-size-1 masking (2L trick) + ScoreFromLogits."""
-    win = verify_window(st, xhat, cfg.mask_id)
+    """Alg. 3, verifier forward under block-size-1 masking (2L trick; plain causal rows for a right-shifted
+    model) + ScoreFromLogits."""
+    win = (shifted_verify_window if getattr(cfg, "right_shifted", False) else verify_window)(st, xhat, cfg.mask_id)
     fo = forward(cfg, W, win.tokens, win.pos, win.vis, cache_k, cache_v, win.logit_rows, forced_experts)
     na = win.n_causal
     out = verify_from_logits(win, fo.logits, xhat, [k[:na] for k in fo.k], [v[:na] for v in fo.v],
@@ -500,10 +544,11 @@ def kv_append(st: SeqState, cache_k: List[np.ndarray], cache_v: List[np.ndarray]
               n_accept: int) -> int:
     """Append to the cache the K/V of every causal verify row up to the accepted prefix:
     the uncached committed tokens left of C_t and C_t[0:n_accept).  Those rows were computed
-    under a causal mask (AR caching, Section 4.2), so they are final.  Returns rows appended;
-    updates cache lists in place and st.seq_len."""
-    n_lead = vo.win.n_causal - vo.win.L
-    rows = n_lead + n_accept
+    under a causal mask (AR caching, Section 4.2), so they are final.  A right-shifted verifier window holds no
+    row for the last drafted token: if all of C_t is accepted that token stays uncached, as the token in front
+    of the next [MASK] must be.  Returns rows appended; updates cache lists in place and st.seq_len."""
+    n_lead = vo.win.n_lead
+    rows = n_lead + min(n_accept, vo.win.n_causal - n_lead)
     for l in range(len(cache_k)):
         cache_k[l] = np.concatenate([f64(cache_k[l]), vo.k[l][:rows]], axis=0)
         cache_v[l] = np.concatenate([f64(cache_v[l]), vo.v[l][:rows]], axis=0)
@@ -643,6 +688,8 @@ def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: Lis
     block (block-diffusion attention), and append of all their K/V.  Returns the rows appended (0 if the
     block is unfinished).  This is the cache update of the variant that does not cache causally inside a
     block (Section 4.2 describes the causal alternative the incremental append relies on)."""
+    if getattr(cfg, "right_shifted", False):
+        raise ValueError("whole-block append is not defined here for right-shifted models (their cache lags one token)")
     block = np.asarray(st.block)
     if (block == cfg.mask_id).any():
         return 0

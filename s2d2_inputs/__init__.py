@@ -44,6 +44,7 @@ class ModelCfg:
     dtype: str = "bf16"  # storage dtype of weights and KV cache: "bf16" | "f32"
     rope_theta: float = 1.0e6
     rms_eps: float = 1.0e-6
+    right_shifted: bool = False  # the output at position i-1 is the distribution of token i (else: of the [MASK] at i)
 
     @property
     def mask_id(self) -> int:
