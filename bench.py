@@ -10,6 +10,7 @@ before the timed region.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -39,6 +40,9 @@ def main():
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call of a step from the host instead of replaying a HIP graph of one step")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--right-shifted", action="store_true",
+                    help="treat the synthetic model as right-shifted (output at position i-1 scores token i): plain causal "
+                         "verifier rows instead of the 2L window; the result is labelled")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="counter calibration: first run a plain elementwise copy kernel over this many MiB "
                          "(read once, written once) so that a rocprofv3 --pmc run of this command holds a kernel of "
@@ -66,6 +70,8 @@ def main():
 
     wl = I.CONFIGS[args.config]
     cfg = wl.cfg if not args.layers else I.shrink(wl.cfg, n_layers=args.layers)
+    if args.right_shifted:
+        cfg = dataclasses.replace(cfg, right_shifted=True)
     N, B, K, Wm = wl.batch, wl.block, args.steps, args.warmup
     dev = "cuda:0"
     t0 = time.time()
@@ -77,6 +83,7 @@ def main():
     table = I.gen_page_table(N, (max_seq + wl.page_size - 1) // wl.page_size, args.seed)
     ses = Session(cfg, weights, N, B, max_seq, wl.page_size, dev, page_table=table)
     t0 = time.time()
+    last = [int(x[-1]) for x in ids]
     ses.prefill(ids)
     log(f"[bench] prefix cache of {lens.tolist()} tokens prefilled on the GPU in {time.time() - t0:.2f}s")
 
@@ -92,7 +99,7 @@ def main():
     run(Wm)
     torch.cuda.synchronize()
     if args.no_graph:
-        ses.reset_blocks(lens)
+        ses.reset_blocks(lens, last)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run(K)
@@ -103,7 +110,7 @@ def main():
     else:
         # one step = one HIP graph (every kernel of draft, verify, accept, append, advance); K replays are timed
         graph = ses.capture_step(prm)
-        ses.reset_blocks(lens)
+        ses.reset_blocks(lens, last)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(K):
@@ -120,7 +127,7 @@ def main():
     roofline, phases = None, {}
     if not args.no_profile_pass:
         Kp = min(K, 8)
-        ses.reset_blocks(lens)
+        ses.reset_blocks(lens, last)
         per_fwd = cfg.n_layers * 8 + 16
         ses.eng.s2d2_profile_start(2 * Kp * per_fwd + 64)
         run(Kp)
@@ -173,7 +180,7 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        ses.reset_blocks(lens)
+        ses.reset_blocks(lens, last)
         torch.cuda.synchronize()
         k_cpu, v_cpu = ses.kv.k.cpu(), ses.kv.v.cpu()
         tb = ses.kv.page_table.cpu().numpy()
@@ -187,6 +194,9 @@ def main():
             ck = [k_cpu[l][pages].permute(0, 2, 1, 3).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
             cv = [v_cpu[l][pages].permute(0, 3, 1, 2).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
             st = O.SeqState(S, S, np.full(B, cfg.mask_id, dtype=np.int64))
+            if args.right_shifted:
+                st = O.shifted_prefill_state(S, last[n], B, cfg.mask_id)
+                ck, cv = [x[:S - 1] for x in ck], [x[:S - 1] for x in cv]
             while True:
                 _, _, a = O.step(cfg, weights, st, ck, cv, prm.tau, args.seed, n_steps, n)
                 tokens += a.n_commit
@@ -205,7 +215,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
         "config": {"workload": f"config {args.config}: {cfg.name} {cfg.n_layers}L d{cfg.d_model} V{cfg.vocab}, batch {N}, "
-                               f"prefix {int(lens.min())}-{int(lens.max())}, block {B}, tau {prm.tau}, {K} consecutive steps",
+                               f"prefix {int(lens.min())}-{int(lens.max())}, block {B}, tau {prm.tau}, {K} consecutive steps"
+                               + (", right-shifted model" if args.right_shifted else ""),
                    "tokens_committed": committed, "drafts_accepted": accepted},
         "roofline": roofline, "cpu_baseline": cpu, "phases": phases,
     }

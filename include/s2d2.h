@@ -77,6 +77,16 @@ typedef struct {
                                            2 (also chosen by 0): as a high- and a low-order bf16 plane, 16 significant
                                            bits, every weight operand multiplied with both (keeps 36-layer models inside
                                            the logit tolerance); 1: one bf16 plane, half the MFMA work */
+  int32_t right_shifted;                /* 1: the model's output at position i-1 is the distribution of token i
+                                           (Section 4.2, right-shifted models).  s2d2_draft then reads the logits of a
+                                           masked block position from the window row in front of it, s2d2_verify runs
+                                           span_len plain causal rows (the uncached committed tokens left of C_t and the
+                                           first span_len - 1 drafted tokens, no [MASK] copies) and s2d2_kv_append never
+                                           caches the last drafted token.  Precondition, kept by these calls once it
+                                           holds: the committed token in front of the first [MASK] is not cached yet
+                                           (after a prompt of S tokens: seq_len = S - 1, block_pos0 = S, carry_tokens[0] =
+                                           last prompt token).  A sequence that violates it gets status S2D2_EINVAL and
+                                           is skipped.  s2d2_block_complete is refused.  0: logits of the [MASK] rows. */
   float rope_theta, rms_eps;
 } s2d2_model_desc;
 

@@ -35,7 +35,8 @@ class S2D2Error(RuntimeError):
 
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn",
-                                         "vocab", "n_experts", "top_k", "d_expert", "dtype", "mask_id", "act_planes")] + \
+                                         "vocab", "n_experts", "top_k", "d_expert", "dtype", "mask_id", "act_planes",
+                                         "right_shifted")] + \
                [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
 
 
@@ -163,7 +164,7 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 def model_desc(cfg, act_planes: int = 0) -> ModelDesc:
     return ModelDesc(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab,
                      cfg.n_experts, cfg.top_k, cfg.d_expert, S2D2_BF16 if cfg.dtype == "bf16" else S2D2_F32,
-                     cfg.mask_id, act_planes, cfg.rope_theta, cfg.rms_eps)
+                     cfg.mask_id, act_planes, int(bool(getattr(cfg, "right_shifted", False))), cfg.rope_theta, cfg.rms_eps)
 
 
 @dataclass

@@ -139,6 +139,7 @@ int32_t check_desc(const s2d2_model_desc* d) {
   }
   if (d->mask_id < 0 || d->mask_id >= d->vocab) return fail(S2D2_EINVAL, "mask_id outside the vocabulary");
   if (d->act_planes < 0 || d->act_planes > 2) return fail(S2D2_EINVAL, "act_planes must be 0, 1 or 2");
+  if (d->right_shifted != 0 && d->right_shifted != 1) return fail(S2D2_EINVAL, "right_shifted must be 0 or 1");
   if (d->vocab > 8192 * 256) return fail(S2D2_EINVAL, "vocab above 2097152 is not supported");
   if (!(d->rope_theta > 1.0f) || !(d->rms_eps >= 0.0f)) return fail(S2D2_EINVAL, "rope_theta must exceed 1 and rms_eps be non-negative");
   return S2D2_OK;
@@ -680,8 +681,8 @@ int32_t s2d2_draft(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* 
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_params(prm)) || (rc = check_draft_out(out))) return rc;
   const s2d2_model_desc& d = c->desc;
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 0, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
-              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr, nullptr); }
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 0, d.right_shifted, N, B, d.mask_id, prm->ar_mask, kv->seq_len, st->block_pos0, st->block_tokens,
+              st->carry_tokens, nullptr, c->plan, out->logit_row_of, out->span_start, out->span_len, nullptr, nullptr, nullptr, kv->status); }
   if ((rc = forward(c, kv, N, B, nullptr, nullptr, out->logits))) return rc;
   { ProfScope ps(c, 2, 0.0); launch_vocab_draft(c->stream, out->logits, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
                      c->plan.logit_idx, B, out->xhat, out->p, out->lse, out->margin, out->entropy_n,
@@ -698,8 +699,8 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
       (rc = check_draft_out(draft)) || (rc = check_verify_out(out)))
     return rc;
   const s2d2_model_desc& d = c->desc;
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 1, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
-              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active); }
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 1, d.right_shifted, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active, kv->status); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
   S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
                      out->logit_row_of, out->q, out->lse_ver);
@@ -732,7 +733,7 @@ int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B
   const KvGeom g = geom(c, kv);
   { ProfScope ps(c, 3, 0.0); launch_kv_append(c->stream, c->desc.dtype, c->desc.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
                    ver->k_stage, ver->v_stage, ver->stage_row0, ver->stage_lead, draft->span_len, n_accept,
-                   kv->seq_len, kv->status, B); }
+                   kv->seq_len, kv->status, B, c->desc.right_shifted); }
   return check_launch("s2d2_kv_append");
 }
 
@@ -741,14 +742,15 @@ int32_t s2d2_block_complete(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_bloc
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_verify_out(scratch))) return rc;
   const s2d2_model_desc& d = c->desc;
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 2, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
-              nullptr, c->plan, scratch->logit_row_of, nullptr, nullptr, scratch->stage_row0, scratch->stage_lead, nullptr); }
+  if (d.right_shifted) return fail(S2D2_EINVAL, "s2d2_block_complete is not defined for right-shifted models (their cache lags one token)");
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 2, 0, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+              nullptr, c->plan, scratch->logit_row_of, nullptr, nullptr, scratch->stage_row0, scratch->stage_lead, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, scratch->k_stage, scratch->v_stage, scratch->logits_ver))) return rc;
   const KvGeom g = geom(c, kv);
   // every staged row is appended: lead = rows, accepted = 0 (the zero array stands in for n_accept and span_len)
   { ProfScope ps(c, 3, 0.0); launch_kv_append(c->stream, d.dtype, d.n_layers, N, c->rows_cap, g, kv->k_pages, kv->v_pages,
                    scratch->k_stage, scratch->v_stage, scratch->stage_row0, scratch->stage_lead, c->zeros_i32, c->zeros_i32,
-                   kv->seq_len, kv->status, B); }
+                   kv->seq_len, kv->status, B, 0); }
   return check_launch("s2d2_block_complete");
 }
 

@@ -11,16 +11,16 @@
 namespace s2d2 {
 
 __global__ __launch_bounds__(1024) void plan_kernel(
-    int verify, int N, int B, int mask_id, int ar_mask, const int32_t* __restrict__ seq_len,
+    int verify, int shifted, int N, int B, int mask_id, int ar_mask, const int32_t* __restrict__ seq_len,
     const int32_t* __restrict__ pos0, const int32_t* __restrict__ block,
     const int32_t* __restrict__ carry, const int32_t* __restrict__ xhat, Plan p,
     int32_t* __restrict__ logit_row_of, int32_t* __restrict__ span_start,
     int32_t* __restrict__ span_len, int32_t* __restrict__ stage_row0, int32_t* __restrict__ stage_lead,
-    const int32_t* __restrict__ active) {
+    const int32_t* __restrict__ active, int32_t* __restrict__ status) {
   __shared__ int32_t s_rows[1024];
   __shared__ int32_t s_lrows[1024];
   const int n = threadIdx.x;
-  int S = 0, c = 0, nc = 0, j = B, L = 0, n_masked = 0, rows = 0, lrows = 0, lead = 0;
+  int S = 0, c = 0, nc = 0, j = B, L = 0, n_masked = 0, rows = 0, lrows = 0, lead = 0, bad = 0;
   if (n < N) {
     S = seq_len[n];
     const int P0 = pos0[n];
@@ -36,12 +36,18 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     c = min(c, j);
     lead = nc + (j - c);
     if (verify == 1 && active && active[n] == 0) { L = 0; lead = 0; }   // routed to the fallback: no verifier window
+    // right-shifted model: the row in front of the first [MASK] scores it and has to be a window row
+    if (shifted && verify != 2 && L > 0 && lead == 0) {
+      if (status) status[n] = S2D2_EINVAL;
+      if (verify) L = 0;
+      bad = 1;
+    }
     if (verify == 2) {            // block completion: all uncached tokens of a finished block, no logits
       rows = n_masked == 0 ? nc + (B - c) : 0;
       lead = rows;
       lrows = 0;
-    } else if (verify) { rows = lead + 2 * L; lrows = L; }
-    else        { rows = nc + (B - c); lrows = n_masked; }
+    } else if (verify) { rows = shifted ? lead + max(L - 1, 0) : lead + 2 * L; lrows = L; }
+    else        { rows = nc + (B - c); lrows = bad ? 0 : n_masked; }
   }
   s_rows[n] = rows;
   s_lrows[n] = lrows;
@@ -68,7 +74,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
   const int32_t* car = carry + (size_t)n * B;
   if (!verify) {
     span_start[n] = j;
-    span_len[n] = L;
+    span_len[n] = bad ? 0 : L;   // a skipped sequence has nothing to verify, accept or append
     for (int i = 0; i < B; ++i) logit_row_of[(size_t)n * B + i] = -1;
     for (int t = 0; t < rows; ++t) {
       const int r = row0 + t;
@@ -80,8 +86,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(
         const int i = c + (t - nc);
         tok = blk[i];
         hi = (i < j && ar_mask) ? r + 1 : row0 + rows;   // Eq. 4: committed prefix causal, rest sees all
-        if (tok == mask_id) {
-          p.logit_src[k] = r;
+        if (tok == mask_id && !bad) {
+          p.logit_src[k] = r - shifted;   // right-shifted model: the row in front (t >= 1 here: lead >= 1)
           p.logit_seq[k] = n;
           p.logit_idx[k] = i;
           logit_row_of[(size_t)n * B + i] = k;
@@ -112,7 +118,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     stage_lead[n] = lead;
     for (int i = 0; i < B; ++i) logit_row_of[(size_t)n * B + i] = -1;
     const int32_t* xh = xhat + (size_t)n * B;
-    for (int t = 0; t < lead + L; ++t) {  // causal half: carry, pending committed, drafted C_t
+    const int n_drafted = shifted ? max(L - 1, 0) : L;   // a right-shifted window has no row for the last drafted token
+    for (int t = 0; t < lead + n_drafted; ++t) {  // causal half: carry, pending committed, drafted C_t
       const int r = row0 + t;
       int tok;
       if (t < nc) tok = car[t];
@@ -124,7 +131,14 @@ __global__ __launch_bounds__(1024) void plan_kernel(
       p.row_lo[r] = row0;
       p.row_hi[r] = r + 1;
     }
-    for (int q = 0; q < L; ++q) {         // [MASK] copies: see causal rows strictly left, and themselves
+    for (int q = 0; q < L && shifted; ++q) {   // right-shifted: row of position i-1 scores the drafted token at i
+      p.logit_src[k] = row0 + lead - 1 + q;
+      p.logit_seq[k] = n;
+      p.logit_idx[k] = j + q;
+      logit_row_of[(size_t)n * B + j + q] = k;
+      ++k;
+    }
+    for (int q = 0; q < L && !shifted; ++q) {   // [MASK] copies: see causal rows strictly left, and themselves
       const int r = row0 + lead + L + q;
       p.row_token[r] = mask_id;
       p.row_pos[r] = S + lead + q;
@@ -140,14 +154,14 @@ __global__ __launch_bounds__(1024) void plan_kernel(
   }
 }
 
-void launch_plan(hipStream_t st, int verify, int N, int B, int mask_id, int ar_mask,
+void launch_plan(hipStream_t st, int verify, int shifted, int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
-                 const int32_t* active) {
-  S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify, N, B, mask_id, ar_mask,
+                 const int32_t* active, int32_t* status) {
+  S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify, shifted, N, B, mask_id, ar_mask,
                      seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
-                     stage_row0, stage_lead, active);
+                     stage_row0, stage_lead, active, status);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -158,9 +172,9 @@ __global__ __launch_bounds__(256) void kv_append_copy_kernel(
     int elt_bytes, int per_seq, int rows_cap, KvGeom g, uint8_t* __restrict__ k_pages,
     uint8_t* __restrict__ v_pages, const uint8_t* __restrict__ k_stage, const uint8_t* __restrict__ v_stage,
     const int32_t* __restrict__ stage_row0, const int32_t* __restrict__ stage_lead,
-    const int32_t* __restrict__ n_accept, const int32_t* __restrict__ span_len) {
+    const int32_t* __restrict__ n_accept, const int32_t* __restrict__ span_len, int hold_back) {
   const int n = blockIdx.x / per_seq, t = blockIdx.x % per_seq, l = blockIdx.y;
-  const int acc = max(0, min(n_accept[n], span_len[n]));
+  const int acc = max(0, min(n_accept[n], span_len[n] - hold_back));   // hold_back: no staged row for the last drafted token
   const int rows = stage_lead[n] + acc;
   if (t >= rows) return;
   const int S = g.seq_len[n];
@@ -192,10 +206,10 @@ __global__ __launch_bounds__(256) void kv_append_copy_kernel(
 __global__ void kv_append_commit_kernel(int N, KvGeom g, const int32_t* __restrict__ stage_lead,
                                         const int32_t* __restrict__ n_accept,
                                         const int32_t* __restrict__ span_len, int32_t* __restrict__ seq_len,
-                                        int32_t* __restrict__ status) {
+                                        int32_t* __restrict__ status, int hold_back) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
-  const int acc = max(0, min(n_accept[n], span_len[n]));
+  const int acc = max(0, min(n_accept[n], span_len[n] - hold_back));
   const int rows = stage_lead[n] + acc;
   const int S = seq_len[n];
   if (S + rows > g.max_pages_per_seq * g.page_size) {
@@ -208,14 +222,14 @@ __global__ void kv_append_commit_kernel(int N, KvGeom g, const int32_t* __restri
 void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
                       void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
                       const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
-                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B) {
+                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B, int hold_back) {
   const int elt = dtype == S2D2_BF16 ? 2 : 4;
   const int per_seq = 2 * B;  // upper bound of staged causal rows per sequence (carry + block)
   S2D2_LAUNCH(kv_append_copy_kernel, dim3(N * per_seq, n_layers), dim3(256), 0, st, elt, per_seq,
                      rows_cap, g, (uint8_t*)k_pages, (uint8_t*)v_pages, (const uint8_t*)k_stage,
-                     (const uint8_t*)v_stage, stage_row0, stage_lead, n_accept, span_len);
+                     (const uint8_t*)v_stage, stage_row0, stage_lead, n_accept, span_len, hold_back);
   S2D2_LAUNCH(kv_append_commit_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, g, stage_lead,
-                     n_accept, span_len, seq_len, status);
+                     n_accept, span_len, seq_len, status, hold_back);
 }
 
 // ---------------------------------------------------------------------------------------------

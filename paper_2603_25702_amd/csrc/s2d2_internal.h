@@ -102,15 +102,17 @@ enum GemmEpilogue {
 };
 
 // plan.hip
-void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block completion */, int N, int B, int mask_id, int ar_mask,
+void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block completion */, int shifted /* right-shifted model */,
+                 int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
-                 const int32_t* active);
+                 const int32_t* active, int32_t* status);
 void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
                       void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
                       const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
-                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B);
+                      const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B,
+                      int hold_back /* 1: the last drafted token has no staged row */);
 void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
                           int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev);
 void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const int32_t* xhat,

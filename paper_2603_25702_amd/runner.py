@@ -73,15 +73,22 @@ class Session:
             self.eng.s2d2_kv_append(self.kv, N, Bc, pd, pv, zeros)
             done = [done[n] + T[n] for n in range(N)]
         torch.cuda.synchronize(self.dev)
-        self.reset_blocks(lens)
+        self.reset_blocks(lens, [int(x[-1]) for x in ids])
 
-    def reset_blocks(self, seq_lens: Sequence[int]):
-        """Fresh [MASK]^B block right after the cached prefix of every sequence."""
+    def reset_blocks(self, seq_lens: Sequence[int], last_tokens: Optional[Sequence[int]] = None):
+        """Fresh [MASK]^B block right after the prefix of every sequence.  For a right-shifted model the last prefix
+        token is carried in front of the block instead of being counted as cached (its row scores the block's
+        first position), so `last_tokens` is required there."""
         self.st = self._state(self.B)
         self.st.block_tokens.fill_(self.cfg.mask_id)
         self.st.carry_tokens.zero_()
         t = torch.as_tensor(list(seq_lens), dtype=torch.int32)
         self.st.block_pos0.copy_(t)
+        if getattr(self.cfg, "right_shifted", False):
+            if last_tokens is None:
+                raise ValueError("a right-shifted model needs the last prefix token of every sequence")
+            self.st.carry_tokens[:, 0].copy_(torch.as_tensor(list(last_tokens), dtype=torch.int32))
+            t = t - 1
         self.kv.seq_len.copy_(t)
         self.kv.status.zero_()
         self.step_dev.zero_()

@@ -94,6 +94,10 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
                     v_pages[l][pg, :, :, sl] = round_to_storage(cv[l][s], cfg)
     case = Case(cfg, W, N, B, page_size, table, k_pages, v_pages, prefix_lens.copy())
     case.states = [O.SeqState(int(prefix_lens[n]), int(prefix_lens[n]), np.full(B, cfg.mask_id, dtype=np.int64)) for n in range(N)]
+    if getattr(cfg, "right_shifted", False):   # the cache lags: the last prompt token is carried, its cache row unused
+        case.seq_len = prefix_lens - 1
+        case.states = [O.shifted_prefill_state(int(prefix_lens[n]), int(I.gen_prefix_ids(cfg, int(prefix_lens[n]), seed, n)[-1]),
+                                               B, cfg.mask_id) for n in range(N)]
     return case
 
 
@@ -212,6 +216,14 @@ class Report:
     router_agree: int = 0
 
 
+def draft_window_of(cfg):
+    return O.shifted_draft_window if getattr(cfg, "right_shifted", False) else O.draft_window
+
+
+def verify_window_of(cfg):
+    return O.shifted_verify_window if getattr(cfg, "right_shifted", False) else O.verify_window
+
+
 def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, seqs=None,
                rep: Optional[Report] = None, check_logits: bool = True, check_kv_layers=None,
                pre_seq_len: Optional[np.ndarray] = None, free_router: bool = False) -> Report:
@@ -229,16 +241,16 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
         ch_d, ch_v = run.choices_draft.cpu().numpy(), run.choices_verify.cpu().numpy()
         row0_d, row0_v, rd, rv = [], [], 0, 0
         for n in range(case.N):
-            wd = O.draft_window(case.states[n], cfg.mask_id, bool(prm.ar_mask))
+            wd = draft_window_of(cfg)(case.states[n], cfg.mask_id, bool(prm.ar_mask))
             row0_d.append(rd)
             row0_v.append(rv)
             rd += len(wd.tokens)
-            rv += len(O.verify_window(case.states[n], np.zeros(B, dtype=np.int64), cfg.mask_id).tokens)
+            rv += len(verify_window_of(cfg)(case.states[n], np.zeros(B, dtype=np.int64), cfg.mask_id).tokens)
     for n in seqs:
         st = case.states[n]
         ck, cv = case.oracle_cache(n)
         # ---- stage 1 + 2: draft -------------------------------------------------------------
-        win = O.draft_window(st, cfg.mask_id, bool(prm.ar_mask))
+        win = draft_window_of(cfg)(st, cfg.mask_id, bool(prm.ar_mask))
         assert g["span_start"][n] == win.j and g["span_len"][n] == win.L
         rows_d = g["logit_row_of"][n]
         assert [(rows_d[i] >= 0) for i in range(B)] == [i in set(win.logit_index) for i in range(B)]
@@ -287,10 +299,10 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
             assert (np.abs(gp[~committed] - tau) < TIE).any(), f"seq {n}: threshold set differs"
             rep.exempt_tau += 1
         # ---- stage 3: verifier logits with the GPU's proposals ----------------------------------
-        vwin = O.verify_window(st, xhat, cfg.mask_id)
+        vwin = verify_window_of(cfg)(st, xhat, cfg.mask_id)
         rows_v = g["logit_row_of_ver"][n]
         gv = np.stack([g["logits_ver"][rows_v[i]] for i in vwin.logit_index]).astype(np.float64)
-        assert g["stage_lead"][n] == vwin.n_causal - vwin.L
+        assert g["stage_lead"][n] == vwin.n_lead
         ov = None
         if check_logits:
             forced = None
@@ -334,8 +346,8 @@ def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, s
         rep.n_commit.append(a.n_commit)
         rep.n_accept.append(a.n_accept)
         # ---- stage 5: cache append -----------------------------------------------------------------
-        n_lead = vwin.n_causal - L
-        rows = n_lead + a.n_accept
+        n_lead = vwin.n_lead
+        rows = n_lead + min(a.n_accept, vwin.n_causal - n_lead)   # (a right-shifted window has no row for the last draft)
         S0 = st.seq_len
         assert int(g["seq_len"][n]) == S0 + rows and int(g["status"][n]) == 0
         if ov is not None and rows:

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert C.sizeof(Bd.ModelDesc) == 13 * 4 + 8
+    assert C.sizeof(Bd.ModelDesc) == 14 * 4 + 8
     assert C.sizeof(Bd.LayerWeights) == 9 * 8
     assert C.sizeof(Bd.KvView) == 5 * 8 + 3 * 4 + 4
     assert C.sizeof(Bd.ParamsC) == 56
