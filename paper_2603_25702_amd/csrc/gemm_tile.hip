@@ -429,7 +429,7 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
   static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aid
-  static const double step_us = getenv("S2D2_TILE_STEP_US") ? atof(getenv("S2D2_TILE_STEP_US")) : 1.3;
+  const double step_us = 1.3;
   if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
     double best = 1e30;
     for (int ks = 1; ks <= 8; ++ks) {
@@ -448,7 +448,8 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
 
 template <int EPI, int PRO>
 static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) {
-  static const int wc = getenv("S2D2_TILE_WC") ? atoi(getenv("S2D2_TILE_WC")) : 4;   // tuning aid
+  const char* e = getenv("S2D2_TILE_WC");   // tuning aid, read per launch so that a test can cover both shapes
+  const int wc = e ? atoi(e) : 4;
   if (wc == 4) launch_tile<EPI, PRO, 4>(st, a, row_tiles);
   else launch_tile<EPI, PRO, 2>(st, a, row_tiles);
 }

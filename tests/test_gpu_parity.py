@@ -163,8 +163,11 @@ def test_config2_full_size_step_in_the_benchmark_launch_configuration():
 SMALL_MOE = I.ModelCfg("small-moe", 2, 512, 8, 4, 128, 0, 32000, n_experts=8, top_k=2, d_expert=256)
 
 
-def test_small_bf16_wide_windows_run_the_tiled_gemm():
-    """Windows of up to 3*3*16 = 144 rows: the LDS-tiled GEMM with every fused epilogue, ragged row tiles."""
+@pytest.mark.parametrize("tile_wc", ["4", "2"])
+def test_small_bf16_wide_windows_run_the_tiled_gemm(monkeypatch, tile_wc):
+    """Windows of up to 3*3*16 = 144 rows: the LDS-tiled GEMM with every fused epilogue, ragged row tiles; with
+    the default workgroup of eight wavefronts and with the four-wavefront shape kept as a tuning aid."""
+    monkeypatch.setenv("S2D2_TILE_WC", tile_wc)
     case = H.make_case(SMALL_BF16, 3, 16, [100, 257, 31], seed=11, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
     run, rep = run_steps(case, 3)
     print("small bf16 wide:", rep)
