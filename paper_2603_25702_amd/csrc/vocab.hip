@@ -234,7 +234,8 @@ __device__ __forceinline__ float uniform01(uint64_t seed, uint32_t step, uint32_
 // Scan of one non-negative float per thread over a 256-thread block with a fixed tree.
 // Returns the inclusive prefix; *excl is the inclusive prefix of the previous thread (0 for
 // thread 0), so the intervals [excl, incl) of consecutive threads tile [0, total) exactly;
-// *total is the inclusive prefix of the last thread.  s_w needs 4 floats.
+// *total is the inclusive prefix of the last thread.  s_w needs 4 floats.  Threads past the first 256 (a wider
+// workgroup) must pass 0 and get an empty interval at the total.
 __device__ __forceinline__ float block_scan_256(float v, float* s_w, float* excl, float* total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   for (int off = 1; off < 64; off <<= 1) {
@@ -242,10 +243,10 @@ __device__ __forceinline__ float block_scan_256(float v, float* s_w, float* excl
     if (lane >= off) v += t;
   }
   __syncthreads();
-  if (lane == 63) s_w[w] = v;
+  if (lane == 63 && w < 4) s_w[w] = v;
   __syncthreads();
   float pre = 0.f;
-  for (int i = 0; i < w; ++i) pre += s_w[i];
+  for (int i = 0; i < min(w, 4); ++i) pre += s_w[i];
   const float incl = v + pre;
   const float prev = __shfl_up(incl, 1, 64);
   *excl = lane == 0 ? pre : prev;
@@ -256,7 +257,7 @@ __device__ __forceinline__ float block_scan_256(float v, float* s_w, float* excl
 static constexpr int RTILE = 256;     // residual tile: one wavefront x float4
 static constexpr int RMAX_TILES = 8192;
 
-// Inverse CDF over V non-negative weights in ascending index order, by the 256 threads of a workgroup:
+// Inverse CDF over V non-negative weights in ascending index order, by a workgroup of 256 threads or more (the tile sums use all of them):
 // returns (in the lanes of wavefront 0; -1 elsewhere) the smallest index whose inclusive prefix sum exceeds
 // u * total, or -1 if the weights have no mass.  w4(i0, r) yields the weights of indices i0 .. i0+3 (zeros
 // past V).  Two levels with a fixed summation order: tile sums (256 indices per tile: one wavefront x 4),
@@ -267,16 +268,25 @@ __device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, fl
                                                  int* s_tile_sel, float* s_before) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tiles = (V + RTILE - 1) / RTILE;
-  for (int t = w; t < tiles; t += 4) {
-    float r4[4];
-    w4(t * RTILE + lane * 4, r4);
-    float r = ((r4[0] + r4[1]) + r4[2]) + r4[3];
-    for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
-    if (lane == 0) s_tile[t] = r;
+  // Tile sums, eight tiles of a wavefront at a time: their loads are all issued before the first reduction (one tile
+  // per iteration made the pass a chain of ~150 memory round trips per wavefront).  A tile's sum does not depend on
+  // which wavefront forms it.
+  constexpr int TU = 8;
+  const int nw = blockDim.x >> 6;   // every wavefront of the workgroup takes part in this pass; the scan uses 256 threads
+  for (int t0 = w * TU; t0 < tiles; t0 += nw * TU) {
+    float r4[TU][4];
+#pragma unroll
+    for (int u_ = 0; u_ < TU; ++u_) w4((t0 + u_) * RTILE + lane * 4, r4[u_]);   // indices at or past V give zeros
+#pragma unroll
+    for (int u_ = 0; u_ < TU; ++u_) {
+      float r = ((r4[u_][0] + r4[u_][1]) + r4[u_][2]) + r4[u_][3];
+      for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
+      if (lane == 0 && t0 + u_ < tiles) s_tile[t0 + u_] = r;
+    }
   }
   __syncthreads();
   // scan tile sums: thread t owns tiles [t*per, (t+1)*per)
-  const int per = (tiles + 255) / 256;
+  const int per = (tiles + 255) / 256;   // (threads past the first 256 own no tiles)
   float mine = 0.f;
   for (int t = tid * per; t < min(tiles, (tid + 1) * per); ++t) mine += s_tile[t];
   float total, excl;
@@ -357,10 +367,11 @@ __global__ __launch_bounds__(256) void vocab_sample_kernel(
   const uint32_t stp = step + (step_dev ? *step_dev : 0u);
   const float u = uniform01(seed, stp, (uint32_t)n, (uint32_t)idx, 2u);
   auto prob4 = [&](int i0, float (&r)[4]) {
-    if ((V & 3) == 0 && i0 + 3 < V) {
-      const float4 a = *(const float4*)(x + i0);
-      r[0] = __expf(a.x * inv_t - z); r[1] = __expf(a.y * inv_t - z);
-      r[2] = __expf(a.z * inv_t - z); r[3] = __expf(a.w * inv_t - z);
+    if ((V & 3) == 0) {   // unconditional load (clamped index) so that the loads of several tiles can be in flight
+      const bool ok = i0 < V;
+      const float4 a = *(const float4*)(x + (ok ? i0 : 0));
+      r[0] = ok ? __expf(a.x * inv_t - z) : 0.f; r[1] = ok ? __expf(a.y * inv_t - z) : 0.f;
+      r[2] = ok ? __expf(a.z * inv_t - z) : 0.f; r[3] = ok ? __expf(a.w * inv_t - z) : 0.f;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) r[e] = (i0 + e < V) ? __expf(x[i0 + e] * inv_t - z) : 0.f;
@@ -375,7 +386,7 @@ __global__ __launch_bounds__(256) void vocab_sample_kernel(
 
 // One workgroup per sequence: accept scan over C_t (thread 0), then, if a drafted token failed,
 // draw from the residual (P_ver - P_draft)_+ by inverse CDF in ascending vocabulary order.
-__global__ __launch_bounds__(256) void accept_kernel(
+__global__ __launch_bounds__(1024) void accept_kernel(
     int B, int V, uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev, float gamma, int resample,
     float inv_t, const int32_t* __restrict__ span_start, const int32_t* __restrict__ span_len,
     const float* __restrict__ logits_d, const int32_t* __restrict__ row_of_d,
@@ -392,7 +403,7 @@ __global__ __launch_bounds__(256) void accept_kernel(
   const int n = blockIdx.x, tid = threadIdx.x;
   const int j = span_start[n], L = (active && active[n] == 0) ? 0 : span_len[n];   // not routed to the verifier: nothing to scan
   const uint32_t stp = step + (step_dev ? *step_dev : 0u);
-  for (int i = tid; i < B; i += 256) u_used[(size_t)n * B + i] = 0.f;
+  for (int i = tid; i < B; i += blockDim.x) u_used[(size_t)n * B + i] = 0.f;
   __syncthreads();
   if (tid == 0) {
     int acc = 0;
@@ -408,7 +419,7 @@ __global__ __launch_bounds__(256) void accept_kernel(
   }
   __syncthreads();
   const int acc = s_nacc;
-  for (int i = tid; i < acc; i += 256) block[n * B + j + i] = xhat[n * B + j + i];
+  for (int i = tid; i < acc; i += blockDim.x) block[n * B + j + i] = xhat[n * B + j + i];
   if (acc >= L || !resample) {
     if (tid == 0) { n_accept[n] = acc; n_commit[n] = acc; resampled[n] = -1; }
     return;
@@ -420,12 +431,14 @@ __global__ __launch_bounds__(256) void accept_kernel(
   const float zd = lse_d[o], zv = lse_v[o];
   const float u2 = uniform01(seed, stp, (uint32_t)n, (uint32_t)(j + acc), 1u);
   auto residual4 = [&](int i0, float (&r)[4]) {
-    if ((V & 3) == 0 && i0 + 3 < V) {
-      const float4 a = *(const float4*)(ld + i0), b = *(const float4*)(lv + i0);
-      r[0] = fmaxf(0.f, __expf(b.x * inv_t - zv) - __expf(a.x * inv_t - zd));
-      r[1] = fmaxf(0.f, __expf(b.y * inv_t - zv) - __expf(a.y * inv_t - zd));
-      r[2] = fmaxf(0.f, __expf(b.z * inv_t - zv) - __expf(a.z * inv_t - zd));
-      r[3] = fmaxf(0.f, __expf(b.w * inv_t - zv) - __expf(a.w * inv_t - zd));
+    if ((V & 3) == 0) {   // unconditional loads (clamped index) so that the loads of several tiles can be in flight
+      const bool ok = i0 < V;
+      const int ic = ok ? i0 : 0;
+      const float4 a = *(const float4*)(ld + ic), b = *(const float4*)(lv + ic);
+      r[0] = ok ? fmaxf(0.f, __expf(b.x * inv_t - zv) - __expf(a.x * inv_t - zd)) : 0.f;
+      r[1] = ok ? fmaxf(0.f, __expf(b.y * inv_t - zv) - __expf(a.y * inv_t - zd)) : 0.f;
+      r[2] = ok ? fmaxf(0.f, __expf(b.z * inv_t - zv) - __expf(a.z * inv_t - zd)) : 0.f;
+      r[3] = ok ? fmaxf(0.f, __expf(b.w * inv_t - zv) - __expf(a.w * inv_t - zd)) : 0.f;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
@@ -448,7 +461,7 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
                    int32_t* resampled, float* u_used, const int32_t* active) {
-  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(256), 0, st, B, V, seed, step, step_dev, gamma, resample, inv_t,
+  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(1024), 0, st, B, V, seed, step, step_dev, gamma, resample, inv_t,
                      span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
                      n_accept, n_commit, resampled, u_used, active);
 }
