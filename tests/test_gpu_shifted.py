@@ -83,3 +83,33 @@ def test_whole_block_append_is_refused():
     run = H.GpuRun(case)
     with pytest.raises(S2D2Error):
         run.eng.s2d2_block_complete(run.kv, run.st, 1, 4, run.v)
+
+
+def test_session_prefill_carries_the_last_prompt_token_and_steps_match_the_oracle():
+    """The runner's session: a prompt prefilled through the library leaves the cache one token behind, the steps that
+    follow are checked against the oracle on the GPU's own cache contents."""
+    from paper_2603_25702_amd.runner import Session
+    cfg, N, B = shifted(SMALL_BF16), 2, 4
+    W = I.gen_weights(cfg, 3)
+    lens = np.array([90, 41], dtype=np.int32)
+    ids = [I.gen_prefix_ids(cfg, int(lens[n]), 3, n) for n in range(N)]
+    table = I.gen_page_table(N, 512 // 16, 3)
+    ses = Session(cfg, W, N, B, 512, 16, "cuda:0", page_table=table)
+    ses.prefill(ids)
+    torch.cuda.synchronize()
+    assert ses.kv.seq_len.tolist() == [89, 40] and ses.st.block_pos0.tolist() == [90, 41]
+    assert ses.st.carry_tokens[:, 0].tolist() == [int(ids[0][-1]), int(ids[1][-1])]
+    case = H.Case(cfg, W, N, B, 16, table, [], [], lens - 1)
+    case.states = [H.O.shifted_prefill_state(int(lens[n]), int(ids[n][-1]), B, cfg.mask_id) for n in range(N)]
+    run = H.GpuRun(case, session=ses)
+    H.sync_case_from_gpu(case, run)
+    rep = H.Report()
+    for s in range(4):
+        prm = Params(step=s, seed=77)
+        run.step(prm, advance=False)
+        g = run.fetch()
+        H.check_step(case, run, g, prm, rep=rep)
+        run.eng.s2d2_block_advance(run.kv, run.st, N, B, None)
+        H.sync_case_from_gpu(case, run)
+    print("shifted session:", rep)
+    assert int(ses.kv.status.abs().sum()) == 0 and sum(rep.n_commit) >= 8
