@@ -82,6 +82,7 @@ struct s2d2_ctx {
   uint64_t* moe_y_or_scratch; // clock stamps of the timing build
   float* tile_partials;      // split-K partials of the tiled GEMM, TILE_PARTIAL_CAP x 64 KB
   int32_t* tile_counters;    // TILE_COUNTER_CAP arrival counters, zero between launches
+  unsigned long long* pair_buf;   // PAIR_CAP x 256 (value, tag) words of the streaming GEMM's paired K split, zero between launches
   uint8_t* fused_act;        // per-layer exchange buffers of the fused forward
   size_t fused_act_stride;
   int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
@@ -98,7 +99,7 @@ struct s2d2_ctx {
 
 namespace {
 
-constexpr int TILE_PARTIAL_CAP = 4096, TILE_COUNTER_CAP = 4096;
+constexpr int TILE_PARTIAL_CAP = 4096, TILE_COUNTER_CAP = 4096, PAIR_CAP = 512;
 
 struct Carver {
   uint8_t* base;
@@ -215,6 +216,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   if (d.dtype == S2D2_BF16) {
     c->tile_partials = cv.take<float>((size_t)TILE_PARTIAL_CAP * 16384);
     c->tile_counters = cv.take<int32_t>(TILE_COUNTER_CAP);
+    c->pair_buf = cv.take<unsigned long long>((size_t)PAIR_CAP * 256);
   }
   c->fused_layers = cv.take<FusedLayer>(d.n_layers);
   c->fused_bar = cv.take<uint32_t>(9 * 64);
@@ -324,6 +326,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     x.m_hint = x.m_count == c->plan.counts + 1 ? N * B : m_hint;   // (logit rows: one per masked position)
     x.tile_partials = c->tile_partials; x.tile_counters = c->tile_counters;
     x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
+    x.pair_buf = c->pair_buf; x.pair_status = c->fused_err + 1; x.pair_cap = PAIR_CAP;
   };
   // GEMM inputs as P bf16 planes per row: [hi | lo]; lo offsets are 0 with a single plane
   const int P = fused && flash ? act_planes(d) : 1;  // the generic attention kernel writes one plane
@@ -623,6 +626,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   launch_fill_i32(c->stream, c->zeros_i32, c->max_batch, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
+  if (c->pair_buf) launch_fill_i32(c->stream, (int32_t*)c->pair_buf, PAIR_CAP * 256 * 2, 0);
   if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
@@ -821,10 +825,11 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
 
 int32_t s2d2_status(s2d2_ctx* c) {
   if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
-  int32_t flag = 0;
-  if (hipStreamSynchronize(c->stream) != hipSuccess || hipMemcpy(&flag, c->fused_err, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+  int32_t flag[2] = {0, 0};
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipMemcpy(flag, c->fused_err, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
     return fail(S2D2_ELAUNCH, "could not read the device status: %s", hipGetErrorString(hipGetLastError()));
-  if (flag) return fail(S2D2_ELAUNCH, "a device-wide barrier of the fused forward timed out (workgroups not co-resident)");
+  if (flag[0]) return fail(S2D2_ELAUNCH, "a device-wide barrier of the fused forward timed out (workgroups not co-resident)");
+  if (flag[1]) return fail(S2D2_ELAUNCH, "a workgroup of the streaming GEMM waited in vain for its partner's share of K");
   return S2D2_OK;
 }
 

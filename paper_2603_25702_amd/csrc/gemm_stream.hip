@@ -98,8 +98,16 @@ __device__ unsigned long long g_stream_ts[4][16];   // [epilogue kind][first wor
 #define S2D2_GTS(k) do {} while (0)
 #endif
 
-template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
+// PAIR (residual-add epilogue, one feature tile per workgroup): K is shared by the 2 NW wavefronts of TWO workgroups,
+// so that a matrix with few feature tiles (d_model / 16 of them for the down projection) still puts a workgroup
+// on every compute unit.  The workgroups x < gridDim.x / 2 ("producers", dispatched first) reduce their NW shares
+// and hand the 16 x 16 partial over as 64-bit (value, tag) words; the workgroup x + gridDim.x / 2 adds its own NW
+// shares, waits for those words with a bounded spin, adds them (own + partner: a fixed order), clears them for
+// the next launch and runs the epilogue.  Every wait ends: the producers never wait and are resident before
+// their consumers; a spin that runs out sets *pair_status and continues with what it has.
+template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT, bool PAIR = false>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
+  static_assert(!PAIR || (EPI == SEPI_ADD_F32 && TPW == 1), "the paired K split exists for the residual-add epilogue only");
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
   extern __shared__ __align__(16) uint8_t smem_raw[];
@@ -113,7 +121,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     M = *a.m_count;
     if (m0 >= M) return;
   }
-  const int nt0 = blockIdx.x * TPW;
+  const int nx = PAIR ? (int)gridDim.x / 2 : (int)gridDim.x;
+  const bool producer = PAIR && (int)blockIdx.x < nx;
+  const int bx = PAIR ? (int)blockIdx.x % nx : (int)blockIdx.x;
+  const int nt0 = bx * TPW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, f = lane & 15;
   const int KT = a.KT;
@@ -121,7 +132,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   float* s_rs = (float*)smem_raw;                                   // [16] 1/rms per row (SPRO_BF16S)
   float* s_red = s_rs + 16;                                         // [NW][TA][256]
 
-  const int kt_begin = (int)((long long)wave * KT / NW), kt_end = (int)((long long)(wave + 1) * KT / NW);
+  constexpr int NS = PAIR ? 2 * NW : NW;                            // K shares
+  const int share = PAIR ? (producer ? NW : 0) + wave : wave;
+  const int kt_begin = (int)((long long)share * KT / NS), kt_end = (int)((long long)(share + 1) * KT / NS);
   const u32x4_t* wp[TA];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -265,9 +278,27 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
         // residual add; also emits the next norm's operand and this tile's share of the row's sum of squares
         const int n = nt * 16 + fe;
         float hv = 0.f;
+        float total = S2D2_TOTAL(t, fe);
+        if (PAIR) {
+          unsigned long long* slot = a.pair_buf + ((size_t)blockIdx.y * nx + bx) * 256 + threadIdx.x;
+          if (producer) {   // (value, tag 1); the store leaves the device-coherent way and the workgroup is done
+            __hip_atomic_store(slot, (unsigned long long)__float_as_uint(total) | (1ull << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+          }
+          unsigned long long v = 0;
+          int spins = 0;
+          for (; spins < (1 << 20); ++spins) {
+            v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v >> 32) break;
+            __builtin_amdgcn_s_sleep(1);
+          }
+          if (!(v >> 32)) { if (a.pair_status) *a.pair_status = 1; }
+          else __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // re-armed for the next launch
+          total += __uint_as_float((uint32_t)v);
+        }
         if (live && n < a.N) {
           float* hp = (float*)a.out + (size_t)m * a.ldo + n;
-          hv = *hp + S2D2_TOTAL(t, fe);
+          hv = *hp + total;
           *hp = hv;
           if (a.xg_out) {
             bf16_t hi, lo;
@@ -353,9 +384,20 @@ static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   S2D2_LAUNCH((gemm_stream_kernel<EPI, PRO, NW, TPW, U, SPLIT>), grid, block, lds, st, a);
 }
 
+// residual-add GEMM with K shared by pairs of workgroups (see the kernel's comment): 2 NT workgroups of NW wavefronts
+template <int NW, int U, bool SPLIT>
+static void launch_pair(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
+  const size_t lds = 16 * sizeof(float) + (size_t)NW * 256 * sizeof(float);
+  dim3 grid(2 * a.NT, (m_cap + 15) / 16), block(NW * 64);
+  S2D2_LAUNCH((gemm_stream_kernel<SEPI_ADD_F32, SPRO_BF16, NW, 1, U, SPLIT, true>), grid, block, lds, st, a);
+}
+
 // Launch shapes (wavefronts per workgroup, feature tiles per workgroup, loads in flight per wavefront): the
 // layer matrices want >= 256 workgroups; with the sliding-window K loop the step time moves by less than 2 %
 // over the twenty shapes selectable through S2D2_GEMM_CFG (one digit per kind: qkv, add, swiglu, store).
+// The down projection has only d_model / 16 feature tiles (128 for the 1.7B shape): there K is shared by pairs of
+// workgroups (256 workgroups: 9.6 us per launch against 13.0 us with 128 workgroups of 16 wavefronts, which
+// streamed at half the rate of the other layer GEMMs; digit 9 for `add` switches the pairing off).
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
   if (m_cap > 32) {  // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16
     launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
@@ -386,6 +428,12 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
       else S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 8);
       break;
     case SEPI_ADD_F32:
+      // long K and few feature tiles (the down projection): pairs of workgroups share K, one workgroup per CU
+      if (a.KT >= 128 && a.pair_buf && variant[1] != 9 && (long long)a.NT * ((m_cap + 15) / 16) <= a.pair_cap) {
+        if (sp) launch_pair<8, 4, true>(st, a, m_cap);
+        else launch_pair<8, 4, false>(st, a, m_cap);   // (16 wavefronts, or 3 to 12 loads in flight: within 1 %)
+        break;
+      }
       if (a.KT >= 128) {
         if (variant[1] == 1) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
         else if (variant[1] == 2) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 6);

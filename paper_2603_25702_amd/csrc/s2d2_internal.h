@@ -180,6 +180,11 @@ struct GemmStreamArgs {
   float* tile_partials;
   int32_t* tile_counters;
   int32_t tile_partial_cap, tile_counter_cap;
+  // streaming kernel, paired K split of the residual-add GEMM: pair_cap x 256 (value, tag) words, zero between
+  // launches; *pair_status is set when a bounded wait ran out
+  unsigned long long* pair_buf;
+  int32_t* pair_status;
+  int32_t pair_cap;
 };
 size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);

@@ -174,6 +174,21 @@ def test_small_bf16_wide_windows_run_the_tiled_gemm(monkeypatch, tile_wc):
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
 
 
+def test_long_k_down_projection_shared_by_pairs_of_workgroups():
+    """d_ffn = 4096: the residual-add GEMM of the down projection splits K over pairs of workgroups that hand
+    their partial over through tagged words (narrow windows only); one and two 16-row tiles, several steps so
+    that the hand-over words are re-armed and reused, and the device status stays clean."""
+    cfg = I.ModelCfg("small-long-k", 2, 512, 8, 4, 128, 4096, 32000)
+    case = H.make_case(cfg, 1, 8, [70], seed=8, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 4)
+    print("long K, paired:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+    run.eng.s2d2_status()
+    case = H.make_case(cfg, 2, 4, [33, 90], seed=9, synthetic_kv=True, page_size=16, room=64)
+    run, rep = run_steps(case, 3)
+    run.eng.s2d2_status()
+
+
 def test_single_activation_plane_narrow_and_wide_windows():
     """`act_planes = 1` in the model description: activations as one bf16 plane (the single-plane instantiations of
     the streaming and tiled GEMMs and of both attention kernels).  Two layers keep the rounding well inside the
