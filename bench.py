@@ -21,8 +21,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the streaming GEMM on this workload, from the FETCH_SIZE / WRITE_SIZE counter runs
-# recorded in profiles/gemm_stream_kernel_config2.md (31.07 MB fetched + 0.13 MB written; 30.45 MB algorithmic)
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 31.2e6
+# recorded in profiles/gemm_stream_kernel_config2.md (31.16 MB fetched + 0.26 MB written; 30.45 MB algorithmic)
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 31.4e6
 
 
 def log(*a):
