@@ -99,8 +99,10 @@ def test_draft_mask_flag_and_block_size_one():
         np.testing.assert_allclose(g["logits"][rows], od.logits, atol=2e-4 * np.abs(od.logits).max())
 
 
-def test_same_inputs_give_bit_identical_outputs():
-    case = H.make_case(SMALL_BF16, 2, 4, [50, 70], seed=4, synthetic_kv=True, page_size=16, room=32)
+@pytest.mark.parametrize("d_ffn", [1536, 4096])   # 4096: down projection with K shared between pairs of workgroups
+def test_same_inputs_give_bit_identical_outputs(d_ffn):
+    cfg = I.ModelCfg("small-bf16-det", 2, 512, 8, 4, 128, d_ffn, 32000)
+    case = H.make_case(cfg, 2, 4, [50, 70], seed=4, synthetic_kv=True, page_size=16, room=32)
     outs = []
     for _ in range(2):
         run = H.GpuRun(case)
@@ -308,11 +310,14 @@ def test_fused_single_launch_forward_matches_the_oracle_and_the_multi_kernel_pat
     assert prof["forward"]["launches"] == 1   # the forward really was one launch
 
 
-def test_captured_step_graph_replays_match_eager_steps():
+@pytest.mark.parametrize("d_ffn", [1536, 4096])
+def test_captured_step_graph_replays_match_eager_steps(d_ffn):
     """A HIP graph of one step, replayed with eager work and synchronisations between the replays: every replay
-    must leave exactly the state the same steps leave when enqueued call by call."""
+    must leave exactly the state the same steps leave when enqueued call by call.  d_ffn = 4096 puts the down
+    projection on the streaming GEMM that shares K between pairs of workgroups (hand-over words re-armed inside
+    the kernel, no memset nodes)."""
     from paper_2603_25702_amd.runner import Session
-    cfg = SMALL_BF16
+    cfg = I.ModelCfg("small-bf16-graph", 2, 512, 8, 4, 128, d_ffn, 32000)
     W = I.gen_weights(cfg, 3)
     ids = [I.gen_prefix_ids(cfg, 90, 3, 0), I.gen_prefix_ids(cfg, 41, 3, 1)]
 
