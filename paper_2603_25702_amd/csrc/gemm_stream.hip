@@ -149,7 +149,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int t = 0; t < TA; ++t) w[t][u] = wp[t][(size_t)max(0, min(kt_begin + u, kt_end - 1)) * 64];
+    for (int t = 0; t < TA; ++t) w[t][u] = ld_stream(&wp[t][(size_t)max(0, min(kt_begin + u, kt_end - 1)) * 64]);
 
   if (blockIdx.y == 0) M = *a.m_count;
   const int Mloc = min(16, M - m0);
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
         mac(u);   // a refilling batch is complete: kt0 + U - 1 < kt_end
         const int kc = max(0, min(kt0 + U + u, kt_end - 1));
 #pragma unroll
-        for (int t = 0; t < TA; ++t) w[t][u] = wp[t][(size_t)kc * 64];
+        for (int t = 0; t < TA; ++t) w[t][u] = ld_stream(&wp[t][(size_t)kc * 64]);
         xb[u] = *(const u32x4_t*)(xg + kc * 32);
         if (SPLIT) xl[u] = *(const u32x4_t*)(xg + a.x_lo + kc * 32);
       }

