@@ -108,9 +108,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   };
   // piece idx of a tile: K row idx / 16, 16-byte piece idx % 16;  V^T row idx / 4, keys 8 (idx % 4) .. + 8.
   // Thread tid handles pieces tid + u T, u < U (each piece in a named register set, never an indexed array).
-  auto fetch1 = [=](int u, int i, uint4& kr, uint4& vr) {
+  auto fetchp = [=](int idx, int i, uint4& kr, uint4& vr) {
     const FwTile t = tile_of(i);
-    const int idx = min(tid + u * T, 511);
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
     const int key = min(t.kbase + kk, t.limit - 1);   // rows beyond the region read a valid row; their scores are masked
     const int key0 = t.kbase + vko;
@@ -127,14 +126,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     kr = *(const uint4*)kp;
     vr = *(const uint4*)vp;
   };
-  auto stash1 = [=](int u, int i, int b, uint4 kr, uint4 vr) {
+  auto fetch1 = [=](int u, int i, uint4& kr, uint4& vr) { fetchp(min(tid + u * T, 511), i, kr, vr); };
+  auto stashp = [=](int idx, int i, int b, uint4 kr, uint4 vr) {
     const FwTile t = tile_of(i);
     unsigned char* base = lds + b * FW_BUF;
-    const int idx = min(tid + u * T, 511);   // clamped duplicates rewrite the same bytes
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
     *(uint4*)(base + kk * FW_KROW + kch * 16) = kr;
     *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = fw_mask(vr, t.limit - (t.kbase + vko));
   };
+  auto stash1 = [=](int u, int i, int b, uint4 kr, uint4 vr) { stashp(min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
   const int kperm = fa_perm(c);
   auto compute = [=](FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) {
     const FwTile t = tile_of(i);
@@ -202,7 +202,54 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     }
   };
 
-  if (n_it > 0) {
+  // A workgroup of 8 wavefronts of which at most half own a query tile with rows (a fresh block fills 4 of the
+  // verifier's 6 tiles): the upper half of the wavefronts does all the fetching, PP pieces per thread in two
+  // register sets, and the wavefronts that compute do nothing else.  With every wavefront fetching its share, the
+  // address arithmetic and LDS stores of the fetch sat on the critical wavefronts; workgroups without idle
+  // wavefronts were slower still for the same reason.  (The same split in 4-wavefront workgroups, two fetching
+  // wavefronts with four pieces each, measured slower on two of three configurations and is not used.)
+  const int n_live = min(per, (nq - qgrp * per * 32 + 31) >> 5);
+  const bool spec = NW == 8 && 2 * n_live <= NW;
+  if (n_it > 0 && spec) {
+    if (wave >= NW / 2) {
+      constexpr int PP = 16 / NW;                       // pieces per fetching thread
+      const int pbase = tid - NW * 32;                  // 0 .. NW*32 - 1; piece u of this thread: pbase + u * NW * 32
+      uint4 ak[PP], av[PP], bk[PP], bv[PP];             // (indices are compile-time constants throughout)
+#pragma unroll
+      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 0, ak[u], av[u]);
+#pragma unroll
+      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 1, bk[u], bv[u]);
+#pragma unroll
+      for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, 0, 0, ak[u], av[u]);
+#pragma unroll
+      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 2, ak[u], av[u]);
+      __syncthreads();
+      for (int i = 0; i < n_it; i += 2) {
+#pragma unroll
+        for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, i + 1, 1, bk[u], bv[u]);
+#pragma unroll
+        for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, i + 3, bk[u], bv[u]);
+        __syncthreads();
+        if (i + 1 < n_it) {
+#pragma unroll
+          for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, i + 2, 0, ak[u], av[u]);
+#pragma unroll
+          for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, i + 4, ak[u], av[u]);
+          __syncthreads();
+        }
+      }
+    } else {
+      __syncthreads();
+      for (int i = 0; i < n_it; i += 2) {
+        if (active) compute(st, qf, ql, i, 0);
+        __syncthreads();
+        if (i + 1 < n_it) {
+          if (active) compute(st, qf, ql, i + 1, 1);
+          __syncthreads();
+        }
+      }
+    }
+  } else if (n_it > 0) {
     if constexpr (U == 1) {
       // two tiles in flight in registers: set B holds tile i + 1 and set A tile i + 2 at the top of an (even) iteration
       uint4 ak, av, bk, bv;
