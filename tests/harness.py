@@ -118,7 +118,7 @@ class LazyF64Weights(dict):
         return super().__getitem__(k)
 
 
-class GpuRun:
+class DeviceRun:
     """Device-side mirror of a Case plus output buffers; methods call the C ABI."""
 
     def __init__(self, case: Case, device: str = "cuda:0", session=None, packed: bool = True, act_planes: int = 0):
@@ -224,7 +224,7 @@ def verify_window_of(cfg):
     return O.shifted_verify_window if getattr(cfg, "right_shifted", False) else O.verify_window
 
 
-def check_step(case: Case, run: GpuRun, g: Dict[str, np.ndarray], prm: Params, seqs=None,
+def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params, seqs=None,
                rep: Optional[Report] = None, check_logits: bool = True, check_kv_layers=None,
                pre_seq_len: Optional[np.ndarray] = None, free_router: bool = False) -> Report:
     """Compares one GPU step (outputs `g`, taken after the step with advance=False) with the oracle.
@@ -381,7 +381,7 @@ def _accept_forced(st, d, vo, prm, n, n_acc):
     return O.AcceptOut(n_acc, n_commit, resampled, block, u)
 
 
-def sync_case_from_gpu(case: Case, run: GpuRun, seqs=None):
+def sync_case_from_gpu(case: Case, run: DeviceRun, seqs=None):
     """Adopts the GPU's cache contents and state as the stored inputs of the next step.  With `seqs`, only
     the pages of those sequences are copied back (full-size caches are tens of GB)."""
     torch.cuda.synchronize(run.dev)

@@ -14,7 +14,7 @@ SMALL_BF16 = I.ModelCfg("small-bf16", 2, 512, 8, 4, 128, 1536, 32000)
 
 
 def run_steps(case, steps, prm_kw=None, check_logits=True, seqs=None, advance=True, packed=True, act_planes=0):
-    run = H.GpuRun(case, packed=packed, act_planes=act_planes)
+    run = H.DeviceRun(case, packed=packed, act_planes=act_planes)
     rep = H.Report()
     for s in range(steps):
         prm = Params(step=s, seed=1234, **(prm_kw or {}))
@@ -75,7 +75,7 @@ def test_small_bf16_real_prefill_b4():
 def test_draft_mask_flag_and_block_size_one():
     # B = 1: drafter and verifier see the same thing, every token is accepted (q == p up to rounding)
     case = H.make_case(TINY, 2, 1, [20, 33], seed=7, synthetic_kv=False, page_size=8, room=32)
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     prm = Params(step=0, seed=9)
     run.step(prm, advance=False)
     g = run.fetch()
@@ -85,7 +85,7 @@ def test_draft_mask_flag_and_block_size_one():
     # ar_mask = 0: committed in-block prefix sees the whole block
     case = H.make_case(TINY, 1, 4, [16], seed=8, synthetic_kv=False, page_size=8, room=32)
     case.states[0].block[:2] = [5, 6]
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     for ar in (1, 0):
         prm = Params(step=0, seed=9, ar_mask=ar)
         run.push_state()
@@ -105,7 +105,7 @@ def test_same_inputs_give_bit_identical_outputs(d_ffn):
     case = H.make_case(cfg, 2, 4, [50, 70], seed=4, synthetic_kv=True, page_size=16, room=32)
     outs = []
     for _ in range(2):
-        run = H.GpuRun(case)
+        run = H.DeviceRun(case)
         run.step(Params(step=3, seed=77), advance=True)
         g = run.fetch()
         outs.append(g)
@@ -119,7 +119,7 @@ def test_same_inputs_give_bit_identical_outputs(d_ffn):
 
 def test_kv_append_reports_enospc_without_writing():
     case = H.make_case(TINY, 1, 4, [30], seed=1, synthetic_kv=True, page_size=8, room=1)  # capacity 32
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     before = run.kv.k.clone()
     run.step(Params(step=0, seed=2), advance=False)
     g = run.fetch()
@@ -147,7 +147,7 @@ def test_config2_full_size_step_in_the_benchmark_launch_configuration():
     ses.prefill(ids)
     case = H.Case(cfg, W, N, B, wl.page_size, table, [], [], lens.copy())
     case.states = [O.SeqState(int(lens[n]), int(lens[n]), np.full(B, cfg.mask_id, dtype=np.int64)) for n in range(N)]
-    run = H.GpuRun(case, session=ses)
+    run = H.DeviceRun(case, session=ses)
     H.sync_case_from_gpu(case, run)
     # sampled prefix check: the first positions of the prefilled cache against an oracle prefill
     ck, cv = O.prefill(cfg, W, ids[0][:12])
@@ -207,7 +207,7 @@ def test_single_activation_plane_narrow_and_wide_windows():
 def test_small_moe_routing_grouped_gemm_and_combine():
     """MoE FFN: the oracle is held to the GPU's expert choices; the free-running router agreement is reported."""
     case = H.make_case(SMALL_MOE, 3, 8, [40, 90, 65], seed=12, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     rep = H.Report()
     for s in range(2):
         prm = Params(step=s, seed=99)
@@ -303,7 +303,7 @@ def test_fused_single_launch_forward_matches_the_oracle_and_the_multi_kernel_pat
     run.eng.s2d2_status()
     print("fused forward:", rep)
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
-    prof_run = H.GpuRun(case)
+    prof_run = H.DeviceRun(case)
     prof_run.eng.s2d2_profile_start(64)
     prof_run.eng.s2d2_draft(prof_run.kv, prof_run.st, 1, 4, Params(), prof_run.d)
     prof = prof_run.eng.s2d2_profile_stop()
@@ -472,7 +472,7 @@ def test_sampling_mode_drafting_at_temperature_half():
         assert all(c >= 1 for c in rep.n_commit)
     # the proposals really are samples: at T = 1 on near-uniform rows they differ from the arg-max somewhere
     case = H.make_case(SMALL_BF16, 2, 8, [40, 41], seed=13, synthetic_kv=True, page_size=16, room=64)
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     run.eng.s2d2_draft(run.kv, run.st, 2, 8, Params(step=0, seed=5), run.d)
     greedy = run.fetch()["xhat"].copy()
     run.eng.s2d2_draft(run.kv, run.st, 2, 8, Params(step=0, seed=5, mode=S2D2_SAMPLE, temperature=4.0), run.d)

@@ -34,7 +34,7 @@ def run_and_check(case, prm, seqs, kv_layers, free_router=False, second_step=Tru
     the resampled token as a leading causal row, whose K/V it appends: that exercises the cache write at
     full size (page arithmetic, key-minor V) against the oracle's causal rows."""
     t0 = time.time()
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     run.step(prm, advance=False)
     g = run.fetch()
     print(f"GPU step done after {time.time() - t0:.0f}s (upload + pack + step)", flush=True)

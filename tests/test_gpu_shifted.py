@@ -66,7 +66,7 @@ def test_cached_front_token_is_reported_and_the_sequence_skipped():
     # sequence 1 breaks the precondition: its front token counts as cached, nothing is carried
     case.states[1] = H.O.SeqState(33, 33, np.full(4, cfg.mask_id, dtype=np.int64))
     case.seq_len[1] = 33
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     before = run.st.block_tokens.clone()
     prm = Params(step=0, seed=9)
     run.step(prm, advance=False)
@@ -80,7 +80,7 @@ def test_cached_front_token_is_reported_and_the_sequence_skipped():
 def test_whole_block_append_is_refused():
     cfg = shifted(SMALL_BF16)
     case = H.make_case(cfg, 1, 4, [40], seed=1, synthetic_kv=True, page_size=16, room=64)
-    run = H.GpuRun(case)
+    run = H.DeviceRun(case)
     with pytest.raises(S2D2Error):
         run.eng.s2d2_block_complete(run.kv, run.st, 1, 4, run.v)
 
@@ -101,7 +101,7 @@ def test_session_prefill_carries_the_last_prompt_token_and_steps_match_the_oracl
     assert ses.st.carry_tokens[:, 0].tolist() == [int(ids[0][-1]), int(ids[1][-1])]
     case = H.Case(cfg, W, N, B, 16, table, [], [], lens - 1)
     case.states = [H.O.shifted_prefill_state(int(lens[n]), int(ids[n][-1]), B, cfg.mask_id) for n in range(N)]
-    run = H.GpuRun(case, session=ses)
+    run = H.DeviceRun(case, session=ses)
     H.sync_case_from_gpu(case, run)
     rep = H.Report()
     for s in range(4):
