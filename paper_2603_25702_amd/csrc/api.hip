@@ -65,9 +65,7 @@ struct s2d2_ctx {
   // MoE scratch
   float* router_logits;   // [rows_cap, E]
   int32_t* moe_choice;    // [n_layers, rows_cap * top_k] experts chosen in the last forward
-  int32_t* moe_pos;       // [rows_cap * top_k] place of the slot inside its expert's group
   float* moe_w;           // [rows_cap * top_k] renormalised routing weights
-  int32_t* moe_cnt;       // [E] group counters, zero between launches
   int32_t* moe_sorted;    // [rows_cap * top_k]
   int32_t *moe_tile_expert, *moe_tile_row0, *moe_tile_rows, *moe_n_tiles;
   int32_t moe_tile_cap;
@@ -201,9 +199,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     const size_t RK = R * (size_t)d.top_k;
     c->router_logits = cv.take<float>(R * (size_t)d.n_experts);
     c->moe_choice = cv.take<int32_t>((size_t)d.n_layers * RK);
-    c->moe_pos = cv.take<int32_t>(RK);
     c->moe_w = cv.take<float>(RK);
-    c->moe_cnt = cv.take<int32_t>(d.n_experts);
     c->moe_sorted = cv.take<int32_t>(RK);
     c->moe_tile_cap = (int32_t)(RK / 128 + d.n_experts + 1);
     c->moe_tile_expert = cv.take<int32_t>(c->moe_tile_cap);
@@ -430,8 +426,8 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         r.X = (const bf16_t*)c->a; r.ldx = ld_a; r.x_lo = lo_a; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
         r.eps = d.rms_eps; r.out = c->router_logits; r.ldo = E;
         { ProfScope ps(c, 0, (double)E * d.d_model * es); sk(r); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
-        { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w, c->moe_pos, c->moe_cnt); }
-        { ProfScope ps(c, 3, 0.0); launch_moe_group(st, E, tk, n_rows, choice, c->moe_pos, c->moe_cnt, c->moe_sorted, c->moe_tile_expert,
+        { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w); }
+        { ProfScope ps(c, 3, 0.0); launch_moe_group(st, E, tk, n_rows, choice, c->moe_sorted, c->moe_tile_expert,
                                                      c->moe_tile_row0, c->moe_tile_rows, c->moe_n_tiles, c->moe_tile_cap); }
         const int tile_cap = std::min(c->moe_tile_cap, R * tk / 128 + E + 1);
         GemmStreamArgs b{};
@@ -627,7 +623,6 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   launch_fill_i32(c->stream, c->zeros_i32, c->max_batch, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->pair_buf) launch_fill_i32(c->stream, (int32_t*)c->pair_buf, PAIR_CAP * 256 * 2, 0);
-  if (c->desc.n_experts > 0) launch_fill_i32(c->stream, c->moe_cnt, c->desc.n_experts, 0);
   if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;

@@ -4,9 +4,11 @@
 //   router logits [rows, E] (fp32, from the GEMM)  ->  softmax over all experts, top-k by value
 //   with ties to the lower index, weights renormalised to sum 1 (no shared expert, no capacity
 //   limit).  Every (token, slot) pair takes a place in its expert's group through an integer
-//   atomic counter; the order inside a group depends on scheduling, but every pair's result is
-//   computed from its own row only and written to its own (token, slot) row, and the combine
-//   adds the k slots of a token in slot order, so the output is deterministic.
+//   atomic counter in LDS (one workgroup groups all pairs; device-scope atomics from every routing
+//   wavefront on E addresses cost 25-40 us per launch); the order inside a group depends on
+//   scheduling, but every pair's result is computed from its own row only and written to its own
+//   (token, slot) row, and the combine adds the k slots of a token in slot order, so the output is
+//   deterministic.
 #include "s2d2_internal.h"
 #include "../../include/s2d2.h"
 
@@ -17,8 +19,7 @@ static constexpr int MOE_MAX_E = 256;   // experts per lane <= 4
 // One wavefront per row.
 __global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits, int E, int top_k,
                                                         const int32_t* __restrict__ m_count,
-                                                        int32_t* __restrict__ choice, float* __restrict__ route_w,
-                                                        int32_t* __restrict__ slot_pos, int32_t* __restrict__ cnt) {
+                                                        int32_t* __restrict__ choice, float* __restrict__ route_w) {
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= *m_count) return;
   float v[4];
@@ -62,23 +63,27 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict_
     const int o = row * top_k + lane;
     choice[o] = esel;
     route_w[o] = wsel / wsum;
-    slot_pos[o] = atomicAdd(&cnt[esel], 1);
   }
 }
 
 // One workgroup: group offsets, the list of 128-row tiles, the expert-sorted slot list; re-arms the counters.
 __global__ __launch_bounds__(1024) void moe_group_kernel(int E, int top_k, const int32_t* __restrict__ m_count,
                                                          const int32_t* __restrict__ choice,
-                                                         const int32_t* __restrict__ slot_pos, int32_t* __restrict__ cnt,
                                                          int32_t* __restrict__ sorted, int32_t* __restrict__ tile_expert,
                                                          int32_t* __restrict__ tile_row0, int32_t* __restrict__ tile_rows,
                                                          int32_t* __restrict__ n_tiles, int tile_cap) {
   __shared__ int s_off[MOE_MAX_E + 1];
+  __shared__ int s_cnt[MOE_MAX_E], s_fill[MOE_MAX_E];
   const int tid = threadIdx.x;
+  const int total = *m_count * top_k;
+  for (int e = tid; e < E; e += 1024) { s_cnt[e] = 0; s_fill[e] = 0; }
+  __syncthreads();
+  for (int i = tid; i < total; i += 1024) atomicAdd(&s_cnt[choice[i]], 1);
+  __syncthreads();
   if (tid == 0) {
     int run = 0, t = 0;
     for (int e = 0; e < E; ++e) {
-      const int c = cnt[e];
+      const int c = s_cnt[e];
       s_off[e] = run;
       for (int r0 = 0; r0 < c && t < tile_cap; r0 += 128, ++t) {
         tile_expert[t] = e;
@@ -91,10 +96,10 @@ __global__ __launch_bounds__(1024) void moe_group_kernel(int E, int top_k, const
     *n_tiles = t;
   }
   __syncthreads();
-  const int total = *m_count * top_k;
-  for (int i = tid; i < total; i += 1024) sorted[s_off[choice[i]] + slot_pos[i]] = i;
-  __syncthreads();
-  for (int e = tid; e < E; e += 1024) cnt[e] = 0;
+  for (int i = tid; i < total; i += 1024) {
+    const int e = choice[i];
+    sorted[s_off[e] + atomicAdd(&s_fill[e], 1)] = i;
+  }
 }
 
 // h[row] += sum over slots (in slot order) of y[row, slot]; also the operand and the partial sums
@@ -142,15 +147,15 @@ __global__ void moe_copy_choices_kernel(const int32_t* __restrict__ src, int32_t
 }
 
 void launch_moe_route(hipStream_t st, const float* logits, int E, int top_k, const int32_t* m_count, int rows_cap,
-                      int32_t* choice, float* route_w, int32_t* slot_pos, int32_t* cnt) {
+                      int32_t* choice, float* route_w) {
   S2D2_LAUNCH(moe_route_kernel, dim3((rows_cap + 3) / 4), dim3(256), 0, st, logits, E, top_k, m_count, choice,
-                     route_w, slot_pos, cnt);
+                     route_w);
 }
 
 void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, const int32_t* choice,
-                      const int32_t* slot_pos, int32_t* cnt, int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0,
-                      int32_t* tile_rows, int32_t* n_tiles, int tile_cap) {
-  S2D2_LAUNCH(moe_group_kernel, dim3(1), dim3(1024), 0, st, E, top_k, m_count, choice, slot_pos, cnt, sorted,
+                      int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0, int32_t* tile_rows, int32_t* n_tiles,
+                      int tile_cap) {
+  S2D2_LAUNCH(moe_group_kernel, dim3(1), dim3(1024), 0, st, E, top_k, m_count, choice, sorted,
                      tile_expert, tile_row0, tile_rows, n_tiles, tile_cap);
 }
 

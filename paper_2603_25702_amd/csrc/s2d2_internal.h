@@ -203,10 +203,10 @@ void launch_gemm_tile(hipStream_t st, int kind, int pro, const GemmStreamArgs& a
 
 // moe.hip
 void launch_moe_route(hipStream_t st, const float* logits, int E, int top_k, const int32_t* m_count, int rows_cap,
-                      int32_t* choice, float* route_w, int32_t* slot_pos, int32_t* cnt);
+                      int32_t* choice, float* route_w);
 void launch_moe_group(hipStream_t st, int E, int top_k, const int32_t* m_count, const int32_t* choice,
-                      const int32_t* slot_pos, int32_t* cnt, int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0,
-                      int32_t* tile_rows, int32_t* n_tiles, int tile_cap);
+                      int32_t* sorted, int32_t* tile_expert, int32_t* tile_row0, int32_t* tile_rows, int32_t* n_tiles,
+                      int tile_cap);
 void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const int32_t* m_count, int rows_cap,
                         float* h, void* xg, int xg_ld, int xg_lo, const float* gain_next, float* ss, int ss_stride);
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
