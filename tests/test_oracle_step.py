@@ -196,6 +196,63 @@ def test_accept_scan_stops_at_first_failure_and_energy_identity():
         assert O.accept_scan(p, q, u, gamma=1.0 + 1e-15) == n
 
 
+def test_tempered_ratio_is_the_plain_rule_on_transformed_uniforms():
+    """Ratio tempering (appendix on tempering the acceptance ratio): u < min(1, (q/p)^gamma) holds exactly when
+    u^(1/gamma) < min(1, q/p), so the tempered scan on u is the plain scan on u^(1/gamma); gamma = 0 accepts
+    everything; for a fixed u a larger gamma never accepts more."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        L = int(rng.integers(1, 8))
+        p, q, u = rng.uniform(0.01, 1, L), rng.uniform(0.01, 1, L), rng.uniform(1e-6, 1, L)
+        for gamma, root in ((2.0, np.sqrt(u)), (0.5, u * u), (4.0, np.sqrt(np.sqrt(u)))):
+            # (skip draws where the two sides of a comparison round to the same number)
+            if np.any(np.abs(root * p - q) < 1e-12):
+                continue
+            assert O.accept_scan(p, q, u, gamma=gamma) == O.accept_scan(p, q, root)
+        assert O.accept_scan(p, q, u, gamma=0.0) == L
+        counts = [O.accept_scan(p, q, u, gamma=g) for g in (0.0, 0.25, 0.5, 1.0, 2.0, 8.0)]
+        assert counts == sorted(counts, reverse=True)
+
+
+def test_tempered_acceptance_frequency_on_a_uniform_grid():
+    """One position, u on the midpoint grid of (0, 1): the accepted share is min(1, (q/p)^gamma) to 1/K; the
+    exponent is written as repeated multiplication / square roots, not as the oracle's power."""
+    K = 4000
+    u = (np.arange(K) + 0.5) / K
+    for p1, q1 in ((0.8, 0.2), (0.5, 0.45), (0.3, 0.9)):
+        r = min(1.0, q1 / p1)
+        for gamma, want in ((2.0, r * r), (3.0, r * r * r), (0.5, np.sqrt(r)), (1.0, r)):
+            share = np.mean([O.accept_scan(np.array([p1]), np.array([q1]), np.array([ui]), gamma=gamma) for ui in u])
+            assert abs(share - want) <= 1.0 / K + 1e-12
+
+
+def test_reject_only_keeps_the_accepted_prefix_and_commits_nothing_else(model):
+    """Reject-only variant (no residual resample): same accepted prefix as the full rule, the rejected position stays
+    masked, nothing is drawn, and the committed count is the accepted count (possibly zero)."""
+    W, prefix, ck, cv = model
+    seen_reject = 0
+    for seed in range(12):
+        st = fresh(len(prefix), 4)
+        d = O.draft(CFG, W, st, ck, cv, tau=0.9)
+        xhat = np.array(d.xhat, copy=True)
+        xhat[1] = (xhat[1] + 1 + seed) % (CFG.vocab - 1)      # a drafted token the verifier will mostly refuse
+        d.xhat = xhat
+        d.p = np.array(d.p, copy=True)
+        d.p[1] = 0.999
+        vo = O.verify(CFG, W, st, ck, cv, xhat)
+        full = O.accept(st, d, vo, seed, 0, 0)
+        ro = O.accept(st, d, vo, seed, 0, 0, resample=False)
+        j, L = vo.win.j, vo.win.L
+        assert ro.n_accept == full.n_accept and ro.resampled == -1 and ro.n_commit == ro.n_accept
+        assert np.array_equal(ro.block[j:j + ro.n_accept], xhat[j:j + ro.n_accept])
+        assert np.all(ro.block[j + ro.n_accept:] == MASK)
+        assert np.array_equal(ro.u, full.u)
+        if full.n_accept < L:
+            seen_reject += 1
+            assert full.n_commit == ro.n_commit + 1 and full.block[j + full.n_accept] == full.resampled
+    assert seen_reject >= 6
+
+
 def test_speculative_step_preserves_the_verifier_law_exact_rational():
     """First-position law: sum_x P(x) min(1,Q/P)(x) 1[x=v] + P(reject) * residual(v) == Q(v), exactly."""
     rng = np.random.default_rng(2)
