@@ -85,6 +85,9 @@ struct s2d2_ctx {
   size_t fused_act_stride;
   int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
   bool no_fused;
+  int64_t prefetch_bytes;   // S2D2_PREFETCH_MB: weight bytes the narrow attention launch reads ahead for the GEMMs behind it
+                            // (< 0: the output projection and the gate / up pair; 0: off)
+  int32_t prefetch_wgs;     // S2D2_PREFETCH_WGS: workgroups that do it (default: half the compute units)
   bool no_wide_attention;   // S2D2_ATTN_WIDE=0: one workgroup per query tile even for wide windows
   int wide_wgs;             // workgroups the split choice of the wide attention kernel aims for
   // profiling (measurement aid)
@@ -390,7 +393,18 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       if (wide)
         launch_attention_wide(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
       else
-        launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters);
+      {
+        // Narrow windows of a few sequences: the launch is a chain of dependent round trips on a fraction of the
+        // compute units.  Workgroups behind the attention's own read the weights of the next two GEMMs (the packed
+        // matrices of a layer lie one behind the other: wo, gate, up, down) into the memory-side cache meanwhile.
+        size_t ahead = 0;
+        if (fused && d.n_experts == 0 && c->prefetch_bytes != 0 && R <= 32 && Z * q_tiles * N * d.n_kv_heads <= 128) {
+          const size_t two = packed_weight_bytes(d.d_model, HqD) + 2 * packed_weight_bytes(d.d_ffn, d.d_model);
+          ahead = c->prefetch_bytes < 0 ? two : std::min((size_t)c->prefetch_bytes, two + packed_weight_bytes(d.d_model, d.d_ffn));
+        }
+        launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters,
+                               ahead ? c->pk[l].wo : nullptr, ahead, c->prefetch_wgs);
+      }
     } else {
       ProfScope ps(c, 1, 0.0);
       launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
@@ -609,6 +623,10 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   }
   c->no_fused = true;   // the fused forward is opt-in: on this hardware its device-wide barriers cost what kernel boundaries cost
   if (const char* e = getenv("S2D2_FUSED")) c->no_fused = atoi(e) == 0;
+  c->prefetch_bytes = -1;
+  c->prefetch_wgs = 128;
+  if (const char* e = getenv("S2D2_PREFETCH_MB")) c->prefetch_bytes = (int64_t)std::max(0, atoi(e)) << 20;
+  if (const char* e = getenv("S2D2_PREFETCH_WGS")) c->prefetch_wgs = std::max(1, atoi(e));
   launch_fill_i32(c->stream, c->fused_err, 64, 0);
   if (use_packed && c->desc.n_experts == 0 && act_planes(c->desc) == 2 && c->desc.head_dim == 128) {
     // one workgroup per compute unit must be resident at the same time for the device-wide barriers

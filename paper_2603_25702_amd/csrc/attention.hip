@@ -111,8 +111,24 @@ __global__ __launch_bounds__(NW * 64) void attn_flash_kernel(
     const bf16_t* __restrict__ q, int q_ld, int q_lo, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
     const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
     int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
-    float* __restrict__ part_ml, int32_t* __restrict__ counters) {
+    float* __restrict__ part_ml, int32_t* __restrict__ counters, int items, const uint4* __restrict__ pf, size_t pf_n16) {
   extern __shared__ float smem[];
+  if ((int)blockIdx.z >= items) {
+    // Workgroups behind the attention's own: they read the weights of the GEMMs that follow this launch, so that
+    // those find them in the memory-side cache.  The attention is bound by dependent round trips, not by
+    // bandwidth, and leaves most compute units and nearly all of the HBM time of its launch unused.
+    const size_t nwg = (size_t)(gridDim.z - items) * gridDim.y * gridDim.x;
+    const size_t wg = ((size_t)(blockIdx.z - items) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    const size_t per = (pf_n16 + nwg - 1) / nwg, b0 = wg * per, b1 = min(pf_n16, b0 + per);
+    for (size_t i = b0 + threadIdx.x; i < b1; i += (size_t)8 * NW * 64) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = pf[min(i + (size_t)u * NW * 64, b1 - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) asm volatile("" ::"v"(v[u].x), "v"(v[u].y), "v"(v[u].z), "v"(v[u].w));
+    }
+    return;
+  }
   attn_flash_body<NW, SPLIT, false>(q, q_ld, q_lo, k_win, vT_win, k_pages, v_pages, g, p, Hq, Z, wpad, scale_log2e, o, o_ld,
                                     o_lo, part_o, part_ml, counters, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y, smem);
 }
@@ -126,21 +142,25 @@ size_t attention_flash_partial_floats(size_t entries) { return entries * (32 * F
 void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
-                            int32_t* counters) {
+                            int32_t* counters, const void* prefetch, size_t prefetch_bytes, int prefetch_wgs) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)g.head_dim);
   const int items = N * g.n_kv_heads;
   float* part_o = part;
   float* part_ml = part + (size_t)items * q_tiles * Z * 32 * FA_D;
+  // extra slabs of Z * q_tiles workgroups that only read `prefetch` (see the kernel)
+  const int slabs = prefetch && prefetch_bytes >= 16 ? std::min(65535 - items, (prefetch_wgs + Z * q_tiles - 1) / (Z * q_tiles)) : 0;
+  const uint4* pf = (const uint4*)prefetch;
+  const size_t pf_n16 = slabs > 0 ? prefetch_bytes / 16 : 0;
   if (q_lo)
-    S2D2_LAUNCH((attn_flash_kernel<8, true>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+    S2D2_LAUNCH((attn_flash_kernel<8, true>), dim3(Z, q_tiles, items + slabs), dim3(8 * 64), fa_lds(8), st,
                        (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
                        (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
-                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
+                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, items, pf, pf_n16);
   else
-    S2D2_LAUNCH((attn_flash_kernel<8, false>), dim3(Z, q_tiles, items), dim3(8 * 64), fa_lds(8), st,
+    S2D2_LAUNCH((attn_flash_kernel<8, false>), dim3(Z, q_tiles, items + slabs), dim3(8 * 64), fa_lds(8), st,
                        (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win,
                        (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,
-                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters);
+                       (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, items, pf, pf_n16);
 }
 
 #ifdef S2D2_FUSED_TIMING

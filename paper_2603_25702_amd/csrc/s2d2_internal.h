@@ -264,7 +264,7 @@ size_t attention_flash_partial_floats(size_t entries);
 void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,
                             const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g, const Plan& p,
                             int N, int Hq, int q_tiles, int Z, int wpad, void* o, int o_ld, int o_lo, float* part,
-                            int32_t* counters);
+                            int32_t* counters, const void* prefetch, size_t prefetch_bytes, int prefetch_wgs);
 // Several query tiles per (sequence, KV head): one workgroup shares each K / V tile among them.
 int attention_wide_init();
 int attention_wide_nw(int q_tiles);
