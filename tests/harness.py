@@ -254,7 +254,9 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
         assert g["span_start"][n] == win.j and g["span_len"][n] == win.L
         rows_d = g["logit_row_of"][n]
         assert [(rows_d[i] >= 0) for i in range(B)] == [i in set(win.logit_index) for i in range(B)]
-        gl = np.stack([g["logits"][rows_d[i]] for i in win.logit_index]).astype(np.float64)
+        V = g["logits"].shape[1]
+        # (a block without [MASK] has no logit rows: the comparisons below then run over empty arrays)
+        gl = np.stack([g["logits"][rows_d[i]] for i in win.logit_index] or [np.zeros((0, V))]).astype(np.float64).reshape(-1, V)
         if check_logits:
             forced = None
             if moe:
@@ -265,8 +267,8 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
                         rep.router_rows += len(win.tokens)
                         rep.router_agree += int((np.sort(free.fwd.experts[l], axis=1) == np.sort(forced[l], axis=1)).all(axis=1).sum())
             od = O.draft(cfg, case.W, st, ck, cv, tau, bool(prm.ar_mask), forced_experts=forced)
-            scale = np.abs(od.logits).max()
-            err = np.abs(gl - od.logits).max() / scale
+            scale = np.abs(od.logits).max() if od.logits.size else 1.0
+            err = np.abs(gl - od.logits).max() / scale if od.logits.size else 0.0
             rep.max_logit_err_draft = max(rep.max_logit_err_draft, err)
             assert err <= LOGIT_RTOL, f"seq {n}: draft logits off by {err:.3e} of max|logit|"
         d = O.draft_from_logits(st, win, gl, cfg.mask_id, tau, mode, T, prm.seed, prm.step, n)
@@ -301,7 +303,7 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
         # ---- stage 3: verifier logits with the GPU's proposals ----------------------------------
         vwin = verify_window_of(cfg)(st, xhat, cfg.mask_id)
         rows_v = g["logit_row_of_ver"][n]
-        gv = np.stack([g["logits_ver"][rows_v[i]] for i in vwin.logit_index]).astype(np.float64)
+        gv = np.stack([g["logits_ver"][rows_v[i]] for i in vwin.logit_index] or [np.zeros((0, V))]).astype(np.float64).reshape(-1, V)
         assert g["stage_lead"][n] == vwin.n_lead
         ov = None
         if check_logits:
@@ -309,7 +311,7 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
             if moe:
                 forced = [ch_v[l, row0_v[n]:row0_v[n] + len(vwin.tokens)] for l in range(cfg.n_layers)]
             ov = O.verify(cfg, case.W, st, ck, cv, xhat, forced_experts=forced)
-            err = np.abs(gv - ov.logits).max() / np.abs(ov.logits).max()
+            err = np.abs(gv - ov.logits).max() / np.abs(ov.logits).max() if ov.logits.size else 0.0
             rep.max_logit_err_verify = max(rep.max_logit_err_verify, err)
             assert err <= LOGIT_RTOL, f"seq {n}: verifier logits off by {err:.3e} of max|logit|"
         vo = O.verify_from_logits(vwin, gv, xhat, ov.k if ov else None, ov.v if ov else None, mode, T)

@@ -72,6 +72,56 @@ def test_small_bf16_real_prefill_b4():
     print("small bf16 prefill:", rep)
 
 
+def test_degenerate_batch_empty_prefix_page_boundary_and_a_finished_block():
+    """Edge cases in one ragged batch: a sequence with an empty cache, one whose prefix ends exactly on a page
+    boundary, and one whose block holds no [MASK] when the step starts (no span, no logit rows, nothing drafted or
+    accepted; its committed, uncached tokens ride through the verifier as causal rows and are appended)."""
+    case = H.make_case(TINY, 3, 4, [0, 16, 37], seed=4, synthetic_kv=True, page_size=8, room=64)
+    case.states[2].block[:] = [5, 6, 7, 8]
+    run = H.DeviceRun(case)
+    rep = H.Report()
+    for s in range(3):
+        prm = Params(step=s, seed=77)
+        run.push_state()
+        run.step(prm, advance=False)
+        g = run.fetch()
+        H.check_step(case, run, g, prm, rep=rep)
+        if s == 0:
+            assert g["span_len"][2] == 0 and g["n_accept"][2] == 0 and g["n_commit"][2] == 0
+            assert int(run.kv.seq_len[2]) == 41      # the four pending tokens were appended
+        run.eng.s2d2_block_advance(run.kv, run.st, case.N, case.B, None)
+        H.sync_case_from_gpu(case, run)
+    print("degenerate batch:", rep)
+    assert rep.max_logit_err_draft < 1e-4 and rep.max_logit_err_verify < 1e-4
+    assert case.states[0].seq_len >= 1 and case.states[2].pos0 == 41
+
+
+@pytest.mark.parametrize("model", ["tiny_fp32", "small_bf16"])
+def test_maximum_block_size_of_64(model):
+    """B = 64, the largest block the boundary admits (per-sequence sets are 64-bit masks): 128 draft rows and 192
+    verifier rows per sequence, spans of up to 64 positions in the accept scan, several steps inside one block."""
+    if model == "tiny_fp32":
+        case = H.make_case(TINY, 2, 64, [40, 9], seed=12, synthetic_kv=True, page_size=8, room=256)
+    else:
+        case = H.make_case(SMALL_BF16, 1, 64, [150], seed=13, synthetic_kv=True, page_size=16, room=256)
+    run, rep = run_steps(case, 3)
+    print("B=64", model, rep)
+    assert rep.max_logit_err_draft <= (1e-4 if model == "tiny_fp32" else H.LOGIT_RTOL)
+    assert all(0 <= n <= 64 for n in rep.n_commit)
+
+
+def test_maximum_batch_of_1024_ragged_sequences():
+    """N = 1024, the largest batch the boundary admits (one planning thread per sequence), ragged prefixes from
+    1 to 60 tokens; the oracle follows the first, the last and 22 sampled sequences over two steps."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, 61, size=1024)
+    case = H.make_case(TINY, 1024, 2, lens, seed=14, synthetic_kv=True, page_size=8, room=32)
+    seqs = sorted({0, 1023, *rng.choice(1024, size=22, replace=False).tolist()})
+    run, rep = run_steps(case, 2, seqs=seqs)
+    print("N=1024:", rep)
+    assert rep.max_logit_err_draft < 1e-4 and rep.max_logit_err_verify < 1e-4
+
+
 def test_draft_mask_flag_and_block_size_one():
     # B = 1: drafter and verifier see the same thing, every token is accepted (q == p up to rounding)
     case = H.make_case(TINY, 2, 1, [20, 33], seed=7, synthetic_kv=False, page_size=8, room=32)
