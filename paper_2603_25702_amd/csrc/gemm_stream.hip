@@ -399,7 +399,11 @@ static void launch_pair(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
 // workgroups (256 workgroups: 9.6 us per launch against 13.0 us with 128 workgroups of 16 wavefronts, which
 // streamed at half the rate of the other layer GEMMs; digit 9 for `add` switches the pairing off).
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
-  if (m_cap > 32) {  // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16
+  // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16.  Not for a matrix
+  // of a few feature tiles (the MoE router, 64 experts): its weights stay in L2, a 256-column tile would be mostly
+  // empty, and a row tile of 16 per workgroup spreads the rows over the whole chip.
+  static const bool narrow_stream = !(getenv("S2D2_ROUTER_TILE") && atoi(getenv("S2D2_ROUTER_TILE")) != 0);
+  if (m_cap > 32 && !(narrow_stream && kind == SEPI_STORE_F32 && a.NT <= 8 && !a.gather)) {
     launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
     return;
   }
