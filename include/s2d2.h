@@ -316,7 +316,9 @@ int32_t s2d2_route(s2d2_ctx* ctx, int32_t N, int32_t B, const s2d2_route_params*
 
 /* Synchronises the context's stream and reports a sticky device-side failure: S2D2_ELAUNCH if a
  * device-wide barrier of the fused forward ran out of its bounded spin (a workgroup was not resident),
- * after which every later fused forward returns at once without computing; S2D2_OK otherwise. */
+ * after which every later fused forward returns at once without computing, or if a workgroup of the
+ * down projection waited in vain for the partial sums of the workgroup it shares K with (results of
+ * that forward are then invalid); S2D2_OK otherwise.  No kernel of the library waits unboundedly. */
 int32_t s2d2_status(s2d2_ctx* ctx);
 
 /* MoE models: the experts chosen by the router in the most recent forward (draft or verifier),
