@@ -171,7 +171,7 @@ def main():
             phases["vocab"]["hbm_GBs"] = round(vocab_bytes / (prof["vocab"]["ms"] * 1e-3 / Kp) / 1e9, 1)
         log(f"[bench] profile pass ({Kp} steps): {json.dumps(phases)}")
 
-    # ---- the fp64 oracle on the host cores: one full step of the same workload ---------------------
+    # ---- the fp64 oracle on the host cores: a bounded sample of full steps of the same workload -----
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import s2d2_oracle as O  # test infrastructure, used for the reported CPU baseline only
