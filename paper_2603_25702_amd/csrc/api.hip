@@ -80,6 +80,8 @@ struct s2d2_ctx {
   uint64_t* moe_y_or_scratch; // clock stamps of the timing build
   float* tile_partials;      // split-K partials of the tiled GEMM, TILE_PARTIAL_CAP x 64 KB
   int32_t* tile_counters;    // TILE_COUNTER_CAP arrival counters, zero between launches
+  float* accept_tiles;       // [max_batch, vocabulary tiles] residual tile sums shared by the workgroups of a sequence
+  int32_t* accept_arrive;    // [max_batch] their arrival counters, zero between launches
   unsigned long long* pair_buf;   // PAIR_CAP x 256 (value, tag) words of the streaming GEMM's paired K split, zero between launches
   uint8_t* fused_act;        // per-layer exchange buffers of the fused forward
   size_t fused_act_stride;
@@ -226,6 +228,8 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   c->moe_y_or_scratch = cv.take<uint64_t>(832);
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
+  c->accept_tiles = cv.take<float>(accept_tile_floats(c->max_batch, d.vocab));
+  c->accept_arrive = cv.take<int32_t>(c->max_batch);
   return (cv.off + 255) & ~(size_t)255;
 }
 
@@ -639,6 +643,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   }
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   launch_fill_i32(c->stream, c->zeros_i32, c->max_batch, 0);
+  launch_fill_i32(c->stream, c->accept_arrive, c->max_batch, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->pair_buf) launch_fill_i32(c->stream, (int32_t*)c->pair_buf, PAIR_CAP * 256 * 2, 0);
   if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
@@ -736,7 +741,7 @@ int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t 
   { ProfScope ps(c, 2, 0.0); launch_accept(c->stream, N, B, c->desc.vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample,
                 inv_temperature(prm), draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver,
                 ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
-                out->n_accept, out->n_commit, out->resampled, out->u_used, prm->active); }
+                out->n_accept, out->n_commit, out->resampled, out->u_used, prm->active, c->accept_tiles, c->accept_arrive); }
   return check_launch("s2d2_accept");
 }
 

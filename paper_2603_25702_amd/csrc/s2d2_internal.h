@@ -307,6 +307,8 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
-                   int32_t* resampled, float* u_used, const int32_t* active);
+                   int32_t* resampled, float* u_used, const int32_t* active, float* tile_scratch /* accept_tile_floats, may be NULL */,
+                   int32_t* arrivals /* [max_batch], zero between launches, may be NULL */);
+size_t accept_tile_floats(int max_batch, int V);
 
 }  // namespace s2d2

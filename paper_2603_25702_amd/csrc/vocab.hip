@@ -263,17 +263,16 @@ static constexpr int RMAX_TILES = 8192;
 // past V).  Two levels with a fixed summation order: tile sums (256 indices per tile: one wavefront x 4),
 // a scan of the tile sums, then a walk of the selected tile; rounding at either level falls back to the
 // nearest index that has mass.  s_tile needs RMAX_TILES floats, s_w four.
-template <typename F>
-__device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, float* s_tile, float* s_w,
-                                                 int* s_tile_sel, float* s_before) {
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int tiles = (V + RTILE - 1) / RTILE;
-  // Tile sums, eight tiles of a wavefront at a time: their loads are all issued before the first reduction (one tile
-  // per iteration made the pass a chain of ~150 memory round trips per wavefront).  A tile's sum does not depend on
-  // which wavefront forms it.
+// First level: the sums of tiles [tb, te) go to dst[tile] (LDS, or global memory with device-coherent stores when
+// several workgroups share the tiles of one row).  Eight tiles of a wavefront at a time: their loads are all issued
+// before the first reduction (one tile per iteration made the pass a chain of ~150 memory round trips per
+// wavefront).  A tile's sum does not depend on which wavefront or workgroup forms it.
+template <bool COH, typename F>
+__device__ __forceinline__ void inverse_cdf_tile_sums(const F& w4, int tb, int te, float* dst) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   constexpr int TU = 8;
   const int nw = blockDim.x >> 6;   // every wavefront of the workgroup takes part in this pass; the scan uses 256 threads
-  for (int t0 = w * TU; t0 < tiles; t0 += nw * TU) {
+  for (int t0 = tb + w * TU; t0 < te; t0 += nw * TU) {
     float r4[TU][4];
 #pragma unroll
     for (int u_ = 0; u_ < TU; ++u_) w4((t0 + u_) * RTILE + lane * 4, r4[u_]);   // indices at or past V give zeros
@@ -281,9 +280,19 @@ __device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, fl
     for (int u_ = 0; u_ < TU; ++u_) {
       float r = ((r4[u_][0] + r4[u_][1]) + r4[u_][2]) + r4[u_][3];
       for (int off = 32; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
-      if (lane == 0 && t0 + u_ < tiles) s_tile[t0 + u_] = r;
+      if (lane == 0 && t0 + u_ < te) {
+        if (COH) st4f_coh(&dst[t0 + u_], r); else dst[t0 + u_] = r;
+      }
     }
   }
+}
+
+// Second and third level, from the tile sums in s_tile (written by this workgroup's threads before the call).
+template <typename F>
+__device__ __forceinline__ int inverse_cdf_finish(const F& w4, int V, float u, float* s_tile, float* s_w,
+                                                  int* s_tile_sel, float* s_before) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tiles = (V + RTILE - 1) / RTILE;
   __syncthreads();
   // scan tile sums: thread t owns tiles [t*per, (t+1)*per)
   const int per = (tiles + 255) / 256;   // (threads past the first 256 own no tiles)
@@ -347,6 +356,13 @@ __device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, fl
   return token;
 }
 
+template <typename F>
+__device__ __forceinline__ int inverse_cdf_block(const F& w4, int V, float u, float* s_tile, float* s_w,
+                                                 int* s_tile_sel, float* s_before) {
+  inverse_cdf_tile_sums<false>(w4, 0, (V + RTILE - 1) / RTILE, s_tile);
+  return inverse_cdf_finish(w4, V, u, s_tile, s_w, s_tile_sel, s_before);
+}
+
 // SampleFromLogits in sampling mode: x_hat ~ softmax(logits / T) by inverse CDF in ascending vocabulary order with
 // the uniform of stream 2 at (step, sequence, block index); p = that token's probability.  One workgroup per
 // logit row; runs after the statistics kernels (reads lse, overwrites the arg-max proposal and its probability).
@@ -384,8 +400,12 @@ __global__ __launch_bounds__(256) void vocab_sample_kernel(
   }
 }
 
-// One workgroup per sequence: accept scan over C_t (thread 0), then, if a drafted token failed,
-// draw from the residual (P_ver - P_draft)_+ by inverse CDF in ascending vocabulary order.
+// gridDim.y workgroups per sequence: accept scan over C_t (thread 0 of each, the same result in all), then, if a
+// drafted token failed, a draw from the residual (P_ver - P_draft)_+ by inverse CDF in ascending vocabulary order.
+// With several workgroups each forms the tile sums of its share of the vocabulary (one sequence alone would stream
+// its two logit rows through a single compute unit), leaves them in tile_scratch[sequence][tile] and counts its
+// arrival; the last one to arrive finishes the draw and re-arms the counter.  Workgroup 0 writes everything that
+// does not depend on the draw.  The result does not depend on gridDim.y.
 __global__ __launch_bounds__(1024) void accept_kernel(
     int B, int V, uint64_t seed, uint32_t step, const uint32_t* __restrict__ step_dev, float gamma, int resample,
     float inv_t, const int32_t* __restrict__ span_start, const int32_t* __restrict__ span_len,
@@ -394,23 +414,25 @@ __global__ __launch_bounds__(1024) void accept_kernel(
     const int32_t* __restrict__ xhat, const float* __restrict__ p, const float* __restrict__ lse_d,
     const float* __restrict__ q, const float* __restrict__ lse_v, int32_t* __restrict__ block,
     int32_t* __restrict__ n_accept, int32_t* __restrict__ n_commit, int32_t* __restrict__ resampled,
-    float* __restrict__ u_used, const int32_t* __restrict__ active) {
+    float* __restrict__ u_used, const int32_t* __restrict__ active, float* __restrict__ tile_scratch,
+    int32_t* __restrict__ arrivals) {
   __shared__ float s_tile[RMAX_TILES];
   __shared__ float s_w[4];
-  __shared__ int s_nacc;
+  __shared__ int s_nacc, s_last;
   __shared__ int s_tile_sel;
   __shared__ float s_before;
-  const int n = blockIdx.x, tid = threadIdx.x;
+  const int n = blockIdx.x, tid = threadIdx.x, g = blockIdx.y, G = gridDim.y;
   const int j = span_start[n], L = (active && active[n] == 0) ? 0 : span_len[n];   // not routed to the verifier: nothing to scan
   const uint32_t stp = step + (step_dev ? *step_dev : 0u);
-  for (int i = tid; i < B; i += blockDim.x) u_used[(size_t)n * B + i] = 0.f;
+  if (g == 0)
+    for (int i = tid; i < B; i += blockDim.x) u_used[(size_t)n * B + i] = 0.f;
   __syncthreads();
   if (tid == 0) {
     int acc = 0;
     for (; acc < L; ++acc) {
       const int o = n * B + j + acc;
       const float u = uniform01(seed, stp, (uint32_t)n, (uint32_t)(j + acc), 0u);
-      u_used[o] = u;
+      if (g == 0) u_used[o] = u;
       const float pi = p[o], qi = q[o];
       const bool ok = gamma == 1.0f ? (u * pi < qi) : (u < fminf(1.0f, powf(qi / pi, gamma)));
       if (!ok) break;
@@ -419,9 +441,10 @@ __global__ __launch_bounds__(1024) void accept_kernel(
   }
   __syncthreads();
   const int acc = s_nacc;
-  for (int i = tid; i < acc; i += blockDim.x) block[n * B + j + i] = xhat[n * B + j + i];
+  if (g == 0)
+    for (int i = tid; i < acc; i += blockDim.x) block[n * B + j + i] = xhat[n * B + j + i];
   if (acc >= L || !resample) {
-    if (tid == 0) { n_accept[n] = acc; n_commit[n] = acc; resampled[n] = -1; }
+    if (g == 0 && tid == 0) { n_accept[n] = acc; n_commit[n] = acc; resampled[n] = -1; }
     return;
   }
   // ---- residual at block index i: r(v) = max(0, Q(v) - P(v)), both at the sampling temperature ----
@@ -445,7 +468,25 @@ __global__ __launch_bounds__(1024) void accept_kernel(
         r[e] = (i0 + e < V) ? fmaxf(0.f, __expf(lv[i0 + e] * inv_t - zv) - __expf(ld[i0 + e] * inv_t - zd)) : 0.f;
     }
   };
-  int token = inverse_cdf_block(residual4, V, u2, s_tile, s_w, &s_tile_sel, &s_before);
+  int token;
+  if (G == 1) {
+    token = inverse_cdf_block(residual4, V, u2, s_tile, s_w, &s_tile_sel, &s_before);
+  } else {
+    const int tiles = (V + RTILE - 1) / RTILE, share = (tiles + G - 1) / G;
+    float* mine = tile_scratch + (size_t)n * tiles;
+    inverse_cdf_tile_sums<true>(residual4, min(tiles, g * share), min(tiles, (g + 1) * share), mine);
+    __builtin_amdgcn_s_waitcnt(0);   // the write-through stores have completed before the arrival is counted
+    __syncthreads();
+    if (tid == 0) {
+      const int prev = __hip_atomic_fetch_add(&arrivals[n], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last = prev == G - 1;
+      if (prev == G - 1) __hip_atomic_store(&arrivals[n], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    for (int t = tid; t < tiles; t += blockDim.x) s_tile[t] = ld4f_coh(&mine[t]);
+    token = inverse_cdf_finish(residual4, V, u2, s_tile, s_w, &s_tile_sel, &s_before);
+  }
   if (tid == 0) {
     if (token < 0) token = xhat[o];  // residual without mass in fp32 (p and q equal to rounding): keep the draft
     block[o] = token;
@@ -460,10 +501,15 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    const float* logits_d, const int32_t* row_of_d, const float* logits_v,
                    const int32_t* row_of_v, const int32_t* xhat, const float* p, const float* lse_d,
                    const float* q, const float* lse_v, int32_t* block, int32_t* n_accept, int32_t* n_commit,
-                   int32_t* resampled, float* u_used, const int32_t* active) {
-  S2D2_LAUNCH(accept_kernel, dim3(N), dim3(1024), 0, st, B, V, seed, step, step_dev, gamma, resample, inv_t,
+                   int32_t* resampled, float* u_used, const int32_t* active, float* tile_scratch, int32_t* arrivals) {
+  // few sequences: up to 8 workgroups share the vocabulary of each (a share is then one round of the tile pass for
+  // vocabularies of up to 2^18 entries)
+  const int G = tile_scratch && arrivals ? std::max(1, std::min(8, 128 / N)) : 1;
+  S2D2_LAUNCH(accept_kernel, dim3(N, G), dim3(1024), 0, st, B, V, seed, step, step_dev, gamma, resample, inv_t,
                      span_start, span_len, logits_d, row_of_d, logits_v, row_of_v, xhat, p, lse_d, q, lse_v, block,
-                     n_accept, n_commit, resampled, u_used, active);
+                     n_accept, n_commit, resampled, u_used, active, tile_scratch, arrivals);
 }
+
+size_t accept_tile_floats(int max_batch, int V) { return (size_t)max_batch * ((V + RTILE - 1) / RTILE); }
 
 }  // namespace s2d2
