@@ -368,9 +368,8 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); sk(a); launch_gemm_stream(st, SEPI_STORE_F32, a, LR); }
     return check_launch("forward (fused)");
   }
-  if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride); }
+  if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride, c->rope_cs, d.head_dim, d.rope_theta); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
-  if (fused) { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
   for (int l = 0; l < d.n_layers; ++l) {
     const s2d2_layer_weights& L = c->layers[l];
     void* kw = k_stage ? (uint8_t*)k_stage + l * stage_layer : c->kwin;
@@ -489,11 +488,6 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
 }
 
 __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
-
-__global__ void clear_unplanned_kernel(int n, const int32_t* __restrict__ row_of, float* a, float* b) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n && row_of[i] < 0) { a[i] = 0.f; b[i] = 0.f; }
-}
 
 }  // namespace
 
@@ -722,10 +716,9 @@ int32_t s2d2_verify(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state*
     return rc;
   const s2d2_model_desc& d = c->desc;
   { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 1, d.right_shifted, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
-              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active, kv->status); }
+              draft->xhat, c->plan, out->logit_row_of, nullptr, nullptr, out->stage_row0, out->stage_lead, prm->active, kv->status,
+              out->q, out->lse_ver); }
   if ((rc = forward(c, kv, N, B, out->k_stage, out->v_stage, out->logits_ver))) return rc;
-  S2D2_LAUNCH(clear_unplanned_kernel, dim3((N * B + 255) / 256), dim3(256), 0, c->stream, N * B,
-                     out->logit_row_of, out->q, out->lse_ver);
   { ProfScope ps(c, 2, 0.0); launch_vocab_score(c->stream, out->logits_ver, d.vocab, c->plan.counts + 1, N * B, c->vws, c->plan.logit_seq,
                      c->plan.logit_idx, B, draft->xhat, out->q, out->lse_ver, inv_temperature(prm)); }
   return check_launch("s2d2_verify");

@@ -479,14 +479,26 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
 #undef S2D2_CFG
 }
 
-// First norm of the forward: xg = bf16(h * gain), one partial sum of squares per row.
+// First norm of the forward: xg = bf16(h * gain), one partial sum of squares per row; and the row's RoPE table
+// (cos / sin of pos * theta^(-2i/D), fp64 phase) when cs is given, which saves the launch of rope_table_kernel.
 __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restrict__ embed, int d, Plan p,
                                                          const float* __restrict__ gain, float* __restrict__ h,
                                                          bf16_t* __restrict__ xg, int xg_ld, int xg_lo,
-                                                         float* __restrict__ ss, int ss_stride) {
+                                                         float* __restrict__ ss, int ss_stride,
+                                                         float2* __restrict__ cs, int D, float theta) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   if (r >= p.counts[0]) return;
+  if (cs) {
+    const double pos = (double)p.row_pos[r];
+    const int half = D >> 1;
+    for (int i = threadIdx.x; i < half; i += 256) {
+      const double inv = exp2(-2.0 * (double)i / (double)D * log2((double)theta));
+      double sn, c;
+      sincos(pos * inv, &sn, &c);
+      cs[(size_t)r * half + i] = make_float2((float)c, (float)sn);
+    }
+  }
   const bf16_t* src = embed + (size_t)p.row_token[r] * d;
   float acc = 0.f;
   for (int i = threadIdx.x; i < d; i += 256) {
@@ -505,9 +517,9 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restric
 }
 
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
-                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride) {
+                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride, void* rope_cs, int D, float theta) {
   S2D2_LAUNCH(embed_norm_kernel, dim3(rows_cap), dim3(256), 0, st, (const bf16_t*)embed, d, p, gain, h,
-                     (bf16_t*)xg, xg_ld, xg_lo, ss, ss_stride);
+                     (bf16_t*)xg, xg_ld, xg_lo, ss, ss_stride, (float2*)rope_cs, D, theta);
 }
 
 }  // namespace s2d2

@@ -16,7 +16,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     const int32_t* __restrict__ carry, const int32_t* __restrict__ xhat, Plan p,
     int32_t* __restrict__ logit_row_of, int32_t* __restrict__ span_start,
     int32_t* __restrict__ span_len, int32_t* __restrict__ stage_row0, int32_t* __restrict__ stage_lead,
-    const int32_t* __restrict__ active, int32_t* __restrict__ status) {
+    const int32_t* __restrict__ active, int32_t* __restrict__ status, float* __restrict__ clear_a,
+    float* __restrict__ clear_b) {
   __shared__ int32_t s_rows[1024];
   __shared__ int32_t s_lrows[1024];
   const int n = threadIdx.x;
@@ -117,6 +118,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     stage_row0[n] = row0;
     stage_lead[n] = lead;
     for (int i = 0; i < B; ++i) logit_row_of[(size_t)n * B + i] = -1;
+    // per-position outputs of the verifier (q, lse) start at zero; the vocabulary pass fills the planned positions
+    if (clear_a)
+      for (int i = 0; i < B; ++i) { clear_a[(size_t)n * B + i] = 0.f; clear_b[(size_t)n * B + i] = 0.f; }
     const int32_t* xh = xhat + (size_t)n * B;
     const int n_drafted = shifted ? max(L - 1, 0) : L;   // a right-shifted window has no row for the last drafted token
     for (int t = 0; t < lead + n_drafted; ++t) {  // causal half: carry, pending committed, drafted C_t
@@ -158,10 +162,10 @@ void launch_plan(hipStream_t st, int verify, int shifted, int N, int B, int mask
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
-                 const int32_t* active, int32_t* status) {
+                 const int32_t* active, int32_t* status, float* clear_a, float* clear_b) {
   S2D2_LAUNCH(plan_kernel, dim3(1), dim3(1024), 0, st, verify, shifted, N, B, mask_id, ar_mask,
                      seq_len, pos0, block, carry, xhat, p, logit_row_of, span_start, span_len,
-                     stage_row0, stage_lead, active, status);
+                     stage_row0, stage_lead, active, status, clear_a, clear_b);
 }
 
 // ---------------------------------------------------------------------------------------------

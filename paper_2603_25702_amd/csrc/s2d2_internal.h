@@ -113,7 +113,8 @@ void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block comp
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
                  int32_t* span_start, int32_t* span_len, int32_t* stage_row0, int32_t* stage_lead,
-                 const int32_t* active, int32_t* status);
+                 const int32_t* active, int32_t* status,
+                 float* clear_a = nullptr, float* clear_b = nullptr /* verifier: [N, B] outputs zeroed for every position */);
 void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_cap, const KvGeom& g,
                       void* k_pages, void* v_pages, const void* k_stage, const void* v_stage,
                       const int32_t* stage_row0, const int32_t* stage_lead, const int32_t* span_len,
@@ -196,7 +197,8 @@ size_t packed_weight_bytes(int N, int K);
 void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
 void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs);
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
-                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride);
+                       float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride,
+                       void* rope_cs /* [rows, D/2] (cos, sin), may be NULL */, int D, float theta);
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap);
 // gemm_tile.hip : 128 x 256 LDS-tiled kernel on the same packed weights and argument block
 void launch_gemm_tile(hipStream_t st, int kind, int pro, const GemmStreamArgs& a, int row_tiles);
