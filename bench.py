@@ -120,6 +120,7 @@ def main():
         committed = int(ses.tot_commit.sum().item())
         accepted = int(ses.tot_accept.sum().item())
     assert int(ses.kv.status.abs().sum().item()) == 0, "a sequence ran out of cache pages"
+    ses.eng.s2d2_status()   # raises if a bounded device-side wait ran out during the timed steps (results would be invalid)
     value = committed / elapsed
     log(f"[bench] {K} steps in {elapsed * 1e3:.2f} ms: {committed} tokens committed ({accepted} accepted drafts)")
 
