@@ -159,11 +159,11 @@ __device__ __forceinline__ void attn_flash_body(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 31, h = lane >> 5;
   const int32_t* pt = g.page_table + (size_t)n * g.max_pages_per_seq;
-  // Tile t of the cached keys belongs to wavefront (t mod GW) of the GW = Z * NW wavefronts that
+  // Tile t of the cached keys belongs to wavefront (t mod GW) of the GW = Zeff * NW wavefronts (Zeff <= Z, below) that
   // share this (sequence, KV head, query tile): the assignment does not depend on seq_len, so the
   // page-table entries of a wavefront's first tile are requested together with seq_len and the
   // plan entries (one round trip), and K / V follow in the second.
-  const int gw = z * NW + wave, GW = Z * NW;
+  const int gw = z * NW + wave;
   const int kperm = fa_perm(c);
   const int cap = g.max_pages_per_seq * ps;
   int page_k = pt[min(gw * 32 + kperm, cap - 1) / ps];
@@ -198,6 +198,11 @@ __device__ __forceinline__ void attn_flash_body(
     for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
 
   const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
+  // The host sizes Z for the cache's CAPACITY; a sequence far below it uses only the first Zeff splits (one tile
+  // per wavefront is the finest useful cut), the others leave at once and are neither waited for nor merged.
+  const int Zeff = max(1, min(Z, (Tc + Tw + NW - 1) / NW));
+  if (z >= Zeff) return;
+  const int GW = Zeff * NW;
   const int n_c = Tc > gw ? (Tc - gw + GW - 1) / GW : 0;           // cached tiles gw, gw + GW, ...
   const int w_first = (GW - 1 - gw) % GW;                          // window tiles go to the last wavefronts
   const int n_w = Tw > w_first ? (Tw - w_first + GW - 1) / GW : 0;
@@ -355,7 +360,7 @@ __device__ __forceinline__ void attn_flash_body(
       const float4 v = ((const float4*)(s_o + (size_t)w2 * 4096))[g16 * 64 + ln];
       acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
     }
-    if (Z == 1) {
+    if (Zeff == 1) {
       const int qi2 = q0 + cc;
       if (qi2 < nq) {
         const float L = s_ML[32 + cc], inv = L > 0.f ? 1.0f / L : 0.f;
@@ -367,8 +372,8 @@ __device__ __forceinline__ void attn_flash_body(
       st16f_coh(part_o + (item0 + z) * 32 * D + (size_t)idx * 4, acc.x, acc.y, acc.z, acc.w);
     }
   }
-  if (Z == 1) return;
-  // Z > 1: this split's partial is written; the workgroup that arrives last merges all splits in split
+  if (Zeff == 1) return;
+  // Zeff > 1: this split's partial is written; the workgroup that arrives last merges all splits in split
   // order (so the result does not depend on which one it is) and re-arms the counter.
   if (threadIdx.x < 32) {
     st4f_coh(&part_ml[(item0 + z) * 64 + threadIdx.x], s_ML[threadIdx.x]);
@@ -380,14 +385,14 @@ __device__ __forceinline__ void attn_flash_body(
   int* s_last = (int*)(s_ML + 64);
   if (threadIdx.x == 0) {
     const int prev = __hip_atomic_fetch_add(&counters[group], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_last = prev == Z - 1;
-    if (prev == Z - 1) __hip_atomic_store(&counters[group], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = prev == Zeff - 1;
+    if (prev == Zeff - 1) __hip_atomic_store(&counters[group], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   S2D2_ATS(5);
   if (!*s_last) return;
   S2D2_ATS_ANY(6);
-  fa_combine<COH, NW * 64>(part_o, part_ml, item0, Z, threadIdx.x, qt, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
+  fa_combine<COH, NW * 64>(part_o, part_ml, item0, Zeff, threadIdx.x, qt, nq, grp, row0, kvh, Hq, o, o_ld, o_lo);
   __builtin_amdgcn_s_waitcnt(0);
   S2D2_ATS_ANY(7);
 }
