@@ -198,9 +198,11 @@ __device__ __forceinline__ void attn_flash_body(
     for (int i = 0; i < 16; ++i) st.o[t][i] = 0.f;
 
   const int Tc = (S + 31) >> 5, Tw = (nw + 31) >> 5;
-  // The host sizes Z for the cache's CAPACITY; a sequence far below it uses only the first Zeff splits (one tile
-  // per wavefront is the finest useful cut), the others leave at once and are neither waited for nor merged.
-  const int Zeff = max(1, min(Z, (Tc + Tw + NW - 1) / NW));
+  // The host sizes Z for the cache's CAPACITY; a sequence far below it uses only the first Zeff splits, the others
+  // leave at once and are neither waited for nor merged.  Up to four splits (one round of the merge below) as soon as
+  // every second wavefront has a tile, more only when a wavefront would otherwise walk several tiles.
+  const int T_all = Tc + Tw;
+  const int Zeff = max(1, min(Z, max((T_all + NW - 1) / NW, min(4, (2 * T_all + NW - 1) / NW))));
   if (z >= Zeff) return;
   const int GW = Zeff * NW;
   const int n_c = Tc > gw ? (Tc - gw + GW - 1) / GW : 0;           // cached tiles gw, gw + GW, ...
