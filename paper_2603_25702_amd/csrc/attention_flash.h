@@ -48,6 +48,15 @@ __device__ __forceinline__ uint4 mask_keys(uint4 v, int nv) {  // keep the first
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// x / d for 0 <= x < 2^20 and d >= 1, exact, without the long reciprocal sequence of an integer division (the
+// divisor below is only known once seq_len has arrived, so nothing of that sequence could be hoisted above the wait).
+__device__ __forceinline__ int fa_div(int x, int d) {
+  int q = (int)((float)x * __builtin_amdgcn_rcpf((float)d));
+  q -= (int)(q * d > x);
+  q += (int)((q + 1) * d <= x);
+  return q;
+}
+
 struct FaState {
   float m, l;
   f32x16_t o[4];
@@ -205,9 +214,9 @@ __device__ __forceinline__ void attn_flash_body(
   const int Zeff = max(1, min(Z, max((T_all + NW - 1) / NW, min(4, (2 * T_all + NW - 1) / NW))));
   if (z >= Zeff) return;
   const int GW = Zeff * NW;
-  const int n_c = Tc > gw ? (Tc - gw + GW - 1) / GW : 0;           // cached tiles gw, gw + GW, ...
-  const int w_first = (GW - 1 - gw) % GW;                          // window tiles go to the last wavefronts
-  const int n_w = Tw > w_first ? (Tw - w_first + GW - 1) / GW : 0;
+  const int n_c = Tc > gw ? fa_div(Tc - gw + GW - 1, GW) : 0;      // cached tiles gw, gw + GW, ...
+  const int w_first = GW - 1 - gw;                                 // window tiles go to the last wavefronts (gw < GW)
+  const int n_w = Tw > w_first ? fa_div(Tw - w_first + GW - 1, GW) : 0;
 
   for (int it = 0; it < n_c + n_w; ++it) {
     const bool win = it >= n_c;
