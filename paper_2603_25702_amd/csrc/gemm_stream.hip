@@ -413,7 +413,7 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
   if (variant[0] < 0) {
     const char* e = getenv("S2D2_GEMM_CFG");
     // qkv: 8 wavefronts x 4 loads in flight (1.8 % over 4 x 8 once the weight loads were non-temporal); swiglu: 4 x 4
-    // (768 workgroups, three per compute unit; 0.4 % over 8 x 4 since the attention launch reads these weights ahead)
+    // (half the wavefronts per feature tile to merge; 0.4 % over 8 x 4 since the attention launch reads these weights ahead)
     static const int defaults[4] = {5, 0, 3, 0};
     for (int i = 0; i < 4; ++i) variant[i] = (e && strlen(e) == 4 && e[i] >= '0' && e[i] <= '9') ? e[i] - '0' : defaults[i];
   }
