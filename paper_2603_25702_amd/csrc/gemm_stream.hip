@@ -450,12 +450,11 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
         else if (variant[1] == 7) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 3);
         else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
       } else {
-        // short K (the output projection): 8 wavefronts x 4 loads (0.25 % of the config-2 step over 16 x 4)
         if (variant[1] == 3) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 8);
         else if (variant[1] == 5) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 2);
-        else if (variant[1] == 7) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
+        else if (variant[1] == 6) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 4);
         else if (variant[1] == 8) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 2);
-        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 4);
+        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
       }
       break;
     case SEPI_SWIGLU:
