@@ -122,6 +122,19 @@ def test_maximum_batch_of_1024_ragged_sequences():
     assert rep.max_logit_err_draft < 1e-4 and rep.max_logit_err_verify < 1e-4
 
 
+def test_narrow_windows_with_k_shares_that_end_in_a_partial_batch_of_loads():
+    """d_model 1280 and d_ffn 2560 (40 and 80 K tiles): the K share of a streaming-GEMM wavefront is 5 or 10 tiles,
+    i.e. full batches of four loads followed by a partial one, which none of the five configurations' shapes has."""
+    cfg = I.ModelCfg("mid-bf16", 2, 1280, 8, 4, 128, 2560, 32000)
+    case = H.make_case(cfg, 1, 4, [70], seed=21, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 2)
+    print("partial batches:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+    case = H.make_case(cfg, 2, 8, [33, 90], seed=22, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 2)       # 32 draft rows: two row tiles of the streaming kernel
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+
+
 def test_draft_mask_flag_and_block_size_one():
     # B = 1: drafter and verifier see the same thing, every token is accepted (q == p up to rounding)
     case = H.make_case(TINY, 2, 1, [20, 33], seed=7, synthetic_kv=False, page_size=8, room=32)
