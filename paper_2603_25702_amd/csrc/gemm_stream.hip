@@ -108,6 +108,7 @@ __device__ unsigned long long g_stream_ts[4][16];   // [epilogue kind][first wor
 template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT, bool PAIR = false>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
   static_assert(!PAIR || (EPI == SEPI_ADD_F32 && TPW == 1), "the paired K split exists for the residual-add epilogue only");
+  static_assert(NW >= 4, "the epilogue maps 256 threads onto the 16 x 16 tile (row = thread / 16, feature = thread % 16)");
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
   extern __shared__ __align__(16) uint8_t smem_raw[];
@@ -125,7 +126,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   const bool producer = PAIR && (int)blockIdx.x < nx;
   const int bx = PAIR ? (int)blockIdx.x % nx : (int)blockIdx.x;
   const int nt0 = bx * TPW;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // The wavefront index is made a scalar: every bound of the K loop derives from it, and a matrix instruction
+  // ignores the execution mask.  With the index left in a vector register the `if (kt0 + u < kt_end) mac(u)` of a
+  // share's last batch compiles to an execution-mask region, and when that region holds nothing but MFMAs the
+  // compiler drops the branch around it: the MFMAs of slots past the share then run with an empty mask and add
+  // the (clamped, duplicated) last tile again.  Scalar bounds give scalar branches, which skip the instructions.
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = lane >> 4, f = lane & 15;
   const int KT = a.KT;
 
@@ -392,87 +398,48 @@ static void launch_pair(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   S2D2_LAUNCH((gemm_stream_kernel<SEPI_ADD_F32, SPRO_BF16, NW, 1, U, SPLIT, true>), grid, block, lds, st, a);
 }
 
-// Launch shapes (wavefronts per workgroup, feature tiles per workgroup, loads in flight per wavefront): the
-// layer matrices want >= 256 workgroups; with the sliding-window K loop the step time moves by less than 2 %
-// over the twenty shapes selectable through S2D2_GEMM_CFG (one digit per kind: qkv, add, swiglu, store).
+// Launch shapes (wavefronts per workgroup, feature tiles per workgroup, loads in flight per wavefront), tuned on the
+// 1.7B shape: the layer matrices want >= 256 workgroups; with the sliding-window K loop the step time moved by less
+// than 2 % over twenty shapes, so one shape per kind is compiled, and each is compared with the CPU reference by the
+// parity tests (also on K shares that end in a partial batch of loads).
 // The down projection has only d_model / 16 feature tiles (128 for the 1.7B shape): there K is shared by pairs of
 // workgroups (256 workgroups: 9.6 us per launch against 13.0 us with 128 workgroups of 16 wavefronts, which
-// streamed at half the rate of the other layer GEMMs; digit 9 for `add` switches the pairing off).
+// streamed at half the rate of the other layer GEMMs).
 void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m_cap) {
   // wide windows: the LDS-tiled kernel reads the weights once per 128 rows instead of once per 16.  Not for a matrix
   // of a few feature tiles (the MoE router, 64 experts): its weights stay in L2, a 256-column tile would be mostly
   // empty, and a row tile of 16 per workgroup spreads the rows over the whole chip.
-  static const bool narrow_stream = !(getenv("S2D2_ROUTER_TILE") && atoi(getenv("S2D2_ROUTER_TILE")) != 0);
-  if (m_cap > 32 && !(narrow_stream && kind == SEPI_STORE_F32 && a.NT <= 8 && !a.gather)) {
+  if (m_cap > 32 && !(kind == SEPI_STORE_F32 && a.NT <= 8 && !a.gather)) {
     launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
     return;
   }
   const bool sp = a.x_lo != 0;
-  // launch shape variant per kind, digits of S2D2_GEMM_CFG in the order qkv, add (long K), swiglu, store (tuning aid)
-  static int variant[4] = {-1, -1, -1, -1};
-  if (variant[0] < 0) {
-    const char* e = getenv("S2D2_GEMM_CFG");
-    // qkv: 8 wavefronts x 4 loads in flight (1.8 % over 4 x 8 once the weight loads were non-temporal); swiglu: 4 x 4
-    // (half the wavefronts per feature tile to merge; 0.4 % over 8 x 4 since the attention launch reads these weights ahead)
-    static const int defaults[4] = {5, 0, 3, 0};
-    for (int i = 0; i < 4; ++i) variant[i] = (e && strlen(e) == 4 && e[i] >= '0' && e[i] <= '9') ? e[i] - '0' : defaults[i];
-  }
 #define S2D2_CFG(EPI, PRO, NW, TPW, U)                                         \
   do {                                                                         \
     if (sp) launch_cfg<EPI, PRO, NW, TPW, U, true>(st, a, m_cap);              \
     else launch_cfg<EPI, PRO, NW, TPW, U, false>(st, a, m_cap);                \
   } while (0)
   switch (kind) {
-    case SEPI_QKV_ROPE:
+    case SEPI_QKV_ROPE:   // 8 wavefronts x 4 loads in flight (1.8 % over 4 x 8 once the weight loads were non-temporal)
       if (a.NT >= 1024) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 2, 4);
-      else if (variant[0] == 1) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 8);
-      else if (variant[0] == 2) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 16, 1, 4);
-      else if (variant[0] == 3) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 2, 1, 8);
-      else if (variant[0] == 4) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 4);
-      else if (variant[0] == 5) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 4);
-      else if (variant[0] == 6) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 2);
-      else if (variant[0] == 7) S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 2);
-      else S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 4, 1, 8);
+      else S2D2_CFG(SEPI_QKV_ROPE, SPRO_BF16S, 8, 1, 4);
       break;
     case SEPI_ADD_F32:
       // long K and few feature tiles (the down projection): pairs of workgroups share K, one workgroup per CU
-      if (a.KT >= 128 && a.pair_buf && variant[1] != 9 && (long long)a.NT * ((m_cap + 15) / 16) <= a.pair_cap) {
+      if (a.KT >= 128 && a.pair_buf && (long long)a.NT * ((m_cap + 15) / 16) <= a.pair_cap) {
         if (sp) launch_pair<8, 4, true>(st, a, m_cap);
         else launch_pair<8, 4, false>(st, a, m_cap);   // (16 wavefronts, or 3 to 12 loads in flight: within 1 %)
-        break;
-      }
-      // Only 16-wavefront shapes are selectable without the pairing: the 8-wavefront one (8 x 4 loads) was 0.25 % faster
-      // on the output projection but gave wrong logits on a 32-row window of a small model (cause not found), and
-      // the other narrower shapes were only ever timed, never checked against the oracle.
-      if (a.KT >= 128) {
-        if (variant[1] == 2) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 6);
-        else if (variant[1] == 5) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 2);
-        else if (variant[1] == 7) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 3);
-        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
-      } else {
-        if (variant[1] == 5) S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 2);
-        else S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
+      } else if (a.KT >= 128) {
+        S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
+      } else {   // short K (the output projection): 0.25 % of the 1.7B step over 16 x 4
+        S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 8, 1, 4);
       }
       break;
-    case SEPI_SWIGLU:
-      if (variant[2] == 1) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 8);
-      else if (variant[2] == 2) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 8);
-      else if (variant[2] == 3) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 4);
-      else if (variant[2] == 4) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 2, 1, 4);
-      else if (variant[2] == 5) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 4);
-      else if (variant[2] == 6) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 8, 1, 2);
-      else if (variant[2] == 7) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 2);
-      else if (variant[2] == 8) S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 16, 1, 2);
-      else S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 8);
+    case SEPI_SWIGLU:     // 4 x 4: half the wavefronts per feature tile to merge (0.4 % over 8 x 4 with the weights read ahead)
+      S2D2_CFG(SEPI_SWIGLU, SPRO_BF16S, 4, 1, 4);
       break;
     case SEPI_STORE_F32:
-      if (variant[3] == 1) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 8);
-      else if (variant[3] == 2) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 2, 2, 4);
-      else if (variant[3] == 3) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 1, 8);
-      else if (variant[3] == 4) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 2);
-      else if (variant[3] == 5) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 8, 2, 2);
-      else if (variant[3] == 6) S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 8, 1, 4);
-      else S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 4);
+      S2D2_CFG(SEPI_STORE_F32, SPRO_BF16S, 4, 2, 4);
       break;
   }
 #undef S2D2_CFG

@@ -332,7 +332,7 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
             assert (np.abs(ratios[:upto] - a.u[:upto]) < TIE).any(), f"seq {n}: n_accept {n_acc_gpu} vs {a.n_accept}"
             rep.exempt_ratio += 1
             # continue the comparison along the GPU's branch
-            a = _accept_forced(st, d, vo, prm, n, n_acc_gpu)
+            a = _accept_forced(st, d, vo, prm, n, n_acc_gpu, T)
         res_gpu = int(g["resampled"][n])
         if res_gpu != a.resampled:
             assert a.resampled >= 0 and res_gpu >= 0
@@ -367,7 +367,7 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
     return rep
 
 
-def _accept_forced(st, d, vo, prm, n, n_acc):
+def _accept_forced(st, d, vo, prm, n, n_acc, T=1.0):
     """Oracle accept along a prescribed accepted count (used after a near-tie exemption)."""
     j, L = vo.win.j, vo.win.L
     u = np.array([O.uniform(prm.seed, prm.step, n, j + r, O.STREAM_ACCEPT) for r in range(L)])
@@ -377,7 +377,7 @@ def _accept_forced(st, d, vo, prm, n, n_acc):
     if n_acc < L and prm.resample:
         i = j + n_acc
         row_d = int(np.nonzero(d.win.logit_index == i)[0][0])
-        resampled = O.residual_resample(d.logits[row_d], vo.logits[n_acc], O.uniform(prm.seed, prm.step, n, i, O.STREAM_RESAMPLE))
+        resampled = O.residual_resample(d.logits[row_d], vo.logits[n_acc], O.uniform(prm.seed, prm.step, n, i, O.STREAM_RESAMPLE), T)
         block[i] = resampled
         n_commit = n_acc + 1
     return O.AcceptOut(n_acc, n_commit, resampled, block, u)
