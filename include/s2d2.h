@@ -253,6 +253,22 @@ int32_t s2d2_accept(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_
                     const s2d2_params* prm, const s2d2_draft_out* draft,
                     const s2d2_verify_out* ver, const s2d2_accept_out* out);
 
+/* s2d2_accept for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as s2d2_accept (bit for
+ * bit), but no context and no workspace: the scratch of the residual draw (tile sums that the workgroups of a
+ * sequence hand to each other, 4 bytes per 256 vocabulary entries and sequence, and one arrival counter per
+ * sequence) lives in a device array inside the library, 512.5 KB on every GPU the library runs on, held until the
+ * process ends.  Limits: N <= 128, vocab <= 262144 (2^18), B <= S2D2_MAX_BLOCK; beyond them the call returns
+ * S2D2_ENOSPC and launches nothing.  `stream` is a hipStream_t (NULL: the default stream), `vocab` the width of
+ * the logit rows; st->block_pos0 and st->carry_tokens are not read.  The call enqueues two kernels (a fill that
+ * zeroes the arrival counters, then the accept kernel) and calls no hipMalloc, hipFree or other allocating routine;
+ * the array's device address is looked up once per device (at s2d2_create, else on the first call on that device,
+ * which must be current).  All calls on one GPU share the array: calls that overlap on one GPU (two streams, two
+ * threads) race; calls on one stream, or otherwise ordered, are safe. */
+int32_t s2d2_accept_static(void* stream, int32_t vocab, const s2d2_block_state* st, int32_t N, int32_t B,
+                           const s2d2_params* prm, const s2d2_draft_out* draft, const s2d2_verify_out* ver,
+                           const s2d2_accept_out* out);
+
 /* Append the staged K/V of the leading committed rows and of C_t[0 : n_accept) to the cache
  * and advance seq_len (Alg. 1 append; Section 4.2 causal caching makes these rows final). */
 int32_t s2d2_kv_append(s2d2_ctx* ctx, const s2d2_kv_view* kv, int32_t N, int32_t B,

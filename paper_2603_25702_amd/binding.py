@@ -21,7 +21,7 @@ S2D2_GREEDY, S2D2_SAMPLE = 0, 1
 
 EXPORTS = [
     "s2d2_last_error", "s2d2_version", "s2d2_stage_rows", "s2d2_workspace_bytes", "s2d2_packed_bytes", "s2d2_create", "s2d2_destroy",
-    "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_kv_append", "s2d2_block_advance",
+    "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_accept_static", "s2d2_kv_append", "s2d2_block_advance",
     "s2d2_commit_threshold", "s2d2_block_complete", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
 PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "forward")
@@ -126,6 +126,9 @@ def load_library():
                                 C.POINTER(ParamsC), C.POINTER(DraftOutC), C.POINTER(VerifyOutC)]
     lib.s2d2_accept.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(ParamsC),
                                 C.POINTER(DraftOutC), C.POINTER(VerifyOutC), C.POINTER(AcceptOutC)]
+    lib.s2d2_accept_static.argtypes = [C.c_void_p, C.c_int32, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(ParamsC),
+                                       C.POINTER(DraftOutC), C.POINTER(VerifyOutC), C.POINTER(AcceptOutC)]
+    lib.s2d2_accept_static.restype = C.c_int32
     lib.s2d2_kv_append.argtypes = [C.c_void_p, C.POINTER(KvView), C.c_int32, C.c_int32, C.POINTER(DraftOutC),
                                    C.POINTER(VerifyOutC), C.c_void_p]
     lib.s2d2_block_advance.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
@@ -317,6 +320,15 @@ class AcceptOut:
             return self.__dict__["t"][k]
         except KeyError:
             raise AttributeError(k)
+
+
+def s2d2_accept_static(stream: Optional[torch.cuda.Stream], vocab: int, st: BlockState, N: int, B: int, prm: Params,
+                       draft: DraftOut, ver: VerifyOut, out: AcceptOut):
+    """The accept step without a context or a workspace (scratch inside the library; N <= 128, vocab <= 2^18)."""
+    lib = load_library()
+    s = stream if stream is not None else torch.cuda.current_stream(draft.logits.device)
+    _check(lib, lib.s2d2_accept_static(C.c_void_p(s.cuda_stream), vocab, C.byref(st.c()), N, B, C.byref(prm.c()),
+                                       C.byref(draft.c()), C.byref(ver.c()), C.byref(out.c())))
 
 
 class Engine:

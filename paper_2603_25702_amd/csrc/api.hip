@@ -640,7 +640,8 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   launch_fill_i32(c->stream, c->accept_arrive, c->max_batch, 0);
   if (c->tile_counters) launch_fill_i32(c->stream, c->tile_counters, TILE_COUNTER_CAP, 0);
   if (c->pair_buf) launch_fill_i32(c->stream, (int32_t*)c->pair_buf, PAIR_CAP * 256 * 2, 0);
-  if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
+  if (accept_static_scratch(nullptr, nullptr)) { (void)hipGetLastError(); free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not look up the device address of the library's scratch array"); }
+  if (attention_init() || attention_wide_init()) { (void)hipGetLastError(); free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "could not raise the LDS limit of the attention kernel"); }
   *out = c;
   return S2D2_OK;
 }
@@ -736,6 +737,29 @@ int32_t s2d2_accept(s2d2_ctx* c, const s2d2_block_state* st, int32_t N, int32_t 
                 ver->logit_row_of, draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens,
                 out->n_accept, out->n_commit, out->resampled, out->u_used, prm->active, c->accept_tiles, c->accept_arrive); }
   return check_launch("s2d2_accept");
+}
+
+int32_t s2d2_accept_static(void* stream, int32_t vocab, const s2d2_block_state* st, int32_t N, int32_t B,
+                           const s2d2_params* prm, const s2d2_draft_out* draft, const s2d2_verify_out* ver,
+                           const s2d2_accept_out* out) {
+  int32_t rc;
+  if (N < 1 || N > ACCEPT_STATIC_MAX_BATCH) return fail(S2D2_ENOSPC, "s2d2_accept_static: N=%d outside [1, %d] (the library's own scratch holds %d sequences; use s2d2_accept with a workspace)", N, ACCEPT_STATIC_MAX_BATCH, ACCEPT_STATIC_MAX_BATCH);
+  if (vocab < 2 || vocab > ACCEPT_STATIC_MAX_VOCAB) return fail(S2D2_ENOSPC, "s2d2_accept_static: vocab=%d outside [2, %d] (size of the library's own scratch; use s2d2_accept with a workspace)", vocab, ACCEPT_STATIC_MAX_VOCAB);
+  if (B < 1 || B > S2D2_MAX_BLOCK) return fail(S2D2_EINVAL, "B=%d outside [1, %d]", B, S2D2_MAX_BLOCK);
+  if (!st || !st->block_tokens) return fail(S2D2_EINVAL, "block state or its block_tokens is NULL");
+  if ((rc = check_params(prm)) || (rc = check_draft_out(draft)) || (rc = check_verify_out(ver))) return rc;
+  if (!out || !out->n_accept || !out->n_commit || !out->resampled || !out->u_used) return fail(S2D2_EINVAL, "accept output or one of its pointers is NULL");
+  float* tiles = nullptr;
+  int32_t* arrivals = nullptr;
+  if (accept_static_scratch(&tiles, &arrivals)) return fail(S2D2_ELAUNCH, "s2d2_accept_static: could not look up the device address of the library's scratch array");
+  hipStream_t s = (hipStream_t)stream;
+  // the array keeps what the last call left: the arrival counters must start at zero (a fill kernel, no memset node)
+  launch_fill_i32(s, arrivals, N, 0);
+  launch_accept(s, N, B, vocab, prm->seed, prm->step, prm->step_dev, prm->gamma, prm->resample, inv_temperature(prm),
+                draft->span_start, draft->span_len, draft->logits, draft->logit_row_of, ver->logits_ver, ver->logit_row_of,
+                draft->xhat, draft->p, draft->lse, ver->q, ver->lse_ver, st->block_tokens, out->n_accept, out->n_commit,
+                out->resampled, out->u_used, prm->active, tiles, arrivals);
+  return check_launch("s2d2_accept_static");
 }
 
 int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, const s2d2_draft_out* draft,

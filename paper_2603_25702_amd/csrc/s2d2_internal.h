@@ -312,5 +312,9 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
                    int32_t* resampled, float* u_used, const int32_t* active, float* tile_scratch /* accept_tile_floats, may be NULL */,
                    int32_t* arrivals /* [max_batch], zero between launches, may be NULL */);
 size_t accept_tile_floats(int max_batch, int V);
+// Limits of the accept step that takes its scratch from a device array of the library, and the per-device address
+// of that array's two parts (looked up on the first call on a device; the device must be current).  0 on success.
+constexpr int ACCEPT_STATIC_MAX_BATCH = 128, ACCEPT_STATIC_MAX_VOCAB = 1 << 18;
+int accept_static_scratch(float** tiles, int32_t** arrivals);
 
 }  // namespace s2d2

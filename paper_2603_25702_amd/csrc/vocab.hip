@@ -8,6 +8,8 @@
 #include "s2d2_internal.h"
 #include "../../include/s2d2.h"
 
+#include <mutex>
+
 namespace s2d2 {
 
 static constexpr int VCHUNK = 4096;  // logits per workgroup: 256 lanes x 4 float4
@@ -517,5 +519,33 @@ void launch_accept(hipStream_t st, int N, int B, int V, uint64_t seed, uint32_t 
 }
 
 size_t accept_tile_floats(int max_batch, int V) { return (size_t)max_batch * ((V + RTILE - 1) / RTILE); }
+
+// ---------------------------------------------------------------------------------------------
+// Scratch of the accept step for callers that cannot allocate (s2d2_accept_static): the residual tile sums that
+// the workgroups of a sequence hand to each other, and their arrival counters, live in a file-scope device array
+// instead of the caller's workspace.  Every GPU holds its own copy of the array at its own address; the address
+// is looked up once per device and only that pointer is ever passed to a kernel.
+// ---------------------------------------------------------------------------------------------
+static constexpr size_t STATIC_TILE_FLOATS = (size_t)ACCEPT_STATIC_MAX_BATCH * (ACCEPT_STATIC_MAX_VOCAB / RTILE);
+static constexpr size_t STATIC_SCRATCH_BYTES = STATIC_TILE_FLOATS * sizeof(float) + ACCEPT_STATIC_MAX_BATCH * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];   // 512.5 KB per GPU, held until the process ends
+
+static constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[STATIC_MAX_DEVICES];   // device address of `scratch` on each GPU, once looked up
+
+int accept_static_scratch(float** tiles, int32_t** arrivals) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) { (void)hipGetLastError(); return -1; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return -1; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  if (tiles) *tiles = (float*)g_scratch_ptr[dev];
+  if (arrivals) *arrivals = (int32_t*)((unsigned char*)g_scratch_ptr[dev] + STATIC_TILE_FLOATS * sizeof(float));
+  return 0;
+}
 
 }  // namespace s2d2
