@@ -682,12 +682,16 @@ def step_routed(cfg, W, st: SeqState, cache_k, cache_v, tau: float, seed: int, s
 # --------------------------------------------------------------------------------------
 # Alg. 1, lines after SampleBlock: forward over the finished block, whole-block cache append.
 # --------------------------------------------------------------------------------------
-def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: List[np.ndarray]) -> int:
+def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: List[np.ndarray],
+                   forced_experts=None, causal: bool = False) -> int:
     """Once the block holds no [MASK]: one forward over its tokens that are not cached yet (and over
     carried tokens of earlier blocks, which stay causal), with the block's rows attending to the whole
     block (block-diffusion attention), and append of all their K/V.  Returns the rows appended (0 if the
     block is unfinished).  This is the cache update of the variant that does not cache causally inside a
-    block (Section 4.2 describes the causal alternative the incremental append relies on)."""
+    block (Section 4.2 describes the causal alternative the incremental append relies on).
+    causal=True is that alternative applied to a whole finished block: every row sees only the rows left of it, so
+    the appended K/V are those a causal prefill of the text would give (used by generate when a block was finished
+    without a verifier forward that could have cached it).  forced_experts (MoE): expert choices per layer."""
     if getattr(cfg, "right_shifted", False):
         raise ValueError("whole-block append is not defined here for right-shifted models (their cache lags one token)")
     block = np.asarray(st.block)
@@ -702,11 +706,12 @@ def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: Lis
     pos = st.seq_len + np.arange(n)
     vis = np.zeros((n, n), dtype=bool)
     for r in range(n):
-        if r < nc:
+        if r < nc or causal:
             vis[r, :r + 1] = True          # carried tokens: causal
         else:
             vis[r, :] = True               # block rows: everything in the window
-    fo = forward(cfg, W, toks, pos, vis, cache_k, cache_v, logit_rows=np.zeros(0, dtype=np.int64))
+    fo = forward(cfg, W, toks, pos, vis, cache_k, cache_v, logit_rows=np.zeros(0, dtype=np.int64),
+                 forced_experts=forced_experts)
     for l in range(cfg.n_layers):
         cache_k[l] = np.concatenate([f64(cache_k[l]), fo.k[l]], axis=0)
         cache_v[l] = np.concatenate([f64(cache_v[l]), fo.v[l]], axis=0)
@@ -717,13 +722,19 @@ def block_complete(cfg, W, st: SeqState, cache_k: List[np.ndarray], cache_v: Lis
 
 def generate(cfg, W, st: SeqState, cache_k, cache_v, n_blocks: int, tau: float, seed: int, rp: RouteParams,
              max_steps_per_block: int, caching: str = "causal", seq: int = 0, mode: int = GREEDY,
-             temperature: float = 1.0):
+             temperature: float = 1.0, carry_cap: Optional[int] = None):
     """Alg. 1's outer loop around the block sampler of Alg. 3, for n_blocks blocks, at most max_steps_per_block
     denoising steps per block (a block that runs out of steps commits the threshold set of a tau = 0 pass, i.e.
     every remaining proposal).  caching = "causal": the accepted prefix is appended after every verified step
     (Section 4.2); "block": nothing is appended inside a block (drafting then sees the block fully
-    bidirectionally) and the finished block is appended by block_complete.  Returns the committed tokens and
-    the per-step records."""
+    bidirectionally) and the finished block is appended by block_complete.  Under causal caching a block that
+    fallback steps finished has tokens no verifier forward cached; they are carried in front of the next block
+    and cached by its first verified step.  Alg. 1 appends every block's K/V before the next block is sampled; the
+    carry only defers that, and it is bounded: when the carried tokens plus the finished block's uncached ones
+    would exceed carry_cap (default B, the carry capacity of the C boundary), they are cached at once by one
+    causal forward (block_complete with causal=True), which is Alg. 1's per-block cache update under the causal
+    mask of Section 4.2.  The committed tokens do not depend on carry_cap (causal K/V are the same whenever they
+    are computed); only seq_len bookkeeping does.  Returns the committed tokens and the per-step records."""
     assert caching in ("causal", "block")
     out, log, h, step_idx = [], [], H_ON, 0
     B = len(st.block)
@@ -752,6 +763,8 @@ def generate(cfg, W, st: SeqState, cache_k, cache_v, n_blocks: int, tau: float, 
         out.extend(int(x) for x in st.block)
         if caching == "block":
             block_complete(cfg, W, st, cache_k, cache_v)
+        elif len(st.carry) + (B - st.n_cached_in_block()) > (B if carry_cap is None else carry_cap):
+            block_complete(cfg, W, st, cache_k, cache_v, causal=True)
         block_advance(st, cfg.mask_id)
     return out, log
 

@@ -254,3 +254,50 @@ def test_generate_step_cap_forces_completion(model):
     toks, log = O.generate(CFG, W, st, list(ck), list(cv), 1, 2.0, seed=1, rp=rp, max_steps_per_block=1, caching="block")
     # tau above 1: a threshold step commits only the arg-max position; the cap then commits the rest at once
     assert [c for _, _, c in log] == [1, 3] and len(toks) == 4
+
+
+def test_causal_block_completion_appends_what_a_causal_prefill_of_the_text_gives(model):
+    # Section 4.2: K/V cached under the causal mask depend only on the tokens to their left, so caching a finished
+    # block (and tokens carried in front of it) in one causal forward = a plain causal prefill of prefix + text.
+    W, prefix, ck, cv = model
+    B = 4
+    st = fresh(len(prefix), B)
+    st.carry = np.array([11, 42], dtype=np.int64)                     # two uncached tokens of the block before
+    st.pos0 = len(prefix) + 2
+    st.block = np.array([3, 17, 29, 5], dtype=np.int64)
+    k, v = list(ck), list(cv)
+    assert O.block_complete(CFG, W, st, k, v, causal=True) == 6 and st.seq_len == st.pos0 + B and len(st.carry) == 0
+    ref_k, ref_v = O.prefill(CFG, W, np.concatenate([prefix, [11, 42, 3, 17, 29, 5]]))
+    for l in range(CFG.n_layers):
+        np.testing.assert_allclose(k[l], ref_k[l], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(v[l], ref_v[l], rtol=0, atol=1e-12)
+    # and it differs from the block-diffusion completion in the deeper layer (the mask matters there)
+    st2 = fresh(len(prefix), B)
+    st2.block = np.array([3, 17, 29, 5], dtype=np.int64)
+    k2, k3 = list(ck), list(ck)
+    O.block_complete(CFG, W, st2, k2, list(cv))
+    st3 = fresh(len(prefix), B)
+    st3.block = st2.block.copy()
+    O.block_complete(CFG, W, st3, k3, list(cv), causal=True)
+    assert np.abs(k2[1][-B:-1] - k3[1][-B:-1]).max() > 1e-6
+
+
+def test_generate_without_any_verified_step_keeps_the_carry_bounded_and_the_tokens_unchanged(model):
+    # A policy that never verifies: no verifier forward ever caches anything.  The carry may defer Alg. 1's per-block
+    # cache update but not beyond its capacity; the committed tokens do not depend on the capacity (causal K/V are
+    # the same whenever they are computed), and whatever is cached equals a causal prefill of the text.
+    W, prefix, ck, cv = model
+    B, nb = 4, 4
+    rp = O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=99)
+    runs = {}
+    for cap in (None, 0, 10 ** 6):
+        st = fresh(len(prefix), B)
+        k, v = list(ck), list(cv)
+        toks, log = O.generate(CFG, W, st, k, v, nb, 0.5, seed=3, rp=rp, max_steps_per_block=3, caching="causal", carry_cap=cap)
+        assert all(kind == "threshold" for kind, _, _ in log) and len(toks) == nb * B
+        assert st.seq_len + len(st.carry) == st.pos0 == len(prefix) + nb * B
+        ref_k, _ = O.prefill(CFG, W, np.concatenate([prefix, toks])[:st.seq_len])
+        np.testing.assert_allclose(k[1], ref_k[1], rtol=0, atol=1e-10)
+        runs[cap] = (toks, len(st.carry))
+    assert runs[None][0] == runs[0][0] == runs[10 ** 6][0]
+    assert runs[None][1] <= B and runs[0][1] == 0 and runs[10 ** 6][1] == nb * B   # default capacity B; none; unbounded
