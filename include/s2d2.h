@@ -276,18 +276,26 @@ int32_t s2d2_kv_append(s2d2_ctx* ctx, const s2d2_kv_view* kv, int32_t N, int32_t
                        const int32_t* n_accept /* device [N] */);
 
 /* Alg. 1: a block without [MASK] is replaced by a fresh [MASK]^B block at block_pos0 + B; its
- * uncached committed tokens move to carry_tokens.  Increments *step_dev if given. */
+ * uncached committed tokens move to carry_tokens (capacity B).  A finished block whose uncached tokens, together
+ * with the tokens already carried, exceed that capacity is left as it is and kv->status[n] is set to S2D2_ENOSPC:
+ * cache them first with s2d2_block_complete(..., causal = 1).  Increments *step_dev if given. */
 int32_t s2d2_block_advance(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_block_state* st,
                            int32_t N, int32_t B, uint32_t* step_dev /* device or NULL */);
 
-/* Alg. 1 after the block sampler, for decoding that does not append to the cache inside a block: for every sequence
- * whose block holds no [MASK], one forward over its tokens that are not cached yet (carried tokens of earlier blocks
- * stay causal, the block's rows attend to the whole block: block-diffusion attention) and append of their K/V;
- * seq_len advances by the rows appended, kv->status reports S2D2_ENOSPC as in s2d2_kv_append.  Sequences whose
- * block still holds a [MASK] are left alone.  `scratch` supplies the staging buffers (a verify output of the same
- * limits; its contents are overwritten).  Call s2d2_block_advance afterwards. */
+/* Alg. 1 after the block sampler: the cache update of a finished block, one forward over its tokens that are not
+ * cached yet (and over the carried tokens of earlier blocks, which stay causal) and append of their K/V; seq_len
+ * advances by the rows appended, kv->status reports S2D2_ENOSPC as in s2d2_kv_append.  Sequences whose block still
+ * holds a [MASK] are left alone.
+ *   causal = 0  for decoding that does not append inside a block: every finished block; the block's rows attend to
+ *               the whole block (block-diffusion attention).
+ *   causal = 1  for decoding that appends causally (Section 4.2): every row sees only the rows left of it, so the
+ *               appended K/V are those of a causal prefill; applied only to the sequences whose finished block the
+ *               carry list cannot take (carried + uncached tokens > B), i.e. blocks that were finished without a
+ *               verifier forward caching them.  The others keep riding in carry_tokens.
+ * `scratch` supplies the staging buffers (a verify output of the same limits; its contents are overwritten).  Call
+ * s2d2_block_advance afterwards. */
 int32_t s2d2_block_complete(s2d2_ctx* ctx, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
-                            const s2d2_verify_out* scratch);
+                            const s2d2_verify_out* scratch, int32_t causal);
 
 /* Alg. 2 commit: x^b_i <- x_hat_i for every i in the draft's threshold set. */
 int32_t s2d2_commit_threshold(s2d2_ctx* ctx, const s2d2_block_state* st, int32_t N, int32_t B,

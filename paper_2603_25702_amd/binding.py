@@ -135,7 +135,7 @@ def load_library():
                                        C.c_void_p]
     lib.s2d2_commit_threshold.argtypes = [C.c_void_p, C.POINTER(BlockStateC), C.c_int32, C.c_int32, C.POINTER(DraftOutC)]
     lib.s2d2_block_complete.argtypes = [C.c_void_p, C.POINTER(KvView), C.POINTER(BlockStateC), C.c_int32, C.c_int32,
-                                        C.POINTER(VerifyOutC)]
+                                        C.POINTER(VerifyOutC), C.c_int32]
     lib.s2d2_route.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(RouteParamsC), C.POINTER(DraftOutC), C.c_void_p,
                                C.POINTER(RouteOutC)]
     lib.s2d2_status.argtypes = [C.c_void_p]
@@ -415,8 +415,9 @@ class Engine:
     def s2d2_commit_threshold(self, st: BlockState, N, B, draft: DraftOut):
         _check(self.lib, self.lib.s2d2_commit_threshold(self.ctx, C.byref(st.c()), N, B, C.byref(draft.c())))
 
-    def s2d2_block_complete(self, kv: KvCache, st: BlockState, N, B, scratch: VerifyOut):
-        _check(self.lib, self.lib.s2d2_block_complete(self.ctx, C.byref(kv.c()), C.byref(st.c()), N, B, C.byref(scratch.c())))
+    def s2d2_block_complete(self, kv: KvCache, st: BlockState, N, B, scratch: VerifyOut, causal: int = 0):
+        _check(self.lib, self.lib.s2d2_block_complete(self.ctx, C.byref(kv.c()), C.byref(st.c()), N, B, C.byref(scratch.c()),
+                                                      int(causal)))
 
     def s2d2_route(self, N, B, rp: RouteParams, draft: DraftOut, hysteresis: Optional[torch.Tensor], out: RouteOut):
         _check(self.lib, self.lib.s2d2_route(self.ctx, N, B, C.byref(rp.c_struct()), C.byref(draft.c()), _ptr(hysteresis),

@@ -777,12 +777,13 @@ int32_t s2d2_kv_append(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B
 }
 
 int32_t s2d2_block_complete(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block_state* st, int32_t N, int32_t B,
-                            const s2d2_verify_out* scratch) {
+                            const s2d2_verify_out* scratch, int32_t causal) {
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv)) || (rc = check_verify_out(scratch))) return rc;
   const s2d2_model_desc& d = c->desc;
   if (d.right_shifted) return fail(S2D2_EINVAL, "s2d2_block_complete is not defined for right-shifted models (their cache lags one token)");
-  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, 2, 0, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
+  if (causal != 0 && causal != 1) return fail(S2D2_EINVAL, "causal must be 0 or 1");
+  { ProfScope ps(c, 3, 0.0); launch_plan(c->stream, causal ? 3 : 2, 0, N, B, d.mask_id, 1, kv->seq_len, st->block_pos0, st->block_tokens, st->carry_tokens,
               nullptr, c->plan, scratch->logit_row_of, nullptr, nullptr, scratch->stage_row0, scratch->stage_lead, nullptr, nullptr); }
   if ((rc = forward(c, kv, N, B, scratch->k_stage, scratch->v_stage, scratch->logits_ver))) return rc;
   const KvGeom g = geom(c, kv);
@@ -798,7 +799,7 @@ int32_t s2d2_block_advance(s2d2_ctx* c, const s2d2_kv_view* kv, const s2d2_block
   int32_t rc;
   if ((rc = check_state(c, st, N, B)) || (rc = check_kv(c, kv))) return rc;
   launch_block_advance(c->stream, N, B, c->desc.mask_id, kv->seq_len, st->block_pos0, st->block_tokens,
-                       st->carry_tokens, step_dev);
+                       st->carry_tokens, step_dev, kv->status);
   return check_launch("s2d2_block_advance");
 }
 

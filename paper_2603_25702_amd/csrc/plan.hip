@@ -38,13 +38,14 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     lead = nc + (j - c);
     if (verify == 1 && active && active[n] == 0) { L = 0; lead = 0; }   // routed to the fallback: no verifier window
     // right-shifted model: the row in front of the first [MASK] scores it and has to be a window row
-    if (shifted && verify != 2 && L > 0 && lead == 0) {
+    if (shifted && verify < 2 && L > 0 && lead == 0) {
       if (status) status[n] = S2D2_EINVAL;
       if (verify) L = 0;
       bad = 1;
     }
-    if (verify == 2) {            // block completion: all uncached tokens of a finished block, no logits
+    if (verify >= 2) {            // block completion: all uncached tokens of a finished block, no logits
       rows = n_masked == 0 ? nc + (B - c) : 0;
+      if (verify == 3 && rows <= B) rows = 0;   // causal variant: only what the carry list (capacity B) cannot take
       lead = rows;
       lrows = 0;
     } else if (verify) { rows = shifted ? lead + max(L - 1, 0) : lead + 2 * L; lrows = L; }
@@ -101,9 +102,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(
       p.row_lo[r] = row0;
       p.row_hi[r] = hi;
     }
-  } else if (verify == 2) {
+  } else if (verify >= 2) {
     // Alg. 1 after the block sampler: carried tokens stay causal, the block's rows attend to the whole window
-    // (block-diffusion attention); every row is staged for the cache
+    // (block-diffusion attention; verify == 3: every row causal, Section 4.2); every row is staged for the cache
     stage_row0[n] = row0;
     stage_lead[n] = rows;
     for (int t = 0; t < rows; ++t) {
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
       p.row_pos[r] = S + t;
       p.row_seq[r] = n;
       p.row_lo[r] = row0;
-      p.row_hi[r] = t < nc ? r + 1 : row0 + rows;
+      p.row_hi[r] = (t < nc || verify == 3) ? r + 1 : row0 + rows;
     }
   } else {
     stage_row0[n] = row0;
@@ -239,11 +240,12 @@ void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_c
 // ---------------------------------------------------------------------------------------------
 // Alg. 1: replace a block that holds no [MASK] by a fresh [MASK]^B block right after it.
 // Uncached committed tokens of the finished block move to the carry list (capacity B); if they
-// would not fit, the block is left as it is.
+// would not fit, the block is left as it is and the sequence's status word says so (the caller
+// caches them first: s2d2_block_complete).
 // ---------------------------------------------------------------------------------------------
 __global__ void block_advance_kernel(int N, int B, int mask_id, const int32_t* __restrict__ seq_len,
                                      int32_t* __restrict__ pos0, int32_t* __restrict__ block,
-                                     int32_t* __restrict__ carry, uint32_t* step_dev) {
+                                     int32_t* __restrict__ carry, uint32_t* step_dev, int32_t* __restrict__ status) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n == 0 && step_dev) *step_dev += 1u;
   if (n >= N) return;
@@ -253,16 +255,19 @@ __global__ void block_advance_kernel(int N, int B, int mask_id, const int32_t* _
     if (blk[i] == mask_id) return;
   const int S = seq_len[n], P0 = pos0[n];
   const int c = max(0, min(B, S - P0)), nc = max(0, min(B, P0 - S));
-  if (nc + (B - c) > B) return;
+  if (nc + (B - c) > B) {
+    if (status) status[n] = S2D2_ENOSPC;
+    return;
+  }
   for (int i = c; i < B; ++i) car[nc + (i - c)] = blk[i];
   for (int i = 0; i < B; ++i) blk[i] = mask_id;
   pos0[n] = P0 + B;
 }
 
 void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
-                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev) {
+                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev, int32_t* status) {
   S2D2_LAUNCH(block_advance_kernel, dim3((N + 255) / 256), dim3(256), 0, st, N, B, mask_id, seq_len,
-                     pos0, block, carry, step_dev);
+                     pos0, block, carry, step_dev, status);
 }
 
 __global__ void commit_threshold_kernel(int N, int B, int32_t* __restrict__ block,

@@ -108,7 +108,7 @@ enum GemmEpilogue {
 };
 
 // plan.hip
-void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block completion */, int shifted /* right-shifted model */,
+void launch_plan(hipStream_t st, int verify /* 0 draft, 1 verifier, 2 block completion, 3 causal block completion of blocks the carry cannot take */, int shifted /* right-shifted model */,
                  int N, int B, int mask_id, int ar_mask,
                  const int32_t* seq_len, const int32_t* pos0, const int32_t* block,
                  const int32_t* carry, const int32_t* xhat, const Plan& p, int32_t* logit_row_of,
@@ -121,7 +121,7 @@ void launch_kv_append(hipStream_t st, int dtype, int n_layers, int N, int rows_c
                       const int32_t* n_accept, int32_t* seq_len, int32_t* status, int B,
                       int hold_back /* 1: the last drafted token has no staged row */);
 void launch_block_advance(hipStream_t st, int N, int B, int mask_id, const int32_t* seq_len,
-                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev);
+                          int32_t* pos0, int32_t* block, int32_t* carry, uint32_t* step_dev, int32_t* status);
 void launch_commit_threshold(hipStream_t st, int N, int B, int32_t* block, const int32_t* xhat,
                              const uint64_t* unmask);
 

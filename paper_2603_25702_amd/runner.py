@@ -163,6 +163,13 @@ class Session:
             if caching == "block":
                 e.s2d2_block_complete(self.kv, self.st, N, B, self.v)
             after = self.st.block_tokens.cpu().numpy()
+            if caching == "causal":
+                # a block finished without a verifier forward is carried in front of the next one; what the carry
+                # list (capacity B) cannot take is cached now by one causal forward (Alg. 1's per-block cache update)
+                S, P0 = self.kv.seq_len.cpu().numpy(), self.st.block_pos0.cpu().numpy()
+                if any((after[n] != mask).all() and max(0, int(P0[n] - S[n])) + B - max(0, min(B, int(S[n] - P0[n]))) > B
+                       for n in range(N)):
+                    e.s2d2_block_complete(self.kv, self.st, N, B, self.v, causal=1)
             n_acc, n_com = self.a.n_accept.cpu().numpy(), self.a.n_commit.cpu().numpy()
             for n in range(N):
                 if blocks_done[n] >= n_blocks:
@@ -178,6 +185,8 @@ class Session:
                 else:
                     steps_in_block[n] += 1
             e.s2d2_block_advance(self.kv, self.st, N, B, None)
+            if int(self.kv.status.abs().sum()):   # a block that could not roll over, or a cache without room
+                raise RuntimeError(f"generate: device status {self.kv.status.cpu().tolist()} after step {step}")
             step += 1
         return out, log
 

@@ -157,7 +157,15 @@ class DeviceRun:
         self.st.block_pos0.copy_(torch.as_tensor([s.pos0 for s in c.states], dtype=torch.int32))
         self.kv.seq_len.copy_(torch.as_tensor([s.seq_len for s in c.states], dtype=torch.int32))
 
-    def step(self, prm: Params, advance: bool = True):
+    def step_fallback(self, prm: Params):
+        """The else-branch of Alg. 3 for every sequence: draft, then the threshold commit of Alg. 2."""
+        N, B, e = self.case.N, self.case.B, self.eng
+        e.s2d2_draft(self.kv, self.st, N, B, prm, self.d)
+        if self.case.cfg.is_moe:
+            self.choices_draft = e.s2d2_moe_choices(2 * N * B)
+        e.s2d2_commit_threshold(self.st, N, B, self.d)
+
+    def step(self, prm: Params, advance: bool = True, append: bool = True):
         N, B, e = self.case.N, self.case.B, self.eng
         moe = self.case.cfg.is_moe
         e.s2d2_draft(self.kv, self.st, N, B, prm, self.d)
@@ -167,7 +175,8 @@ class DeviceRun:
         if moe:
             self.choices_verify = e.s2d2_moe_choices(3 * N * B)
         e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
-        e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
+        if append:
+            e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
         if advance:
             e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
 
@@ -226,10 +235,12 @@ def verify_window_of(cfg):
 
 def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params, seqs=None,
                rep: Optional[Report] = None, check_logits: bool = True, check_kv_layers=None,
-               pre_seq_len: Optional[np.ndarray] = None, free_router: bool = False) -> Report:
+               pre_seq_len: Optional[np.ndarray] = None, free_router: bool = False, append: bool = True,
+               verified: bool = True) -> Report:
     """Compares one GPU step (outputs `g`, taken after the step with advance=False) with the oracle.
     case.states must still hold the state from BEFORE the step; on return they hold the oracle's
-    state after accept + append (not advanced)."""
+    state after accept + append (not advanced).  append=False: a step of decoding that appends nothing inside a
+    block (no s2d2_kv_append was called).  verified=False: a fallback step (draft, then s2d2_commit_threshold)."""
     cfg, B = case.cfg, case.B
     rep = rep or Report()
     seqs = range(case.N) if seqs is None else seqs
@@ -238,7 +249,8 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
     # MoE: window rows are packed sequence after sequence; the oracle is held to the GPU's expert choices
     moe = cfg.is_moe
     if moe:
-        ch_d, ch_v = run.choices_draft.cpu().numpy(), run.choices_verify.cpu().numpy()
+        ch_d = run.choices_draft.cpu().numpy()
+        ch_v = run.choices_verify.cpu().numpy() if verified else None
         row0_d, row0_v, rd, rv = [], [], 0, 0
         for n in range(case.N):
             wd = draft_window_of(cfg)(case.states[n], cfg.mask_id, bool(prm.ar_mask))
@@ -300,6 +312,15 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
         if not (S_gpu == S_or).all() or g["n_hi"][n] != n_hi:
             assert (np.abs(gp[~committed] - tau) < TIE).any(), f"seq {n}: threshold set differs"
             rep.exempt_tau += 1
+        if not verified:   # Alg. 2 commit of the (GPU's) threshold set; nothing is appended
+            want = np.array(st.block, copy=True)
+            want[S_gpu] = xhat[S_gpu]
+            np.testing.assert_array_equal(g["block_tokens"][n], want)
+            assert int(g["seq_len"][n]) == st.seq_len
+            st.block = want
+            rep.n_commit.append(int(S_gpu.sum()))
+            rep.rows_checked += len(win.logit_index)
+            continue
         # ---- stage 3: verifier logits with the GPU's proposals ----------------------------------
         vwin = verify_window_of(cfg)(st, xhat, cfg.mask_id)
         rows_v = g["logit_row_of_ver"][n]
@@ -347,6 +368,11 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
         np.testing.assert_array_equal(g["block_tokens"][n], a.block)
         rep.n_commit.append(a.n_commit)
         rep.n_accept.append(a.n_accept)
+        if not append:
+            assert int(g["seq_len"][n]) == st.seq_len
+            st.block = a.block
+            rep.rows_checked += len(win.logit_index) + L
+            continue
         # ---- stage 5: cache append -----------------------------------------------------------------
         n_lead = vwin.n_lead
         rows = n_lead + min(a.n_accept, vwin.n_causal - n_lead)   # (a right-shifted window has no row for the last draft)
@@ -364,6 +390,45 @@ def check_step(case: Case, run: DeviceRun, g: Dict[str, np.ndarray], prm: Params
         st.seq_len = S0 + rows
         st.carry = np.zeros(0, dtype=np.int64)
         rep.rows_checked += len(win.logit_index) + L
+    return rep
+
+
+def check_block_complete(case: Case, run: DeviceRun, causal: bool, rep: Optional[Report] = None) -> Report:
+    """s2d2_block_complete on the device against the oracle's block_complete, sequence by sequence, on the state
+    and cache held in `case` (synchronised with the device before the call).  Compares seq_len and the appended
+    K/V rows of every layer; MoE: the oracle is held to the device's expert choices.  On return case.states hold
+    the state after the append (not advanced)."""
+    cfg, N, B = case.cfg, case.N, case.B
+    rep = rep or Report()
+    S0 = [s.seq_len for s in case.states]
+    run.eng.s2d2_block_complete(run.kv, run.st, N, B, run.v, int(causal))
+    choices = run.eng.s2d2_moe_choices(3 * N * B).cpu().numpy() if cfg.is_moe else None
+    torch.cuda.synchronize(run.dev)
+    run.eng.s2d2_status()
+    sl = run.kv.seq_len.cpu().numpy()
+    assert int(run.kv.status.abs().sum()) == 0
+    row0 = 0
+    for n, st in enumerate(case.states):
+        finished = not (np.asarray(st.block) == cfg.mask_id).any()
+        rows = len(st.carry) + (B - st.n_cached_in_block()) if finished else 0
+        if causal and rows <= B:
+            rows = 0
+        if rows == 0:
+            assert int(sl[n]) == S0[n]
+            continue
+        ck, cv = case.oracle_cache(n)
+        forced = [choices[l, row0:row0 + rows] for l in range(cfg.n_layers)] if choices is not None else None
+        k, v = [O.f64(x) for x in ck], [O.f64(x) for x in cv]
+        assert O.block_complete(cfg, case.W, st, k, v, forced_experts=forced, causal=causal) == rows
+        assert int(sl[n]) == S0[n] + rows == st.seq_len
+        for l in range(cfg.n_layers):
+            gk, gvv = run.cache_rows(n, S0[n], S0[n] + rows, l)
+            for got, want in ((gk, k[l][S0[n]:]), (gvv, v[l][S0[n]:])):
+                err = np.abs(got - want).max() / max(np.abs(want).max(), 1e-30)
+                rep.max_kv_err = max(rep.max_kv_err, err)
+                assert err <= LOGIT_RTOL, f"seq {n} layer {l}: completed-block K/V off by {err:.3e}"
+        rep.rows_checked += rows
+        row0 += rows
     return rep
 
 

@@ -544,29 +544,35 @@ def test_sampling_mode_drafting_at_temperature_half():
     assert (sampled["p"] > 0).all() and (sampled["p"] <= 1).all()
 
 
-def test_generate_loop_routed_with_step_cap_under_both_cachings():
+@pytest.mark.parametrize("tau_span", [2, 99])
+def test_generate_loop_routed_with_step_cap_under_both_cachings(tau_span):
     """Alg. 1's outer loop on the device (draft, DoVerify, verify+accept or threshold commit, cache append per step or
-    per finished block, block roll-over) against the oracle's generate, free-running on the tiny fp32 model."""
+    per finished block, block roll-over) against the oracle's generate, free-running on the tiny fp32 model; with a
+    minimum-span policy that verifies most fresh blocks, and with one that never verifies (four blocks finished by
+    fallback steps only: the carry fills up and is cached by the causal block completion)."""
     from oracle import s2d2_oracle as O
     from paper_2603_25702_amd.binding import RouteParams
     from paper_2603_25702_amd.runner import Session
-    cfg, N, B, nb, cap = TINY, 2, 3, 3, 4
+    cfg, N, B, nb, cap = TINY, 2, 3, 4, 4
     for caching in ("causal", "block"):
         W = I.gen_weights(cfg, 15, norm_jitter=0.1)
         prefixes = [I.gen_prefix_ids(cfg, L, 15, n) for n, L in enumerate([21, 34])]
         sess = Session(cfg, W, N, B, max_seq=34 + nb * B + 16, page_size=8)
         sess.prefill(prefixes)
-        rp = RouteParams(policy=0, tau_span=2)
+        rp = RouteParams(policy=0, tau_span=tau_span)
         toks, log = sess.generate(Params(seed=77), rp, nb, cap, caching)
+        sl, p0 = sess.kv.seq_len.cpu().numpy(), sess.st.block_pos0.cpu().numpy()
         for n in range(N):
             ck, cv = O.prefill(cfg, W, np.asarray(prefixes[n]))
             st = O.SeqState(seq_len=len(prefixes[n]), pos0=len(prefixes[n]), block=np.full(B, cfg.mask_id, dtype=np.int64))
             ot, ol = O.generate(cfg, W, st, ck, cv, nb, float(np.float32(0.9)), seed=77,
-                                rp=O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=2), max_steps_per_block=cap,
+                                rp=O.RouteParams(policy=O.ROUTE_MIN_SPAN, tau_span=tau_span), max_steps_per_block=cap,
                                 caching=caching, seq=n)
             assert toks[n] == ot, (caching, n, toks[n], ot)
             assert log[n] == ol, (caching, n, log[n], ol)
-        sl = sess.kv.seq_len.cpu().numpy()
+            assert len(ot) == nb * B and (int(sl[n]), int(p0[n])) == (st.seq_len, st.pos0), (caching, n, sl[n], p0[n], st.seq_len, st.pos0)
+            if tau_span == 99:
+                assert all(kind == "threshold" for kind, _, _ in ol)
         if caching == "block":
             assert [int(x) for x in sl] == [len(p) + nb * B for p in prefixes]
-        print("generate", caching, "tokens", toks, "steps", [len(l) for l in log])
+        print("generate", caching, "tau_span", tau_span, "tokens", toks, "steps", [len(l) for l in log])
