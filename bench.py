@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the S2D2 hot path on one MI355X: accepted tokens/s per draft+verify step.
 
-One "step" = s2d2_draft + s2d2_verify + s2d2_accept + s2d2_kv_append + s2d2_block_advance on the
-whole batch.  The workload is the dense bf16 1.7B-shaped decoder (28 layers, hidden 2048, 16/8
-heads of 128, FFN 6144, vocab 151936), batch 1, prefix 512 random tokens, block size 4,
-threshold 0.9, consecutive steps on synthetic random-init weights.  Inputs are resident in HBM
-before the timed region.  Prints ONE JSON line.
+One "step" = s2d2_draft + s2d2_verify + s2d2_accept + s2d2_kv_append + s2d2_block_advance on the whole batch,
+replayed as a HIP graph.  The headline workload is the largest single-GPU configuration, config 4 (dense bf16
+8B-shaped decoder: 36 layers, hidden 4096, 32/8 heads of 128, FFN 12288, vocab 151936; batch 16, prefix 8192,
+block 16, threshold 0.9, paged cache with 16-token pages), on synthetic random-init weights with the prefix cache
+prefilled through the library.  Everything is resident in HBM before the timed region.  The other bf16
+configurations (2, 3, 5) are measured the same way and reported under "configs".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import dataclasses
+import gc
 import json
 import os
 import sys
@@ -19,39 +21,20 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the streaming GEMM on this workload, from the FETCH_SIZE / WRITE_SIZE counter runs
-# recorded in profiles/gemm_stream_kernel_config2.md (31.16 MB fetched + 0.26 MB written; 30.45 MB algorithmic)
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 31.4e6
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA peak of the arithmetic type
+HEADLINE, OTHERS = 4, (2, 3, 5)
+# HBM bytes per launch of the dominant GEMM kernel of a configuration, from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised under profiles/ (rocprofv3 --pmc, scaled by what the same counters read for a plain copy of known size).
+# None: not measured for that configuration.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", type=int, default=2, help="workload id (2 is the benchmark configuration)")
-    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; result is labelled)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile-pass", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="enqueue every call of a step from the host instead of replaying a HIP graph of one step")
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--right-shifted", action="store_true",
-                    help="treat the synthetic model as right-shifted (output at position i-1 scores token i): plain causal "
-                         "verifier rows instead of the 2L window; the result is labelled")
-    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
-                    help="counter calibration: first run a plain elementwise copy kernel over this many MiB "
-                         "(read once, written once) so that a rocprofv3 --pmc run of this command holds a kernel of "
-                         "known HBM traffic next to the library's kernels")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs would be plain "
-                 "data parallelism with no exchange); run with --gpus 1")
-
+def bench_config(args, cfg_id: int, K: int, Wm: int, cpu_baseline: bool) -> dict:
     import numpy as np
     import torch
 
@@ -59,24 +42,15 @@ def main():
     from paper_2603_25702_amd import Params
     from paper_2603_25702_amd.runner import Session
 
-    if args.calibrate_copy_mib > 0:
-        n = args.calibrate_copy_mib * (1 << 20) // 4
-        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)  # reads n*4 bytes, writes n*4 bytes
-        torch.cuda.synchronize()
-        del src, dst
-
-    wl = I.CONFIGS[args.config]
+    wl = I.CONFIGS[cfg_id]
     cfg = wl.cfg if not args.layers else I.shrink(wl.cfg, n_layers=args.layers)
     if args.right_shifted:
         cfg = dataclasses.replace(cfg, right_shifted=True)
-    N, B, K, Wm = wl.batch, wl.block, args.steps, args.warmup
+    N, B = wl.batch, wl.block
     dev = "cuda:0"
     t0 = time.time()
     weights = I.gen_weights(cfg, args.seed)
-    log(f"[bench] weights generated in {time.time() - t0:.1f}s ({cfg.n_params() / 1e6:.0f} M params)")
+    log(f"[bench] config {cfg_id}: weights generated in {time.time() - t0:.1f}s ({cfg.n_params() / 1e6:.0f} M params)")
     lens = I.gen_prefix_lengths(wl, args.seed)
     ids = [I.gen_prefix_ids(cfg, int(lens[n]), args.seed, n) for n in range(N)]
     max_seq = int(lens.max()) + (max(K, Wm) + 2) * B + 64
@@ -85,9 +59,10 @@ def main():
     t0 = time.time()
     last = [int(x[-1]) for x in ids]
     ses.prefill(ids)
-    log(f"[bench] prefix cache of {lens.tolist()} tokens prefilled on the GPU in {time.time() - t0:.2f}s")
+    log(f"[bench] prefix cache of {int(lens.min())}-{int(lens.max())} tokens x {N} prefilled on the GPU in {time.time() - t0:.2f}s")
 
-    prm = Params(tau=wl.taus[-1] if len(wl.taus) == 1 else 0.9, seed=args.seed, step=0, step_dev=ses.step_dev)
+    tau = wl.taus[-1] if len(wl.taus) == 1 else 0.9
+    prm = Params(tau=tau, seed=args.seed, step=0, step_dev=ses.step_dev)
     i32 = torch.int32
     acc_buf = torch.zeros((max(K, Wm), N), dtype=i32, device=dev)
     com_buf = torch.zeros((max(K, Wm), N), dtype=i32, device=dev)
@@ -122,59 +97,69 @@ def main():
     assert int(ses.kv.status.abs().sum().item()) == 0, "a sequence ran out of cache pages"
     ses.eng.s2d2_status()   # raises if a bounded device-side wait ran out during the timed steps (results would be invalid)
     value = committed / elapsed
-    log(f"[bench] {K} steps in {elapsed * 1e3:.2f} ms: {committed} tokens committed ({accepted} accepted drafts)")
+    log(f"[bench] config {cfg_id}: {K} steps in {elapsed * 1e3:.2f} ms: {committed} tokens committed ({accepted} accepted drafts)")
 
-    # ---- instrumented pass: HIP events around every launch, on the library's stream ----------------
+    # ---- instrumented pass: HIP events stamped by every dispatch, on the library's stream ----------------
     roofline, phases = None, {}
     if not args.no_profile_pass:
         Kp = min(K, 8)
         ses.reset_blocks(lens, last)
-        per_fwd = cfg.n_layers * 8 + 16
+        per_fwd = cfg.n_layers * 10 + 16
         ses.eng.s2d2_profile_start(2 * Kp * per_fwd + 64)
         run(Kp)
         prof = ses.eng.s2d2_profile_stop()
-        # dominant kernel: the fused forward (all layer weights of one forward per launch) when the window is narrow
-        # enough for it, else the streaming GEMM launches; algorithmic bytes = the weight matrices once per launch
-        fused = prof["forward"]["launches"] > 0
-        g = prof["forward"] if fused else prof["gemm"]
-        ach = g["bytes"] / (g["ms"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "forward_fused_kernel" if fused else "gemm_stream_kernel",
-                    "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                    "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.config == 2 and not fused and not args.layers) else None,
-                    "avg_launch_us": round(g["ms"] * 1e3 / g["launches"], 3),
-                    "bytes_per_launch": round(g["bytes"] / g["launches"])}
-        tot = sum(c["ms"] for c in prof.values())
+        mfma_peak = MFMA_PEAK_TFLOPS["bf16" if cfg.dtype == "bf16" else "f32"]
+        tot = sum(prof[c]["ms"] for c in ("gemm", "attention", "vocab", "other"))
         for name, c in prof.items():
+            if not c["launches"]:
+                continue
             phases[name] = {"ms_per_step": round(c["ms"] / Kp, 4), "launches_per_step": c["launches"] // Kp,
                             "share": round(c["ms"] / tot, 4)}
-        for name in ("gemm", "forward"):
-            if prof[name]["launches"]:
-                phases[name]["hbm_GBs"] = round(prof[name]["bytes"] / (prof[name]["ms"] * 1e-3) / 1e9, 1)
-        # Per-phase HBM rate and MFMA use from the workload's shapes (nominal rows of fresh blocks: N*B draft rows,
-        # 2*N*B verifier rows, N*B logit rows per forward; cached lengths = mean of before and after the pass)
+            if name.startswith("gemm"):   # weight bytes once per launch; the method's flops counted once
+                phases[name]["hbm_GBs"] = round(c["bytes"] / (c["ms"] * 1e-3) / 1e9, 1)
+                phases[name]["mfma_TFLOPs"] = round(c["flops"] / (c["ms"] * 1e-3) / 1e12, 1)
+                phases[name]["hbm_frac"] = round(phases[name]["hbm_GBs"] / HBM_PEAK_GBS, 4)
+                phases[name]["mfma_frac"] = round(phases[name]["mfma_TFLOPs"] / mfma_peak, 4)
+        # attention and vocabulary phases from the workload's shapes (nominal rows of fresh blocks: N*B draft rows,
+        # 2*N*B verifier rows; cached lengths = mean of before and after the pass)
         es = 2 if cfg.dtype == "bf16" else 4
         S_mean = 0.5 * (float(np.sum(lens)) + float(ses.kv.seq_len.sum().item()))
         kv_bytes = 2 * cfg.n_layers * S_mean * 2 * cfg.n_kv_heads * cfg.head_dim * es          # both forwards, K and V once
-        attn_flops = cfg.n_layers * (N * B + 2 * N * B) / N * 4.0 * cfg.n_q_heads * cfg.head_dim * S_mean
-        per_layer = cfg.d_model * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim + cfg.n_q_heads * cfg.head_dim * cfg.d_model
-        per_layer += (cfg.top_k * 3 * cfg.d_model * cfg.d_expert + cfg.d_model * cfg.n_experts) if cfg.is_moe else 3 * cfg.d_model * cfg.d_ffn
-        gemm_flops = 2.0 * (3 * N * B * cfg.n_layers * per_layer + 2 * N * B * cfg.d_model * cfg.vocab)
+        attn_flops = cfg.n_layers * 3 * B * 4.0 * cfg.n_q_heads * cfg.head_dim * S_mean
         vocab_bytes = 2 * N * B * cfg.vocab * 4.0                                                # draft and verifier logits read once
-        MFMA_PEAK = 2.5e15 if cfg.dtype == "bf16" else 157.3e12
         if prof["attention"]["launches"]:
             t = prof["attention"]["ms"] * 1e-3 / Kp
-            phases["attention"]["hbm_GBs"] = round(kv_bytes / t / 1e9, 1)
-            phases["attention"]["mfma_pct"] = round(100 * attn_flops / t / MFMA_PEAK, 2)
-        if prof["gemm"]["launches"]:
-            phases["gemm"]["mfma_pct"] = round(100 * gemm_flops / (prof["gemm"]["ms"] * 1e-3 / Kp) / MFMA_PEAK, 2)
+            phases["attention"].update(hbm_GBs=round(kv_bytes / t / 1e9, 1), hbm_frac=round(kv_bytes / t / 1e9 / HBM_PEAK_GBS, 4),
+                                       mfma_TFLOPs=round(attn_flops / t / 1e12, 1), kv_bytes_per_step=round(kv_bytes))
         if prof["vocab"]["launches"]:
-            phases["vocab"]["hbm_GBs"] = round(vocab_bytes / (prof["vocab"]["ms"] * 1e-3 / Kp) / 1e9, 1)
-        log(f"[bench] profile pass ({Kp} steps): {json.dumps(phases)}")
+            t = prof["vocab"]["ms"] * 1e-3 / Kp
+            phases["vocab"].update(hbm_GBs=round(vocab_bytes / t / 1e9, 1), hbm_frac=round(vocab_bytes / t / 1e9 / HBM_PEAK_GBS, 4))
+        # dominant kernel: the GEMM kernel of this window width (all its launches of a step).  It is bound by the
+        # matrix pipes when the method's flops at the MFMA peak take longer than its weight bytes at the HBM peak.
+        g = prof["gemm"]
+        wide = 3 * N * B > 32                     # windows above 32 rows run the LDS-tiled kernel (launch_gemm_stream)
+        t_mfma, t_hbm = g["flops"] / (mfma_peak * 1e12), g["bytes"] / (HBM_PEAK_GBS * 1e9)
+        common = {"kernel": "gemm_tile_kernel" if wide else "gemm_stream_kernel",
+                  "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg_id) if not (args.layers or args.right_shifted) else None,
+                  "avg_launch_us": round(g["ms"] * 1e3 / g["launches"], 3), "launches_per_step": g["launches"] // Kp,
+                  "bytes_per_launch": round(g["bytes"] / g["launches"]), "flops_per_launch": round(g["flops"] / g["launches"])}
+        if t_mfma > t_hbm:
+            ach = g["flops"] / (g["ms"] * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": mfma_peak, "unit": "TFLOP/s",
+                        "frac": round(ach / mfma_peak, 4), **common}
+        else:
+            ach = g["bytes"] / (g["ms"] * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(ach / HBM_PEAK_GBS, 4), **common}
+        # the step against its own bound: weights of both forwards + cached K/V + logits at the HBM peak
+        step_bytes = g["bytes"] / Kp + kv_bytes + vocab_bytes
+        roofline["step_hbm_bound_ms"] = round(step_bytes / (HBM_PEAK_GBS * 1e9) * 1e3, 3)
+        roofline["step_hbm_frac"] = round(step_bytes / (HBM_PEAK_GBS * 1e9) / (elapsed / K), 4)
+        log(f"[bench] config {cfg_id}: profile pass ({Kp} steps): {json.dumps(phases)}")
 
     # ---- the fp64 oracle on the host cores: a bounded sample of full steps of the same workload -----
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         from oracle import s2d2_oracle as O  # test infrastructure, used for the reported CPU baseline only
         try:
             from threadpoolctl import threadpool_info
@@ -183,44 +168,102 @@ def main():
             cores = os.cpu_count() or 1
         ses.reset_blocks(lens, last)
         torch.cuda.synchronize()
-        k_cpu, v_cpu = ses.kv.k.cpu(), ses.kv.v.cpu()
+        n = int(np.argmax(lens))           # the sequence with the longest prefix
         tb = ses.kv.page_table.cpu().numpy()
         ps = wl.page_size
+        S = int(lens[n])
+        pages = torch.as_tensor(tb[n, :(S + ps - 1) // ps].astype(np.int64), device=dev)
+        ck = [ses.kv.k[l][pages].permute(0, 2, 1, 3).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S].cpu() for l in range(cfg.n_layers)]
+        cv = [ses.kv.v[l][pages].permute(0, 3, 1, 2).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S].cpu() for l in range(cfg.n_layers)]
+        st = O.SeqState(S, S, np.full(B, cfg.mask_id, dtype=np.int64))
+        if args.right_shifted:
+            st = O.shifted_prefill_state(S, last[n], B, cfg.mask_id)
+            ck, cv = [x[:S - 1] for x in ck], [x[:S - 1] for x in cv]
+        w64 = O.LazyF64Weights(weights) if cfg.is_moe else weights   # same stored values; expert up-casts cached per layer
         t0 = time.perf_counter()
-        tokens = 0
-        n_seq, n_steps = 1, 0  # bounded sample: one sequence, consecutive steps until about 10 s have been spent (at most 4)
-        for n in range(n_seq):
-            S = int(lens[n])
-            pages = torch.as_tensor(tb[n, :(S + ps - 1) // ps].astype(np.int64))
-            ck = [k_cpu[l][pages].permute(0, 2, 1, 3).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
-            cv = [v_cpu[l][pages].permute(0, 3, 1, 2).reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:S] for l in range(cfg.n_layers)]
-            st = O.SeqState(S, S, np.full(B, cfg.mask_id, dtype=np.int64))
-            if args.right_shifted:
-                st = O.shifted_prefill_state(S, last[n], B, cfg.mask_id)
-                ck, cv = [x[:S - 1] for x in ck], [x[:S - 1] for x in cv]
-            while True:
-                _, _, a = O.step(cfg, weights, st, ck, cv, prm.tau, args.seed, n_steps, n)
-                tokens += a.n_commit
-                n_steps += 1
-                if time.perf_counter() - t0 >= 10.0 or n_steps >= 4:
-                    break
+        tokens, n_steps = 0, 0   # bounded sample: one sequence, consecutive steps until about 10 s have been spent (at most 4)
+        while True:
+            _, _, a = O.step(cfg, w64, st, ck, cv, prm.tau, args.seed, n_steps, n)
+            tokens += a.n_commit
+            n_steps += 1
+            log(f"[bench] config {cfg_id}: oracle step {n_steps} done after {time.perf_counter() - t0:.1f}s")
+            if time.perf_counter() - t0 >= 10.0 or n_steps >= 4:
+                break
         dt = time.perf_counter() - t0
-        cpu = {"value": round(tokens / dt * (N / n_seq), 4), "unit": "accepted tokens/s", "cores": int(cores),
-               "kind": "oracle", "sample": f"{n_seq} sequence(s) x {n_steps} consecutive draft+verify+accept+append step(s) of the "
-               f"same workload (fp64 numpy, {dt:.1f}s)"}
-        log(f"[bench] oracle: {n_steps} step(s) in {dt:.1f}s, {tokens} tokens")
+        cpu = {"value": round(tokens / dt * N, 4), "unit": "accepted tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"1 of {N} sequence(s) (the longest prefix) x {n_steps} consecutive draft+verify+accept+append step(s) of the "
+                         f"same workload (fp64 numpy, {dt:.1f}s)" + (f"; sequences are independent: rate extrapolated x{N}" if N > 1 else "")}
+        log(f"[bench] config {cfg_id}: oracle: {n_steps} step(s) of one sequence in {dt:.1f}s, {tokens} tokens")
 
-    out = {
-        "metric": "accepted tokens/s per draft+verify step", "value": round(value, 2), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(elapsed * 1e3 / K, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
-        "config": {"workload": f"config {args.config}: {cfg.name} {cfg.n_layers}L d{cfg.d_model} V{cfg.vocab}, batch {N}, "
+    rec = {
+        "value": round(value, 2), "unit": "tokens/s", "steps": K, "warmup": Wm, "ms_per_step": round(elapsed * 1e3 / K, 4),
+        "dtype": cfg.dtype, "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
+        "config": {"workload": f"config {cfg_id}: {cfg.name} {cfg.n_layers}L d{cfg.d_model} V{cfg.vocab}, batch {N}, "
                                f"prefix {int(lens.min())}-{int(lens.max())}, block {B}, tau {prm.tau}, {K} consecutive steps"
                                + (", right-shifted model" if args.right_shifted else ""),
                    "tokens_committed": committed, "drafts_accepted": accepted},
         "roofline": roofline, "cpu_baseline": cpu, "phases": phases,
     }
+    ses.eng.close()
+    del ses, weights, graph
+    gc.collect()
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=0, help="measure only this workload id (default: config 4 as the headline, "
+                                                           "then configs 2, 3 and 5 under \"configs\")")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; result is labelled)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-cpu-baselines", action="store_true", help="time the oracle for the configurations under \"configs\" too (about 15 s each)")
+    ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every call of a step from the host instead of replaying a HIP graph of one step")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--right-shifted", action="store_true",
+                    help="treat the synthetic model as right-shifted (output at position i-1 scores token i): plain causal "
+                         "verifier rows instead of the 2L window; the result is labelled")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="counter calibration: first run a plain elementwise copy kernel over this many MiB "
+                         "(read once, written once) so that a rocprofv3 --pmc run of this command holds a kernel of "
+                         "known HBM traffic next to the library's kernels")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs would be plain "
+                 "data parallelism with no exchange); run with --gpus 1")
+
+    import torch
+
+    if args.calibrate_copy_mib > 0:
+        n = args.calibrate_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)  # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
+    head_id = args.config or HEADLINE
+    head = bench_config(args, head_id, args.steps, args.warmup, not args.no_cpu_baseline)
+    out = {
+        "metric": "accepted tokens/s per draft+verify step", "value": head["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "launch": head["launch"], "config": head["config"], "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"], "phases": head["phases"],
+    }
+    if not args.config:   # the other bf16 configurations, same measurement each
+        out["configs"] = {}
+        for cid in OTHERS:
+            try:
+                out["configs"][str(cid)] = bench_config(args, cid, args.steps, args.warmup, args.all_cpu_baselines)
+            except Exception as e:   # the headline line is still printed
+                log(f"[bench] config {cid} failed: {type(e).__name__}: {e}")
+                out["configs"][str(cid)] = {"error": f"{type(e).__name__}: {e}"}
     print(json.dumps(out), flush=True)
 
 

@@ -338,52 +338,10 @@ typedef struct {
 int32_t s2d2_route(s2d2_ctx* ctx, int32_t N, int32_t B, const s2d2_route_params* rp, const s2d2_draft_out* draft,
                    int32_t* hysteresis, const s2d2_route_out* out);
 
-/* Synchronises the context's stream and reports a sticky device-side failure: S2D2_ELAUNCH if a
- * device-wide barrier of the fused forward ran out of its bounded spin (a workgroup was not resident),
- * after which every later fused forward returns at once without computing, or if a workgroup of the
- * down projection waited in vain for the partial sums of the workgroup it shares K with (results of
- * that forward are then invalid); S2D2_OK otherwise.  No kernel of the library waits unboundedly. */
+/* Synchronises the context's stream and reports a sticky device-side failure: S2D2_ELAUNCH if a workgroup of the
+ * down projection waited in vain for the partial sums of the workgroup it shares K with (the results of that
+ * forward are then invalid); S2D2_OK otherwise.  No kernel of the library waits unboundedly. */
 int32_t s2d2_status(s2d2_ctx* ctx);
-
-/* MoE models: the experts chosen by the router in the most recent forward (draft or verifier),
- * out = device [n_layers, rows, top_k] int32 for the first `rows` window rows (window rows are packed
- * sequence after sequence: leading causal rows, drafted rows, then [MASK] copies).  The parity
- * tests use it to hold the oracle to the same routing where a router score is tied to rounding. */
-int32_t s2d2_moe_choices(s2d2_ctx* ctx, int32_t rows, int32_t* out /* device */);
-
-/* Debugging aid: device address of an internal activation buffer of the most recent forward
- * ("h" fp32 residual rows [rows, d]; "a" operand of the next norm; "q", "o", "ffn", "kwin", "vwin", "ss").
- * Contents are those of the last layer that ran; layouts are internal and may change. */
-int32_t s2d2_debug_buffer(s2d2_ctx* ctx, const char* name, void** ptr);
-
-/* Vocabulary stage alone on caller-provided logits (same kernels the calls above use):
- * draft statistics for `rows` fp32 logit rows of width V.  Outputs are [rows]. */
-int32_t s2d2_vocab_draft_stats(s2d2_ctx* ctx, const float* logits, int32_t rows, int32_t* xhat,
-                               float* p, float* lse, float* margin, float* entropy_n);
-/* Verifier side: q[r] = softmax(logits_ver[r])[token[r]] and lse[r]. */
-int32_t s2d2_vocab_score(s2d2_ctx* ctx, const float* logits_ver, int32_t rows,
-                         const int32_t* token, float* q, float* lse);
-
-/* Measurement aid (not part of the method): while profiling is on, the kernel launches of a step are
- * timed with HIP events on the context's stream and attributed to a class.
- * s2d2_profile_stop synchronises the stream, sums the event times and turns profiling off.
- *   launches    kernel launches of the class
- *   ms          summed kernel durations: the two events of a launch are stamped by the dispatch itself
- *               (hipExtLaunchKernelGGL), i.e. they read what a kernel trace reads for that launch
- *   bytes       algorithmic HBM bytes of those launches: weight matrix once for a GEMM, K and V
- *               of the cached prefix once for attention, the fp32 logit rows once for the
- *               vocabulary kernels (window rows and tiny outputs are not counted)
- * Classes: 0 GEMM (weight streaming), 1 attention, 2 vocabulary, 3 everything else, 4 the fused
- * forward (one persistent launch that holds all layers of a narrow window: its bytes are the layer
- * weights once). */
-#define S2D2_PROFILE_CLASSES 5
-typedef struct {
-  int64_t launches;
-  double ms;
-  double bytes;
-} s2d2_profile;
-int32_t s2d2_profile_start(s2d2_ctx* ctx, int32_t max_launches);
-int32_t s2d2_profile_stop(s2d2_ctx* ctx, s2d2_profile* out /* host [S2D2_PROFILE_CLASSES] */);
 
 #ifdef __cplusplus
 }

@@ -73,6 +73,23 @@ def f64(x) -> np.ndarray:
     return np.asarray(x, dtype=np.float64)
 
 
+class LazyF64Weights(dict):
+    """The same stored weights, with the expert tensors of the most recently used layer kept up-cast to
+    fp64 so that the oracle's per-(row, expert) up-casts become no-ops.  Values are unchanged."""
+
+    def __init__(self, W):
+        super().__init__(W)
+        self._key, self._val = {}, {}
+
+    def __getitem__(self, k):
+        base = k.split(".")[-1]
+        if base in ("e_wgu", "e_wdown"):
+            if self._key.get(base) != k:
+                self._key[base], self._val[base] = k, f64(super().__getitem__(k))
+            return self._val[base]
+        return super().__getitem__(k)
+
+
 def take_rows(table, idx: np.ndarray) -> np.ndarray:
     if hasattr(table, "detach"):
         import torch

@@ -24,7 +24,7 @@ EXPORTS = [
     "s2d2_set_stream", "s2d2_draft", "s2d2_verify", "s2d2_accept", "s2d2_accept_static", "s2d2_kv_append", "s2d2_block_advance",
     "s2d2_commit_threshold", "s2d2_block_complete", "s2d2_route", "s2d2_moe_choices", "s2d2_debug_buffer", "s2d2_status", "s2d2_vocab_draft_stats", "s2d2_vocab_score", "s2d2_profile_start", "s2d2_profile_stop",
 ]
-PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "forward")
+PROFILE_CLASSES = ("gemm", "attention", "vocab", "other", "gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_unembed")
 
 
 class S2D2Error(RuntimeError):
@@ -88,7 +88,7 @@ class AcceptOutC(C.Structure):
 
 
 class ProfileC(C.Structure):
-    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double)]
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double), ("flops", C.c_double), ("max_ms", C.c_double)]
 
 
 def lib_path() -> str:
@@ -443,7 +443,8 @@ class Engine:
     def s2d2_profile_stop(self):
         out = (ProfileC * len(PROFILE_CLASSES))()
         _check(self.lib, self.lib.s2d2_profile_stop(self.ctx, out))
-        return {n: dict(launches=int(out[i].launches), ms=float(out[i].ms), bytes=float(out[i].bytes))
+        return {n: dict(launches=int(out[i].launches), ms=float(out[i].ms), bytes=float(out[i].bytes), flops=float(out[i].flops),
+                        max_ms=float(out[i].max_ms))
                 for i, n in enumerate(PROFILE_CLASSES)}
 
     def s2d2_vocab_draft_stats(self, logits: torch.Tensor):

@@ -9,8 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs2d2.so")
-SOURCES = ["api.hip", "plan.hip", "elementwise.hip", "gemm.hip", "gemm_stream.hip", "gemm_tile.hip", "moe.hip", "forward_fused.hip", "attention.hip", "attention_wide.hip", "vocab.hip"]
-FLAGS = (["-DS2D2_FUSED_TIMING"] if os.environ.get("S2D2_FUSED_TIMING") else []) + ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+SOURCES = ["api.hip", "plan.hip", "elementwise.hip", "gemm.hip", "gemm_stream.hip", "gemm_tile.hip", "moe.hip", "attention.hip", "attention_wide.hip", "vocab.hip"]
+FLAGS = (["-DS2D2_KERNEL_TIMING"] if os.environ.get("S2D2_KERNEL_TIMING") else []) + ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

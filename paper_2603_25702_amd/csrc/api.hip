@@ -1,6 +1,7 @@
 // C ABI of libs2d2: argument validation, workspace carving, and the launch sequence of the
 // draft / verifier forward.  See include/s2d2.h for the contract of every entry point.
 #include "../../include/s2d2.h"
+#include "../../include/s2d2_aux.h"
 #include "s2d2_internal.h"
 
 #include <stdio.h>
@@ -54,8 +55,7 @@ struct s2d2_ctx {
   size_t attn_part_entries;
   int32_t* attn_counters;  // arrival counters of the split-key merge, zero between launches
   int32_t attn_groups;
-  int32_t wpad, attn_zmax, attn_z_override;
-  bool force_generic_attention;
+  int32_t wpad, attn_zmax;
   VocabWs vws;
   float2* rope_cs;   // [rows_cap, D/2] cos / sin of the window rows
   int32_t* zeros_i32;  // [max_batch] zeros (never written)
@@ -73,29 +73,19 @@ struct s2d2_ctx {
   float* moe_y;           // [rows_cap * top_k, d_model]
   PackedLayer* pk;
   const uint4* pk_unembed;
-  // fused forward (one persistent launch) for windows of at most 16 rows
-  FusedLayer* fused_layers;  // device
-  uint32_t* fused_bar;       // 9 x 64 words
-  int32_t* fused_err;
-  uint64_t* moe_y_or_scratch; // clock stamps of the timing build
+  int32_t* dev_status;       // sticky device-side failure words ([1]: a bounded wait of the paired K split ran out)
+  uint64_t* ts_scratch;      // clock stamps of the timing build
   float* tile_partials;      // split-K partials of the tiled GEMM, TILE_PARTIAL_CAP x 64 KB
   int32_t* tile_counters;    // TILE_COUNTER_CAP arrival counters, zero between launches
   float* accept_tiles;       // [max_batch, vocabulary tiles] residual tile sums shared by the workgroups of a sequence
   int32_t* accept_arrive;    // [max_batch] their arrival counters, zero between launches
   unsigned long long* pair_buf;   // PAIR_CAP x 256 (value, tag) words of the streaming GEMM's paired K split, zero between launches
-  uint8_t* fused_act;        // per-layer exchange buffers of the fused forward
-  size_t fused_act_stride;
-  int32_t fused_G;           // workgroups to launch (= compute units); 0: not available
-  bool no_fused;
-  int64_t prefetch_bytes;   // S2D2_PREFETCH_MB: weight bytes the narrow attention launch reads ahead for the GEMMs behind it
-                            // (< 0: the output projection and the gate / up pair; 0: off)
-  int32_t prefetch_wgs;     // S2D2_PREFETCH_WGS: workgroups that do it (default: half the compute units)
-  bool no_wide_attention;   // S2D2_ATTN_WIDE=0: one workgroup per query tile even for wide windows
+  int32_t prefetch_wgs;     // workgroups of the narrow attention launch that read the next two GEMMs' weights ahead
   int wide_wgs;             // workgroups the split choice of the wide attention kernel aims for
   // profiling (measurement aid)
   bool prof_on;
   int32_t prof_cap;
-  struct ProfRec { int cls; double bytes; hipEvent_t a, b; };
+  struct ProfRec { int cls, sub; double bytes, flops; hipEvent_t a, b; };
   std::vector<ProfRec>* prof;
   std::vector<hipEvent_t>* prof_pool;
 };
@@ -117,11 +107,7 @@ struct Carver {
 
 int elt_size(int dtype) { return dtype == S2D2_BF16 ? 2 : 4; }
 // bf16 planes in which GEMM inputs are carried (the workspace is sized for this; the plain kernels use one)
-int act_planes(const s2d2_model_desc& d) {
-  static const int forced = getenv("S2D2_ACT_PLANES") ? atoi(getenv("S2D2_ACT_PLANES")) : 0;   // measurement aid
-  const int want = forced == 1 || forced == 2 ? forced : d.act_planes;
-  return d.dtype == S2D2_BF16 && want != 1 ? 2 : 1;
-}
+int act_planes(const s2d2_model_desc& d) { return d.dtype == S2D2_BF16 && d.act_planes != 1 ? 2 : 1; }
 
 int32_t check_desc(const s2d2_model_desc* d) {
   if (!d) return fail(S2D2_EINVAL, "model description is NULL");
@@ -219,13 +205,8 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     c->tile_counters = cv.take<int32_t>(TILE_COUNTER_CAP);
     c->pair_buf = cv.take<unsigned long long>((size_t)PAIR_CAP * 256);
   }
-  c->fused_layers = cv.take<FusedLayer>(d.n_layers);
-  c->fused_bar = cv.take<uint32_t>(9 * 64);
-  c->fused_err = cv.take<int32_t>(64);
-  c->fused_act_stride = d.n_experts == 0 && d.dtype == S2D2_BF16 && d.d_model <= 4096
-                            ? forward_fused_act_bytes(d.d_model, d.n_q_heads * d.head_dim, d.d_ffn) : 0;
-  c->fused_act = cv.take<uint8_t>(c->fused_act_stride * (size_t)(d.n_layers + 1));
-  c->moe_y_or_scratch = cv.take<uint64_t>(832);
+  c->dev_status = cv.take<int32_t>(64);
+  c->ts_scratch = cv.take<uint64_t>(832);
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   c->accept_tiles = cv.take<float>(accept_tile_floats(c->max_batch, d.vocab));
@@ -236,10 +217,10 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
 // Arms the event pair of the next kernel launch (S2D2_LAUNCH) and books it under a class.  A scope that holds
 // several launches times the first one.
 struct ProfScope {
-  ProfScope(s2d2_ctx* c, int cls, double bytes) {
+  ProfScope(s2d2_ctx* c, int cls, double bytes, double flops = 0.0, int sub = -1) {
     if (!c->prof_on || (int32_t)c->prof->size() >= c->prof_cap) return;
     hipEvent_t a = (*c->prof_pool)[2 * c->prof->size()], b = (*c->prof_pool)[2 * c->prof->size() + 1];
-    c->prof->push_back({cls, bytes, a, b});
+    c->prof->push_back({cls, sub, bytes, flops, a, b});
     g_prof_start = a;
     g_prof_stop = b;
   }
@@ -293,11 +274,11 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   hipStream_t st = c->stream;
   const KvGeom g = geom(c, kv);
   // MFMA flash attention for bf16 / head_dim 128 / pages that hold whole 8-key groups; else the generic kernel
-  const bool flash = dt == S2D2_BF16 && d.head_dim == 128 && kv->page_size % 8 == 0 && !c->force_generic_attention;
+  const bool flash = dt == S2D2_BF16 && d.head_dim == 128 && kv->page_size % 8 == 0;
   const int q_tiles = ((k_stage ? 3 : 2) * B * (d.n_q_heads / d.n_kv_heads) + 31) / 32;   // 32-row query tiles of this call's windows
   int Z = 1;
   // several query tiles per (sequence, KV head): the kernel that shares K / V tiles among them
-  bool wide = flash && q_tiles >= 2 && !c->no_wide_attention && (kv->page_size & (kv->page_size - 1)) == 0;
+  bool wide = flash && q_tiles >= 2 && (kv->page_size & (kv->page_size - 1)) == 0;
   if (flash) {
     // Splits until there are ~512 workgroups or a wavefront is down to one 32-key tile; the last
     // split to finish merges, so extra splits cost one atomic, not a launch.
@@ -305,12 +286,10 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     const int groups = N * d.n_kv_heads * q_tiles;
     const int want = (512 + groups - 1) / groups;
     Z = std::max(1, std::min(std::min(want, (cap_tiles + 7) / 8), c->attn_zmax));
-    if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, want));
     if (wide) {
       // one workgroup per (sequence, KV head, group of query tiles, split); a split keeps at least 4 key tiles
       const int wg = N * d.n_kv_heads * ((q_tiles + 7) / 8);
       Z = std::max(1, std::min((c->wide_wgs + wg - 1) / wg, std::min((cap_tiles + 3) / 4, c->attn_zmax)));
-      if (c->attn_z_override > 0) Z = std::max(1, std::min(c->attn_z_override, cap_tiles));
       while (Z > 1 && ((size_t)Z * N * d.n_kv_heads * q_tiles > c->attn_part_entries ||
                        attention_wide_lds_bytes(attention_wide_pt_cap(g, Z)) > 160 * 1024)) --Z;
       if (attention_wide_lds_bytes(attention_wide_pt_cap(g, Z)) > 160 * 1024) wide = false, Z = 1;
@@ -325,11 +304,12 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int ss_stride = (d.d_model + 15) / 16;
   // rows a fresh block gives: N*B draft rows, 2*N*B verifier rows (more only with carried or pending committed tokens)
   const int m_hint = (k_stage ? 2 : 1) * N * B;
+  const double fr = 2.0 * m_hint, fl = 2.0 * N * B;   // flops per weight element: layer GEMMs, unembedding (method's flops, one plane)
   auto sk = [&](GemmStreamArgs& x) {   // split-K buffers of the tiled GEMM, expected rows
     x.m_hint = x.m_count == c->plan.counts + 1 ? N * B : m_hint;   // (logit rows: one per masked position)
     x.tile_partials = c->tile_partials; x.tile_counters = c->tile_counters;
     x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
-    x.pair_buf = c->pair_buf; x.pair_status = c->fused_err + 1; x.pair_cap = PAIR_CAP;
+    x.pair_buf = c->pair_buf; x.pair_status = c->dev_status + 1; x.pair_cap = PAIR_CAP;
   };
   // GEMM inputs as P bf16 planes per row: [hi | lo]; lo offsets are 0 with a single plane
   const int P = fused && flash ? act_planes(d) : 1;  // the generic attention kernel writes one plane
@@ -337,37 +317,6 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int ld_o = P * HqD, lo_o = P == 2 ? HqD : 0;
   const int ld_f = P * d.d_ffn, lo_f = P == 2 ? d.d_ffn : 0;
   const int ld_e = P * d.d_expert, lo_e = P == 2 ? d.d_expert : 0;
-  // ---- one persistent launch for narrow windows ----
-  const int grp = d.n_q_heads / d.n_kv_heads;
-  if (fused && flash && P == 2 && c->fused_G > 0 && c->fused_act_stride > 0 && !c->no_fused && R <= 16 && R * grp <= 32 && d.d_model / 16 <= c->fused_G &&
-      N * d.n_kv_heads * Z <= c->fused_G - d.d_model / 16) {
-    { ProfScope ps(c, 3, 0.0); launch_rope_table(st, c->plan, R, d.head_dim, d.rope_theta, c->rope_cs); }
-    { ProfScope ps(c, 3, 0.0); launch_fill_i32(st, (int32_t*)c->fused_bar, 9 * 64, 0); }
-    FusedArgs fa{};
-    fa.n_layers = d.n_layers; fa.d = d.d_model; fa.Hq = d.n_q_heads; fa.Hkv = d.n_kv_heads; fa.D = d.head_dim; fa.F = d.d_ffn; fa.n_seq = N;
-    fa.layers = c->fused_layers; fa.norm_f = c->w.norm_f; fa.embed = (const bf16_t*)c->w.embed; fa.plan = c->plan;
-    fa.rope_cs = c->rope_cs; fa.g = g; fa.k_pages = (const bf16_t*)kv->k_pages; fa.v_pages = (const bf16_t*)kv->v_pages;
-    fa.page_layer = page_layer / es;
-    fa.k_stage = (bf16_t*)(k_stage ? k_stage : c->kwin); fa.v_stage = (bf16_t*)(v_stage ? v_stage : c->vwin);
-    fa.stage_layer = k_stage ? stage_layer / es : 0;
-    fa.vT_win = (bf16_t*)c->vT_win; fa.wpad = c->wpad;
-    fa.xg = (bf16_t*)c->a; fa.q = (bf16_t*)c->qbuf; fa.ss = c->ss; fa.h_out = c->h;
-    fa.act = (char*)c->fused_act; fa.act_stride = c->fused_act_stride;
-    fa.part = c->attn_part; fa.attn_counters = c->attn_counters; fa.Z = Z;
-    fa.eps = d.rms_eps; fa.scale_log2e = 1.4426950408889634f / sqrtf((float)d.head_dim);
-    fa.bar = c->fused_bar; fa.err = c->fused_err; fa.spin_limit = 1 << 20;
-    fa.tstamp = (unsigned long long*)c->moe_y_or_scratch;
-    const double wbytes = (double)d.n_layers * ((double)qkv_n * d.d_model + (double)d.d_model * HqD + 3.0 * d.d_ffn * d.d_model) * es;
-    { ProfScope ps(c, 4, wbytes); launch_forward_fused(st, fa, c->fused_G); }
-    const int32_t* n_logit = c->plan.counts + 1;
-    GemmStreamArgs a{};
-    a.Wp = c->pk_unembed; a.NT = (d.vocab + 15) / 16; a.KT = d.d_model / 32; a.N = d.vocab; a.K = d.d_model;
-    a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.gather = c->plan.logit_src;
-    a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
-    a.out = logits; a.ldo = d.vocab;
-    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); sk(a); launch_gemm_stream(st, SEPI_STORE_F32, a, LR); }
-    return check_launch("forward (fused)");
-  }
   if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride, c->rope_cs, d.head_dim, d.rope_theta); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   for (int l = 0; l < d.n_layers; ++l) {
@@ -382,11 +331,11 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
       a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_o; a.q_lo = lo_o; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
-      ProfScope ps(c, 0, (double)qkv_n * d.d_model * es);
+      ProfScope ps(c, 0, (double)qkv_n * d.d_model * es, fr * qkv_n * d.d_model, 4);
       sk(a); launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
     } else {
       { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm1, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
-      { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
+      { ProfScope ps(c, 0, (double)qkv_n * d.d_model * es, fr * qkv_n * d.d_model, 4); launch_gemm(st, dt, EPI_STORE_F32, c->a, d.d_model, L.wqkv, d.d_model, qkv_n, n_rows, R, c->qkv, qkv_n); }
       { ProfScope ps(c, 3, 0.0); launch_rope_split(st, dt, c->qkv, c->plan, R, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_theta, c->qbuf, kw, vw, flash ? c->vT_win : nullptr, c->wpad); }
     }
     const void* kp = (const uint8_t*)kv->k_pages + l * page_layer;
@@ -401,10 +350,8 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         // compute units.  Workgroups behind the attention's own read the weights of the next two GEMMs (the packed
         // matrices of a layer lie one behind the other: wo, gate, up, down) into the memory-side cache meanwhile.
         size_t ahead = 0;
-        if (fused && d.n_experts == 0 && c->prefetch_bytes != 0 && R <= 32 && Z * q_tiles * N * d.n_kv_heads <= 128) {
-          const size_t two = packed_weight_bytes(d.d_model, HqD) + 2 * packed_weight_bytes(d.d_ffn, d.d_model);
-          ahead = c->prefetch_bytes < 0 ? two : std::min((size_t)c->prefetch_bytes, two + packed_weight_bytes(d.d_model, d.d_ffn));
-        }
+        if (fused && d.n_experts == 0 && R <= 32 && Z * q_tiles * N * d.n_kv_heads <= 128)
+          ahead = packed_weight_bytes(d.d_model, HqD) + 2 * packed_weight_bytes(d.d_ffn, d.d_model);
         launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters,
                                ahead ? c->pk[l].wo : nullptr, ahead, c->prefetch_wgs);
       }
@@ -418,7 +365,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.Wp = c->pk[l].wo; a.NT = d.d_model / 16; a.KT = HqD / 32; a.N = d.d_model; a.K = HqD;
       a.X = (const bf16_t*)c->obuf; a.ldx = ld_o; a.x_lo = lo_o; a.out = c->h; a.ldo = d.d_model;
       a.xg_out = (bf16_t*)c->a; a.xg_ld = ld_a; a.xg_lo = lo_a; a.gain_next = L.norm2; a.ss_out = c->ss; a.ss_stride = ss_stride;
-      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); sk(a); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
+      { ProfScope ps(c, 0, (double)d.d_model * HqD * es, fr * d.d_model * HqD, 5); sk(a); launch_gemm_stream(st, SEPI_ADD_F32, a, R); }
       const float* gain_after = l + 1 < d.n_layers ? c->layers[l + 1].norm1 : c->w.norm_f;
       if (d.n_experts == 0) {
         GemmStreamArgs b{};
@@ -426,13 +373,13 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         b.Wp = c->pk[l].wg; b.Wp2 = c->pk[l].wu; b.NT = d.d_ffn / 16; b.KT = d.d_model / 32; b.N = d.d_ffn; b.K = d.d_model;
         b.X = (const bf16_t*)c->a; b.ldx = ld_a; b.x_lo = lo_a; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
         b.eps = d.rms_eps; b.out = c->ffn; b.ldo = ld_f; b.out_lo = lo_f;
-        { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); sk(b); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
+        { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es, fr * 2.0 * d.d_ffn * d.d_model, 6); sk(b); launch_gemm_stream(st, SEPI_SWIGLU, b, R); }
         GemmStreamArgs e{};
         e.m_count = n_rows;
         e.Wp = c->pk[l].wdown; e.NT = d.d_model / 16; e.KT = d.d_ffn / 32; e.N = d.d_model; e.K = d.d_ffn;
         e.X = (const bf16_t*)c->ffn; e.ldx = ld_f; e.x_lo = lo_f; e.out = c->h; e.ldo = d.d_model;
         e.xg_out = (bf16_t*)c->a; e.xg_ld = ld_a; e.xg_lo = lo_a; e.gain_next = gain_after; e.ss_out = c->ss; e.ss_stride = ss_stride;
-        { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); sk(e); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
+        { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es, fr * d.d_model * d.d_ffn, 7); sk(e); launch_gemm_stream(st, SEPI_ADD_F32, e, R); }
       } else {
         // MoE FFN: router -> top-k -> group by expert -> grouped gate/up + SwiGLU -> grouped down -> combine
         const int E = d.n_experts, Fe = d.d_expert, tk = d.top_k;
@@ -442,7 +389,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         r.Wp = c->pk[l].router; r.NT = (E + 15) / 16; r.KT = d.d_model / 32; r.N = E; r.K = d.d_model;
         r.X = (const bf16_t*)c->a; r.ldx = ld_a; r.x_lo = lo_a; r.ss_part = c->ss; r.ss_stride = ss_stride; r.ss_count = ss_stride;
         r.eps = d.rms_eps; r.out = c->router_logits; r.ldo = E;
-        { ProfScope ps(c, 0, (double)E * d.d_model * es); sk(r); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
+        { ProfScope ps(c, 0, (double)E * d.d_model * es, fr * E * d.d_model); sk(r); launch_gemm_stream(st, SEPI_STORE_F32, r, R); }
         { ProfScope ps(c, 3, 0.0); launch_moe_route(st, c->router_logits, E, tk, n_rows, R, choice, c->moe_w); }
         { ProfScope ps(c, 3, 0.0); launch_moe_group(st, E, tk, n_rows, choice, c->moe_sorted, c->moe_tile_expert,
                                                      c->moe_tile_row0, c->moe_tile_rows, c->moe_n_tiles, c->moe_tile_cap); }
@@ -454,21 +401,21 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         b.Wp = c->pk[l].eg; b.Wp2 = c->pk[l].eu; b.NT = Fe / 16; b.KT = d.d_model / 32; b.N = Fe; b.K = d.d_model;
         b.X = (const bf16_t*)c->a; b.ldx = ld_a; b.x_lo = lo_a; b.ss_part = c->ss; b.ss_stride = ss_stride; b.ss_count = ss_stride;
         b.eps = d.rms_eps; b.out = c->moe_act; b.ldo = ld_e; b.out_lo = lo_e;
-        { ProfScope ps(c, 0, 2.0 * E * (double)Fe * d.d_model * es); launch_gemm_tile(st, SEPI_SWIGLU, SPRO_BF16S, b, tile_cap); }
+        { ProfScope ps(c, 0, 2.0 * E * (double)Fe * d.d_model * es, fr * tk * 2.0 * Fe * d.d_model, 6); launch_gemm_tile(st, SEPI_SWIGLU, SPRO_BF16S, b, tile_cap); }
         GemmStreamArgs e{};
         e.grouped = GROUP_SCATTER; e.top_k = tk; e.n_tiles = c->moe_n_tiles; e.tile_expert = c->moe_tile_expert;
         e.tile_row0 = c->moe_tile_row0; e.tile_rows = c->moe_tile_rows; e.sorted = c->moe_sorted; e.route_w = c->moe_w;
         e.expert_stride = packed_weight_bytes(d.d_model, Fe) / 16;
         e.Wp = c->pk[l].ed; e.NT = d.d_model / 16; e.KT = Fe / 32; e.N = d.d_model; e.K = Fe;
         e.X = (const bf16_t*)c->moe_act; e.ldx = ld_e; e.x_lo = lo_e; e.out = c->moe_y; e.ldo = d.d_model;
-        { ProfScope ps(c, 0, (double)E * d.d_model * Fe * es); launch_gemm_tile(st, SEPI_STORE_F32, SPRO_BF16, e, tile_cap); }
+        { ProfScope ps(c, 0, (double)E * d.d_model * Fe * es, fr * tk * (double)d.d_model * Fe, 7); launch_gemm_tile(st, SEPI_STORE_F32, SPRO_BF16, e, tile_cap); }
         { ProfScope ps(c, 3, 0.0); launch_moe_combine(st, c->moe_y, d.d_model, tk, n_rows, R, c->h, c->a, ld_a, lo_a, gain_after, c->ss, ss_stride); }
       }
     } else {
-      { ProfScope ps(c, 0, (double)d.d_model * HqD * es); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
+      { ProfScope ps(c, 0, (double)d.d_model * HqD * es, fr * d.d_model * HqD, 5); launch_gemm(st, dt, EPI_ADD_F32, c->obuf, HqD, L.wo, HqD, d.d_model, n_rows, R, c->h, d.d_model); }
       { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, L.norm2, d.d_model, d.rms_eps, n_rows, nullptr, R, c->a); }
-      { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
-      { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es); launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model); }
+      { ProfScope ps(c, 0, 2.0 * d.d_ffn * d.d_model * es, fr * 2.0 * d.d_ffn * d.d_model, 6); launch_gemm(st, dt, EPI_SWIGLU, c->a, d.d_model, L.wgu, d.d_model, d.d_ffn, n_rows, R, c->ffn, d.d_ffn); }
+      { ProfScope ps(c, 0, (double)d.d_model * d.d_ffn * es, fr * d.d_model * d.d_ffn, 7); launch_gemm(st, dt, EPI_ADD_F32, c->ffn, d.d_ffn, L.wdown, d.d_ffn, d.d_model, n_rows, R, c->h, d.d_model); }
     }
   }
   const int32_t* n_logit = c->plan.counts + 1;
@@ -478,11 +425,11 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     a.m_count = n_logit; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.gather = c->plan.logit_src;
     a.ss_part = c->ss; a.ss_stride = ss_stride; a.ss_count = ss_stride; a.eps = d.rms_eps;
     a.out = logits; a.ldo = d.vocab;
-    ProfScope ps(c, 0, (double)d.vocab * d.d_model * es);
+    ProfScope ps(c, 0, (double)d.vocab * d.d_model * es, fl * d.vocab * d.d_model, 8);
     sk(a); launch_gemm_stream(st, SEPI_STORE_F32, a, LR);
   } else {
     { ProfScope ps(c, 3, 0.0); launch_rmsnorm(st, dt, c->h, c->w.norm_f, d.d_model, d.rms_eps, n_logit, c->plan.logit_src, LR, c->af); }
-    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
+    { ProfScope ps(c, 0, (double)d.vocab * d.d_model * es, fl * d.vocab * d.d_model, 8); launch_gemm(st, dt, EPI_STORE_F32, c->af, d.d_model, c->w.unembed, d.d_model, d.vocab, n_logit, LR, logits, d.vocab); }
   }
   return check_launch("forward");
 }
@@ -574,12 +521,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   c->ws = (uint8_t*)workspace;
   c->ws_bytes = workspace_bytes;
   carve(c, c->ws);
-  if (const char* e = getenv("S2D2_ATTN_Z")) c->attn_z_override = atoi(e);
-  c->no_wide_attention = false;
-  if (const char* e = getenv("S2D2_ATTN_WIDE")) c->no_wide_attention = atoi(e) == 0;
   c->wide_wgs = 512;
-  if (const char* e = getenv("S2D2_ATTN_WIDE_WGS")) c->wide_wgs = std::max(1, atoi(e));
-  if (const char* e = getenv("S2D2_GENERIC_ATTENTION")) c->force_generic_attention = atoi(e) != 0;
   if (use_packed) {  // re-lay the projection weights out for the streaming GEMM (enqueued on the stream)
     const s2d2_model_desc& d = c->desc;
     const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
@@ -619,22 +561,8 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     c->pk_unembed = put(c->w.unembed, d.vocab, d.d_model, 0);
     if (hipGetLastError() != hipSuccess) { free(c->pk); free(c->layers); free(c); return fail(S2D2_ELAUNCH, "weight packing failed to launch"); }
   }
-  c->no_fused = true;   // the fused forward is opt-in: on this hardware its device-wide barriers cost what kernel boundaries cost
-  if (const char* e = getenv("S2D2_FUSED")) c->no_fused = atoi(e) == 0;
-  c->prefetch_bytes = -1;
   c->prefetch_wgs = 128;
-  if (const char* e = getenv("S2D2_PREFETCH_MB")) c->prefetch_bytes = (int64_t)std::max(0, atoi(e)) << 20;
-  if (const char* e = getenv("S2D2_PREFETCH_WGS")) c->prefetch_wgs = std::max(1, atoi(e));
-  launch_fill_i32(c->stream, c->fused_err, 64, 0);
-  if (use_packed && c->desc.n_experts == 0 && act_planes(c->desc) == 2 && c->desc.head_dim == 128) {
-    // one workgroup per compute unit must be resident at the same time for the device-wide barriers
-    if (forward_fused_init() == 0 && forward_fused_occupancy() >= 1 && prop.multiProcessorCount >= 8) c->fused_G = prop.multiProcessorCount;
-    (void)hipGetLastError();
-    for (int l = 0; l < c->desc.n_layers && c->fused_G; ++l) {
-      FusedLayer fl{c->pk[l].wqkv, c->pk[l].wo, c->pk[l].wg, c->pk[l].wu, c->pk[l].wdown, c->layers[l].norm1, c->layers[l].norm2};
-      launch_fused_set_layer(c->stream, c->fused_layers + l, fl);
-    }
-  }
+  launch_fill_i32(c->stream, c->dev_status, 64, 0);
   launch_fill_i32(c->stream, c->attn_counters, c->attn_groups, 0);
   launch_fill_i32(c->stream, c->zeros_i32, c->max_batch, 0);
   launch_fill_i32(c->stream, c->accept_arrive, c->max_batch, 0);
@@ -848,13 +776,18 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
   if (!c->prof_on) return fail(S2D2_EINVAL, "profiling is not on");
   c->prof_on = false;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(S2D2_ELAUNCH, "stream synchronize failed");
-  for (int k = 0; k < S2D2_PROFILE_CLASSES; ++k) out[k] = s2d2_profile{0, 0.0, 0.0};
+  for (int k = 0; k < S2D2_PROFILE_CLASSES; ++k) out[k] = s2d2_profile{0, 0.0, 0.0, 0.0, 0.0};
   for (const auto& r : *c->prof) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { (void)hipGetLastError(); continue; }   // scope without a launch
-    out[r.cls].launches += 1;
-    out[r.cls].ms += ms;
-    out[r.cls].bytes += r.bytes;
+    for (int k : {r.cls, r.sub}) {
+      if (k < 0) continue;
+      out[k].launches += 1;
+      out[k].ms += ms;
+      out[k].bytes += r.bytes;
+      out[k].flops += r.flops;
+      if (ms > out[k].max_ms) out[k].max_ms = ms;
+    }
   }
   return S2D2_OK;
 }
@@ -862,9 +795,8 @@ int32_t s2d2_profile_stop(s2d2_ctx* c, s2d2_profile* out) {
 int32_t s2d2_status(s2d2_ctx* c) {
   if (!c) return fail(S2D2_EINVAL, "ctx is NULL");
   int32_t flag[2] = {0, 0};
-  if (hipStreamSynchronize(c->stream) != hipSuccess || hipMemcpy(flag, c->fused_err, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipMemcpy(flag, c->dev_status, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
     return fail(S2D2_ELAUNCH, "could not read the device status: %s", hipGetErrorString(hipGetLastError()));
-  if (flag[0]) return fail(S2D2_ELAUNCH, "a device-wide barrier of the fused forward timed out (workgroups not co-resident)");
   if (flag[1]) return fail(S2D2_ELAUNCH, "a workgroup of the streaming GEMM waited in vain for its partner's share of K");
   return S2D2_OK;
 }
@@ -872,10 +804,10 @@ int32_t s2d2_status(s2d2_ctx* c) {
 int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
   if (!c || !name || !ptr) return fail(S2D2_EINVAL, "NULL argument");
   const struct { const char* n; void* p; } tab[] = {{"h", c->h}, {"a", c->a}, {"q", c->qbuf}, {"o", c->obuf}, {"ffn", c->ffn},
-                                                    {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->moe_y_or_scratch}};
-  if (!strcmp(name, "stream_ts")) { launch_stream_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
-  if (!strcmp(name, "tile_ts")) { launch_tile_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
-  if (!strcmp(name, "attn_ts")) { launch_attn_ts_copy(c->stream, c->moe_y_or_scratch); *ptr = c->moe_y_or_scratch; return S2D2_OK; }
+                                                    {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->ts_scratch}};
+  if (!strcmp(name, "stream_ts")) { launch_stream_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
+  if (!strcmp(name, "tile_ts")) { launch_tile_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
+  if (!strcmp(name, "attn_ts")) { launch_attn_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
   for (const auto& t : tab)
     if (!strcmp(t.n, name)) { *ptr = t.p; return S2D2_OK; }
   return fail(S2D2_EINVAL, "unknown buffer %s", name);

@@ -163,7 +163,7 @@ void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, c
                        (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, items, pf, pf_n16);
 }
 
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __global__ void attn_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_attn_ts[threadIdx.x]; }
 void launch_attn_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(attn_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
 #else

@@ -1,11 +1,10 @@
-// MFMA flash attention over the paged prefix cache plus the window: device-side body, shared by the
-// stand-alone kernel (attention.hip) and the fused forward (forward_fused.hip).
+// MFMA flash attention over the paged prefix cache plus the window: device-side body of the kernel in attention.hip.
 #pragma once
 #include "s2d2_internal.h"
 
 namespace s2d2 {
 
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __device__ unsigned long long g_attn_ts[64];
 #define S2D2_ATS(k) do { if (threadIdx.x == 0 && z == 0 && item_zy == 0) g_attn_ts[k] = wall_clock64(); } while (0)
 #define S2D2_ATS_ANY(k) do { if (threadIdx.x == 0 && item_zy == 0) g_attn_ts[k] = wall_clock64(); } while (0)
@@ -26,8 +25,8 @@ __device__ unsigned long long g_attn_ts[64];
 // beyond one exchange between the two half-waves.  The rows of the K tile are fed in a permuted
 // order chosen so that the fp32 S^T accumulators of a lane, packed to bf16, are exactly the B
 // operand (8 consecutive keys) of O^T = V^T P^T; the cache stores V key-minor ([D, page_size])
-// so that the matching A operand is one 16-byte load.  Wavefronts merge through LDS in a fixed
-// tree; splits merge in attn_combine_kernel (fixed order) unless there is only one split.
+// so that the matching A operand is one 16-byte load.  Wavefronts merge through LDS in wavefront
+// order; key splits are merged, in split order, by the workgroup of a tile that arrives last at the tile's counter.
 // ---------------------------------------------------------------------------------------------
 static constexpr int FA_D = 128;
 
@@ -151,8 +150,9 @@ __device__ __forceinline__ void fa_combine(const float* part_o, const float* par
 
 // SPLIT: queries and softmax weights are used as high + low bf16 planes (16 significant bits): the
 // score and the P*V products are each issued twice against the same K / V operands.
-// COH: q, the window K / V and o are exchanged with other workgroups of the SAME launch (fused forward), so
-// they are read and written with device-coherent accesses.  The split partials always are.
+// COH: q, the window K / V and o are read and written with device-coherent accesses (for a caller whose producer
+// or consumer is another workgroup of the SAME launch; the stand-alone kernel passes false).  The split partials
+// always are.
 // (z, qt, item) = (key split, query tile, sequence * Hkv + KV head); q_tiles = query tiles per item.
 template <int NW, bool SPLIT, bool COH>
 __device__ __forceinline__ void attn_flash_body(

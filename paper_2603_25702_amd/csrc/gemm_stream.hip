@@ -89,7 +89,7 @@ __device__ __forceinline__ float tile_total(const float* s_red, int t, int fe, i
   return v;
 }
 
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __device__ unsigned long long g_stream_ts[4][16];   // [epilogue kind][first workgroup: 0-7, last workgroup: 8-15]
 // stamps are kept in registers and written once at the end: a store in the middle of the kernel would turn the
 // scalar loads after it into vector loads (possible aliasing) and so change what is being timed
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
   extern __shared__ __align__(16) uint8_t smem_raw[];
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
   unsigned long long ts_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #endif
   S2D2_GTS(0);
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #pragma unroll
   for (int t = 0; t < TA; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   S2D2_GTS(1);
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
   if (w[0][0][0] == 0x12345678u && Mloc < 0) return;   // (timing aid: the first weight tile has arrived)
   S2D2_GTS(2);
 #endif
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     }
   }
   // acc[t][i] = Y[m0 + f][tile t, feature 4 g + i]
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
   if (acc[0][0] == 12345.678f && Mloc < 0) return;
 #endif
   S2D2_GTS(3);
@@ -367,7 +367,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
     }
   }
 #undef S2D2_TOTAL
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
   __builtin_amdgcn_s_waitcnt(0);
   S2D2_GTS(5);
   if (threadIdx.x == 0 && blockIdx.y == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1))
@@ -375,7 +375,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
 #endif
 }
 
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __global__ void stream_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = (&g_stream_ts[0][0])[threadIdx.x]; }
 void launch_stream_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(stream_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
 #else

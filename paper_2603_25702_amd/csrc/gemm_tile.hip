@@ -35,7 +35,7 @@
 namespace s2d2 {
 
 static constexpr int TM = 128, TK = 64;
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __device__ unsigned long long g_tile_ts[64];
 #define S2D2_TTS(k) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && (blockIdx.z == 0 || (k) >= 4)) g_tile_ts[(k)] = wall_clock64(); } while (0)
 #else
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   S2D2_TTS(6);
 }
 
-#ifdef S2D2_FUSED_TIMING
+#ifdef S2D2_KERNEL_TIMING
 __global__ void tile_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_tile_ts[threadIdx.x]; }
 void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
 #else
@@ -428,7 +428,6 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
   const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
-  static const int ks_override = getenv("S2D2_TILE_KS") ? atoi(getenv("S2D2_TILE_KS")) : 0;   // tuning aid
   const double step_us = 1.3;
   if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
     double best = 1e30;
@@ -439,7 +438,6 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
       if (ks > 1) t += 8.0 + (double)live * ks * PART_BYTES * 2.0 / 3.0e6;
       if (t < best - 1e-9) { best = t; KS = ks; }
     }
-    if (ks_override > 0 && nk / ks_override >= 4 && tiles * ks_override * (WC / 2) <= a.tile_partial_cap) KS = ks_override;
   }
   dim3 grid(col_tiles, row_tiles, KS), block(128 * WC);
   if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true, WC>), grid, block, 0, st, a);

@@ -214,49 +214,6 @@ void launch_moe_combine(hipStream_t st, const float* y, int d, int top_k, const 
 void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, int layers, int per_layer_src,
                              int per_layer_dst);
 
-// forward_fused.hip : the whole forward of a window of at most 16 rows in one persistent launch
-struct FusedLayer {            // device-resident, one per layer
-  const uint4 *wqkv, *wo, *wg, *wu, *wdown;   // packed weights
-  const float *norm1, *norm2;
-};
-struct FusedArgs {
-  int32_t n_layers, d, Hq, Hkv, D, F, n_seq;
-  const FusedLayer* layers;    // device [n_layers]
-  const float* norm_f;
-  const bf16_t* embed;
-  Plan plan;
-  const float2* rope_cs;
-  KvGeom g;
-  const bf16_t* k_pages;
-  const bf16_t* v_pages;
-  size_t page_layer;           // elements per layer of the page arrays
-  bf16_t* k_stage;             // window K / V of every layer ([layer, rows_cap, Hkv, D]) or a one-layer scratch
-  bf16_t* v_stage;
-  size_t stage_layer;          // elements per layer (0 for the scratch)
-  bf16_t* vT_win;
-  int32_t wpad;
-  bf16_t* xg;                  // [16, 2, d]   operand of the FINAL norm, row-major (read by the unembedding GEMM)
-  bf16_t* q;                   // [16, 2, Hq D]
-  float* ss;                   // [16, d / 16] partial sums of squares of the final residual rows
-  char* act;                   // per-layer exchange buffers, act_stride bytes per layer (forward_fused_act_bytes)
-  size_t act_stride;
-  float* h_out;                // [16, d] final residual rows (inspection only)
-  float* part;                 // split-key partials of the attention
-  int32_t* attn_counters;
-  int32_t Z;
-  float eps, scale_log2e;
-  uint32_t* bar;               // 9 counters at 64-word spacing, zero at launch
-  int32_t* err;                // sticky: set when a barrier wait ran out of spins
-  int32_t spin_limit;
-  unsigned long long* tstamp;  // timing build only: 2 x 400 clock stamps
-};
-size_t forward_fused_act_bytes(int d, int HqD, int F);   // per layer
-size_t forward_fused_lds();
-int forward_fused_init();
-int forward_fused_occupancy();
-void launch_fused_set_layer(hipStream_t st, FusedLayer* dst, const FusedLayer& v);
-void launch_forward_fused(hipStream_t st, const FusedArgs& a, int G);
-
 // attention.hip
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,
                               const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,

@@ -63,7 +63,7 @@ def compile_to_asm(src: str, out_dir: str) -> str:
 
 def lint_sources(sources=None, jobs: int = 6) -> List[Tuple[str, str, int, str]]:
     sources = [s for s in (sources or SOURCES)
-               if "mfma" in open(os.path.join(CSRC, s)).read() or s in ("attention.hip", "attention_wide.hip", "forward_fused.hip")]
+               if "mfma" in open(os.path.join(CSRC, s)).read() or s in ("attention.hip", "attention_wide.hip")]
     with tempfile.TemporaryDirectory() as tmp:
         with ThreadPoolExecutor(max_workers=jobs) as ex:
             paths = list(ex.map(lambda s: compile_to_asm(s, tmp), sources))

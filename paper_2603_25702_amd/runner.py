@@ -93,7 +93,8 @@ class Session:
         self.kv.status.zero_()
         self.step_dev.zero_()
 
-    def step(self, prm: Params, n_accept: Optional[torch.Tensor] = None, n_commit: Optional[torch.Tensor] = None):
+    def step(self, prm: Params, n_accept: Optional[torch.Tensor] = None, n_commit: Optional[torch.Tensor] = None,
+             advance: bool = True):
         """draft -> verify -> accept -> kv_append -> block_advance, enqueued without any sync."""
         N, B, e = self.N, self.B, self.eng
         if n_accept is not None:
@@ -102,7 +103,8 @@ class Session:
         e.s2d2_verify(self.kv, self.st, N, B, prm, self.d, self.v)
         e.s2d2_accept(self.st, N, B, prm, self.d, self.v, self.a)
         e.s2d2_kv_append(self.kv, N, B, self.d, self.v, self.a.n_accept)
-        e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
+        if advance:
+            e.s2d2_block_advance(self.kv, self.st, N, B, prm.step_dev)
 
     def step_routed(self, prm: Params, rp: RouteParams):
         """Alg. 3 with its routing: draft -> DoVerify -> (verify -> accept -> kv_append for the sequences routed to the
@@ -190,10 +192,12 @@ class Session:
             step += 1
         return out, log
 
-    def capture_step(self, prm: Params):
+    def capture_step(self, prm: Params, advance: bool = True):
         """Records one step (plus the on-device running totals of accepted and committed tokens) into a HIP graph
         and returns it; `graph.replay()` then enqueues the whole step with one host call.  The RNG step word advances
-        on the device (prm.step_dev), so every replay is a new step of the same session."""
+        on the device (prm.step_dev), so every replay is a new step of the same session.  advance=False leaves
+        s2d2_block_advance (which also bumps the step word) out of the graph, for a caller that wants to look at the
+        block before it rolls over."""
         assert prm.step_dev is not None, "a captured step needs the device-resident step counter"
         self.tot_accept = torch.zeros(self.N, dtype=torch.int32, device=self.dev)
         self.tot_commit = torch.zeros(self.N, dtype=torch.int32, device=self.dev)
@@ -203,7 +207,7 @@ class Session:
         self.eng.set_stream(side)
         try:
             with torch.cuda.graph(graph, stream=side):
-                self.step(prm)
+                self.step(prm, advance=advance)
                 self.tot_accept += self.a.n_accept
                 self.tot_commit += self.a.n_commit
         finally:

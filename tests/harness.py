@@ -101,21 +101,7 @@ def make_case(cfg: I.ModelCfg, N: int, B: int, prefix_lens, seed: int = 0, page_
     return case
 
 
-class LazyF64Weights(dict):
-    """The same stored weights, with the expert tensors of the most recently used layer kept up-cast to
-    fp64 so that the oracle's per-(row, expert) up-casts become no-ops.  Values are unchanged."""
-
-    def __init__(self, W):
-        super().__init__(W)
-        self._key, self._val = {}, {}
-
-    def __getitem__(self, k):
-        base = k.split(".")[-1]
-        if base in ("e_wgu", "e_wdown"):
-            if self._key.get(base) != k:
-                self._key[base], self._val[base] = k, super().__getitem__(k).to(torch.float64).numpy()
-            return self._val[base]
-        return super().__getitem__(k)
+LazyF64Weights = O.LazyF64Weights
 
 
 class DeviceRun:

@@ -21,9 +21,12 @@ def lib():
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "s2d2.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(s2d2_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for h in ("s2d2.h", "s2d2_aux.h"):   # the step's boundary, and the inspection / measurement aids
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(s2d2_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
