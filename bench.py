@@ -22,7 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
-MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA peak of the arithmetic type
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA peak of the arithmetic type (f16 and bf16 MFMA run at the same rate)
 HEADLINE, OTHERS = 4, (2, 3, 5)
 # HBM bytes per launch of the dominant GEMM kernel of a configuration, from the FETCH_SIZE / WRITE_SIZE counter runs
 # summarised under profiles/ (rocprofv3 --pmc, scaled by what the same counters read for a plain copy of known size).
@@ -55,7 +55,7 @@ def bench_config(args, cfg_id: int, K: int, Wm: int, cpu_baseline: bool) -> dict
     ids = [I.gen_prefix_ids(cfg, int(lens[n]), args.seed, n) for n in range(N)]
     max_seq = int(lens.max()) + (max(K, Wm) + 2) * B + 64
     table = I.gen_page_table(N, (max_seq + wl.page_size - 1) // wl.page_size, args.seed)
-    ses = Session(cfg, weights, N, B, max_seq, wl.page_size, dev, page_table=table)
+    ses = Session(cfg, weights, N, B, max_seq, wl.page_size, dev, page_table=table, act_planes=args.act_planes)
     t0 = time.time()
     last = [int(x[-1]) for x in ids]
     ses.prefill(ids)
@@ -73,6 +73,7 @@ def bench_config(args, cfg_id: int, K: int, Wm: int, cpu_baseline: bool) -> dict
 
     run(Wm)
     torch.cuda.synchronize()
+    graph = None
     if args.no_graph:
         ses.reset_blocks(lens, last)
         torch.cuda.synchronize()
@@ -197,10 +198,16 @@ def bench_config(args, cfg_id: int, K: int, Wm: int, cpu_baseline: bool) -> dict
 
     rec = {
         "value": round(value, 2), "unit": "tokens/s", "steps": K, "warmup": Wm, "ms_per_step": round(elapsed * 1e3 / K, 4),
-        "dtype": cfg.dtype, "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
+        "dtype": ("f16" if args.act_planes in (0, 3) else "bf16") if cfg.dtype == "bf16" else cfg.dtype,
+        "operands": {0: "GEMM inputs as IEEE half against a half copy of the bf16 weights (f16 MFMA, fp32 accumulate); queries, keys, values and the KV cache bf16",
+                     3: "GEMM inputs as IEEE half against a half copy of the bf16 weights (f16 MFMA, fp32 accumulate); queries, keys, values and the KV cache bf16",
+                     2: "GEMM inputs as bf16 hi + lo planes against the bf16 weights (bf16 MFMA issued twice, fp32 accumulate)",
+                     1: "GEMM inputs as one bf16 plane (outside the logit tolerance on the 36-layer configurations)"}[args.act_planes] if cfg.dtype == "bf16" else "fp32",
+        "launch": "host calls" if args.no_graph else "hip graph of one step, replayed",
         "config": {"workload": f"config {cfg_id}: {cfg.name} {cfg.n_layers}L d{cfg.d_model} V{cfg.vocab}, batch {N}, "
                                f"prefix {int(lens.min())}-{int(lens.max())}, block {B}, tau {prm.tau}, {K} consecutive steps"
-                               + (", right-shifted model" if args.right_shifted else ""),
+                               + (", right-shifted model" if args.right_shifted else "")
+                               + (f", act_planes={args.act_planes}" if args.act_planes else ""),
                    "tokens_committed": committed, "drafts_accepted": accepted},
         "roofline": roofline, "cpu_baseline": cpu, "phases": phases,
     }
@@ -224,6 +231,8 @@ def main():
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call of a step from the host instead of replaying a HIP graph of one step")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--act-planes", type=int, default=0, help="operand mode of the GEMMs (s2d2_model_desc.act_planes): 0/3 half "
+                                                               "values (default), 2 two bf16 planes, 1 one bf16 plane; the result is labelled")
     ap.add_argument("--right-shifted", action="store_true",
                     help="treat the synthetic model as right-shifted (output at position i-1 scores token i): plain causal "
                          "verifier rows instead of the 2L window; the result is labelled")
@@ -252,7 +261,7 @@ def main():
     out = {
         "metric": "accepted tokens/s per draft+verify step", "value": head["value"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "operands": head["operands"], "data": "synthetic",
         "launch": head["launch"], "config": head["config"], "roofline": head["roofline"],
         "cpu_baseline": head["cpu_baseline"], "phases": head["phases"],
     }

@@ -74,9 +74,16 @@ typedef struct {
   int32_t dtype;                        /* S2D2_F32 or S2D2_BF16: weights, KV cache, activations */
   int32_t mask_id;                      /* token id of [MASK] */
   int32_t act_planes;                   /* bf16 models with packed weights: how the inputs of the GEMMs are carried.
-                                           2 (also chosen by 0): as a high- and a low-order bf16 plane, 16 significant
-                                           bits, every weight operand multiplied with both (keeps 36-layer models inside
-                                           the logit tolerance); 1: one bf16 plane, half the MFMA work */
+                                           3 (also chosen by 0, the default): as IEEE half values, 11 significant
+                                           bits, against a half copy of the weights made when the packed buffer is
+                                           filled (bf16 -> half is exact for |w| >= 2^-17, absolute error <= 2^-25
+                                           below), on the f16 MFMA, whose rate equals the bf16 one; needs activations
+                                           within the half range (|x| < 65504);
+                                           2: as a high- and a low-order bf16 plane, 16 significant bits, every bf16
+                                           weight operand multiplied with both (twice the matrix instructions);
+                                           1: one bf16 plane, 8 significant bits (36-layer models leave the 2e-2 logit
+                                           tolerance against an fp64 reference with it).
+                                           Queries, keys, values and the KV cache are bf16 in every mode. */
   int32_t right_shifted;                /* 1: the model's output at position i-1 is the distribution of token i
                                            (Section 4.2, right-shifted models).  s2d2_draft then reads the logits of a
                                            masked block position from the window row in front of it, s2d2_verify runs

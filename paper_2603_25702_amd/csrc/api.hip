@@ -106,8 +106,14 @@ struct Carver {
 };
 
 int elt_size(int dtype) { return dtype == S2D2_BF16 ? 2 : 4; }
-// bf16 planes in which GEMM inputs are carried (the workspace is sized for this; the plain kernels use one)
-int act_planes(const s2d2_model_desc& d) { return d.dtype == S2D2_BF16 && d.act_planes != 1 ? 2 : 1; }
+// planes the workspace reserves per GEMM input row (bf16 models: room for two, whatever the operand mode)
+int act_planes(const s2d2_model_desc& d) { return d.dtype == S2D2_BF16 ? 2 : 1; }
+// how the packed-weight GEMMs of a bf16 model take their inputs (s2d2_model_desc.act_planes)
+int operand_mode_of(const s2d2_model_desc& d) {
+  if (d.act_planes == 1) return OPM_BF16;
+  if (d.act_planes == 2) return OPM_BF16X2;
+  return OPM_F16;   // 0 (default) and 3
+}
 
 int32_t check_desc(const s2d2_model_desc* d) {
   if (!d) return fail(S2D2_EINVAL, "model description is NULL");
@@ -128,7 +134,7 @@ int32_t check_desc(const s2d2_model_desc* d) {
     if (d->d_ffn) return fail(S2D2_EINVAL, "d_ffn must be 0 for a MoE model");
   }
   if (d->mask_id < 0 || d->mask_id >= d->vocab) return fail(S2D2_EINVAL, "mask_id outside the vocabulary");
-  if (d->act_planes < 0 || d->act_planes > 2) return fail(S2D2_EINVAL, "act_planes must be 0, 1 or 2");
+  if (d->act_planes < 0 || d->act_planes > 3) return fail(S2D2_EINVAL, "act_planes must be 0, 1, 2 or 3");
   if (d->right_shifted != 0 && d->right_shifted != 1) return fail(S2D2_EINVAL, "right_shifted must be 0 or 1");
   if (d->vocab > 8192 * 256) return fail(S2D2_EINVAL, "vocab above 2097152 is not supported");
   if (!(d->rope_theta > 1.0f) || !(d->rms_eps >= 0.0f)) return fail(S2D2_EINVAL, "rope_theta must exceed 1 and rms_eps be non-negative");
@@ -311,12 +317,21 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
     x.pair_buf = c->pair_buf; x.pair_status = c->dev_status + 1; x.pair_cap = PAIR_CAP;
   };
-  // GEMM inputs as P bf16 planes per row: [hi | lo]; lo offsets are 0 with a single plane
-  const int P = fused && flash ? act_planes(d) : 1;  // the generic attention kernel writes one plane
-  const int ld_a = P * d.d_model, lo_a = P == 2 ? d.d_model : 0;
-  const int ld_o = P * HqD, lo_o = P == 2 ? HqD : 0;
-  const int ld_f = P * d.d_ffn, lo_f = P == 2 ? d.d_ffn : 0;
-  const int ld_e = P * d.d_expert, lo_e = P == 2 ? d.d_expert : 0;
+  // GEMM inputs: one plane of half values, or P bf16 planes per row ([hi | lo]); the low-plane offsets say which
+  // (0: one bf16 plane; LO_F16: half).  The plain kernels (no packed copy, or the generic attention) use one bf16 plane.
+  // (the generic attention kernel reads and writes single planes: two-plane models then run on their high plane)
+  const int mode = operand_mode_of(d);
+  const int opm = !fused ? OPM_BF16 : (flash || mode == OPM_F16 ? mode : OPM_BF16);
+  const int P = opm == OPM_BF16X2 ? 2 : 1;
+  auto lo_of = [&](int width) { return opm == OPM_F16 ? LO_F16 : (P == 2 ? width : 0); };
+  const int ld_a = P * d.d_model, lo_a = lo_of(d.d_model);
+  const int ld_o = P * HqD, lo_o = lo_of(HqD);
+  const int ld_f = P * d.d_ffn, lo_f = lo_of(d.d_ffn);
+  const int ld_e = P * d.d_expert, lo_e = lo_of(d.d_expert);
+  // queries stay bf16 (the attention kernels multiply them with the cache's bf16 keys): hi + lo planes unless the
+  // model asked for single bf16 planes
+  const int PQ = fused && flash && opm != OPM_BF16 ? 2 : 1;
+  const int ld_q = PQ * HqD, lo_q = PQ == 2 ? HqD : 0;
   if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride, c->rope_cs, d.head_dim, d.rope_theta); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   for (int l = 0; l < d.n_layers; ++l) {
@@ -329,7 +344,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.m_count = n_rows; a.X = (const bf16_t*)c->a; a.ldx = ld_a; a.x_lo = lo_a; a.ss_part = c->ss; a.ss_stride = ss_stride;
       a.ss_count = l == 0 ? 1 : ss_stride; a.eps = d.rms_eps;
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
-      a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_o; a.q_lo = lo_o; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
+      a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_q; a.q_lo = lo_q; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
       ProfScope ps(c, 0, (double)qkv_n * d.d_model * es, fr * qkv_n * d.d_model, 4);
       sk(a); launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
@@ -343,7 +358,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     if (flash) {
       ProfScope ps(c, 1, 0.0);
       if (wide)
-        launch_attention_wide(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
+        launch_attention_wide(st, c->qbuf, fused ? ld_q : HqD, fused ? lo_q : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
       else
       {
         // Narrow windows of a few sequences: the launch is a chain of dependent round trips on a fraction of the
@@ -352,12 +367,12 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
         size_t ahead = 0;
         if (fused && d.n_experts == 0 && R <= 32 && Z * q_tiles * N * d.n_kv_heads <= 128)
           ahead = packed_weight_bytes(d.d_model, HqD) + 2 * packed_weight_bytes(d.d_ffn, d.d_model);
-        launch_attention_flash(st, c->qbuf, fused ? ld_o : HqD, fused ? lo_o : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters,
+        launch_attention_flash(st, c->qbuf, fused ? ld_q : HqD, fused ? lo_q : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_counters,
                                ahead ? c->pk[l].wo : nullptr, ahead, c->prefetch_wgs);
       }
     } else {
       ProfScope ps(c, 1, 0.0);
-      launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds);
+      launch_attention_generic(st, dt, c->qbuf, kw, vw, kp, vp, g, c->plan, R, d.n_q_heads, c->obuf, lds, opm == OPM_F16);
     }
     if (fused) {
       GemmStreamArgs a{};
@@ -527,9 +542,10 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
     const int HqD = d.n_q_heads * d.head_dim, qkv_n = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     c->pk = (s2d2_ctx::PackedLayer*)malloc(sizeof(s2d2_ctx::PackedLayer) * d.n_layers);
     uint8_t* p = (uint8_t*)packed;
+    const int to_f16 = operand_mode_of(d) == OPM_F16;
     auto put = [&](const void* W, int N, int K, int rope) {
       const uint4* at = (const uint4*)p;
-      launch_pack_weight(c->stream, W, N, K, rope, d.head_dim, p);
+      launch_pack_weight(c->stream, W, N, K, rope, d.head_dim, p, to_f16);
       p += packed_weight_bytes(N, K);
       return at;
     };

@@ -24,7 +24,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_generic_kernel(
     const T* __restrict__ q, const T* __restrict__ k_win, const T* __restrict__ v_win,
     const T* __restrict__ k_pages, const T* __restrict__ v_pages, KvGeom g, Plan p, int Hq,
-    T* __restrict__ o, float scale) {
+    T* __restrict__ o, float scale, int o_f16) {
   extern __shared__ float smem[];
   const int r = blockIdx.x, hq = blockIdx.y;
   if (r >= p.counts[0]) return;
@@ -102,7 +102,8 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(
   if (tid < D) {
     float t = 0.f;
     for (int i = 0; i < nslice; ++i) t += s_red[i * D + tid];
-    o[((size_t)r * Hq + hq) * D + tid] = from_f32<T>(t / denom);
+    if (sizeof(T) == 2 && o_f16) ((bf16_t*)o)[((size_t)r * Hq + hq) * D + tid] = f32_to_f16_bits(t / denom);   // the consuming GEMM runs on half operands
+    else o[((size_t)r * Hq + hq) * D + tid] = from_f32<T>(t / denom);
   }
 }
 
@@ -194,17 +195,17 @@ size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows) {
 
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,
                               const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,
-                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes) {
+                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes, int o_f16) {
   const float scale = 1.0f / sqrtf((float)g.head_dim);
   dim3 grid(rows_cap, Hq), block(256);
   if (dtype == S2D2_BF16) {
     S2D2_LAUNCH(attn_generic_kernel<bf16_t>, grid, block, lds_bytes, st, (const bf16_t*)q,
                        (const bf16_t*)k_win, (const bf16_t*)v_win, (const bf16_t*)k_pages_layer,
-                       (const bf16_t*)v_pages_layer, g, p, Hq, (bf16_t*)o, scale);
+                       (const bf16_t*)v_pages_layer, g, p, Hq, (bf16_t*)o, scale, o_f16);
   } else {
     S2D2_LAUNCH(attn_generic_kernel<float>, grid, block, lds_bytes, st, (const float*)q,
                        (const float*)k_win, (const float*)v_win, (const float*)k_pages_layer,
-                       (const float*)v_pages_layer, g, p, Hq, (float*)o, scale);
+                       (const float*)v_pages_layer, g, p, Hq, (float*)o, scale, 0);
   }
 }
 

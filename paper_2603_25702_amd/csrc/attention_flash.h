@@ -73,22 +73,14 @@ __device__ __forceinline__ void fa_merge(FaState& a, float m2, float l2, const f
     for (int i = 0; i < 16; ++i) a.o[t][i] = a.o[t][i] * f1 + o2[t][i] * f2;
 }
 
-// Four consecutive output elements as bf16, plus their low-order plane o_lo elements further on if o_lo != 0.
+// Four consecutive output elements in the storage the low-plane offset o_lo names (bf16, bf16 hi + lo planes, or half).
 template <bool COH>
 __device__ __forceinline__ void fa_store4(bf16_t* p, int o_lo, float a, float b, float c, float d) {
-  bf16_t hi[4], lo[4];
-  split_bf16(a, hi[0], lo[0]);
-  split_bf16(b, hi[1], lo[1]);
-  split_bf16(c, hi[2], lo[2]);
-  split_bf16(d, hi[3], lo[3]);
-  uint2 pk;
-  pk.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16);
-  pk.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-  if (COH) st8_coh(p, pk); else *(uint2*)p = pk;
-  if (o_lo) {
-    pk.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16);
-    pk.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-    if (COH) st8_coh(p + o_lo, pk); else *(uint2*)(p + o_lo) = pk;
+  uint2 first, second;
+  act_pack4(o_lo, a, b, c, d, first, second);
+  if (COH) st8_coh(p, first); else *(uint2*)p = first;
+  if (o_lo > 0) {
+    if (COH) st8_coh(p + o_lo, second); else *(uint2*)(p + o_lo) = second;
   }
 }
 

@@ -30,8 +30,13 @@ __device__ __forceinline__ int packed_row(int nt, int f, int rope_pairs, int D) 
   return head * D + (f < 8 ? 8 * j + f : D / 2 + 8 * j + (f - 8));
 }
 
+// to_f16: the packed copy holds IEEE half values (the caller's bf16 weights converted; see LO_F16).
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
+  return (uint32_t)f32_to_f16_bits(bf16_to_f32((bf16_t)(v & 0xffffu))) | ((uint32_t)f32_to_f16_bits(bf16_to_f32((bf16_t)(v >> 16))) << 16);
+}
+
 __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16_t* __restrict__ W, int N, int K, int NT, int KT,
-                                                          int rope_pairs, int D, uint4* __restrict__ out) {
+                                                          int rope_pairs, int D, uint4* __restrict__ out, int to_f16) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)NT * KT * 64) return;
   const int lane = (int)(idx & 63);
@@ -40,16 +45,17 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16_t* __restri
   const int row = packed_row(nt, lane & 15, rope_pairs, D);
   uint4 v = make_uint4(0, 0, 0, 0);
   if (row < N) v = *(const uint4*)(W + (size_t)row * K + kt * 32 + (lane >> 4) * 8);
+  if (to_f16) v = make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));
   out[idx] = v;
 }
 
 size_t packed_weight_bytes(int N, int K) { return (size_t)((N + 15) / 16) * (K / 32) * 1024; }
 
-void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out) {
+void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out, int to_f16) {
   const int NT = (N + 15) / 16, KT = K / 32;
   const size_t total = (size_t)NT * KT * 64;
   S2D2_LAUNCH(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)W, N,
-                     K, NT, KT, rope_pairs, D, (uint4*)out);
+                     K, NT, KT, rope_pairs, D, (uint4*)out, to_f16);
 }
 
 // cos / sin of pos * theta^(-2i/D) for every window row (fp64 phase), [rows, D/2] float2
@@ -105,12 +111,13 @@ __device__ unsigned long long g_stream_ts[4][16];   // [epilogue kind][first wor
 // shares, waits for those words with a bounded spin, adds them (own + partner: a fixed order), clears them for
 // the next launch and runs the epilogue.  Every wait ends: the producers never wait and are resident before
 // their consumers; a spin that runs out sets *pair_status and continues with what it has.
-template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT, bool PAIR = false>
+template <int EPI, int PRO, int NW, int TPW, int U, int OPM, bool PAIR = false>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamArgs a) {
   static_assert(!PAIR || (EPI == SEPI_ADD_F32 && TPW == 1), "the paired K split exists for the residual-add epilogue only");
   static_assert(NW >= 4, "the epilogue maps 256 threads onto the 16 x 16 tile (row = thread / 16, feature = thread % 16)");
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
   constexpr int TA = TPW * NACC;
+  constexpr bool SPLIT = OPM == OPM_BF16X2;   // the activations come as two bf16 planes
   extern __shared__ __align__(16) uint8_t smem_raw[];
 #ifdef S2D2_KERNEL_TIMING
   unsigned long long ts_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -217,11 +224,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
   auto mac = [&](int u) {
 #pragma unroll
     for (int t = 0; t < TA; ++t) {
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
-                                                       __builtin_bit_cast(bf16x8_t, xb[u]), acc[t], 0, 0, 0);
+      acc[t] = mfma_16x16x32<OPM>(w[t][u], xb[u], acc[t]);
       if (SPLIT)  // low-order plane of the activations: same weights, second product
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[t][u]),
-                                                         __builtin_bit_cast(bf16x8_t, xl[u]), acc[t], 0, 0, 0);
+        acc[t] = mfma_16x16x32<OPM>(w[t][u], xl[u], acc[t]);
     }
   };
   for (int kt0 = kt_begin; kt0 < kt_end; kt0 += U) {
@@ -306,12 +311,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
           float* hp = (float*)a.out + (size_t)m * a.ldo + n;
           hv = *hp + total;
           *hp = hv;
-          if (a.xg_out) {
-            bf16_t hi, lo;
-            split_bf16(hv * a.gain_next[n], hi, lo);
-            a.xg_out[(size_t)m * a.xg_ld + n] = hi;
-            if (a.xg_lo) a.xg_out[(size_t)m * a.xg_ld + a.xg_lo + n] = lo;
-          }
+          if (a.xg_out) act_store1(a.xg_out + (size_t)m * a.xg_ld + n, a.xg_lo, hv * a.gain_next[n]);
         }
         if (a.ss_out) {
           float sq = hv * hv;
@@ -324,12 +324,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
       } else if (EPI == SEPI_SWIGLU) {
         const int n = nt * 16 + fe;
         const float gate = S2D2_TOTAL(2 * t, fe), up = S2D2_TOTAL(2 * t + 1, fe);
-        if (live && n < a.N) {
-          bf16_t hi, lo;
-          split_bf16(gate / (1.0f + __expf(-gate)) * up, hi, lo);
-          ((bf16_t*)a.out)[(size_t)m * a.ldo + n] = hi;
-          if (a.out_lo) ((bf16_t*)a.out)[(size_t)m * a.ldo + a.out_lo + n] = lo;
-        }
+        if (live && n < a.N) act_store1((bf16_t*)a.out + (size_t)m * a.ldo + n, a.out_lo, gate / (1.0f + __expf(-gate)) * up);
       } else if (live && fe < 8) {  // SEPI_QKV_ROPE: lanes fe < 8 own the pair (i, i + D/2) of one head
         const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
         const int head = nt / tiles_per_head, i = 8 * (nt % tiles_per_head) + fe;
@@ -382,20 +377,20 @@ void launch_stream_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(stream_ts_co
 void launch_stream_ts_copy(hipStream_t, void*) {}
 #endif
 
-template <int EPI, int PRO, int NW, int TPW, int U, bool SPLIT>
+template <int EPI, int PRO, int NW, int TPW, int U, int OPM>
 static void launch_cfg(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   constexpr int TA = TPW * (EPI == SEPI_SWIGLU ? 2 : 1);
   const size_t lds = 16 * sizeof(float) + (size_t)NW * TA * 256 * sizeof(float);
   dim3 grid((a.NT + TPW - 1) / TPW, (m_cap + 15) / 16), block(NW * 64);
-  S2D2_LAUNCH((gemm_stream_kernel<EPI, PRO, NW, TPW, U, SPLIT>), grid, block, lds, st, a);
+  S2D2_LAUNCH((gemm_stream_kernel<EPI, PRO, NW, TPW, U, OPM>), grid, block, lds, st, a);
 }
 
 // residual-add GEMM with K shared by pairs of workgroups (see the kernel's comment): 2 NT workgroups of NW wavefronts
-template <int NW, int U, bool SPLIT>
+template <int NW, int U, int OPM>
 static void launch_pair(hipStream_t st, const GemmStreamArgs& a, int m_cap) {
   const size_t lds = 16 * sizeof(float) + (size_t)NW * 256 * sizeof(float);
   dim3 grid(2 * a.NT, (m_cap + 15) / 16), block(NW * 64);
-  S2D2_LAUNCH((gemm_stream_kernel<SEPI_ADD_F32, SPRO_BF16, NW, 1, U, SPLIT, true>), grid, block, lds, st, a);
+  S2D2_LAUNCH((gemm_stream_kernel<SEPI_ADD_F32, SPRO_BF16, NW, 1, U, OPM, true>), grid, block, lds, st, a);
 }
 
 // Launch shapes (wavefronts per workgroup, feature tiles per workgroup, loads in flight per wavefront), tuned on the
@@ -413,11 +408,12 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
     launch_gemm_tile(st, kind, kind == SEPI_ADD_F32 ? SPRO_BF16 : SPRO_BF16S, a, (m_cap + 127) / 128);
     return;
   }
-  const bool sp = a.x_lo != 0;
-#define S2D2_CFG(EPI, PRO, NW, TPW, U)                                         \
-  do {                                                                         \
-    if (sp) launch_cfg<EPI, PRO, NW, TPW, U, true>(st, a, m_cap);              \
-    else launch_cfg<EPI, PRO, NW, TPW, U, false>(st, a, m_cap);                \
+  const int opm = operand_mode(a.x_lo);
+#define S2D2_CFG(EPI, PRO, NW, TPW, U)                                                     \
+  do {                                                                                     \
+    if (opm == OPM_F16) launch_cfg<EPI, PRO, NW, TPW, U, OPM_F16>(st, a, m_cap);           \
+    else if (opm == OPM_BF16X2) launch_cfg<EPI, PRO, NW, TPW, U, OPM_BF16X2>(st, a, m_cap); \
+    else launch_cfg<EPI, PRO, NW, TPW, U, OPM_BF16>(st, a, m_cap);                         \
   } while (0)
   switch (kind) {
     case SEPI_QKV_ROPE:   // 8 wavefronts x 4 loads in flight (1.8 % over 4 x 8 once the weight loads were non-temporal)
@@ -427,8 +423,9 @@ void launch_gemm_stream(hipStream_t st, int kind, const GemmStreamArgs& a, int m
     case SEPI_ADD_F32:
       // long K and few feature tiles (the down projection): pairs of workgroups share K, one workgroup per CU
       if (a.KT >= 128 && a.pair_buf && (long long)a.NT * ((m_cap + 15) / 16) <= a.pair_cap) {
-        if (sp) launch_pair<8, 4, true>(st, a, m_cap);
-        else launch_pair<8, 4, false>(st, a, m_cap);   // (16 wavefronts, or 3 to 12 loads in flight: within 1 %)
+        if (opm == OPM_F16) launch_pair<8, 4, OPM_F16>(st, a, m_cap);   // (16 wavefronts, or 3 to 12 loads in flight: within 1 %)
+        else if (opm == OPM_BF16X2) launch_pair<8, 4, OPM_BF16X2>(st, a, m_cap);
+        else launch_pair<8, 4, OPM_BF16>(st, a, m_cap);
       } else if (a.KT >= 128) {
         S2D2_CFG(SEPI_ADD_F32, SPRO_BF16, 16, 1, 4);
       } else {   // short K (the output projection): 0.25 % of the 1.7B step over 16 x 4
@@ -470,10 +467,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const bf16_t* __restric
   for (int i = threadIdx.x; i < d; i += 256) {
     const float v = bf16_to_f32(src[i]);
     h[(size_t)r * d + i] = v;
-    bf16_t hi, lo;
-    split_bf16(v * gain[i], hi, lo);
-    xg[(size_t)r * xg_ld + i] = hi;
-    if (xg_lo) xg[(size_t)r * xg_ld + xg_lo + i] = lo;
+    act_store1(xg + (size_t)r * xg_ld + i, xg_lo, v * gain[i]);
     acc += v * v;
   }
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);

@@ -44,8 +44,9 @@ __device__ unsigned long long g_tile_ts[64];
 
 // SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
 // of a row sit side by side in LDS and every weight operand is multiplied with both.
-template <int EPI, int PRO, bool SPLIT, int WC>
+template <int EPI, int PRO, int OPM, int WC>
 __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
+  constexpr bool SPLIT = OPM == OPM_BF16X2;       // the activations come as two bf16 planes
   constexpr int NTH = 128 * WC;                   // 2 x WC wavefronts of 64 rows x 64 features each
   constexpr int XI = 1024 / NTH;                  // 16-byte chunks of an activation plane tile per thread
   constexpr int XD = WC == 4 ? 2 : 1;             // K steps the activation loads run ahead of their LDS store
@@ -210,14 +211,12 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
           const u32x4_t b = *(const u32x4_t*)(xb + rb * 16 * XROW + k2 * 64);
 #pragma unroll
           for (int t = 0; t < 4; ++t)
-            acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wst[st_][k2][t]),
-                                                                 __builtin_bit_cast(bf16x8_t, b), acc[rb][t], 0, 0, 0);
+            acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], b, acc[rb][t]);
           if (SPLIT) {
             const u32x4_t bl = *(const u32x4_t*)(xb + rb * 16 * XROW + 128 + k2 * 64);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-              acc[rb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wst[st_][k2][t]),
-                                                                   __builtin_bit_cast(bf16x8_t, bl), acc[rb][t], 0, 0, 0);
+              acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], bl, acc[rb][t]);
           }
         }
         load_w1(wst[rs_][k2][rb], kb + WS - 1, k2, rb);
@@ -273,20 +272,29 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
     for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
       for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    for (int zz = 0; zz < KS; ++zz) {
-      const uint64_t* src = (const uint64_t*)a.tile_partials + (tile_id * KS + zz) * (32 * NTH) + tid;
+    // The partials of all splits (at most 8) of a 16-row block are requested together and then added in split
+    // order: one memory round trip per block.  (One split at a time was a chain of 4 KS dependent round trips of
+    // device-coherent loads, 30-40 us of a 55 us launch for the projections with long K and few output tiles.)
+    const uint64_t* src0 = (const uint64_t*)a.tile_partials + (tile_id * KS) * (32 * NTH) + tid;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        if (wr * 64 + rb * 16 >= Mloc) continue;
-        uint64_t v[8];
+    for (int rb = 0; rb < 4; ++rb) {
+      if (wr * 64 + rb * 16 >= Mloc) continue;
+      uint64_t v[8][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = __hip_atomic_load(src + (rb * 8 + e) * NTH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int zz = 0; zz < 8; ++zz) {
+        if (zz >= KS) break;   // uniform
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[zz][e] = __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + (rb * 8 + e) * NTH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int zz = 0; zz < 8; ++zz) {
+        if (zz >= KS) break;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          acc[rb][t][0] += __uint_as_float((uint32_t)v[2 * t]);
-          acc[rb][t][1] += __uint_as_float((uint32_t)(v[2 * t] >> 32));
-          acc[rb][t][2] += __uint_as_float((uint32_t)v[2 * t + 1]);
-          acc[rb][t][3] += __uint_as_float((uint32_t)(v[2 * t + 1] >> 32));
+          acc[rb][t][0] += __uint_as_float((uint32_t)v[zz][2 * t]);
+          acc[rb][t][1] += __uint_as_float((uint32_t)(v[zz][2 * t] >> 32));
+          acc[rb][t][2] += __uint_as_float((uint32_t)v[zz][2 * t + 1]);
+          acc[rb][t][3] += __uint_as_float((uint32_t)(v[zz][2 * t + 1] >> 32));
         }
       }
     }
@@ -327,13 +335,7 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
           *hp = make_float4(hv[0], hv[1], hv[2], hv[3]);
           if (a.xg_out) {
             const float4 gn = *(const float4*)(a.gain_next + n);
-            const float xv[4] = {hv[0] * gn.x, hv[1] * gn.y, hv[2] * gn.z, hv[3] * gn.w};
-            bf16_t hi[4], lo[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) split_bf16(xv[i], hi[i], lo[i]);
-            bf16_t* xp = a.xg_out + (size_t)orow * a.xg_ld + n;
-            *(uint2*)xp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-            if (a.xg_lo) *(uint2*)(xp + a.xg_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+            act_store4(a.xg_out + (size_t)orow * a.xg_ld + n, a.xg_lo, hv[0] * gn.x, hv[1] * gn.y, hv[2] * gn.z, hv[3] * gn.w);
           }
         }
         if (a.ss_out) {
@@ -344,15 +346,13 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
         }
       } else if (EPI == SEPI_SWIGLU) {
         if (live) {
-          bf16_t* op = (bf16_t*)a.out + (size_t)orow * a.ldo + n;
-          bf16_t hi[4], lo[4];
+          float sv[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gate = acc[rb][NACC == 2 ? 2 * t : 0][i] * rs, up = acc[rb][NACC == 2 ? 2 * t + 1 : 0][i] * rs;
-            split_bf16(gate / (1.0f + __expf(-gate)) * up, hi[i], lo[i]);
+            sv[i] = gate / (1.0f + __expf(-gate)) * up;
           }
-          *(uint2*)op = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-          if (a.out_lo) *(uint2*)(op + a.out_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+          act_store4((bf16_t*)a.out + (size_t)orow * a.ldo + n, a.out_lo, sv[0], sv[1], sv[2], sv[3]);
         }
       } else {  // SEPI_QKV_ROPE: features 0-7 of a tile pair with features 8-15 (lanes 32 apart)
         const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
@@ -440,8 +440,10 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
     }
   }
   dim3 grid(col_tiles, row_tiles, KS), block(128 * WC);
-  if (a.x_lo) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, true, WC>), grid, block, 0, st, a);
-  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, false, WC>), grid, block, 0, st, a);
+  const int opm = operand_mode(a.x_lo);
+  if (opm == OPM_F16) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_F16, WC>), grid, block, 0, st, a);
+  else if (opm == OPM_BF16X2) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>), grid, block, 0, st, a);
+  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16, WC>), grid, block, 0, st, a);
 }
 
 template <int EPI, int PRO>

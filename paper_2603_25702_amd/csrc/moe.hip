@@ -120,18 +120,7 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const float* __restric
     *(float4*)(h + (size_t)row * d + c) = acc;
     const float4 gn = *(const float4*)(gain_next + c);
     const float xv[4] = {acc.x * gn.x, acc.y * gn.y, acc.z * gn.z, acc.w * gn.w};
-    bf16_t hi[4], lo[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) split_bf16(xv[i], hi[i], lo[i]);
-    uint2 pk;
-    pk.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16);
-    pk.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-    *(uint2*)(xg + (size_t)row * xg_ld + c) = pk;
-    if (xg_lo) {
-      pk.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16);
-      pk.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-      *(uint2*)(xg + (size_t)row * xg_ld + xg_lo + c) = pk;
-    }
+    act_store4(xg + (size_t)row * xg_ld + c, xg_lo, xv[0], xv[1], xv[2], xv[3]);
     float sq = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
     sq += __shfl_xor(sq, 1, 64);
     sq += __shfl_xor(sq, 2, 64);

@@ -24,6 +24,7 @@ extern thread_local hipEvent_t g_prof_start, g_prof_stop;
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -47,6 +48,57 @@ __device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
   hi = f32_to_bf16(v);
   lo = f32_to_bf16(v - bf16_to_f32(hi));
 }
+// ---- how an activation row that feeds a GEMM is stored -------------------------------------------------------
+// Every such row comes with a "low-plane offset" next to its pointer:
+//   0        one plane of bf16 values                                   (8 significant bits)
+//   > 0      two planes, [hi | lo] that many elements apart: v ~= hi + lo (16 significant bits; every weight
+//            operand is multiplied with both: twice the matrix instructions)
+//   LO_F16   one plane of IEEE half values (11 significant bits); the GEMMs then run the f16 MFMA against weights
+//            whose packed copy was converted from bf16 to half (exact for |w| >= 2^-17; below that the absolute
+//            error is at most 2^-25), at the same matrix rate as bf16 and half the instructions of two planes.
+constexpr int LO_F16 = -1;
+enum OperandMode { OPM_BF16 = 0, OPM_BF16X2 = 1, OPM_F16 = 2 };
+__host__ __device__ inline int operand_mode(int lo) { return lo == LO_F16 ? OPM_F16 : (lo > 0 ? OPM_BF16X2 : OPM_BF16); }
+__device__ __forceinline__ bf16_t f32_to_f16_bits(float f) {   // round to nearest even, as 16 raw bits
+  const _Float16 h = (_Float16)f;
+  return __builtin_bit_cast(bf16_t, h);
+}
+// Stores one value / four consecutive values of such a row at p (the lo plane, if there is one, at p + lo).
+__device__ __forceinline__ void act_store1(bf16_t* p, int lo, float v) {
+  if (lo == LO_F16) { *p = f32_to_f16_bits(v); return; }
+  bf16_t hi, l;
+  split_bf16(v, hi, l);
+  *p = hi;
+  if (lo > 0) p[lo] = l;
+}
+__device__ __forceinline__ void act_pack4(int lo, float a, float b, float c, float d, uint2& first, uint2& second) {
+  if (lo == LO_F16) {
+    first = make_uint2((uint32_t)f32_to_f16_bits(a) | ((uint32_t)f32_to_f16_bits(b) << 16),
+                       (uint32_t)f32_to_f16_bits(c) | ((uint32_t)f32_to_f16_bits(d) << 16));
+    second = first;
+    return;
+  }
+  bf16_t hi[4], l[4];
+  split_bf16(a, hi[0], l[0]);
+  split_bf16(b, hi[1], l[1]);
+  split_bf16(c, hi[2], l[2]);
+  split_bf16(d, hi[3], l[3]);
+  first = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  second = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+}
+__device__ __forceinline__ void act_store4(bf16_t* p, int lo, float a, float b, float c, float d) {
+  uint2 f, s2;
+  act_pack4(lo, a, b, c, d, f, s2);
+  *(uint2*)p = f;
+  if (lo > 0) *(uint2*)(p + lo) = s2;
+}
+// One MFMA 16x16x32 on 16-byte operand fragments in either operand type.
+template <int OPM>
+__device__ __forceinline__ f32x4_t mfma_16x16x32(const u32x4_t& a, const u32x4_t& b, const f32x4_t& c) {
+  if (OPM == OPM_F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
 // Device-coherent accesses (agent scope, relaxed: write-through stores, loads that bypass the non-coherent
 // caches) for data that workgroups of one launch hand to each other.  The producer waits for its stores
 // (s_waitcnt) before it signals; no cache-wide fence is involved.
@@ -149,17 +201,17 @@ struct GemmStreamArgs {
   int32_t m_hint;           // host: rows the caller expects (0 = unknown); only steers the choice of launch shape
   const bf16_t* X;          // activations [*, ldx] (for SPRO_BF16S: h * gain, not yet divided by the rms)
   int32_t ldx;
-  int32_t x_lo;             // element offset, inside a row of X, of the low-order bf16 plane (0: single plane)
+  int32_t x_lo;             // low-plane offset of X's rows (0: one bf16 plane, > 0: two planes, LO_F16: half values)
   const int32_t* gather;    // optional row indices into X / ss_part
   const float* ss_part;     // SPRO_BF16S: [*, ss_stride] partial sums of squares of the residual rows
   int32_t ss_stride, ss_count;
   float eps;
   void* out;
   int32_t ldo;
-  int32_t out_lo;           // SEPI_SWIGLU: element offset of the low-order plane inside an output row (0: none)
+  int32_t out_lo;           // SEPI_SWIGLU: low-plane offset of the output rows (as x_lo)
   // SEPI_ADD_F32 extras (all optional): operand of the next norm and its partial sums of squares
   bf16_t* xg_out;           // [*, xg_ld]
-  int32_t xg_ld, xg_lo;     // row stride and low-order plane offset of xg_out
+  int32_t xg_ld, xg_lo;     // row stride and low-plane offset (as x_lo) of xg_out
   const float* gain_next;   // [N]
   float* ss_out;            // [*, ss_stride], entry nt of a row = this tile's share
   // SEPI_QKV_ROPE
@@ -194,7 +246,7 @@ struct GemmStreamArgs {
   int32_t pair_cap;
 };
 size_t packed_weight_bytes(int N, int K);
-void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out);
+void launch_pack_weight(hipStream_t st, const void* W, int N, int K, int rope_pairs, int D, void* out, int to_f16 /* convert bf16 -> half */);
 void launch_rope_table(hipStream_t st, const Plan& p, int rows_cap, int D, float theta, void* cs);
 void launch_embed_norm(hipStream_t st, const void* embed, int d, const Plan& p, int rows_cap, const float* gain,
                        float* h, void* xg, int xg_ld, int xg_lo, float* ss, int ss_stride,
@@ -217,7 +269,7 @@ void launch_moe_copy_choices(hipStream_t st, const int32_t* src, int32_t* dst, i
 // attention.hip
 void launch_attention_generic(hipStream_t st, int dtype, const void* q, const void* k_win, const void* v_win,
                               const void* k_pages_layer, const void* v_pages_layer, const KvGeom& g,
-                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes);
+                              const Plan& p, int rows_cap, int Hq, void* o, size_t lds_bytes, int o_f16 /* bf16 models: write o as half values */);
 int attention_init();
 size_t attention_flash_partial_floats(size_t entries);
 void launch_attention_flash(hipStream_t st, const void* q, int q_ld, int q_lo, const void* k_win, const void* vT_win,

@@ -18,10 +18,11 @@ PREFILL_BLOCK = 64  # window used to push prompt tokens through the causal rows 
 
 class Session:
     def __init__(self, cfg, weights: Dict[str, torch.Tensor], N: int, B: int, max_seq: int, page_size: int = 16,
-                 device: str = "cuda:0", page_table: Optional[np.ndarray] = None, max_block: Optional[int] = None):
+                 device: str = "cuda:0", page_table: Optional[np.ndarray] = None, max_block: Optional[int] = None,
+                 act_planes: int = 0):
         self.cfg, self.N, self.B = cfg, N, B
         self.dev = torch.device(device)
-        self.eng = Engine(cfg, weights, N, max_block or max(B, PREFILL_BLOCK), device)
+        self.eng = Engine(cfg, weights, N, max_block or max(B, PREFILL_BLOCK), device, act_planes=act_planes)
         i32 = torch.int32
         max_pages = (max_seq + page_size - 1) // page_size
         if page_table is None:

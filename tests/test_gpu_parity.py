@@ -264,17 +264,30 @@ def test_long_k_down_projection_shared_by_pairs_of_workgroups():
     run.eng.s2d2_status()
 
 
-def test_single_activation_plane_narrow_and_wide_windows():
-    """`act_planes = 1` in the model description: activations as one bf16 plane (the single-plane instantiations of
-    the streaming and tiled GEMMs and of both attention kernels).  Two layers keep the rounding well inside the
-    tolerance; the 28- and 36-layer configurations need both planes."""
+@pytest.mark.parametrize("act_planes", [1, 2, 3])
+def test_operand_modes_narrow_wide_long_k_and_moe(act_planes):
+    """`act_planes` of the model description: GEMM inputs as one bf16 plane (1), as a high + low bf16 plane (2), or as
+    IEEE half values against a half copy of the weights (3, which the default 0 also selects and every other test
+    runs).  Each mode through the streaming GEMM (narrow windows, also the paired K split of a long down projection),
+    the tiled GEMM (wide windows), both attention kernels and the MoE FFN.  Two layers keep even the single bf16
+    plane inside the tolerance; the 28- and 36-layer configurations need 11 bits or more."""
     case = H.make_case(SMALL_BF16, 3, 4, [100, 257, 31], seed=21, synthetic_kv=True, page_size=16, room=64)
-    run, rep = run_steps(case, 2, act_planes=1)
-    print("one plane, narrow:", rep)
+    run, rep = run_steps(case, 2, act_planes=act_planes)
+    print("planes", act_planes, "narrow:", rep)
     case = H.make_case(SMALL_BF16, 3, 16, [100, 257, 31], seed=22, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
-    run, rep2 = run_steps(case, 2, act_planes=1)
-    print("one plane, wide:", rep2)
-    assert max(rep.max_logit_err_draft, rep2.max_logit_err_draft) <= H.LOGIT_RTOL
+    run, rep2 = run_steps(case, 2, act_planes=act_planes)
+    print("planes", act_planes, "wide:", rep2)
+    cfg = I.ModelCfg("small-long-k", 2, 512, 8, 4, 128, 4096, 32000)
+    case = H.make_case(cfg, 1, 8, [70], seed=8, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep3 = run_steps(case, 2, act_planes=act_planes)
+    run.eng.s2d2_status()
+    case = H.make_case(SMALL_MOE, 2, 8, [40, 90], seed=12, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep4 = run_steps(case, 2, act_planes=act_planes)
+    print("planes", act_planes, "long K:", rep3.max_logit_err_draft, "moe:", rep4.max_logit_err_draft)
+    errs = [r.max_logit_err_draft for r in (rep, rep2, rep3, rep4)] + [r.max_logit_err_verify for r in (rep, rep2, rep3, rep4)]
+    assert max(errs) <= H.LOGIT_RTOL
+    if act_planes != 1:
+        assert max(errs) <= 0.5 * H.LOGIT_RTOL
 
 
 def test_small_moe_routing_grouped_gemm_and_combine():
