@@ -51,6 +51,7 @@ struct s2d2_ctx {
   void* kwin;
   void* vwin;
   void* vT_win;      // [max_batch, Hkv, D, wpad] key-minor V of the window (MFMA attention)
+  void* kwin16;      // [rows_cap, Hkv, D] the window's keys as half values (wide attention kernel in the half mode)
   float* attn_part;  // split-key partial outputs
   size_t attn_part_entries;
   int32_t* attn_counters;  // arrival counters of the split-key merge, zero between launches
@@ -181,6 +182,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   c->wpad = (3 * c->max_block + 31) / 32 * 32;
   c->attn_zmax = 64;
   c->vT_win = cv.take<uint8_t>(NB * (size_t)d.n_kv_heads * d.head_dim * c->wpad * es);
+  c->kwin16 = cv.take<uint8_t>(d.dtype == S2D2_BF16 ? R * (size_t)d.n_kv_heads * d.head_dim * 2 : 0);
   {
     const int q_tiles = (3 * c->max_block * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
     // Z * items * q_tiles < 512 * 8 + items * q_tiles by the choice of Z in forward()
@@ -330,8 +332,11 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   const int ld_e = P * d.d_expert, lo_e = lo_of(d.d_expert);
   // queries stay bf16 (the attention kernels multiply them with the cache's bf16 keys): hi + lo planes unless the
   // model asked for single bf16 planes
-  const int PQ = fused && flash && opm != OPM_BF16 ? 2 : 1;
-  const int ld_q = PQ * HqD, lo_q = PQ == 2 ? HqD : 0;
+  // model asked for single bf16 planes; the kernel for wide windows takes them as half values in the half mode
+  // (it converts the keys and values on their way into LDS)
+  const bool q_f16 = fused && wide && opm == OPM_F16;
+  const int PQ = fused && flash && opm != OPM_BF16 && !q_f16 ? 2 : 1;
+  const int ld_q = PQ * HqD, lo_q = q_f16 ? LO_F16 : (PQ == 2 ? HqD : 0);
   if (fused) { ProfScope ps(c, 3, 0.0); launch_embed_norm(st, c->w.embed, d.d_model, c->plan, R, c->layers[0].norm1, c->h, c->a, ld_a, lo_a, c->ss, ss_stride, c->rope_cs, d.head_dim, d.rope_theta); }
   else { ProfScope ps(c, 3, 0.0); launch_embed(st, dt, c->w.embed, d.d_model, c->plan, R, c->h); }
   for (int l = 0; l < d.n_layers; ++l) {
@@ -346,6 +351,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
       a.rope_cs = c->rope_cs; a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.D = d.head_dim; a.wpad = c->wpad;
       a.q_out = (bf16_t*)c->qbuf; a.q_ld = ld_q; a.q_lo = lo_q; a.k_out = (bf16_t*)kw; a.v_out = (bf16_t*)vw; a.vT_out = flash ? (bf16_t*)c->vT_win : nullptr;
       a.row_seq = c->plan.row_seq; a.seq_row0 = c->plan.seq_row0;
+      if (q_f16) { a.k16_out = (bf16_t*)c->kwin16; a.win_f16 = 1; }
       ProfScope ps(c, 0, (double)qkv_n * d.d_model * es, fr * qkv_n * d.d_model, 4);
       sk(a); launch_gemm_stream(st, SEPI_QKV_ROPE, a, R);
     } else {
@@ -358,7 +364,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
     if (flash) {
       ProfScope ps(c, 1, 0.0);
       if (wide)
-        launch_attention_wide(st, c->qbuf, fused ? ld_q : HqD, fused ? lo_q : 0, kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
+        launch_attention_wide(st, c->qbuf, fused ? ld_q : HqD, fused ? lo_q : 0, q_f16 ? c->kwin16 : kw, c->vT_win, kp, vp, g, c->plan, N, d.n_q_heads, q_tiles, Z, c->wpad, c->obuf, ld_o, lo_o, c->attn_part, c->attn_part_entries, c->attn_counters);
       else
       {
         // Narrow windows of a few sequences: the launch is a chain of dependent round trips on a fraction of the

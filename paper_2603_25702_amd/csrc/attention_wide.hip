@@ -38,13 +38,28 @@ __device__ __forceinline__ uint4 fw_mask(uint4 v, int nv) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-template <int NW, bool SPLIT>
+// 8 bf16 values (one 16-byte operand piece) as IEEE half: exact for magnitudes in the half range (the 8-bit
+// significand fits), values below 2^-14 land on half subnormals (absolute error below 2^-24).
+__device__ __forceinline__ uint32_t fw_bf16x2_to_f16x2(uint32_t w) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u)));
+}
+__device__ __forceinline__ uint4 fw_to_f16(uint4 v) {
+  return make_uint4(fw_bf16x2_to_f16x2(v.x), fw_bf16x2_to_f16x2(v.y), fw_bf16x2_to_f16x2(v.z), fw_bf16x2_to_f16x2(v.w));
+}
+
+// QM: how the queries come and the arithmetic type of both products.  OPM_BF16 / OPM_BF16X2: bf16 MFMA on the
+// cache's bf16 keys and values, queries and softmax weights as one or as a high + low bf16 plane.  OPM_F16: queries
+// as IEEE half, keys and values converted to half on their way into LDS (by the fetching wavefronts), softmax
+// weights as half: one 11-bit plane on the f16 MFMA, half the matrix instructions of the two-plane form and no
+// high / low split of the weights.
+template <int NW, int QM>
 __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     const bf16_t* __restrict__ q, int q_ld, int q_lo, const bf16_t* __restrict__ k_win, const bf16_t* __restrict__ vT_win,
     const bf16_t* __restrict__ k_pages, const bf16_t* __restrict__ v_pages, KvGeom g, Plan p, int Hq, int Z,
     int wpad, float scale_log2e, bf16_t* __restrict__ o, int o_ld, int o_lo, float* __restrict__ part_o,
     float* __restrict__ part_ml, int32_t* __restrict__ counters, int q_tiles, int per, int pt_cap, int ps_shift) {
   constexpr int D = FA_D, T = NW * 64, U = 512 / T;
+  constexpr bool SPLIT = QM == OPM_BF16X2, F16 = QM == OPM_F16;
   static_assert(U == 1 || U == 2 || U == 4, "8, 4 or 2 wavefronts");
   extern __shared__ __align__(16) unsigned char lds[];
   int32_t* s_pt = (int32_t*)(lds + FW_RING * FW_BUF);
@@ -131,8 +146,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     const FwTile t = tile_of(i);
     unsigned char* base = lds + b * FW_BUF;
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
-    *(uint4*)(base + kk * FW_KROW + kch * 16) = kr;
-    *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = fw_mask(vr, t.limit - (t.kbase + vko));
+    // half mode: cached tiles are bf16 and are converted here; the window's own rows already come as half values
+    // (k_win / vT_win then point at the half copies the QKV projection wrote: 11 bits instead of the cache's 8)
+    const uint4 vm = fw_mask(vr, t.limit - (t.kbase + vko));
+    const bool cvt = F16 && !t.win;
+    *(uint4*)(base + kk * FW_KROW + kch * 16) = cvt ? fw_to_f16(kr) : kr;
+    *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = cvt ? fw_to_f16(vm) : vm;
   };
   auto stash1 = [=](int u, int i, int b, uint4 kr, uint4 vr) { stashp(min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
   const int kperm = fa_perm(c);
@@ -145,9 +164,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     for (int j = 0; j < 16; ++j) sacc[j] = 0.f;
 #pragma unroll
     for (int ds = 0; ds < 8; ++ds) {
-      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(kb + ds * 32));
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
-      if (SPLIT) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, ql[ds]), sacc, 0, 0, 0);
+      const uint4 kraw = *(const uint4*)(kb + ds * 32);
+      if (F16) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, kraw), __builtin_bit_cast(f16x8_t, qf[ds]), sacc, 0, 0, 0);
+      } else {
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, kraw);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, qf[ds]), sacc, 0, 0, 0);
+        if (SPLIT) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8_t, ql[ds]), sacc, 0, 0, 0);
+      }
     }
     // sacc[j]: key kbase + 16 (j / 8) + 8 h + (j % 8), query row c.  Scores stay unscaled until the exponent:
     // the running maximum is kept in scaled units, exp2(s * scale - m) is one fused multiply-add per element.
@@ -173,13 +197,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
     float ls = 0.f;
     bf16x8_t pb[2], pl[SPLIT ? 2 : 1];
+    f16x8_t ph16[2];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j], scale_log2e, -m_ref));
       ls += pv;
-      const __bf16 ph = (__bf16)pv;
-      pb[j >> 3][j & 7] = ph;
-      if (SPLIT) pl[j >> 3][j & 7] = (__bf16)(pv - (float)ph);
+      if (F16) {
+        ph16[j >> 3][j & 7] = (_Float16)pv;
+      } else {
+        const __bf16 ph = (__bf16)pv;
+        pb[j >> 3][j & 7] = ph;
+        if (SPLIT) pl[j >> 3][j & 7] = (__bf16)(pv - (float)ph);
+      }
     }
     ls += __shfl_xor(ls, 32, 64);
     st.l = st.l * alpha + ls;
@@ -195,9 +224,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(vb + dt * 32 * FW_VROW + j * 32));
-        st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[j], st.o[dt], 0, 0, 0);
-        if (SPLIT) st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[j], st.o[dt], 0, 0, 0);
+        const uint4 vraw = *(const uint4*)(vb + dt * 32 * FW_VROW + j * 32);
+        if (F16) {
+          st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, vraw), ph16[j], st.o[dt], 0, 0, 0);
+        } else {
+          const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, vraw);
+          st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[j], st.o[dt], 0, 0, 0);
+          if (SPLIT) st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[j], st.o[dt], 0, 0, 0);
+        }
       }
     }
   };
@@ -345,16 +379,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
 }
 
 template <int NW>
-static void launch_wide(hipStream_t st, bool split, dim3 grid, size_t lds, const bf16_t* q, int q_ld, int q_lo,
+static void launch_wide(hipStream_t st, int qm, dim3 grid, size_t lds, const bf16_t* q, int q_ld, int q_lo,
                         const bf16_t* k_win, const bf16_t* vT_win, const bf16_t* kp, const bf16_t* vp, const KvGeom& g,
                         const Plan& p, int Hq, int Z, int wpad, float scale_log2e, bf16_t* o, int o_ld, int o_lo,
                         float* part_o, float* part_ml, int32_t* counters, int q_tiles, int per, int pt_cap, int ps_shift) {
-  if (split)
-    S2D2_LAUNCH((attn_flash_wide_kernel<NW, true>), grid, dim3(NW * 64), lds, st, q, q_ld, q_lo, k_win, vT_win, kp, vp, g, p,
-                Hq, Z, wpad, scale_log2e, o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift);
-  else
-    S2D2_LAUNCH((attn_flash_wide_kernel<NW, false>), grid, dim3(NW * 64), lds, st, q, q_ld, q_lo, k_win, vT_win, kp, vp, g, p,
-                Hq, Z, wpad, scale_log2e, o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift);
+#define S2D2_WIDE_QM(QMV)                                                                                                    \
+  S2D2_LAUNCH((attn_flash_wide_kernel<NW, QMV>), grid, dim3(NW * 64), lds, st, q, q_ld, q_lo, k_win, vT_win, kp, vp, g, p, \
+              Hq, Z, wpad, scale_log2e, o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift)
+  if (qm == OPM_F16) S2D2_WIDE_QM(OPM_F16);
+  else if (qm == OPM_BF16X2) S2D2_WIDE_QM(OPM_BF16X2);
+  else S2D2_WIDE_QM(OPM_BF16);
+#undef S2D2_WIDE_QM
 }
 
 // Wavefronts per workgroup for q_tiles query tiles: as few query groups as 8-wavefront workgroups allow,
@@ -387,7 +422,7 @@ void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, co
   int ps_shift = 0;
   while ((1 << ps_shift) < g.page_size) ++ps_shift;   // the caller has checked that page_size is a power of two
 #define S2D2_WIDE(NWV)                                                                                                  \
-  launch_wide<NWV>(st, q_lo != 0, grid, lds, (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win, \
+  launch_wide<NWV>(st, operand_mode(q_lo), grid, lds, (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win, \
                    (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,          \
                    (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift)
   if (nw == 2) S2D2_WIDE(2);
@@ -396,14 +431,19 @@ void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, co
 #undef S2D2_WIDE
 }
 
+template <int NW, int QM>
+static hipError_t wide_lds_limit() {
+  return hipFuncSetAttribute((const void*)attn_flash_wide_kernel<NW, QM>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
 int attention_wide_init() {
-  const int lim = 160 * 1024;
-  hipError_t e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_flash_wide_kernel<8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  hipError_t e = hipSuccess;
+#define S2D2_LIM(NWV)                                                          \
+  if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_BF16>();                    \
+  if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_BF16X2>();                  \
+  if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_F16>();
+  S2D2_LIM(2) S2D2_LIM(4) S2D2_LIM(8)
+#undef S2D2_LIM
   return e == hipSuccess ? 0 : -1;
 }
 

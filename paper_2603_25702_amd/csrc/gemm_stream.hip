@@ -334,16 +334,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
           const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
           if (head < a.Hq) {  // queries: both planes when the attention kernel multiplies with both
             bf16_t* dst = a.q_out + (size_t)m * a.q_ld + head * D;
-            bf16_t h1, l1, h2, l2;
-            split_bf16(y1, h1, l1);
-            split_bf16(y2, h2, l2);
-            dst[i] = h1;
-            dst[i + half] = h2;
-            if (a.q_lo) { dst[a.q_lo + i] = l1; dst[a.q_lo + i + half] = l2; }
+            act_store1(dst + i, a.q_lo, y1);
+            act_store1(dst + i + half, a.q_lo, y2);
           } else {
-            bf16_t* dst = a.k_out + ((size_t)m * a.Hkv + (head - a.Hq)) * D;
-            dst[i] = f32_to_bf16(y1);
-            dst[i + half] = f32_to_bf16(y2);
+            const size_t ko = ((size_t)m * a.Hkv + (head - a.Hq)) * D;
+            a.k_out[ko + i] = f32_to_bf16(y1);
+            a.k_out[ko + i + half] = f32_to_bf16(y2);
+            if (a.k16_out) { a.k16_out[ko + i] = f32_to_f16_bits(y1); a.k16_out[ko + i + half] = f32_to_f16_bits(y2); }
           }
         } else {
           const int vh = head - a.Hq - a.Hkv;
@@ -354,8 +351,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const GemmStreamAr
           if (a.vT_out) {  // key-minor copy of the window's V: [seq, Hkv, D, wpad]
             const int n = a.row_seq[m], tw = m - a.seq_row0[n];
             bf16_t* vt = a.vT_out + ((size_t)(n * a.Hkv + vh) * D) * a.wpad + tw;
-            vt[(size_t)i * a.wpad] = b1;
-            vt[(size_t)(i + half) * a.wpad] = b2;
+            vt[(size_t)i * a.wpad] = a.win_f16 ? f32_to_f16_bits(x1) : b1;
+            vt[(size_t)(i + half) * a.wpad] = a.win_f16 ? f32_to_f16_bits(x2) : b2;
           }
         }
       }

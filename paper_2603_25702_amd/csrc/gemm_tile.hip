@@ -371,15 +371,13 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
                                : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
             const float4 c01 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0), c23 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0 + 2);
             const float cs_c[4] = {c01.x, c01.z, c23.x, c23.z}, cs_s[4] = {c01.y, c01.w, c23.y, c23.w};
-            bf16_t hi[4], lo[4];
+            float y[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const float y = second ? own[i] * cs_c[i] + oth[i] * cs_s[i] : own[i] * cs_c[i] - oth[i] * cs_s[i];
-              split_bf16(y, hi[i], lo[i]);
-            }
-            bf16_t* dp = dst + i0 + (second ? half : 0);
-            *(uint2*)dp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-            if (is_q && a.q_lo) *(uint2*)(dp + a.q_lo) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+            for (int i = 0; i < 4; ++i) y[i] = second ? own[i] * cs_c[i] + oth[i] * cs_s[i] : own[i] * cs_c[i] - oth[i] * cs_s[i];
+            // queries in the storage the attention kernel reads (q_lo); keys always as one bf16 plane (the cache's type)
+            act_store4(dst + i0 + (second ? half : 0), is_q ? a.q_lo : 0, y[0], y[1], y[2], y[3]);
+            if (!is_q && a.k16_out)   // the window's keys once more as half values (the attention kernel's copy)
+              act_store4(a.k16_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D + i0 + (second ? half : 0), LO_F16, y[0], y[1], y[2], y[3]);
           } else {
             const int vh = head - a.Hq - a.Hkv;
             bf16_t* dst = a.v_out + ((size_t)orow * a.Hkv + vh) * D + (second ? half : 0);
@@ -391,7 +389,7 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
             if (a.vT_out) {
 #pragma unroll
               for (int i = 0; i < 4; ++i)
-                a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = b[i];
+                a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = a.win_f16 ? f32_to_f16_bits(own[i]) : b[i];
             }
           }
         }

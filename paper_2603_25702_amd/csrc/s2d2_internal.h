@@ -222,6 +222,9 @@ struct GemmStreamArgs {
   bf16_t* k_out;
   bf16_t* v_out;
   bf16_t* vT_out;
+  bf16_t* k16_out;          // optional second copy of the window's keys as IEEE half, same layout as k_out (read by the
+                            // attention kernel for wide windows in the half mode instead of the bf16 rows)
+  int32_t win_f16;          // vT_out holds IEEE half instead of bf16 (same reader)
   const int32_t* row_seq;
   const int32_t* seq_row0;
   // expert-grouped rows (tile kernel): row tile t covers sorted slots [tile_row0[t], +tile_rows[t]) of expert
