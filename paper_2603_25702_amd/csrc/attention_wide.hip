@@ -13,6 +13,7 @@
 // per tile separates that from the reads of tile i + 1.  The page-table entries of the split's key range are copied to LDS
 // once, so address generation never waits on a dependent global load.
 #include "attention_flash.h"
+#include <stdlib.h>
 
 namespace s2d2 {
 
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     float* __restrict__ part_ml, int32_t* __restrict__ counters, int q_tiles, int per, int pt_cap, int ps_shift) {
   constexpr int D = FA_D, T = NW * 64, U = 512 / T;
   constexpr bool SPLIT = QM == OPM_BF16X2, F16 = QM == OPM_F16;
-  static_assert(U == 1 || U == 2 || U == 4, "8, 4 or 2 wavefronts");
+  static_assert(U == 1 || U == 2, "8 or 4 wavefronts");
   extern __shared__ __align__(16) unsigned char lds[];
   int32_t* s_pt = (int32_t*)(lds + FW_RING * FW_BUF);
   int* s_last = (int*)(s_pt + pt_cap);
@@ -306,16 +307,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
       }
     } else {
       // smaller workgroups hold several pieces per thread: one tile in flight (two workgroups share a CU)
-      uint4 k0, v0, k1, v1, k2, v2, k3, v3;
+      uint4 k0, v0, k1, v1;
       auto fetch_all = [&](int i) {
         fetch1(0, i, k0, v0);
         fetch1(1, i, k1, v1);
-        if constexpr (U > 2) { fetch1(2, i, k2, v2); fetch1(3, i, k3, v3); }
       };
       auto stash_all = [&](int i, int b) {
         stash1(0, i, b, k0, v0);
         stash1(1, i, b, k1, v1);
-        if constexpr (U > 2) { stash1(2, i, b, k2, v2); stash1(3, i, b, k3, v3); }
       };
       fetch_all(0);
       stash_all(0, 0);
@@ -396,7 +395,7 @@ static void launch_wide(hipStream_t st, int qm, dim3 grid, size_t lds, const bf1
 // then the smallest supported workgroup that covers a group.
 int attention_wide_nw(int q_tiles) {
   const int groups = (q_tiles + 7) / 8, need = (q_tiles + groups - 1) / groups;
-  return need <= 2 ? 2 : need <= 4 ? 4 : 8;
+  return need <= 4 ? 4 : 8;   // (two wavefronts for two tiles measured slower: four share the fetch work, 3.76 -> 3.27 ms of attention per step on the 4B shape)
 }
 
 // Page-table entries a split can touch (plus slack for the ragged ends).
@@ -425,8 +424,7 @@ void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, co
   launch_wide<NWV>(st, operand_mode(q_lo), grid, lds, (const bf16_t*)q, q_ld, q_lo, (const bf16_t*)k_win, (const bf16_t*)vT_win, \
                    (const bf16_t*)k_pages_layer, (const bf16_t*)v_pages_layer, g, p, Hq, Z, wpad, scale_log2e,          \
                    (bf16_t*)o, o_ld, o_lo, part_o, part_ml, counters, q_tiles, per, pt_cap, ps_shift)
-  if (nw == 2) S2D2_WIDE(2);
-  else if (nw == 4) S2D2_WIDE(4);
+  if (nw == 4) S2D2_WIDE(4);
   else S2D2_WIDE(8);
 #undef S2D2_WIDE
 }
@@ -442,7 +440,7 @@ int attention_wide_init() {
   if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_BF16>();                    \
   if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_BF16X2>();                  \
   if (e == hipSuccess) e = wide_lds_limit<NWV, OPM_F16>();
-  S2D2_LIM(2) S2D2_LIM(4) S2D2_LIM(8)
+  S2D2_LIM(4) S2D2_LIM(8)
 #undef S2D2_LIM
   return e == hipSuccess ? 0 : -1;
 }
