@@ -76,6 +76,7 @@ struct s2d2_ctx {
   const uint4* pk_unembed;
   int32_t* dev_status;       // sticky device-side failure words ([1]: a bounded wait of the paired K split ran out)
   uint64_t* ts_scratch;      // clock stamps of the timing build
+  int n_cus;                 // compute units of the device
   float* tile_partials;      // split-K partials of the tiled GEMM, TILE_PARTIAL_CAP x 64 KB
   int32_t* tile_counters;    // TILE_COUNTER_CAP arrival counters, zero between launches
   float* accept_tiles;       // [max_batch, vocabulary tiles] residual tile sums shared by the workgroups of a sequence
@@ -316,7 +317,7 @@ int32_t forward(s2d2_ctx* c, const s2d2_kv_view* kv, int32_t N, int32_t B, void*
   auto sk = [&](GemmStreamArgs& x) {   // split-K buffers of the tiled GEMM, expected rows
     x.m_hint = x.m_count == c->plan.counts + 1 ? N * B : m_hint;   // (logit rows: one per masked position)
     x.tile_partials = c->tile_partials; x.tile_counters = c->tile_counters;
-    x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP;
+    x.tile_partial_cap = TILE_PARTIAL_CAP; x.tile_counter_cap = TILE_COUNTER_CAP; x.coop_wgs = c->n_cus;
     x.pair_buf = c->pair_buf; x.pair_status = c->dev_status + 1; x.pair_cap = PAIR_CAP;
   };
   // GEMM inputs: one plane of half values, or P bf16 planes per row ([hi | lo]); the low-plane offsets say which
@@ -535,6 +536,7 @@ int32_t s2d2_create(const s2d2_model_desc* desc, const s2d2_weights* weights, in
   memcpy(c->layers, weights->layers, sizeof(s2d2_layer_weights) * desc->n_layers);
   c->w.layers = c->layers;
   c->max_batch = max_batch;
+  c->n_cus = prop.multiProcessorCount;
   c->max_block = max_block;
   c->rows_cap = 3 * max_batch * max_block;
   c->logit_cap = max_batch * max_block;

@@ -17,8 +17,21 @@
 //
 // K can be split over blockIdx.z when the tiles alone would leave compute units idle (few rows, narrow
 // outputs): every split writes its accumulators as an fp32 partial in register order (write-through
-// stores), the workgroup that arrives last at the tile's counter adds all partials in split order and
-// runs the epilogue, so the result does not depend on which workgroup that is.
+// stores) and counts itself in at the tile's counter.  The merge is shared: split z finishes every KS-th
+// accumulator of the tile (adds the KS partials in split order, runs the epilogue), after a short bounded
+// wait for the other splits; all of a split's partials of all splits are requested at once, so the merge
+// is one memory round trip per workgroup, and KS compute units share it.  Nothing depends on that wait
+// succeeding: a split that gives up says so in the counter word and leaves, and the split that arrives
+// last finishes its own share and every share given up before its arrival (a split that gives up after
+// the last arrival finds everybody there and finishes its own share after all).  Launches with more
+// workgroups than compute units do not wait at all (the last arrival finishes the whole tile).  Every sum
+// is formed in split order, so the result does not depend on who forms it.
+//
+// blockIdx.y covers the row tiles the host expects (m_hint); a workgroup walks on to the row tiles beyond
+// that if the device-side row count is larger.  The usual launch therefore has no workgroup without rows:
+// the hardware deals workgroups to the shader engines in turn whether they exit at once or not, and
+// launches with such workgroups in between were measured to leave a fifth of the compute units empty
+// while others held two workgroups one after the other.
 //
 // The prologue / epilogues are the ones of the streaming kernel (same argument block): 1/rms from
 // the producer's partial sums of squares, fp32 store, residual add with the operand and partial
@@ -44,8 +57,9 @@ __device__ unsigned long long g_tile_ts[64];
 
 // SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
 // of a row sit side by side in LDS and every weight operand is multiplied with both.
+// One row tile (index ty) of the workgroup's column tile and K split; false: there is no such row tile.
 template <int EPI, int PRO, int OPM, int WC>
-__global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
+__device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const int ty) {
   constexpr bool SPLIT = OPM == OPM_BF16X2;       // the activations come as two bf16 planes
   constexpr int NTH = 128 * WC;                   // 2 x WC wavefronts of 64 rows x 64 features each
   constexpr int XI = 1024 / NTH;                  // 16-byte chunks of an activation plane tile per thread
@@ -57,21 +71,26 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   __shared__ __align__(16) uint8_t s_x[2][TM * XROW];
   __shared__ int s_xrow[TM], s_orow[TM];
   __shared__ float s_rs[TM];
+  __shared__ int s_share;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the thread index passes through an opaque statement: otherwise everything that depends on the lane alone is
+  // computed ahead of the loop over row tiles, for all epilogues at once, and spilled across the K loop)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, f = lane & 15;
   const int wr = wave / WC, wc = wave % WC;
   S2D2_TTS(0);
   int m0, Mloc, expert = 0;
   if (a.grouped != GROUP_NONE) {
-    if ((int)blockIdx.y >= *a.n_tiles) return;
-    expert = a.tile_expert[blockIdx.y];
-    m0 = a.tile_row0[blockIdx.y];
-    Mloc = a.tile_rows[blockIdx.y];
+    if (ty >= *a.n_tiles) return false;
+    expert = a.tile_expert[ty];
+    m0 = a.tile_row0[ty];
+    Mloc = a.tile_rows[ty];
   } else {
     const int M = *a.m_count;
-    m0 = blockIdx.y * TM;
-    if (m0 >= M) return;
+    m0 = ty * TM;
+    if (m0 >= M) return false;
     Mloc = min(TM, M - m0);
   }
   const int KT = a.KT;
@@ -234,15 +253,119 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   for (; kbase + UN <= kb1; kbase += UN) group(std::true_type{}, kbase);
   if (kbase < kb1) group(std::false_type{}, kbase);
 
-  if (acc[0][0][0] == 12345.678f) return;
+  if (acc[0][0][0] == 12345.678f) return true;
   S2D2_TTS(2);
-  // ---- split K: partials in register order, the last arrival adds them in split order ----
-  // Device-coherent write-through stores and loads around the arrival counter (a __threadfence pair per
-  // workgroup instead made the launches 60 % slower: the fences are cache-wide); words are laid out
-  // [accumulator][half][thread] so that every wavefront instruction covers 512 contiguous bytes; 16-row blocks
-  // past the tile's rows are neither written nor read.
-  if (KS > 1) {
-    const size_t tile_id = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+
+  // ---- epilogue of one unit: v0 (and v1, the up projection, for SwiGLU) = accumulator(s) of row block rb, feature
+  // tile nt0 + t of this wavefront: v[i] = Y[row wr*64 + rb*16 + f][feature (nt0 + t)*16 + 4 g + i].  rb and t may
+  // be run-time values (the merge of a K split hands over sums it has just formed). ----
+  auto epi_unit = [&](const int rb, const int t, const f32x4_t& v0, const f32x4_t& v1) __attribute__((always_inline)) {
+    const int r = wr * 64 + rb * 16 + f;
+    const bool live = r < Mloc;
+    const int orow = live ? s_orow[r] : 0;
+    const float rs = s_rs[r];
+    const int nt = nt0 + t;
+    if (nt >= a.NT) return;   // uniform over the wavefront
+    const int n = nt * 16 + 4 * g;
+    if (EPI == SEPI_STORE_F32) {
+      if (live) {
+        float* op = (float*)a.out + (size_t)orow * a.ldo + n;
+        const f32x4_t v = v0 * rs;
+        if (n + 3 < a.N) *(float4*)op = make_float4(v[0], v[1], v[2], v[3]);
+        else
+          for (int i = 0; i < 4; ++i)
+            if (n + i < a.N) op[i] = v[i];
+      }
+    } else if (EPI == SEPI_ADD_F32) {   // N is a multiple of 16 here: four features per lane as one 16-byte access
+      float hv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        float4* hp = (float4*)((float*)a.out + (size_t)orow * a.ldo + n);
+        const float4 h0 = *hp;
+        hv[0] = h0.x + v0[0] * rs;
+        hv[1] = h0.y + v0[1] * rs;
+        hv[2] = h0.z + v0[2] * rs;
+        hv[3] = h0.w + v0[3] * rs;
+        *hp = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        if (a.xg_out) {
+          const float4 gn = *(const float4*)(a.gain_next + n);
+          act_store4(a.xg_out + (size_t)orow * a.xg_ld + n, a.xg_lo, hv[0] * gn.x, hv[1] * gn.y, hv[2] * gn.z, hv[3] * gn.w);
+        }
+      }
+      if (a.ss_out) {
+        float sq = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
+        sq += __shfl_xor(sq, 16, 64);
+        sq += __shfl_xor(sq, 32, 64);
+        if (live && g == 0) a.ss_out[(size_t)orow * a.ss_stride + nt] = sq;
+      }
+    } else if (EPI == SEPI_SWIGLU) {
+      if (live) {
+        float sv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float gate = v0[i] * rs, up = v1[i] * rs;
+          sv[i] = gate / (1.0f + __expf(-gate)) * up;
+        }
+        act_store4((bf16_t*)a.out + (size_t)orow * a.ldo + n, a.out_lo, sv[0], sv[1], sv[2], sv[3]);
+      }
+    } else {  // SEPI_QKV_ROPE: features 0-7 of a tile pair with features 8-15 (lanes 32 apart)
+      const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
+      const int head = nt / tiles_per_head, i0 = 8 * (nt % tiles_per_head) + 4 * (g & 1);
+      float own[4], oth[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        own[i] = v0[i] * rs;
+        oth[i] = __shfl_xor(own[i], 32, 64);
+      }
+      if (live) {
+        const bool second = g >= 2;   // this lane holds x2 (element i + D/2) of the pair
+        if (head < a.Hq + a.Hkv) {
+          const bool is_q = head < a.Hq;
+          bf16_t* dst = is_q ? a.q_out + (size_t)orow * a.q_ld + head * D
+                             : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
+          const float4 c01 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0), c23 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0 + 2);
+          const float cs_c[4] = {c01.x, c01.z, c23.x, c23.z}, cs_s[4] = {c01.y, c01.w, c23.y, c23.w};
+          float y[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) y[i] = second ? own[i] * cs_c[i] + oth[i] * cs_s[i] : own[i] * cs_c[i] - oth[i] * cs_s[i];
+          // queries in the storage the attention kernel reads (q_lo); keys always as one bf16 plane (the cache's type)
+          act_store4(dst + i0 + (second ? half : 0), is_q ? a.q_lo : 0, y[0], y[1], y[2], y[3]);
+          if (!is_q && a.k16_out)   // the window's keys once more as half values (the attention kernel's copy)
+            act_store4(a.k16_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D + i0 + (second ? half : 0), LO_F16, y[0], y[1], y[2], y[3]);
+        } else {
+          const int vh = head - a.Hq - a.Hkv;
+          bf16_t* dst = a.v_out + ((size_t)orow * a.Hkv + vh) * D + (second ? half : 0);
+          const int sq = a.row_seq[orow], tw = orow - a.seq_row0[sq];
+          bf16_t b[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) b[i] = f32_to_bf16(own[i]);
+          *(uint2*)(dst + i0) = make_uint2((uint32_t)b[0] | ((uint32_t)b[1] << 16), (uint32_t)b[2] | ((uint32_t)b[3] << 16));
+          if (a.vT_out) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = a.win_f16 ? f32_to_f16_bits(own[i]) : b[i];
+          }
+        }
+      }
+    }
+  };
+
+  if (KS == 1) {
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+      for (int t = 0; t < FT; ++t) epi_unit(rb, t, acc[rb][NACC * t], acc[rb][NACC == 2 ? 2 * t + 1 : 0]);
+    __builtin_amdgcn_s_waitcnt(0);
+    S2D2_TTS(6);
+    return true;
+  }
+
+  // ---- split K ----
+  // Partials in register order, [accumulator][half][thread] 8-byte words (every wavefront instruction covers 512
+  // contiguous bytes), device-coherent write-through stores and loads around the tile's counter word (a
+  // __threadfence pair per workgroup instead made the launches 60 % slower: the fences are cache-wide); 16-row
+  // blocks past the tile's rows are neither written nor read.
+  const size_t tile_id = (size_t)ty * gridDim.x + blockIdx.x;
+  {
     uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
@@ -256,148 +379,99 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0);   // write-through stores completed before the arrival is counted
-    __syncthreads();
-    __shared__ int s_last;
-    if (tid == 0) {
-      const int prev = __hip_atomic_fetch_add(&a.tile_counters[tile_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = prev == KS - 1;
-      if (prev == KS - 1) __hip_atomic_store(&a.tile_counters[tile_id], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    S2D2_TTS(3);
-    if (!s_last) return;
-    S2D2_TTS(4);
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // The partials of all splits (at most 8) of a 16-row block are requested together and then added in split
-    // order: one memory round trip per block.  (One split at a time was a chain of 4 KS dependent round trips of
-    // device-coherent loads, 30-40 us of a 55 us launch for the projections with long K and few output tiles.)
-    const uint64_t* src0 = (const uint64_t*)a.tile_partials + (tile_id * KS) * (32 * NTH) + tid;
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      if (wr * 64 + rb * 16 >= Mloc) continue;
-      uint64_t v[8][8];
-#pragma unroll
-      for (int zz = 0; zz < 8; ++zz) {
-        if (zz >= KS) break;   // uniform
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[zz][e] = __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + (rb * 8 + e) * NTH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-#pragma unroll
-      for (int zz = 0; zz < 8; ++zz) {
-        if (zz >= KS) break;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          acc[rb][t][0] += __uint_as_float((uint32_t)v[zz][2 * t]);
-          acc[rb][t][1] += __uint_as_float((uint32_t)(v[zz][2 * t] >> 32));
-          acc[rb][t][2] += __uint_as_float((uint32_t)v[zz][2 * t + 1]);
-          acc[rb][t][3] += __uint_as_float((uint32_t)(v[zz][2 * t + 1] >> 32));
-        }
-      }
-    }
   }
-
-  if (acc[0][0][0] == 12345.678f) return;
-  S2D2_TTS(5);
-  // ---- epilogue: acc[rb][t][i] = Y[row wr*64 + rb*16 + f][feature (nt0 + t)*16 + 4 g + i] ----
+  __builtin_amdgcn_s_waitcnt(0);   // write-through stores completed before the arrival is counted
+  __syncthreads();
+  // Counter word of the tile: bits 0-7 arrivals, bits 8-15 workgroups that are done with the word (the last of them
+  // clears it for the next launch), bits 16-23 shares given up (bit 16 + z: split z will not finish its share).
+  if (tid == 0) {
+    int* ctr = &a.tile_counters[tile_id];
+    const bool wait_ok = (long long)gridDim.x * gridDim.y * KS <= (long long)a.coop_wgs;   // all workgroups of the launch can be resident at once
+    int share = 0;
+    const int prev = __hip_atomic_fetch_add(ctr, wait_ok ? 1 : 1 + (1 << (16 + z)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((prev & 0xff) == KS - 1) {
+      share = (1 << z) | ((prev >> 16) & 0xff);   // the last arrival: its own share and every share given up so far
+    } else if (wait_ok) {
+      bool all = false;
+      for (int spins = 0; spins < 96 && !all; ++spins) {
+        __builtin_amdgcn_s_sleep(8);
+        all = (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
+      }
+      if (!all)   // give the share up; if everybody has arrived in the meantime, nobody will take it: keep it
+        all = (__hip_atomic_fetch_or(ctr, 1 << (16 + z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
+      if (all) share = 1 << z;
+    }
+    const int done = __hip_atomic_fetch_add(ctr, 1 << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (((done >> 8) & 0xff) == KS - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_share = share;
+  }
+  __syncthreads();
+  S2D2_TTS(3);
+  const int share = s_share;
+  if (!share) return true;
+  S2D2_TTS(4);
+  // Share zs = units zs, zs + KS, ... of every wavefront (a unit: one accumulator, for SwiGLU the gate / up pair).
+  // The partials of all units of a share and of all splits are requested together (at most 128 registers) and
+  // added in split order: one memory round trip per share.
+  const uint64_t* src0 = (const uint64_t*)a.tile_partials + (tile_id * KS) * (32 * NTH) + tid;
+  constexpr int NU = 4 * FT;
+  auto merge = [&](auto ksm_tag) __attribute__((always_inline)) {
+    constexpr int KSM = decltype(ksm_tag)::value;   // KS <= KSM
+    constexpr int BU = 32 / (NACC * KSM) < NU / 2 ? 32 / (NACC * KSM) : NU / 2;   // units per round: a whole share (at most NU / 2 units) within 128 registers
+    for (int zs = 0; zs < KS; ++zs) {
+      if (!((share >> zs) & 1)) continue;
+      for (int u0 = zs; u0 < NU; u0 += KS * BU) {
+        uint64_t v[BU][NACC][KSM][2];
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) {
-    const int r = wr * 64 + rb * 16 + f;
-    const bool live = r < Mloc;
-    const int orow = live ? s_orow[r] : 0;
-    const float rs = s_rs[r];
+        for (int j = 0; j < BU; ++j) {
+          const int u = u0 + KS * j, rb = u / FT, t = u % FT;
+          const bool ok = u < NU && wr * 64 + rb * 16 < Mloc;   // uniform over the wavefront
 #pragma unroll
-    for (int t = 0; t < FT; ++t) {
-      const int nt = nt0 + t;
-      if (nt >= a.NT) continue;   // uniform over the wavefront
-      const int n = nt * 16 + 4 * g;
-      if (EPI == SEPI_STORE_F32) {
-        if (live) {
-          float* op = (float*)a.out + (size_t)orow * a.ldo + n;
-          const f32x4_t v = acc[rb][t] * rs;
-          if (n + 3 < a.N) *(float4*)op = make_float4(v[0], v[1], v[2], v[3]);
-          else
-            for (int i = 0; i < 4; ++i)
-              if (n + i < a.N) op[i] = v[i];
+          for (int c = 0; c < NACC; ++c)
+#pragma unroll
+            for (int zz = 0; zz < KSM; ++zz)
+#pragma unroll
+              for (int e = 0; e < 2; ++e)
+                v[j][c][zz][e] = (ok && zz < KS) ? __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + ((rb * 4 + NACC * t + c) * 2 + e) * NTH,
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
         }
-      } else if (EPI == SEPI_ADD_F32) {   // N is a multiple of 16 here: four features per lane as one 16-byte access
-        float hv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (live) {
-          float4* hp = (float4*)((float*)a.out + (size_t)orow * a.ldo + n);
-          const float4 h0 = *hp;
-          hv[0] = h0.x + acc[rb][t][0] * rs;
-          hv[1] = h0.y + acc[rb][t][1] * rs;
-          hv[2] = h0.z + acc[rb][t][2] * rs;
-          hv[3] = h0.w + acc[rb][t][3] * rs;
-          *hp = make_float4(hv[0], hv[1], hv[2], hv[3]);
-          if (a.xg_out) {
-            const float4 gn = *(const float4*)(a.gain_next + n);
-            act_store4(a.xg_out + (size_t)orow * a.xg_ld + n, a.xg_lo, hv[0] * gn.x, hv[1] * gn.y, hv[2] * gn.z, hv[3] * gn.w);
-          }
-        }
-        if (a.ss_out) {
-          float sq = (hv[0] * hv[0] + hv[1] * hv[1]) + (hv[2] * hv[2] + hv[3] * hv[3]);
-          sq += __shfl_xor(sq, 16, 64);
-          sq += __shfl_xor(sq, 32, 64);
-          if (live && g == 0) a.ss_out[(size_t)orow * a.ss_stride + nt] = sq;
-        }
-      } else if (EPI == SEPI_SWIGLU) {
-        if (live) {
-          float sv[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float gate = acc[rb][NACC == 2 ? 2 * t : 0][i] * rs, up = acc[rb][NACC == 2 ? 2 * t + 1 : 0][i] * rs;
-            sv[i] = gate / (1.0f + __expf(-gate)) * up;
-          }
-          act_store4((bf16_t*)a.out + (size_t)orow * a.ldo + n, a.out_lo, sv[0], sv[1], sv[2], sv[3]);
-        }
-      } else {  // SEPI_QKV_ROPE: features 0-7 of a tile pair with features 8-15 (lanes 32 apart)
-        const int D = a.D, half = D >> 1, tiles_per_head = D / 16;
-        const int head = nt / tiles_per_head, i0 = 8 * (nt % tiles_per_head) + 4 * (g & 1);
-        float own[4], oth[4];
+        for (int j = 0; j < BU; ++j) {
+          const int u = u0 + KS * j, rb = u / FT, t = u % FT;
+          if (u >= NU || wr * 64 + rb * 16 >= Mloc) continue;   // uniform over the wavefront
+          f32x4_t sum[NACC];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          own[i] = acc[rb][t][i] * rs;
-          oth[i] = __shfl_xor(own[i], 32, 64);
-        }
-        if (live) {
-          const bool second = g >= 2;   // this lane holds x2 (element i + D/2) of the pair
-          if (head < a.Hq + a.Hkv) {
-            const bool is_q = head < a.Hq;
-            bf16_t* dst = is_q ? a.q_out + (size_t)orow * a.q_ld + head * D
-                               : a.k_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D;
-            const float4 c01 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0), c23 = *(const float4*)(a.rope_cs + (size_t)orow * half + i0 + 2);
-            const float cs_c[4] = {c01.x, c01.z, c23.x, c23.z}, cs_s[4] = {c01.y, c01.w, c23.y, c23.w};
-            float y[4];
+          for (int c = 0; c < NACC; ++c) {
+            sum[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) y[i] = second ? own[i] * cs_c[i] + oth[i] * cs_s[i] : own[i] * cs_c[i] - oth[i] * cs_s[i];
-            // queries in the storage the attention kernel reads (q_lo); keys always as one bf16 plane (the cache's type)
-            act_store4(dst + i0 + (second ? half : 0), is_q ? a.q_lo : 0, y[0], y[1], y[2], y[3]);
-            if (!is_q && a.k16_out)   // the window's keys once more as half values (the attention kernel's copy)
-              act_store4(a.k16_out + ((size_t)orow * a.Hkv + (head - a.Hq)) * D + i0 + (second ? half : 0), LO_F16, y[0], y[1], y[2], y[3]);
-          } else {
-            const int vh = head - a.Hq - a.Hkv;
-            bf16_t* dst = a.v_out + ((size_t)orow * a.Hkv + vh) * D + (second ? half : 0);
-            const int sq = a.row_seq[orow], tw = orow - a.seq_row0[sq];
-            bf16_t b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) b[i] = f32_to_bf16(own[i]);
-            *(uint2*)(dst + i0) = make_uint2((uint32_t)b[0] | ((uint32_t)b[1] << 16), (uint32_t)b[2] | ((uint32_t)b[3] << 16));
-            if (a.vT_out) {
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                a.vT_out[((size_t)(sq * a.Hkv + vh) * D + i0 + i + (second ? half : 0)) * a.wpad + tw] = a.win_f16 ? f32_to_f16_bits(own[i]) : b[i];
+            for (int zz = 0; zz < KSM; ++zz) {
+              if (zz >= KS) break;   // uniform
+              sum[c][0] += __uint_as_float((uint32_t)v[j][c][zz][0]);
+              sum[c][1] += __uint_as_float((uint32_t)(v[j][c][zz][0] >> 32));
+              sum[c][2] += __uint_as_float((uint32_t)v[j][c][zz][1]);
+              sum[c][3] += __uint_as_float((uint32_t)(v[j][c][zz][1] >> 32));
             }
           }
+          epi_unit(rb, t, sum[0], sum[NACC - 1]);
         }
       }
     }
-  }
+  };
+  if (KS <= 2) merge(std::integral_constant<int, 2>{});
+  else if (KS <= 4) merge(std::integral_constant<int, 4>{});
+  else merge(std::integral_constant<int, 8>{});
   __builtin_amdgcn_s_waitcnt(0);
   S2D2_TTS(6);
+  return true;
+}
+
+// blockIdx.y = first row tile of the workgroup; it walks on in steps of gridDim.y while there are rows.
+template <int EPI, int PRO, int OPM, int WC>
+__global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
+  for (int ty = blockIdx.y;; ty += gridDim.y) {
+    if (!gemm_tile_body<EPI, PRO, OPM, WC>(a, ty)) break;
+    __syncthreads();   // the next tile reuses the LDS arrays
+  }
 }
 
 #ifdef S2D2_KERNEL_TIMING
@@ -416,28 +490,31 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   // K is split over blockIdx.z when that shortens the launch.  The choice minimises a small cost model fitted to
   // kernel traces of the batched configurations (microseconds; a round is as many workgroups as are resident on
   // the chip at once):
-  //   rounds * (K steps per split * 1.3 + 6)                        K loop (both planes) + prologue / epilogue per round
-  //   + [splits > 1] * (8 + live tiles * splits * partial bytes * 2 / 3 TB/s)   partial write + read by the last arrival
-  // It is judged on the rows the caller expects (m_hint; the grid still covers the row capacity, workgroups of
-  // row tiles past the device-side row count exit at once).  Every split keeps at least 4 K steps and the
-  // partials must fit their buffer.
+  //   rounds * (K steps per split * 1.05 + 6)                       K loop + prologue / epilogue per round
+  //   + [splits > 1] * 10                                           partial write, wait and shared merge, or, when the
+  //     launch has more workgroups than compute units (nobody waits, the last arrival merges the tile):
+  //     8 + live tiles * splits * partial bytes * 2 / 3 TB/s
+  // It is judged on the rows the caller expects (m_hint).  Every split keeps at least 4 K steps and the partials
+  // must fit their buffer.
   int KS = 1;
   const long long tiles = (long long)col_tiles * row_tiles;
   const int hint_tiles = a.m_hint > 0 ? std::min(row_tiles, (a.m_hint + TM - 1) / TM) : row_tiles;
   const long long live = (long long)col_tiles * hint_tiles;
   const int nk = (a.K + TK - 1) / TK;
-  const double step_us = 1.3;
+  const double step_us = 1.05, merge_us = 10.0, round_us = 6.0;
   if (a.tile_partials && a.grouped == GROUP_NONE && tiles <= a.tile_counter_cap) {
     double best = 1e30;
     for (int ks = 1; ks <= 8; ++ks) {
       if (ks > 1 && (nk / ks < 4 || tiles * ks * (WC / 2) > a.tile_partial_cap)) break;
       const double rounds = (double)((live * ks + RESIDENT - 1) / RESIDENT), steps = (double)((nk + ks - 1) / ks);
-      double t = rounds * (steps * step_us + 6.0);
-      if (ks > 1) t += 8.0 + (double)live * ks * PART_BYTES * 2.0 / 3.0e6;
+      double t = rounds * (steps * step_us + round_us);
+      if (ks > 1) t += live * ks <= a.coop_wgs ? merge_us : 8.0 + (double)live * ks * PART_BYTES * 2.0 / 3.0e6;
       if (t < best - 1e-9) { best = t; KS = ks; }
     }
   }
-  dim3 grid(col_tiles, row_tiles, KS), block(128 * WC);
+  // blockIdx.y: the row tiles the caller expects (a workgroup walks on if there are more); all of them for the
+  // expert-grouped launches, whose tile list lives on the device
+  dim3 grid(col_tiles, a.grouped == GROUP_NONE ? hint_tiles : row_tiles, KS), block(128 * WC);
   const int opm = operand_mode(a.x_lo);
   if (opm == OPM_F16) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_F16, WC>), grid, block, 0, st, a);
   else if (opm == OPM_BF16X2) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>), grid, block, 0, st, a);
