@@ -14,6 +14,7 @@
 // once, so address generation never waits on a dependent global load.
 #include "attention_flash.h"
 #include <stdlib.h>
+#include <type_traits>
 
 namespace s2d2 {
 
@@ -114,6 +115,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   __syncthreads();   // s_pt
 
   // (closures capture scalars by value: captured references would pin the locals to memory)
+  // Leading tiles of this split that are full tiles of cached keys (all but, at most, the last cached tile of the
+  // last split).  The loops below run them through forms of fetch / park / compute that are compiled for exactly
+  // that case (FAST): no clamps, no second address form, no visibility mask.  Both kinds of wavefronts are bound
+  // by their vector-ALU instructions, not by the matrix pipes or by memory.
+  const int n_fast = max(0, min(n_c, (S >> 5) - t0));
+  auto tile_fast = [=](int i) {
+    FwTile t;
+    t.win = false;
+    t.kbase = (t0 + i) * 32;
+    t.limit = S;
+    return t;
+  };
   auto tile_of = [=](int i) {
     FwTile t;
     i = min(i, n_it - 1);
@@ -124,40 +137,58 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   };
   // piece idx of a tile: K row idx / 16, 16-byte piece idx % 16;  V^T row idx / 4, keys 8 (idx % 4) .. + 8.
   // Thread tid handles pieces tid + u T, u < U (each piece in a named register set, never an indexed array).
-  auto fetchp = [=](int idx, int i, uint4& kr, uint4& vr) {
-    const FwTile t = tile_of(i);
+  // (offsets are written as  page * page_stride + [terms that depend on the thread alone] + [32-bit terms of the
+  // tile]: the middle part is computed once per thread ahead of the loop, and a piece costs one table look-up and
+  // one 64-bit multiply-add per tile; the fetching wavefronts share their SIMDs with the computing ones)
+  const size_t pstride = (size_t)Hkv * ps * D;   // elements of a page
+  auto fetchp = [=](auto fast, int idx, int i, uint4& kr, uint4& vr) {
+    constexpr bool FAST = decltype(fast)::value;
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
+    if (FAST) {
+      const int key = (t0 + i) * 32 + kk, kv0 = (t0 + i) * 32 + vko;
+      const int pk = s_pt[min((key >> ps_shift) - pb0, pt_cap - 1)];
+      const int pv = s_pt[min((kv0 >> ps_shift) - pb0, pt_cap - 1)];
+      kr = *(const uint4*)(k_pages + ((size_t)kvh * ps * D + kch * 8) + (size_t)pk * pstride + (key & (ps - 1)) * D);
+      vr = *(const uint4*)(v_pages + ((size_t)kvh * D + vd) * ps + (size_t)pv * pstride + (kv0 & (ps - 1)));
+      return;
+    }
+    const FwTile t = tile_of(i);
     const int key = min(t.kbase + kk, t.limit - 1);   // rows beyond the region read a valid row; their scores are masked
     const int key0 = t.kbase + vko;
     // both address forms are computed and one is selected: no control flow around the loads
     const int kv0 = min(key0, cap - 8);
     const int pk = s_pt[max(0, min((key >> ps_shift) - pb0, pt_cap - 1))];
     const int pv = s_pt[max(0, min((kv0 >> ps_shift) - pb0, pt_cap - 1))];
-    const size_t k_off_c = (((size_t)pk * Hkv + kvh) * ps + (key & (ps - 1))) * D + kch * 8;
-    const size_t v_off_c = (((size_t)pv * Hkv + kvh) * D + vd) * ps + (kv0 & (ps - 1));
-    const size_t k_off_w = ((size_t)(row0 + key) * Hkv + kvh) * D + kch * 8;
-    const size_t v_off_w = ((size_t)(n * Hkv + kvh) * D + vd) * wpad + min(key0, wpad - 8);
-    const bf16_t* kp = t.win ? k_win + k_off_w : k_pages + k_off_c;
-    const bf16_t* vp = t.win ? vT_win + v_off_w : v_pages + v_off_c;
-    kr = *(const uint4*)kp;
-    vr = *(const uint4*)vp;
+    const bf16_t* kp_c = k_pages + ((size_t)kvh * ps * D + kch * 8) + (size_t)pk * pstride + (key & (ps - 1)) * D;
+    const bf16_t* vp_c = v_pages + ((size_t)kvh * D + vd) * ps + (size_t)pv * pstride + (kv0 & (ps - 1));
+    const bf16_t* kp_w = k_win + ((size_t)row0 * Hkv + kvh) * D + kch * 8 + (size_t)key * (Hkv * D);
+    const bf16_t* vp_w = vT_win + ((size_t)(n * Hkv + kvh) * D + vd) * wpad + min(key0, wpad - 8);
+    kr = *(const uint4*)(t.win ? kp_w : kp_c);
+    vr = *(const uint4*)(t.win ? vp_w : vp_c);
   };
-  auto fetch1 = [=](int u, int i, uint4& kr, uint4& vr) { fetchp(min(tid + u * T, 511), i, kr, vr); };
-  auto stashp = [=](int idx, int i, int b, uint4 kr, uint4 vr) {
-    const FwTile t = tile_of(i);
+  auto fetch1 = [=](auto fast, int u, int i, uint4& kr, uint4& vr) { fetchp(fast, min(tid + u * T, 511), i, kr, vr); };
+  auto stashp = [=](auto fast, int idx, int i, int b, uint4 kr, uint4 vr) {
+    constexpr bool FAST = decltype(fast)::value;
     unsigned char* base = lds + b * FW_BUF;
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
+    if (FAST) {
+      *(uint4*)(base + kk * FW_KROW + kch * 16) = F16 ? fw_to_f16(kr) : kr;
+      *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = F16 ? fw_to_f16(vr) : vr;
+      return;
+    }
+    const FwTile t = tile_of(i);
     // half mode: cached tiles are bf16 and are converted here; the window's own rows already come as half values
     // (k_win / vT_win then point at the half copies the QKV projection wrote: 11 bits instead of the cache's 8)
-    const uint4 vm = fw_mask(vr, t.limit - (t.kbase + vko));
+    const uint4 vm = t.kbase + 32 <= t.limit ? vr : fw_mask(vr, t.limit - (t.kbase + vko));   // (uniform: only a region's last tile is partial)
     const bool cvt = F16 && !t.win;
     *(uint4*)(base + kk * FW_KROW + kch * 16) = cvt ? fw_to_f16(kr) : kr;
     *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = cvt ? fw_to_f16(vm) : vm;
   };
-  auto stash1 = [=](int u, int i, int b, uint4 kr, uint4 vr) { stashp(min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
+  auto stash1 = [=](auto fast, int u, int i, int b, uint4 kr, uint4 vr) { stashp(fast, min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
   const int kperm = fa_perm(c);
-  auto compute = [=](FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) {
-    const FwTile t = tile_of(i);
+  auto compute = [=](auto fast, FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) {
+    constexpr bool FAST = decltype(fast)::value;
+    const FwTile t = FAST ? tile_fast(i) : tile_of(i);
     const unsigned char* kb = lds + b * FW_BUF + kperm * FW_KROW + 16 * h;
     const unsigned char* vb = lds + b * FW_BUF + FW_KBUF + c * FW_VROW + 16 * h;
     f32x16_t sacc;
@@ -177,7 +208,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     // sacc[j]: key kbase + 16 (j / 8) + 8 h + (j % 8), query row c.  Scores stay unscaled until the exponent:
     // the running maximum is kept in scaled units, exp2(s * scale - m) is one fused multiply-add per element.
     float mx = -INFINITY;
-    if (!t.win && t.kbase + 32 <= t.limit) {   // a full tile of cached keys: every key is visible
+    if (FAST || (!t.win && t.kbase + 32 <= t.limit)) {   // a full tile of cached keys: every key is visible
 #pragma unroll
       for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sacc[j]);
     } else {
@@ -245,87 +276,100 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   // wavefronts with four pieces each, measured slower on two of three configurations and is not used.)
   const int n_live = min(per, (nq - qgrp * per * 32 + 31) >> 5);
   const bool spec = NW == 8 && 2 * n_live <= NW;
+  constexpr std::true_type FT_{};
+  constexpr std::false_type GT_{};
   if (n_it > 0 && spec) {
     if (wave >= NW / 2) {
       constexpr int PP = 16 / NW;                       // pieces per fetching thread
       const int pbase = tid - NW * 32;                  // 0 .. NW*32 - 1; piece u of this thread: pbase + u * NW * 32
       uint4 ak[PP], av[PP], bk[PP], bv[PP];             // (indices are compile-time constants throughout)
 #pragma unroll
-      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 0, ak[u], av[u]);
+      for (int u = 0; u < PP; ++u) fetchp(GT_, pbase + u * NW * 32, 0, ak[u], av[u]);
 #pragma unroll
-      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 1, bk[u], bv[u]);
+      for (int u = 0; u < PP; ++u) fetchp(GT_, pbase + u * NW * 32, 1, bk[u], bv[u]);
 #pragma unroll
-      for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, 0, 0, ak[u], av[u]);
+      for (int u = 0; u < PP; ++u) stashp(GT_, pbase + u * NW * 32, 0, 0, ak[u], av[u]);
 #pragma unroll
-      for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, 2, ak[u], av[u]);
+      for (int u = 0; u < PP; ++u) fetchp(GT_, pbase + u * NW * 32, 2, ak[u], av[u]);
       __syncthreads();
-      for (int i = 0; i < n_it; i += 2) {
+      // one pass: parks tiles i + 1, i + 2 and requests tiles i + 3, i + 4
+      auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, i + 1, 1, bk[u], bv[u]);
+        for (int u = 0; u < PP; ++u) stashp(fast, pbase + u * NW * 32, i + 1, 1, bk[u], bv[u]);
 #pragma unroll
-        for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, i + 3, bk[u], bv[u]);
+        for (int u = 0; u < PP; ++u) fetchp(fast, pbase + u * NW * 32, i + 3, bk[u], bv[u]);
         __syncthreads();
         if (i + 1 < n_it) {
 #pragma unroll
-          for (int u = 0; u < PP; ++u) stashp(pbase + u * NW * 32, i + 2, 0, ak[u], av[u]);
+          for (int u = 0; u < PP; ++u) stashp(fast, pbase + u * NW * 32, i + 2, 0, ak[u], av[u]);
 #pragma unroll
-          for (int u = 0; u < PP; ++u) fetchp(pbase + u * NW * 32, i + 4, ak[u], av[u]);
+          for (int u = 0; u < PP; ++u) fetchp(fast, pbase + u * NW * 32, i + 4, ak[u], av[u]);
           __syncthreads();
         }
-      }
+      };
+      int i = 0;
+      for (; i + 4 < n_fast; i += 2) pass(FT_, i);
+      for (; i < n_it; i += 2) pass(GT_, i);
     } else {
       __syncthreads();
-      for (int i = 0; i < n_it; i += 2) {
-        if (active) compute(st, qf, ql, i, 0);
+      auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
+        if (active) compute(fast, st, qf, ql, i, 0);
         __syncthreads();
         if (i + 1 < n_it) {
-          if (active) compute(st, qf, ql, i + 1, 1);
+          if (active) compute(fast, st, qf, ql, i + 1, 1);
           __syncthreads();
         }
-      }
+      };
+      int i = 0;
+      for (; i + 4 < n_fast; i += 2) pass(FT_, i);   // (the same split of the passes as in the fetching wavefronts: equal barrier counts)
+      for (; i < n_it; i += 2) pass(GT_, i);
     }
   } else if (n_it > 0) {
     if constexpr (U == 1) {
       // two tiles in flight in registers: set B holds tile i + 1 and set A tile i + 2 at the top of an (even) iteration
       uint4 ak, av, bk, bv;
-      fetch1(0, 0, ak, av);
-      fetch1(0, 1, bk, bv);
-      stash1(0, 0, 0, ak, av);
-      fetch1(0, 2, ak, av);
+      fetch1(GT_, 0, 0, ak, av);
+      fetch1(GT_, 0, 1, bk, bv);
+      stash1(GT_, 0, 0, 0, ak, av);
+      fetch1(GT_, 0, 2, ak, av);
       __syncthreads();
-      for (int i = 0; i < n_it; i += 2) {
-        if (active) compute(st, qf, ql, i, 0);
-        stash1(0, i + 1, 1, bk, bv);
-        fetch1(0, i + 3, bk, bv);
+      auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
+        if (active) compute(fast, st, qf, ql, i, 0);
+        stash1(fast, 0, i + 1, 1, bk, bv);
+        fetch1(fast, 0, i + 3, bk, bv);
         __syncthreads();
         if (i + 1 < n_it) {
-          if (active) compute(st, qf, ql, i + 1, 1);
-          stash1(0, i + 2, 0, ak, av);
-          fetch1(0, i + 4, ak, av);
+          if (active) compute(fast, st, qf, ql, i + 1, 1);
+          stash1(fast, 0, i + 2, 0, ak, av);
+          fetch1(fast, 0, i + 4, ak, av);
           __syncthreads();
         }
-      }
+      };
+      int i = 0;
+      for (; i + 4 < n_fast; i += 2) pass(FT_, i);
+      for (; i < n_it; i += 2) pass(GT_, i);
     } else {
       // smaller workgroups hold several pieces per thread: one tile in flight (two workgroups share a CU)
       uint4 k0, v0, k1, v1;
-      auto fetch_all = [&](int i) {
-        fetch1(0, i, k0, v0);
-        fetch1(1, i, k1, v1);
-      };
-      auto stash_all = [&](int i, int b) {
-        stash1(0, i, b, k0, v0);
-        stash1(1, i, b, k1, v1);
-      };
-      fetch_all(0);
-      stash_all(0, 0);
-      fetch_all(1);
+      fetch1(GT_, 0, 0, k0, v0);
+      fetch1(GT_, 1, 0, k1, v1);
+      stash1(GT_, 0, 0, 0, k0, v0);
+      stash1(GT_, 1, 0, 0, k1, v1);
+      fetch1(GT_, 0, 1, k0, v0);
+      fetch1(GT_, 1, 1, k1, v1);
       __syncthreads();
-      for (int i = 0; i < n_it; ++i) {
-        if (active) compute(st, qf, ql, i, i & 1);
-        stash_all(i + 1, (i + 1) & 1);
-        fetch_all(i + 2);
+      // one pass: computes tile i, parks tile i + 1, requests tile i + 2
+      auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
+        if (active) compute(fast, st, qf, ql, i, i & 1);
+        stash1(fast, 0, i + 1, (i + 1) & 1, k0, v0);
+        stash1(fast, 1, i + 1, (i + 1) & 1, k1, v1);
+        fetch1(fast, 0, i + 2, k0, v0);
+        fetch1(fast, 1, i + 2, k1, v1);
         __syncthreads();
-      }
+      };
+      int i = 0;
+      for (; i + 2 < n_fast; ++i) pass(FT_, i);
+      for (; i < n_it; ++i) pass(GT_, i);
     }
   }
 
