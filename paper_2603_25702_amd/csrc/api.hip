@@ -831,6 +831,7 @@ int32_t s2d2_debug_buffer(s2d2_ctx* c, const char* name, void** ptr) {
                                                     {"kwin", c->kwin}, {"vwin", c->vwin}, {"ss", c->ss}, {"tstamp", c->ts_scratch}};
   if (!strcmp(name, "stream_ts")) { launch_stream_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
   if (!strcmp(name, "tile_ts")) { launch_tile_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
+  if (!strcmp(name, "wide_ts")) { launch_wide_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
   if (!strcmp(name, "attn_ts")) { launch_attn_ts_copy(c->stream, c->ts_scratch); *ptr = c->ts_scratch; return S2D2_OK; }
   for (const auto& t : tab)
     if (!strcmp(t.n, name)) { *ptr = t.p; return S2D2_OK; }

@@ -18,6 +18,17 @@
 
 namespace s2d2 {
 
+#ifdef S2D2_KERNEL_TIMING
+__device__ unsigned long long g_wide_ts[64];
+// stamps of the first computing (k < 8) and the first fetching wavefront (k >= 8) of workgroup (0, 0, 0), tile 16
+#define S2D2_WTS(k, cond) do { if ((cond) && lane == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) g_wide_ts[(k)] = wall_clock64(); } while (0)
+__global__ void wide_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_wide_ts[threadIdx.x]; }
+void launch_wide_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(wide_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
+#else
+#define S2D2_WTS(k, cond) do {} while (0)
+void launch_wide_ts_copy(hipStream_t, void*) {}
+#endif
+
 static constexpr int FW_KROW = 272;               // bytes per K row in LDS: 128 bf16 + 16 bytes (bank spread)
 static constexpr int FW_VROW = 80;                // bytes per V^T row in LDS: 32 keys bf16 + 16 bytes
 static constexpr int FW_KBUF = 32 * FW_KROW;
@@ -192,6 +203,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     const unsigned char* kb = lds + b * FW_BUF + kperm * FW_KROW + 16 * h;
     const unsigned char* vb = lds + b * FW_BUF + FW_KBUF + c * FW_VROW + 16 * h;
     f32x16_t sacc;
+    S2D2_WTS(0, FAST && wave == 0 && i == 16);
 #pragma unroll
     for (int j = 0; j < 16; ++j) sacc[j] = 0.f;
 #pragma unroll
@@ -207,6 +219,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     }
     // sacc[j]: key kbase + 16 (j / 8) + 8 h + (j % 8), query row c.  Scores stay unscaled until the exponent:
     // the running maximum is kept in scaled units, exp2(s * scale - m) is one fused multiply-add per element.
+#ifdef S2D2_KERNEL_TIMING
+    if (sacc[0] == 12345.678f) return;
+    S2D2_WTS(1, FAST && wave == 0 && i == 16);
+#endif
     float mx = -INFINITY;
     if (FAST || (!t.win && t.kbase + 32 <= t.limit)) {   // a full tile of cached keys: every key is visible
 #pragma unroll
@@ -245,6 +261,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     ls += __shfl_xor(ls, 32, 64);
     st.l = st.l * alpha + ls;
     st.m = m_new;
+#ifdef S2D2_KERNEL_TIMING
+    if (ls == 12345.678f) return;
+    S2D2_WTS(2, FAST && wave == 0 && i == 16);
+#endif
     // the accumulators are rescaled only when some row's maximum moved (alpha = 1 leaves them as they are)
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
@@ -266,6 +286,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
         }
       }
     }
+#ifdef S2D2_KERNEL_TIMING
+    if (st.o[3][15] == 12345.678f) return;
+    S2D2_WTS(3, FAST && wave == 0 && i == 16);
+#endif
   };
 
   // A workgroup of 8 wavefronts of which at most half own a query tile with rows (a fresh block fills 4 of the
@@ -294,17 +318,23 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
       __syncthreads();
       // one pass: parks tiles i + 1, i + 2 and requests tiles i + 3, i + 4
       auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
+        S2D2_WTS(8, wave == NW / 2 && i == 16);
 #pragma unroll
         for (int u = 0; u < PP; ++u) stashp(fast, pbase + u * NW * 32, i + 1, 1, bk[u], bv[u]);
+        S2D2_WTS(9, wave == NW / 2 && i == 16);
 #pragma unroll
         for (int u = 0; u < PP; ++u) fetchp(fast, pbase + u * NW * 32, i + 3, bk[u], bv[u]);
+        S2D2_WTS(10, wave == NW / 2 && i == 16);
         __syncthreads();
+        S2D2_WTS(11, wave == NW / 2 && i == 16);
         if (i + 1 < n_it) {
 #pragma unroll
           for (int u = 0; u < PP; ++u) stashp(fast, pbase + u * NW * 32, i + 2, 0, ak[u], av[u]);
 #pragma unroll
           for (int u = 0; u < PP; ++u) fetchp(fast, pbase + u * NW * 32, i + 4, ak[u], av[u]);
+          S2D2_WTS(12, wave == NW / 2 && i == 16);
           __syncthreads();
+          S2D2_WTS(13, wave == NW / 2 && i == 16);
         }
       };
       int i = 0;
@@ -315,9 +345,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
       auto pass = [&](auto fast, int i) __attribute__((always_inline)) {
         if (active) compute(fast, st, qf, ql, i, 0);
         __syncthreads();
+        S2D2_WTS(4, wave == 0 && i == 16);
         if (i + 1 < n_it) {
           if (active) compute(fast, st, qf, ql, i + 1, 1);
           __syncthreads();
+          S2D2_WTS(5, wave == 0 && i == 16);
         }
       };
       int i = 0;

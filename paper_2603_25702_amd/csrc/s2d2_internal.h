@@ -292,6 +292,7 @@ void launch_attention_wide(hipStream_t st, const void* q, int q_ld, int q_lo, co
                            size_t part_entries, int32_t* counters);
 void launch_fill_i32(hipStream_t st, int32_t* p, int n, int32_t v);
 void launch_attn_ts_copy(hipStream_t st, void* out);   // timing build only
+void launch_wide_ts_copy(hipStream_t st, void* out);   // timing build only
 void launch_tile_ts_copy(hipStream_t st, void* out);   // timing build only
 void launch_stream_ts_copy(hipStream_t st, void* out); // timing build only
 size_t attention_generic_lds_bytes(const KvGeom& g, int max_window_rows);
