@@ -24,10 +24,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA peak of the arithmetic type (f16 and bf16 MFMA run at the same rate)
 HEADLINE, OTHERS = 4, (2, 3, 5)
-# HBM bytes per launch of the dominant GEMM kernel of a configuration, from the FETCH_SIZE / WRITE_SIZE counter runs
-# summarised under profiles/ (rocprofv3 --pmc, scaled by what the same counters read for a plain copy of known size).
-# None: not measured for that configuration.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {}
+# HBM-side bytes (L2 misses, both directions) per launch of the dominant GEMM kernel of a configuration and per
+# step, from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (rocprofv3 --pmc on this file with
+# the default operand mode; a plain copy of 1 GiB reads FETCH_SIZE = 524300 KiB and WRITE_SIZE = 1048576 KiB, so
+# bytes = FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024).  Averages over all GEMM launches of two steps.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31226163, 3: 99851571, 4: 214282854, 5: 342542804}
+STEP_TRAFFIC_BYTES = {   # all kernels of a step: (FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024) summed over the step's launches
+    2: (1690604.8 + 3417585.5 + 3215.8) * 2048 + (44688.0 + 56515.0 + 649.7) * 1024,
+    3: (3967121.5 + 11857950.8 + 41641.8) * 2048 + (1853523.1 + 4562378.3 + 10579.1) * 1024,
+    4: (20326855.9 + 25632438.4 + 159396.3) * 2048 + (3799751.6 + 9420704.5 + 29411.1) * 1024,
+    5: (4894689.1 + 277405.0 + 29207328.0 + 2658021.7) * 2048 + (2777070.1 + 14202.5 + 8588263.6 + 834874.7) * 1024,
+}
 
 
 def log(*a):
@@ -156,6 +163,9 @@ def bench_config(args, cfg_id: int, K: int, Wm: int, cpu_baseline: bool) -> dict
         step_bytes = g["bytes"] / Kp + kv_bytes + vocab_bytes
         roofline["step_hbm_bound_ms"] = round(step_bytes / (HBM_PEAK_GBS * 1e9) * 1e3, 3)
         roofline["step_hbm_frac"] = round(step_bytes / (HBM_PEAK_GBS * 1e9) / (elapsed / K), 4)
+        if common["traffic"] is not None:   # counters: what the whole step moved over what it must move at least once
+            roofline["step_traffic"] = round(STEP_TRAFFIC_BYTES[cfg_id])
+            roofline["step_traffic_over_algorithmic"] = round(STEP_TRAFFIC_BYTES[cfg_id] / step_bytes, 3)
         log(f"[bench] config {cfg_id}: profile pass ({Kp} steps): {json.dumps(phases)}")
 
     # ---- the fp64 oracle on the host cores: a bounded sample of full steps of the same workload -----

@@ -131,14 +131,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   // that case (FAST): no clamps, no second address form, no visibility mask.  Both kinds of wavefronts are bound
   // by their vector-ALU instructions, not by the matrix pipes or by memory.
   const int n_fast = max(0, min(n_c, (S >> 5) - t0));
-  auto tile_fast = [=](int i) {
+  auto tile_fast = [=](int i) __attribute__((always_inline)) {
     FwTile t;
     t.win = false;
     t.kbase = (t0 + i) * 32;
     t.limit = S;
     return t;
   };
-  auto tile_of = [=](int i) {
+  auto tile_of = [=](int i) __attribute__((always_inline)) {
     FwTile t;
     i = min(i, n_it - 1);
     t.win = i >= n_c;
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
   // tile]: the middle part is computed once per thread ahead of the loop, and a piece costs one table look-up and
   // one 64-bit multiply-add per tile; the fetching wavefronts share their SIMDs with the computing ones)
   const size_t pstride = (size_t)Hkv * ps * D;   // elements of a page
-  auto fetchp = [=](auto fast, int idx, int i, uint4& kr, uint4& vr) {
+  auto fetchp = [=](auto fast, int idx, int i, uint4& kr, uint4& vr) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast)::value;
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
     if (FAST) {
@@ -177,8 +177,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     kr = *(const uint4*)(t.win ? kp_w : kp_c);
     vr = *(const uint4*)(t.win ? vp_w : vp_c);
   };
-  auto fetch1 = [=](auto fast, int u, int i, uint4& kr, uint4& vr) { fetchp(fast, min(tid + u * T, 511), i, kr, vr); };
-  auto stashp = [=](auto fast, int idx, int i, int b, uint4 kr, uint4 vr) {
+  auto fetch1 = [=](auto fast, int u, int i, uint4& kr, uint4& vr) __attribute__((always_inline)) { fetchp(fast, min(tid + u * T, 511), i, kr, vr); };
+  auto stashp = [=](auto fast, int idx, int i, int b, uint4 kr, uint4 vr) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast)::value;
     unsigned char* base = lds + b * FW_BUF;
     const int kk = idx >> 4, kch = idx & 15, vd = idx >> 2, vko = (idx & 3) * 8;
@@ -195,9 +195,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_flash_wide_kernel(
     *(uint4*)(base + kk * FW_KROW + kch * 16) = cvt ? fw_to_f16(kr) : kr;
     *(uint4*)(base + FW_KBUF + vd * FW_VROW + vko * 2) = cvt ? fw_to_f16(vm) : vm;
   };
-  auto stash1 = [=](auto fast, int u, int i, int b, uint4 kr, uint4 vr) { stashp(fast, min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
+  auto stash1 = [=](auto fast, int u, int i, int b, uint4 kr, uint4 vr) __attribute__((always_inline)) { stashp(fast, min(tid + u * T, 511), i, b, kr, vr); };   // clamped duplicates rewrite the same bytes
   const int kperm = fa_perm(c);
-  auto compute = [=](auto fast, FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) {
+  auto compute = [=](auto fast, FaState& st, const uint4 (&qf)[8], const uint4 (&ql)[SPLIT ? 8 : 1], int i, int b) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast)::value;
     const FwTile t = FAST ? tile_fast(i) : tile_of(i);
     const unsigned char* kb = lds + b * FW_BUF + kperm * FW_KROW + 16 * h;
