@@ -67,7 +67,9 @@ typedef struct s2d2_ctx s2d2_ctx;
 /* Decoder shape.  Pre-norm blocks: RMSNorm, GQA attention with half-split RoPE, SwiGLU FFN
  * (n_experts == 0) or softmax-top-k MoE of SwiGLU experts (n_experts > 0: bf16 only, n_experts <= 256,
  * top_k <= 64; router = softmax over all experts, top-k by value with ties to the lower index, weights
- * renormalised to sum 1, no shared expert, no capacity limit). */
+ * renormalised to sum 1, no shared expert, no capacity limit).
+ * Limits (S2D2_EINVAL beyond them): n_layers <= 4096, 32 <= d_model <= 65536, n_q_heads <= 1024, head_dim in
+ * {32, 64, 128, 256}, d_ffn and d_expert <= 1048576, vocab <= 2097152. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t n_experts, top_k, d_expert;   /* all 0 for a dense model */

@@ -44,5 +44,33 @@ def build_lib(jobs: int = 6) -> str:
     return LIB
 
 
+def build_host_check() -> str:
+    """Builds tests/host/host_check: the library's objects with api.hip (all host-side argument checks and size
+    arithmetic) rebuilt under AddressSanitizer and UndefinedBehaviorSanitizer on the host side, linked with a driver
+    that calls every entry point with extreme and invalid arguments.  Device code is not instrumented."""
+    root = os.path.dirname(HERE)
+    out = os.path.join(HERE, "_build", "host_check")
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+        if src == "api.hip" or not os.path.exists(obj):
+            obj = _compile(src) if src != "api.hip" else obj
+        objs.append(obj)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xarch_host", "-fno-omit-frame-pointer"]
+    api_san = os.path.join(HERE, "_build", "api_san.o")
+    drv = os.path.join(HERE, "_build", "host_check.o")
+    host_san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+    cmds = [[_hipcc(), *FLAGS, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", api_san],
+            ["/opt/rocm/lib/llvm/bin/clang++", "-O1", "-g", "-std=c++17", *host_san, "-c", os.path.join(root, "tests", "host", "host_check.cpp"), "-o", drv],
+            [_hipcc(), "--offload-arch=gfx950", *host_san, "-fno-gpu-sanitize", drv, api_san,
+             *[o for o in objs if not o.endswith(os.sep + "api.o")], "-o", out]]
+    for cmd in cmds:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("host check build failed:\n" + " ".join(cmd) + "\n" + r.stderr)
+    return out
+
+
 if __name__ == "__main__":
     print(build_lib())

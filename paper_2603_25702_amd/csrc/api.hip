@@ -120,8 +120,9 @@ int operand_mode_of(const s2d2_model_desc& d) {
 int32_t check_desc(const s2d2_model_desc* d) {
   if (!d) return fail(S2D2_EINVAL, "model description is NULL");
   if (d->dtype != S2D2_F32 && d->dtype != S2D2_BF16) return fail(S2D2_EINVAL, "dtype must be S2D2_F32 or S2D2_BF16");
-  if (d->n_layers < 1 || d->d_model < 32 || d->vocab < 2) return fail(S2D2_EINVAL, "n_layers, d_model or vocab out of range");
-  if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) return fail(S2D2_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (d->n_layers < 1 || d->n_layers > 4096 || d->d_model < 32 || d->d_model > 65536 || d->vocab < 2) return fail(S2D2_EINVAL, "n_layers (1-4096), d_model (32-65536) or vocab out of range");
+  if (d->n_q_heads < 1 || d->n_q_heads > 1024 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) return fail(S2D2_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads, at most 1024");
+  if (d->d_ffn > (1 << 20) || d->d_expert > (1 << 20)) return fail(S2D2_EINVAL, "d_ffn and d_expert must not exceed 1048576");
   if (d->head_dim != 32 && d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return fail(S2D2_EINVAL, "head_dim must be 32, 64, 128 or 256");
   const int kq = d->dtype == S2D2_BF16 ? 32 : 16;  // one MFMA fragment must not straddle the end of K
   if (d->d_model % kq || (d->n_q_heads * d->head_dim) % kq) return fail(S2D2_EINVAL, "d_model and Hq*D must be multiples of %d", kq);
