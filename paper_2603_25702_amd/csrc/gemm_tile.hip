@@ -59,7 +59,10 @@ __device__ unsigned long long g_tile_ts[64];
 // of a row sit side by side in LDS and every weight operand is multiplied with both.
 // One row tile (index ty) of the workgroup's column tile and K split; false: there is no such row tile.
 template <int EPI, int PRO, int OPM, int WC>
-__device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const int bx, const int ty) {
+// z of KS: this workgroup's share of K; ncol: column tiles of the launch (numbering of the tiles' counters and
+// partials); wait_ok: every workgroup of the launch is resident at once, so the splits of a tile may wait for each other.
+__device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const int bx, const int ty, const int z, const int KS,
+                                               const int ncol, const bool wait_ok) {
   constexpr bool SPLIT = OPM == OPM_BF16X2;       // the activations come as two bf16 planes
   constexpr int NTH = 128 * WC;                   // 2 x WC wavefronts of 64 rows x 64 features each
   constexpr int XI = 1024 / NTH;                  // 16-byte chunks of an activation plane tile per thread
@@ -168,7 +171,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (a.K + TK - 1) / TK, KS = gridDim.z, z = blockIdx.z;
+  const int nk = (a.K + TK - 1) / TK;
   const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
   u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1], wst[WS][2][4];
   constexpr int XL = XI * (SPLIT ? 2 : 1);   // activation loads per thread and step
@@ -364,7 +367,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // contiguous bytes), device-coherent write-through stores and loads around the tile's counter word (a
   // __threadfence pair per workgroup instead made the launches 60 % slower: the fences are cache-wide); 16-row
   // blocks past the tile's rows are neither written nor read.
-  const size_t tile_id = (size_t)ty * gridDim.x + bx;
+  const size_t tile_id = (size_t)ty * ncol + bx;
   {
     uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
 #pragma unroll
@@ -386,7 +389,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // clears it for the next launch), bits 16-23 shares given up (bit 16 + z: split z will not finish its share).
   if (tid == 0) {
     int* ctr = &a.tile_counters[tile_id];
-    const bool wait_ok = (long long)gridDim.x * gridDim.y * KS <= (long long)a.coop_wgs;   // all workgroups of the launch can be resident at once
     int share = 0;
     const int prev = __hip_atomic_fetch_add(ctr, wait_ok ? 1 : 1 + (1 << (16 + z)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((prev & 0xff) == KS - 1) {
@@ -477,6 +479,13 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 template <int EPI, int PRO, int OPM, int WC>
 __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStreamArgs a) {
   constexpr int COLS = (EPI == SEPI_SWIGLU ? 2 : 4) * WC;   // 16-feature tiles per workgroup
+  // Three forms of the launch.  (1) plain: blockIdx = (column tile, first row tile, K split).  (2) xcd_order, see
+  // above.  (3) stream_k (= row tiles of the launch): 3/2 tiles per workgroup.  A launch of 1.5 x as many tiles as
+  // compute units otherwise runs two rounds, the second half empty; here workgroups 2j and 2j + 1 take tiles 3j and
+  // 3j + 2 whole and then one half of K of tile 3j + 1 each, so both arrive at the shared tile together and merge
+  // it as two splits (per XCD: its column tiles as in (2), tiles numbered row tile fastest, pairs = workgroups w, w + 8).  In every form a workgroup walks on over the row tiles past
+  // the expected ones (device-side row count above m_hint) as whole tiles.
+  const int w = blockIdx.x, sk_rows = a.stream_k, sk_cols = (a.NT + COLS - 1) / COLS;
   int bx = blockIdx.x, by = blockIdx.y;
   if (a.xcd_order) {
     const int i = blockIdx.x + gridDim.x * blockIdx.y, s_ = i >> 3;
@@ -484,9 +493,26 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
     by = s_ % (int)gridDim.y;
     if (bx * COLS >= a.NT) return;   // padding of the grid
   }
-  for (int ty = by;; ty += gridDim.y) {
-    if (!gemm_tile_body<EPI, PRO, OPM, WC>(a, bx, ty)) break;
-    __syncthreads();   // the next tile reuses the LDS arrays
+  const bool wait_ok = sk_rows > 0 || (long long)gridDim.x * gridDim.y * gridDim.z <= (long long)a.coop_wgs;
+  for (int it = 0;; ++it) {
+    int tx = bx, ty = by + it * (int)gridDim.y, z = blockIdx.z, ks = gridDim.z, ncol = gridDim.x;
+    bool open_end = true;   // the items of this kind end with the first row tile that does not exist
+    if (sk_rows > 0) {
+      ncol = sk_cols; z = 0; ks = 1;
+      if (it < 2) {
+        // pairs are formed inside an XCD (workgroups w and w + 8), and XCD w % 8 owns the column tiles c % 8 == w % 8
+        const int pair = w >> 4, role = (w >> 3) & 1;
+        const int t = 3 * pair + (it == 0 ? 2 * role : 1);   // tile of this XCD's list, row tile fastest
+        tx = (t / sk_rows) * 8 + (w & 7); ty = t % sk_rows; open_end = false;
+        if (it == 1) { z = role; ks = 2; }
+      } else {
+        const int t = w + (it - 2) * (int)gridDim.x;
+        tx = t % sk_cols; ty = sk_rows + t / sk_cols;
+      }
+    }
+    const bool did = gemm_tile_body<EPI, PRO, OPM, WC>(a, tx, ty, z, ks, ncol, wait_ok);
+    if (did) __syncthreads();   // the next tile reuses the LDS arrays
+    else if (open_end) break;
   }
 }
 
@@ -533,6 +559,13 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   dim3 grid(col_tiles, a.grouped == GROUP_NONE ? hint_tiles : row_tiles, KS), block(128 * WC);
   GemmStreamArgs b = a;
   b.xcd_order = a.grouped == GROUP_NONE && KS == 1 && grid.y > 1;
+  b.stream_k = 0;
+  if (b.xcd_order && WC == 4 && a.tile_partials && a.coop_wgs > 0 && 2 * live == 3LL * a.coop_wgs && (a.coop_wgs & 15) == 0 && (col_tiles & 7) == 0 &&
+      live <= a.tile_counter_cap && live * 2 * (WC / 2) <= a.tile_partial_cap && nk >= 8) {
+    b.stream_k = hint_tiles;   // see the kernel: 3/2 tiles per workgroup, one workgroup per compute unit
+    b.xcd_order = 0;
+    grid = dim3(a.coop_wgs, 1, 1);
+  }
   if (b.xcd_order) grid.x = (grid.x + 7) / 8 * 8;
   const int opm = operand_mode(a.x_lo);
   if (opm == OPM_F16) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_F16, WC>), grid, block, 0, st, b);

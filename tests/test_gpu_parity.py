@@ -264,6 +264,21 @@ def test_long_k_down_projection_shared_by_pairs_of_workgroups():
     run.eng.s2d2_status()
 
 
+def test_one_and_a_half_rounds_of_tiles_and_several_row_tiles_per_column():
+    """Launch forms of the tiled GEMM that only larger windows reach: 32 x 16 verifier rows against d_ffn = 6144 give
+    the gate / up projection 48 x 8 = 384 tiles, 1.5 per compute unit: pairs of workgroups take one tile each and
+    share a third one as two K splits; the same launch with the draft's 512 rows (192 tiles, four row tiles per
+    column) and the unembedding (several row tiles) deal their tiles XCD by XCD.  Two steps: the partial buffers and
+    tile counters are reused; the device status stays clean."""
+    cfg = I.ModelCfg("small-wide-ffn", 2, 512, 8, 4, 128, 6144, 32000)
+    lens = [20 + 7 * (n % 9) for n in range(32)]
+    case = H.make_case(cfg, 32, 16, lens, seed=31, synthetic_kv=True, page_size=16, room=64, norm_jitter=0.1)
+    run, rep = run_steps(case, 2, seqs=[0, 13, 31])
+    print("wide FFN, 384 tiles:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+    run.eng.s2d2_status()
+
+
 @pytest.mark.parametrize("act_planes", [1, 2, 3])
 def test_operand_modes_narrow_wide_long_k_and_moe(act_planes):
     """`act_planes` of the model description: GEMM inputs as one bf16 plane (1), as a high + low bf16 plane (2), or as
