@@ -395,7 +395,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
       share = (1 << z) | ((prev >> 16) & 0xff);   // the last arrival: its own share and every share given up so far
     } else if (wait_ok) {
       bool all = false;
-      for (int spins = 0; spins < 96 && !all; ++spins) {
+      for (int spins = 0; spins < a.merge_spins && !all; ++spins) {
         __builtin_amdgcn_s_sleep(8);
         all = (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
       }
@@ -558,6 +558,8 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   // expert-grouped launches, whose tile list lives on the device
   dim3 grid(col_tiles, a.grouped == GROUP_NONE ? hint_tiles : row_tiles, KS), block(128 * WC);
   GemmStreamArgs b = a;
+  const char* sp = getenv("S2D2_TILE_SPINS");   // test aid: 0 makes every split give its share up at once (the hand-over path)
+  b.merge_spins = sp ? atoi(sp) : 96;            // polls of about 1 us each
   b.xcd_order = a.grouped == GROUP_NONE && KS == 1 && grid.y > 1;
   b.stream_k = 0;
   if (b.xcd_order && WC == 4 && a.tile_partials && a.coop_wgs > 0 && 2 * live == 3LL * a.coop_wgs && (a.coop_wgs & 15) == 0 && (col_tiles & 7) == 0 &&

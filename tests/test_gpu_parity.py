@@ -249,6 +249,20 @@ def test_small_bf16_wide_windows_run_the_tiled_gemm(monkeypatch, tile_wc):
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
 
 
+def test_k_split_hand_over_when_no_split_waits(monkeypatch):
+    """The K splits of a tile of the tiled GEMM share its merge after a bounded wait; a split whose wait runs out
+    hands its share to the split that arrives last.  With the wait set to zero polls every split but the last gives
+    up at once, so the hand-over path (and the late give-up of a split that finds everybody there) does all the
+    merging; results are sums in split order either way.  Several steps with carried tokens: row counts above and
+    below the expected ones (workgroups that walk on to further row tiles, workgroups without rows)."""
+    monkeypatch.setenv("S2D2_TILE_SPINS", "0")
+    case = H.make_case(SMALL_BF16, 3, 16, [100, 257, 31], seed=13, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
+    run, rep = run_steps(case, 3)
+    print("hand-over:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+    run.eng.s2d2_status()
+
+
 def test_long_k_down_projection_shared_by_pairs_of_workgroups():
     """d_ffn = 4096: the residual-add GEMM of the down projection splits K over pairs of workgroups that hand
     their partial over through tagged words (narrow windows only); one and two 16-row tiles, several steps so
