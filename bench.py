@@ -28,12 +28,12 @@ HEADLINE, OTHERS = 4, (2, 3, 5)
 # step, from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (rocprofv3 --pmc on this file with
 # the default operand mode; a plain copy of 1 GiB reads FETCH_SIZE = 524300 KiB and WRITE_SIZE = 1048576 KiB, so
 # bytes = FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024).  Averages over all GEMM launches of two steps.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31226163, 3: 99851571, 4: 214282854, 5: 342542804}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31224730, 3: 99838362, 4: 248961946, 5: 342234516}
 STEP_TRAFFIC_BYTES = {   # all kernels of a step: (FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024) summed over the step's launches
-    2: (1690604.8 + 3417585.5 + 3215.8) * 2048 + (44688.0 + 56515.0 + 649.7) * 1024,
-    3: (3967121.5 + 11857950.8 + 41641.8) * 2048 + (1853523.1 + 4562378.3 + 10579.1) * 1024,
-    4: (20326855.9 + 25632438.4 + 159396.3) * 2048 + (3799751.6 + 9420704.5 + 29411.1) * 1024,
-    5: (4894689.1 + 277405.0 + 29207328.0 + 2658021.7) * 2048 + (2777070.1 + 14202.5 + 8588263.6 + 834874.7) * 1024,
+    2: (1690711.7 + 3417442.4 + 3216.7) * 2048 + (44688.0 + 56514.7 + 649.7) * 1024,
+    3: (3967150.0 + 11855898.6 + 41642.1) * 2048 + (1853714.9 + 4562755.6 + 10579.1) * 1024,
+    4: (20327096.9 + 29962083.2 + 159397.1) * 2048 + (3798303.6 + 10582643.0 + 29411.1) * 1024,
+    5: (4894710.8 + 277405.0 + 29176762.2 + 2658023.8) * 2048 + (2776547.1 + 14202.5 + 8588556.2 + 834879.3) * 1024,
 }
 
 
