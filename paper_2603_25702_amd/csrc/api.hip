@@ -216,7 +216,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
     c->pair_buf = cv.take<unsigned long long>((size_t)PAIR_CAP * 256);
   }
   c->dev_status = cv.take<int32_t>(64);
-  c->ts_scratch = cv.take<uint64_t>(832);
+  c->ts_scratch = cv.take<uint64_t>(1024);
   c->vws.chunks = vocab_chunks(d.vocab);
   c->vws.part = cv.take<float>(LR * (size_t)c->vws.chunks * 8);
   c->accept_tiles = cv.take<float>(accept_tile_floats(c->max_batch, d.vocab));

@@ -49,8 +49,15 @@ namespace s2d2 {
 
 static constexpr int TM = 128, TK = 64;
 #ifdef S2D2_KERNEL_TIMING
-__device__ unsigned long long g_tile_ts[64];
-#define S2D2_TTS(k) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && (blockIdx.z == 0 || (k) >= 4)) g_tile_ts[(k)] = wall_clock64(); } while (0)
+__device__ unsigned long long g_tile_ts[128 + 3 * 256];   // [128 + 3 id + k]: start, loop end, share known of every workgroup of the last down projection
+// stamps of the workgroup of column tile 0, row tile 0, split 0 in [slot * 24 + k], of the last column tile's last split
+// in [slot * 24 + 8 + k]; slot = epilogue kind, 4 = residual add with K <= 4096 (output projection)
+#define S2D2_TTS(k) do { if (threadIdx.x == 0 && ty == 0) { \
+    const int slot_ = (EPI == SEPI_ADD_F32 && a.K <= 4096) ? 4 : EPI; \
+    if (bx == 0 && z == 0) g_tile_ts[slot_ * 24 + (k)] = wall_clock64(); \
+    if (bx == ncol - 1 && z == KS - 1) g_tile_ts[slot_ * 24 + 8 + (k)] = wall_clock64(); } \
+  if (threadIdx.x == 0 && EPI == SEPI_ADD_F32 && a.K > 4096 && ((k) == 0 || (k) == 2 || (k) == 3)) { \
+    const int id_ = bx + ncol * (ty + (int)gridDim.y * z); if (id_ < 256) g_tile_ts[128 + 3 * id_ + ((k) == 0 ? 0 : (k) - 1)] = wall_clock64(); } } while (0)
 #else
 #define S2D2_TTS(k) do {} while (0)
 #endif
@@ -83,7 +90,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   const int tid = tid_, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, f = lane & 15;
   const int wr = wave / WC, wc = wave % WC;
-  S2D2_TTS(0);
   int m0, Mloc, expert = 0;
   if (a.grouped != GROUP_NONE) {
     if (ty >= *a.n_tiles) return false;
@@ -96,6 +102,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     if (m0 >= M) return false;
     Mloc = min(TM, M - m0);
   }
+  S2D2_TTS(0);
   const int KT = a.KT;
   // live 16-row blocks of this wavefront's 64 rows, as a scalar: the skips in the K loop are then plain scalar
   // branches and not execution-mask regions
@@ -214,6 +221,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     for (int j = 0; j < XL; ++j) load_x1(xr[d], xl[d], kb0 + d, j);
   store_x(xr[0], xl[0], 0, kb0);
   __syncthreads();
+  S2D2_TTS(7);
   constexpr int UN = WS * 2;   // unrolled steps: weight stage and register set / LDS buffer are compile-time
   // FULL: all UN steps exist.  The group that may end early is a second copy of the body: an exit out of the
   // unrolled body makes the compiler's wait-count bookkeeping drain every outstanding load in the first step of
@@ -517,8 +525,8 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
 }
 
 #ifdef S2D2_KERNEL_TIMING
-__global__ void tile_ts_copy_kernel(unsigned long long* out) { if (threadIdx.x < 64) out[threadIdx.x] = g_tile_ts[threadIdx.x]; }
-void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)out); }
+__global__ void tile_ts_copy_kernel(unsigned long long* out) { for (int i = threadIdx.x; i < 128 + 3 * 256; i += blockDim.x) out[i] = g_tile_ts[i]; }
+void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_kernel, dim3(1), dim3(128), 0, st, (unsigned long long*)out); }
 #else
 void launch_tile_ts_copy(hipStream_t, void*) {}
 #endif
