@@ -36,6 +36,9 @@
  *   carry_tokens[n,B] committed tokens of earlier blocks that are not cached yet; they occupy
  *                     positions seq_len .. block_pos0-1 (count = block_pos0 - seq_len if > 0).
  *   If seq_len >= block_pos0, the first seq_len - block_pos0 block positions are cached.
+ *   Token ids are device data the host cannot check: a forward reads an id outside [0, vocab) as mask_id
+ *   (never as an embedding row outside the table), and a logit row without one comparable value (all NaN)
+ *   proposes token 0.
  */
 #ifndef S2D2_H
 #define S2D2_H

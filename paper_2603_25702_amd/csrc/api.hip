@@ -157,6 +157,7 @@ size_t carve(s2d2_ctx* c, uint8_t* base) {
   const size_t R = c->rows_cap, LR = c->logit_cap, NB = c->max_batch;
   const size_t es = elt_size(d.dtype);
   c->plan.counts = cv.take<int32_t>(8);
+  c->plan.vocab = d.vocab;
   c->tmp_count = cv.take<int32_t>(8);
   c->plan.row_token = cv.take<int32_t>(R);
   c->plan.row_pos = cv.take<int32_t>(R);

@@ -3,17 +3,19 @@
 // (verifier / draft forwards of the batched configurations, the prompt prefill, and the grouped
 // expert GEMMs of the MoE FFN).
 //
-// A workgroup of eight wavefronts (2 x 4, one workgroup per compute unit) owns a tile of 128 rows x 256 output
-// features and walks K in steps of 64.  The activation tile goes through LDS (double-buffered, rows padded to 144
-// bytes per plane so that the 16-byte operand reads of a wavefront hit 64 distinct banks); it is requested two
-// steps before the step that multiplies it and is loaded once per compute unit.  The weight operands are read
-// straight from the packed copy, where one wavefront-wide 16-byte load is a complete A operand of
-// v_mfma_f32_16x16x32_bf16, through a ring of three register stages: while a step multiplies out of one stage, the
-// stage of the step before is refilled for the step after the next (HBM latency is more than a step of MFMA work).
-// All loads of a step are issued one or two at a time between its eight MFMA blocks.  Each wavefront computes
-// 64 rows x 64 features (4 x 4 MFMA tiles); for the gate/up pair of SwiGLU 64 rows x 32 features of each matrix, so
-// a workgroup tile is 128 x 128 there.  (A four-wavefront variant on 128 x 128 tiles, two workgroups per compute
-// unit, is kept as a tuning aid: it loads every activation tile twice per compute unit and measured 2-10 % slower.)
+// A workgroup of eight wavefronts (one workgroup per compute unit) owns a tile of 128 rows x 256 output features
+// and walks K in steps of 64.  The wavefronts stand side by side: each computes all 128 rows x 32 features (8 x 2
+// MFMA tiles; for the gate/up pair of SwiGLU 16 features of each matrix, so a workgroup tile is 128 x 128 there).
+// Every weight operand is then requested by exactly one wavefront, straight from the packed copy, where one
+// wavefront-wide 16-byte load is a complete A operand of v_mfma_f32_16x16x32_bf16, through a ring of three
+// register stages: while a step multiplies out of one stage, the stage of the step before is refilled for the
+// step after the next (HBM latency is more than a step of MFMA work).  (With the wavefronts 2 x 4 on 64 x 64
+// each, every weight operand was requested twice per compute unit: 80 KB per step through an address path of
+// 64 bytes per clock.)  The activation tile is loaded once per compute unit and goes through LDS (three buffers,
+// rows padded to 144 bytes per plane so that the 16-byte operand reads of a wavefront hit 64 distinct banks);
+// all eight wavefronts read all of it, four operand reads ahead of the MFMA pair that uses them.  All memory
+// requests of a step are issued one at a time between its MFMA pairs.  (A four-wavefront variant on 128 x 128
+// tiles, two workgroups per compute unit, is kept as a tuning aid.)
 //
 // K can be split over blockIdx.z when the tiles alone would leave compute units idle (few rows, narrow
 // outputs): every split writes its accumulators as an fp32 partial in register order (write-through
@@ -48,8 +50,16 @@
 namespace s2d2 {
 
 static constexpr int TM = 128, TK = 64;
+// Tuning constants of the K loop (measured on the batched configurations: 3 to 6 weight stages and 2 to 8 operand
+// reads in flight gave the same times within the run-to-run spread)
+#ifndef S2D2_TILE_WS
+#define S2D2_TILE_WS 3   // weight stages in flight
+#endif
+#ifndef S2D2_TILE_PD
+#define S2D2_TILE_PD 4   // LDS operand reads in flight per wavefront
+#endif
 #ifdef S2D2_KERNEL_TIMING
-__device__ unsigned long long g_tile_ts[128 + 3 * 256];   // [128 + 3 id + k]: start, loop end, share known of every workgroup of the last down projection
+__device__ unsigned long long g_tile_ts[1024];   // [128 + 3 id + k]: start, loop end, share known of every workgroup of the last down projection
 // stamps of the workgroup of column tile 0, row tile 0, split 0 in [slot * 24 + k], of the last column tile's last split
 // in [slot * 24 + 8 + k]; slot = epilogue kind, 4 = residual add with K <= 4096 (output projection)
 #define S2D2_TTS(k) do { if (threadIdx.x == 0 && ty == 0) { \
@@ -58,8 +68,18 @@ __device__ unsigned long long g_tile_ts[128 + 3 * 256];   // [128 + 3 id + k]: s
     if (bx == ncol - 1 && z == KS - 1) g_tile_ts[slot_ * 24 + 8 + (k)] = wall_clock64(); } \
   if (threadIdx.x == 0 && EPI == SEPI_ADD_F32 && a.K > 4096 && ((k) == 0 || (k) == 2 || (k) == 3)) { \
     const int id_ = bx + ncol * (ty + (int)gridDim.y * z); if (id_ < 256) g_tile_ts[128 + 3 * id_ + ((k) == 0 ? 0 : (k) - 1)] = wall_clock64(); } } while (0)
+// shader-clock sums over the K steps of the gate / up workgroup of tile (0, 0), per wavefront, in [896 + 16 wave + k]:
+// 8: whole steps, 15: number of steps; with S2D2_STEP_EIGHTHS=1 also k < 8: eighth k of the step's MFMA pairs (then
+// 8 holds the rest; every stamp waits for the LDS reads in flight, so the eighths cost about 35 clocks each)
+#ifndef S2D2_STEP_EIGHTHS
+#define S2D2_STEP_EIGHTHS 0
+#endif
+#define S2D2_STEP_CLK(k) do { __builtin_amdgcn_sched_barrier(0); const unsigned long long c_ = clock64(); \
+    if (k) step_sum[(k) - 1] += c_ - step_c; else { step_sum[15] += 1; if (step_c) step_sum[8] += c_ - step_c; } step_c = c_; __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define S2D2_TTS(k) do {} while (0)
+#define S2D2_STEP_CLK(k) do {} while (0)
+#define S2D2_STEP_EIGHTHS 0
 #endif
 
 // SPLIT: the activations come as a high- and a low-order bf16 plane (16 significant bits); both planes
@@ -71,14 +91,16 @@ template <int EPI, int PRO, int OPM, int WC>
 __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const int bx, const int ty, const int z, const int KS,
                                                const int ncol, const bool wait_ok) {
   constexpr bool SPLIT = OPM == OPM_BF16X2;       // the activations come as two bf16 planes
-  constexpr int NTH = 128 * WC;                   // 2 x WC wavefronts of 64 rows x 64 features each
+  constexpr int NTH = 128 * WC;                   // 2 WC wavefronts side by side, each all 128 rows x 32 features
+  constexpr int RBN = TM / 16, TN = 2;            // 16-row blocks and 16-feature accumulator columns of a wavefront
   constexpr int XI = 1024 / NTH;                  // 16-byte chunks of an activation plane tile per thread
-  constexpr int XD = WC == 4 ? 2 : 1;             // K steps the activation loads run ahead of their LDS store
+  constexpr int XD = 2;                           // register sets of the activation tile on its way to LDS
   constexpr int NACC = EPI == SEPI_SWIGLU ? 2 : 1;
-  constexpr int FT = 4 / NACC;                    // feature tiles per wavefront and matrix; FT * NACC = 4 accumulator columns
-  constexpr int WS = 3;                           // weight stages in flight
+  constexpr int FT = TN / NACC;                   // feature tiles per wavefront and matrix; FT * NACC = TN accumulator columns
+  constexpr int WS = S2D2_TILE_WS;                // weight stages in flight
   constexpr int XROW = (SPLIT ? 256 : 128) + 16;  // bytes per LDS row: 64 bf16 per plane + 16 bytes of padding
-  __shared__ __align__(16) uint8_t s_x[2][TM * XROW];
+  constexpr int XBUF = TM * XROW;                 // bytes of one activation tile in LDS
+  extern __shared__ __align__(16) uint8_t s_xd[];   // three activation tiles (dynamic: 102 KB with two planes)
   __shared__ int s_xrow[TM], s_orow[TM];
   __shared__ float s_rs[TM];
   __shared__ int s_share;
@@ -89,7 +111,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   asm volatile("" : "+v"(tid_));
   const int tid = tid_, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, f = lane & 15;
-  const int wr = wave / WC, wc = wave % WC;
   int m0, Mloc, expert = 0;
   if (a.grouped != GROUP_NONE) {
     if (ty >= *a.n_tiles) return false;
@@ -106,8 +127,8 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   const int KT = a.KT;
   // live 16-row blocks of this wavefront's 64 rows, as a scalar: the skips in the K loop are then plain scalar
   // branches and not execution-mask regions
-  const int rb_live = __builtin_amdgcn_readfirstlane(min(4, max(0, (Mloc - wr * 64 + 15) >> 4)));
-  const int nt0 = bx * (WC * FT) + wc * FT;
+  const int rb_live = __builtin_amdgcn_readfirstlane(min(RBN, (Mloc + 15) >> 4));
+  const int nt0 = (bx * (2 * WC) + wave) * FT;
 
   // ---- row maps: source row of X, row of the partial sums of squares, destination row, scale ----
   if (tid < 256) {
@@ -163,7 +184,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     xok[i] = xr_ >= 0;
     xsrc[i] = a.X + (size_t)(xok[i] ? xr_ : 0) * a.ldx + c16 * 8;
   }
-  const u32x4_t* wp[4];
+  const u32x4_t* wp[TN];
 #pragma unroll
   for (int t = 0; t < FT; ++t) {
     const int nt = min(nt0 + t, a.NT - 1);
@@ -172,20 +193,22 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   }
   const u32x4_t zero = {0u, 0u, 0u, 0u};
 
-  f32x4_t acc[4][4];
+  f32x4_t acc[RBN][TN];
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb)
+  for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TN; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int nk = (a.K + TK - 1) / TK;
   const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
-  u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1], wst[WS][2][4];
+  u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1], wst[WS][2][TN];
   constexpr int XL = XI * (SPLIT ? 2 : 1);   // activation loads per thread and step
   // One of the XL activation loads of a step: chunk j % XI of plane j / XI.  Unconditional: past the split's last
   // step the loads re-read an earlier tile into a register set nobody stores any more.
-  auto load_x1 = [&](u32x4_t (&r)[XI], u32x4_t (&l)[SPLIT ? XI : 1], int kb, int j) {
-    const int ko = min(min(kb, nk - 1) * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
+  // (plain: K is a multiple of the step, so the step's offset is the same for every lane)
+  auto load_x1 = [&](u32x4_t (&r)[XI], u32x4_t (&l)[SPLIT ? XI : 1], int kb, int j, bool plain = false) __attribute__((always_inline)) {
+    const int ko = plain ? min(kb, nk - 1) * TK
+                         : min(min(kb, nk - 1) * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
     if (j < XI) r[j] = *(const u32x4_t*)(xsrc[j] + ko);
     else l[j - XI] = *(const u32x4_t*)(xsrc[j - XI] + a.x_lo + ko);
   };
@@ -193,85 +216,145 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
     w = wp[t][(size_t)kt * 64];   // (no non-temporal hint here: the other row tiles re-read the weights through L2; with it the GEMMs of the batched configurations took 8-11 % longer)
   };
-  auto store_x = [&](const u32x4_t (&r)[XI], const u32x4_t (&l)[SPLIT ? XI : 1], int buf, int kb) {
+  // (plain: every row of the tile is live and K is a multiple of the step: nothing to zero)
+  auto store_x = [&](const u32x4_t (&r)[XI], const u32x4_t (&l)[SPLIT ? XI : 1], int buf, int kb, bool plain = false) __attribute__((always_inline)) {
     const bool kok = kb * TK + c16 * 8 < a.K;
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
-      const bool ok = xok[i] && kok;
-      *(u32x4_t*)(s_x[buf] + (rbase + (NTH / 8) * i) * XROW + c16 * 16) = ok ? r[i] : zero;
-      if (SPLIT) *(u32x4_t*)(s_x[buf] + (rbase + (NTH / 8) * i) * XROW + 128 + c16 * 16) = ok ? l[i] : zero;
+      const bool ok = plain || (xok[i] && kok);
+      *(u32x4_t*)(s_xd + buf * XBUF + (rbase + (NTH / 8) * i) * XROW + c16 * 16) = ok ? r[i] : zero;
+      if (SPLIT) *(u32x4_t*)(s_xd + buf * XBUF + (rbase + (NTH / 8) * i) * XROW + 128 + c16 * 16) = ok ? l[i] : zero;
     }
   };
 
-  // Step j (counted from this split's first step) multiplies out of weight stage j % WS and LDS buffer j & 1.
-  // Its activation tile travels through register set j % XD: requested during step j - XD, stored to LDS at the
-  // end of step j - 1.  The weights of step j + WS - 1 are requested during step j into the stage step j - 1 has
-  // just left.  Both kinds of requests are issued one at a time between the MFMA blocks of the step: a burst of
-  // all of them at the step's end keeps the address unit busy for as long as the MFMAs of the step take, with
-  // every wavefront of the workgroup waiting in it at the same time.
+  // Step j (counted from this split's first step) multiplies out of weight stage j % WS and LDS buffer j % 3.
+  // The weights of step j + WS - 1 are requested during step j into the stage step j - 1 has just left.  The
+  // activation tile of step j travels through register set j & 1: requested in the second half of step j - 4,
+  // stored to LDS in the middle of step j - 2.  The workgroup's one barrier per step sits in the first quarter of
+  // the step, ahead of that store.  So the store of step j (tile j + 2, into the buffer step j - 1 has read) comes
+  // after a barrier every wavefront reached after its step j - 1, and the reads of tile j + 2, which begin at the
+  // end of step j + 1, come after the barrier of step j + 1.  Nothing at a step's end waits for anything: the
+  // operand reads run PD MFMA pairs ahead straight across the step boundary (an LDS read takes 130-250 clocks
+  // here, an MFMA pair 32).  With two buffers, the store at the step's end and the barrier after it, every step
+  // began with that latency on all eight wavefronts at once and ended with the wait for the stores: a third of
+  // the step, measured with clock stamps per phase.
+  // All memory requests are issued one at a time between the MFMA pairs: a burst of all of them at one place
+  // keeps the address unit busy for as long as the MFMAs of the step take, with every wavefront of the
+  // workgroup waiting in it at the same time.
 #pragma unroll
   for (int st_ = 0; st_ < WS - 1; ++st_)
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) load_w1(wst[st_][k2][t], kb0 + st_, k2, t);
+      for (int t = 0; t < TN; ++t) load_w1(wst[st_][k2][t], kb0 + st_, k2, t);
 #pragma unroll
-  for (int d = 0; d < XD; ++d)
+  for (int d = 0; d < 2; ++d)
 #pragma unroll
     for (int j = 0; j < XL; ++j) load_x1(xr[d], xl[d], kb0 + d, j);
   store_x(xr[0], xl[0], 0, kb0);
+  store_x(xr[1], xl[1], 1, kb0 + 1);
+#pragma unroll
+  for (int d = 0; d < 2; ++d)
+#pragma unroll
+    for (int j = 0; j < XL; ++j) load_x1(xr[d], xl[d], kb0 + 2 + d, j);
   __syncthreads();
   S2D2_TTS(7);
-  constexpr int UN = WS * 2;   // unrolled steps: weight stage and register set / LDS buffer are compile-time
+  constexpr int UN = (WS % 3 ? 3 : 1) * (WS % 2 ? 2 : 1) * WS;   // unrolled steps: weight stage, register set and LDS buffer are compile-time
+  constexpr int PL = SPLIT ? 2 : 1, NB = 2 * RBN * PL, PD = S2D2_TILE_PD;   // operand reads (= MFMA pairs) of a step; reads in flight
+  constexpr int PB = 2, SB = RBN - 1;   // 16-row blocks (of 2 RBN) after which the barrier / the store come
+  const uint8_t* xlds = s_xd + f * XROW + g * 16;
+  auto xop = [&](int buf, int i) __attribute__((always_inline)) {   // operand of MFMA pair i of a step: K half, row block, plane
+    const int k2 = i / (RBN * PL), rb = (i / PL) % RBN, pl = i % PL;
+    return *(const u32x4_t*)(xlds + buf * XBUF + rb * 16 * XROW + pl * 128 + k2 * 64);
+  };
+  u32x4_t bq[PD];
+#pragma unroll
+  for (int i = 0; i < PD; ++i) bq[i] = xop(0, i);
+#ifdef S2D2_KERNEL_TIMING
+  unsigned long long step_sum[16] = {}, step_c = 0;
+#endif
   // FULL: all UN steps exist.  The group that may end early is a second copy of the body: an exit out of the
   // unrolled body makes the compiler's wait-count bookkeeping drain every outstanding load in the first step of
   // each group (weights and activations requested for later steps included), and with it the weight pipeline.
-  auto group = [&](auto full_tag, int kbase) __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_tag)::value;
+  // ROWS: all 128 rows live and K a multiple of the step: no branches in the step, no zeroing of operands, and the
+  // operand reads run ahead.
+  auto group = [&](auto full_tag, auto rows_tag, int kbase) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value, ROWS = decltype(rows_tag)::value;
 #pragma unroll
     for (int u_ = 0; u_ < UN; ++u_) {
       const int st_ = u_ % WS, rs_ = (u_ + WS - 1) % WS;   // stage multiplied from, stage refilled
       const int kb = kbase + u_;
       if (!FULL && kb >= kb1) break;
-      const uint8_t* xb = s_x[u_ & 1] + (wr * 64 + f) * XROW + g * 16;
-#pragma unroll
-      for (int blk = 0; blk < 8; ++blk) {
-        const int k2 = blk >> 2, rb = blk & 3;
-        if (rb < rb_live) {   // else: 16-row block past the tile's rows
-          const u32x4_t b = *(const u32x4_t*)(xb + rb * 16 * XROW + k2 * 64);
-#pragma unroll
-          for (int t = 0; t < 4; ++t)
-            acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], b, acc[rb][t]);
-          if (SPLIT) {
-            const u32x4_t bl = *(const u32x4_t*)(xb + rb * 16 * XROW + 128 + k2 * 64);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-              acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], bl, acc[rb][t]);
-          }
-        }
-        load_w1(wst[rs_][k2][rb], kb + WS - 1, k2, rb);
-        // activation loads: over the first four blocks when they are stored at this step's end, over all eight else
-        constexpr int XB = XD == 1 ? 4 : 8;
+      // what follows 16-row block blk of the step's 2 RBN: one of the 2 TN weight loads after every fourth block,
+      // the barrier, the store of tile kb + 2, and after it the loads of tile kb + 4 into the same register set
+      auto after_block = [&](int blk) __attribute__((always_inline)) {
+        constexpr int WEVERY = 2 * RBN / (2 * TN);
+        if (blk % WEVERY == 0) load_w1(wst[rs_][(blk / WEVERY) / TN][(blk / WEVERY) % TN], kb + WS - 1, (blk / WEVERY) / TN, (blk / WEVERY) % TN);
+        // The barrier is the bare instruction: no wait for outstanding LDS traffic in front of it (the operand reads
+        // in flight would have to drain, and the pipeline to refill, on all wavefronts at once).  None is needed: a
+        // wavefront's LDS accesses complete in order, the store of the step before was followed by operand reads whose
+        // values this wavefront has already multiplied, and so were its reads of the buffer the others overwrite next.
+        // (The "memory" clobber keeps the compiler from moving LDS accesses across it.)
+        if (blk == PB) asm volatile("s_barrier" ::: "memory");
+        if (blk == SB && kb + 2 < kb1) store_x(xr[u_ & 1], xl[u_ & 1], (u_ + 2) % 3, kb + 2, ROWS);
 #pragma unroll
         for (int j = 0; j < XL; ++j)
-          if (j * XB / XL == blk) load_x1(xr[u_ % XD], xl[u_ % XD], kb + XD, j);
+          if (SB + 1 + j * (2 * RBN - SB - 1) / XL == blk) load_x1(xr[u_ & 1], xl[u_ & 1], kb + 4, j, ROWS);
+      };
+      if (ROWS) {
+        S2D2_STEP_CLK(0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const int k2 = i / (RBN * PL), rb = (i / PL) % RBN;
+#pragma unroll
+          for (int t = 0; t < TN; ++t)
+            acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], bq[i % PD], acc[rb][t]);
+          // (past the split's last step this reads some tile nobody multiplies)
+          bq[i % PD] = i + PD < NB ? xop(u_ % 3, i + PD) : xop((u_ + 1) % 3, i + PD - NB);
+          if (i % PL == PL - 1) after_block(i / PL);
+          // (without this fence the instruction scheduler moves every read back down to right before its MFMA pair)
+          __builtin_amdgcn_sched_barrier(0);
+          if (S2D2_STEP_EIGHTHS && i % (NB / 8) == NB / 8 - 1) S2D2_STEP_CLK(1 + i / (NB / 8));
+        }
+      } else {
+#pragma unroll
+        for (int blk = 0; blk < 2 * RBN; ++blk) {
+          const int k2 = blk / RBN, rb = blk % RBN;
+          if (rb < rb_live) {   // else: 16-row block past the tile's rows
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) {
+              const u32x4_t b = xop(u_ % 3, blk * PL + pl);
+#pragma unroll
+              for (int t = 0; t < TN; ++t)
+                acc[rb][t] = mfma_16x16x32<OPM>(wst[st_][k2][t], b, acc[rb][t]);
+            }
+          }
+          after_block(blk);
+        }
       }
-      if (kb + 1 < kb1) store_x(xr[(u_ + 1) % XD], xl[(u_ + 1) % XD], (u_ + 1) & 1, kb + 1);
-      __syncthreads();
     }
   };
   int kbase = kb0;
-  for (; kbase + UN <= kb1; kbase += UN) group(std::true_type{}, kbase);
-  if (kbase < kb1) group(std::false_type{}, kbase);
+  if (rb_live == RBN && a.K % TK == 0) {
+    for (; kbase + UN <= kb1; kbase += UN) group(std::true_type{}, std::true_type{}, kbase);
+    if (kbase < kb1) group(std::false_type{}, std::true_type{}, kbase);
+  } else {
+    for (; kbase + UN <= kb1; kbase += UN) group(std::true_type{}, std::false_type{}, kbase);
+    if (kbase < kb1) group(std::false_type{}, std::false_type{}, kbase);
+  }
 
   if (acc[0][0][0] == 12345.678f) return true;
+#ifdef S2D2_KERNEL_TIMING
+  if (EPI == SEPI_SWIGLU && bx == 0 && ty == 0 && z == 0 && lane == 0)
+    for (int k = 0; k < 16; ++k) g_tile_ts[896 + 16 * wave + k] = step_sum[k];
+#endif
   S2D2_TTS(2);
 
   // ---- epilogue of one unit: v0 (and v1, the up projection, for SwiGLU) = accumulator(s) of row block rb, feature
   // tile nt0 + t of this wavefront: v[i] = Y[row wr*64 + rb*16 + f][feature (nt0 + t)*16 + 4 g + i].  rb and t may
   // be run-time values (the merge of a K split hands over sums it has just formed). ----
   auto epi_unit = [&](const int rb, const int t, const f32x4_t& v0, const f32x4_t& v1) __attribute__((always_inline)) {
-    const int r = wr * 64 + rb * 16 + f;
+    const int r = rb * 16 + f;
     const bool live = r < Mloc;
     const int orow = live ? s_orow[r] : 0;
     const float rs = s_rs[r];
@@ -362,7 +445,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 
   if (KS == 1) {
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RBN; ++rb)
 #pragma unroll
       for (int t = 0; t < FT; ++t) epi_unit(rb, t, acc[rb][NACC * t], acc[rb][NACC == 2 ? 2 * t + 1 : 0]);
     __builtin_amdgcn_s_waitcnt(0);
@@ -379,14 +462,14 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   {
     uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      if (wr * 64 + rb * 16 >= Mloc) continue;   // uniform over the wavefront
+    for (int rb = 0; rb < RBN; ++rb) {
+      if (rb * 16 >= Mloc) continue;   // uniform over the wavefront
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
+      for (int t = 0; t < TN; ++t) {
         const f32x4_t v = acc[rb][t];
-        __hip_atomic_store(mine + ((rb * 4 + t) * 2) * NTH, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
+        __hip_atomic_store(mine + ((rb * TN + t) * 2) * NTH, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mine + ((rb * 4 + t) * 2 + 1) * NTH, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
+        __hip_atomic_store(mine + ((rb * TN + t) * 2 + 1) * NTH, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
@@ -424,7 +507,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // The partials of all units of a share and of all splits are requested together (at most 128 registers) and
   // added in split order: one memory round trip per share.
   const uint64_t* src0 = (const uint64_t*)a.tile_partials + (tile_id * KS) * (32 * NTH) + tid;
-  constexpr int NU = 4 * FT;
+  constexpr int NU = RBN * FT;
   auto merge = [&](auto ksm_tag) __attribute__((always_inline)) {
     constexpr int KSM = decltype(ksm_tag)::value;   // KS <= KSM
     constexpr int BU = 32 / (NACC * KSM) < NU / 2 ? 32 / (NACC * KSM) : NU / 2;   // units per round: a whole share (at most NU / 2 units) within 128 registers
@@ -435,20 +518,20 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 #pragma unroll
         for (int j = 0; j < BU; ++j) {
           const int u = u0 + KS * j, rb = u / FT, t = u % FT;
-          const bool ok = u < NU && wr * 64 + rb * 16 < Mloc;   // uniform over the wavefront
+          const bool ok = u < NU && rb * 16 < Mloc;   // uniform over the wavefront
 #pragma unroll
           for (int c = 0; c < NACC; ++c)
 #pragma unroll
             for (int zz = 0; zz < KSM; ++zz)
 #pragma unroll
               for (int e = 0; e < 2; ++e)
-                v[j][c][zz][e] = (ok && zz < KS) ? __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + ((rb * 4 + NACC * t + c) * 2 + e) * NTH,
+                v[j][c][zz][e] = (ok && zz < KS) ? __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + ((rb * TN + NACC * t + c) * 2 + e) * NTH,
                                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
         }
 #pragma unroll
         for (int j = 0; j < BU; ++j) {
           const int u = u0 + KS * j, rb = u / FT, t = u % FT;
-          if (u >= NU || wr * 64 + rb * 16 >= Mloc) continue;   // uniform over the wavefront
+          if (u >= NU || rb * 16 >= Mloc) continue;   // uniform over the wavefront
           f32x4_t sum[NACC];
 #pragma unroll
           for (int c = 0; c < NACC; ++c) {
@@ -525,7 +608,7 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
 }
 
 #ifdef S2D2_KERNEL_TIMING
-__global__ void tile_ts_copy_kernel(unsigned long long* out) { for (int i = threadIdx.x; i < 128 + 3 * 256; i += blockDim.x) out[i] = g_tile_ts[i]; }
+__global__ void tile_ts_copy_kernel(unsigned long long* out) { for (int i = threadIdx.x; i < 1024; i += blockDim.x) out[i] = g_tile_ts[i]; }
 void launch_tile_ts_copy(hipStream_t st, void* out) { S2D2_LAUNCH(tile_ts_copy_kernel, dim3(1), dim3(128), 0, st, (unsigned long long*)out); }
 #else
 void launch_tile_ts_copy(hipStream_t, void*) {}
@@ -578,9 +661,22 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   }
   if (b.xcd_order) grid.x = (grid.x + 7) / 8 * 8;
   const int opm = operand_mode(a.x_lo);
-  if (opm == OPM_F16) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_F16, WC>), grid, block, 0, st, b);
-  else if (opm == OPM_BF16X2) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>), grid, block, 0, st, b);
-  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16, WC>), grid, block, 0, st, b);
+  // three activation tiles in LDS (54 KB; 102 KB with two planes, above the 64 KB a kernel gets without asking)
+  const unsigned lds = 3u * TM * ((opm == OPM_BF16X2 ? 256 : 128) + 16);
+  static bool lds_set[3][64];
+  const int oi = opm == OPM_F16 ? 0 : opm == OPM_BF16X2 ? 1 : 2;
+  int dev = 0;
+  hipGetDevice(&dev);
+  if (dev >= 0 && dev < 64 && !lds_set[oi][dev]) {
+    const void* fn = opm == OPM_F16      ? (const void*)gemm_tile_kernel<EPI, PRO, OPM_F16, WC>
+                     : opm == OPM_BF16X2 ? (const void*)gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>
+                                         : (const void*)gemm_tile_kernel<EPI, PRO, OPM_BF16, WC>;
+    // on failure the launch below fails too, and the entry point reports that error
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess) lds_set[oi][dev] = true;
+  }
+  if (opm == OPM_F16) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_F16, WC>), grid, block, lds, st, b);
+  else if (opm == OPM_BF16X2) S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>), grid, block, lds, st, b);
+  else S2D2_LAUNCH((gemm_tile_kernel<EPI, PRO, OPM_BF16, WC>), grid, block, lds, st, b);
 }
 
 template <int EPI, int PRO>

@@ -10,6 +10,11 @@
 
 namespace s2d2 {
 
+// The token arrays live on the device and cannot be checked by the host: an id outside the vocabulary (a caller's
+// mistake, or the proposal of a logit row without a single comparable value) becomes [MASK] instead of an
+// embedding row outside the table.
+__device__ __forceinline__ int in_vocab(int tok, int vocab, int mask_id) { return (unsigned)tok < (unsigned)vocab ? tok : mask_id; }
+
 __global__ __launch_bounds__(1024) void plan_kernel(
     int verify, int shifted, int N, int B, int mask_id, int ar_mask, const int32_t* __restrict__ seq_len,
     const int32_t* __restrict__ pos0, const int32_t* __restrict__ block,
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
           ++k;
         }
       }
-      p.row_token[r] = tok;
+      p.row_token[r] = in_vocab(tok, p.vocab, mask_id);
       p.row_pos[r] = S + t;
       p.row_seq[r] = n;
       p.row_lo[r] = row0;
@@ -109,7 +114,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
     stage_lead[n] = rows;
     for (int t = 0; t < rows; ++t) {
       const int r = row0 + t;
-      p.row_token[r] = t < nc ? car[t] : blk[c + (t - nc)];
+      p.row_token[r] = in_vocab(t < nc ? car[t] : blk[c + (t - nc)], p.vocab, mask_id);
       p.row_pos[r] = S + t;
       p.row_seq[r] = n;
       p.row_lo[r] = row0;
@@ -130,7 +135,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(
       if (t < nc) tok = car[t];
       else if (t < lead) tok = blk[c + (t - nc)];
       else tok = xh[j + (t - lead)];
-      p.row_token[r] = tok;
+      p.row_token[r] = in_vocab(tok, p.vocab, mask_id);
       p.row_pos[r] = S + t;
       p.row_seq[r] = n;
       p.row_lo[r] = row0;

@@ -144,6 +144,7 @@ struct Plan {
   int32_t* seq_lead;    // [max_batch] leading causal rows before C_t (carry + pending)
   int32_t* seq_j;       // [max_batch] first masked block index (B if none)
   int32_t* seq_L;       // [max_batch] |C_t|
+  int32_t vocab;        // token ids outside [0, vocab) in the caller's state are read as [MASK]
 };
 
 struct KvGeom {

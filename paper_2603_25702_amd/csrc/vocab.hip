@@ -130,7 +130,7 @@ __global__ void vocab_draft_final_kernel(const float* __restrict__ part, int chu
   if (threadIdx.x != 0) return;
   const int o = logit_seq ? logit_seq[row] * B + logit_idx[row] : row;
   const float inv = 1.0f / s.z;
-  xhat[o] = s.arg;
+  xhat[o] = s.arg < V ? s.arg : 0;   // no comparable logit in the row (all NaN): the first index, as an arg-max over NaNs gives
   p[o] = inv;
   lse[o] = s.m + logf(s.z);
   margin[o] = inv - expf(s.m2 - s.m) * inv;

@@ -180,6 +180,35 @@ def test_same_inputs_give_bit_identical_outputs(d_ffn):
             assert np.array_equal(outs[0][k], outs[1][k]), k
 
 
+def test_token_ids_outside_the_vocabulary_are_read_as_mask_and_nothing_else_changes():
+    """Device-side ids cannot be checked by the host.  A committed block token with an id outside [0, vocab)
+    must embed as [MASK]: the step equals, bit for bit, the step of a model whose token T has the [MASK]
+    embedding row, run with T at that position."""
+    cfg = I.ModelCfg("small-bf16-ids", 2, 512, 8, 4, 128, 1536, 32000)
+    W = I.gen_weights(cfg, 6)
+    T = 1234
+    W["embed"][T] = W["embed"][cfg.mask_id]
+    outs = []
+    for bad in (T, 2 ** 30, -7):
+        case = H.make_case(cfg, 2, 4, [50, 70], seed=6, synthetic_kv=True, page_size=16, room=32, W=W)
+        case.states[0].block[0] = bad          # a committed position in front of the masked span
+        case.states[1].block[:2] = [17, bad]
+        run = H.DeviceRun(case)
+        run.step(Params(step=1, seed=5), advance=False)
+        g = run.fetch()
+        assert (g["status"] == 0).all()
+        outs.append(g)
+    for other in outs[1:]:
+        for k in outs[0]:
+            if k in ("block_tokens",):
+                continue   # holds the id itself
+            if k in ("logits", "logits_ver"):
+                n = int((outs[0]["logit_row_of" if k == "logits" else "logit_row_of_ver"] >= 0).sum())
+                assert np.isfinite(other[k][:n]).all() and np.array_equal(outs[0][k][:n], other[k][:n]), k
+            else:
+                assert np.array_equal(outs[0][k], other[k]), k
+
+
 def test_kv_append_reports_enospc_without_writing():
     case = H.make_case(TINY, 1, 4, [30], seed=1, synthetic_kv=True, page_size=8, room=1)  # capacity 32
     run = H.DeviceRun(case)
