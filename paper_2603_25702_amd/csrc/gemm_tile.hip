@@ -130,9 +130,27 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   const int rb_live = __builtin_amdgcn_readfirstlane(min(RBN, (Mloc + 15) >> 4));
   const int nt0 = (bx * (2 * WC) + wave) * FT;
 
+  // ---- the weights of the first steps: their addresses need no row map, and their way from memory is the longest
+  // of the prologue; they are requested below while the row maps' partial sums are on their way ----
+  const int nk = (a.K + TK - 1) / TK;
+  const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
+  const u32x4_t* wp[TN];
+#pragma unroll
+  for (int t = 0; t < FT; ++t) {
+    const int nt = min(nt0 + t, a.NT - 1);
+    wp[t * NACC] = (const u32x4_t*)a.Wp + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
+    if (NACC == 2) wp[t * NACC + 1] = (const u32x4_t*)a.Wp2 + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
+  }
+  u32x4_t wst[WS][2][TN];
+  auto load_w1 = [&](u32x4_t& w, int kb, int k2, int t) __attribute__((always_inline)) {
+    const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
+    w = wp[t][(size_t)kt * 64];   // (no non-temporal hint here: the other row tiles re-read the weights through L2; with it the GEMMs of the batched configurations took 8-11 % longer)
+  };
+
   // ---- row maps: source row of X, row of the partial sums of squares, destination row, scale ----
-  if (tid < 256) {
-    const int r = tid >> 1, hf = tid & 1;   // two threads per row
+  {
+    constexpr int TPR = NTH / TM;           // threads per row
+    const int r = tid / TPR, hf = tid % TPR;
     int xrow = -1, orow = -1, ssrow = 0;
     float ow = 1.f;
     if (r < Mloc) {
@@ -145,25 +163,37 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
         xrow = a.gather ? a.gather[s] : s; ssrow = xrow; orow = s;
       }
     }
+    // 1/rms from the producer's partial sums of squares: independent 16-byte loads, 16 in flight per thread and round
+    // (one round up to 64 TPR partials per row), not a chain of L2 round trips
+    const float* pp = PRO == SPRO_BF16S ? a.ss_part + (size_t)ssrow * a.ss_stride : nullptr;
+    const bool vec = PRO == SPRO_BF16S && (a.ss_count & 3) == 0 && (a.ss_stride & 3) == 0;
+    const int n4 = (PRO == SPRO_BF16S && r < Mloc && vec) ? a.ss_count >> 2 : 0;
+    float4 t[16];
+    if (PRO == SPRO_BF16S) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) t[j] = (hf + TPR * j < n4) ? ((const float4*)pp)[hf + TPR * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int st_ = 0; st_ < WS - 1; ++st_)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int tt = 0; tt < TN; ++tt) load_w1(wst[st_][k2][tt], kb0 + st_, k2, tt);
     float rs = ow;
     if (PRO == SPRO_BF16S) {
       float v = 0.f;
-      if (r < Mloc) {   // independent 16-byte loads, all in flight at once per round (not a chain of L2 round trips)
-        const float* pp = a.ss_part + (size_t)ssrow * a.ss_stride;
-        if ((a.ss_count & 3) == 0 && (a.ss_stride & 3) == 0) {
-          const int n4 = a.ss_count >> 2;
-          for (int i0 = hf; i0 < n4; i0 += 32) {
-            float4 t[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) t[j] = (i0 + 2 * j < n4) ? ((const float4*)pp)[i0 + 2 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int j = 0; j < 16; ++j) v += (t[j].x + t[j].y) + (t[j].z + t[j].w);
+      for (int i0 = hf + 16 * TPR; i0 < n4; i0 += 16 * TPR) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v += (t[j].x + t[j].y) + (t[j].z + t[j].w);
-          }
-        } else {
-          for (int i = hf; i < a.ss_count; i += 2) v += pp[i];
-        }
+        for (int j = 0; j < 16; ++j) t[j] = (i0 + TPR * j < n4) ? ((const float4*)pp)[i0 + TPR * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v += (t[j].x + t[j].y) + (t[j].z + t[j].w);
       }
-      v += __shfl_xor(v, 1, 64);
+      if (!vec && r < Mloc)
+        for (int i = hf; i < a.ss_count; i += TPR) v += pp[i];
+#pragma unroll
+      for (int off = 1; off < TPR; off <<= 1) v += __shfl_xor(v, off, 64);
       rs *= 1.0f / sqrtf(v / (float)a.K + a.eps);
     }
     if (hf == 0) { s_xrow[r] = xrow; s_orow[r] = orow; s_rs[r] = rs; }
@@ -184,13 +214,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     xok[i] = xr_ >= 0;
     xsrc[i] = a.X + (size_t)(xok[i] ? xr_ : 0) * a.ldx + c16 * 8;
   }
-  const u32x4_t* wp[TN];
-#pragma unroll
-  for (int t = 0; t < FT; ++t) {
-    const int nt = min(nt0 + t, a.NT - 1);
-    wp[t * NACC] = (const u32x4_t*)a.Wp + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
-    if (NACC == 2) wp[t * NACC + 1] = (const u32x4_t*)a.Wp2 + (size_t)expert * a.expert_stride + (size_t)nt * KT * 64 + lane;
-  }
   const u32x4_t zero = {0u, 0u, 0u, 0u};
 
   f32x4_t acc[RBN][TN];
@@ -199,9 +222,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 #pragma unroll
     for (int t = 0; t < TN; ++t) acc[rb][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (a.K + TK - 1) / TK;
-  const int kb0 = (int)((long long)z * nk / KS), kb1 = (int)((long long)(z + 1) * nk / KS);   // this split's K steps
-  u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1], wst[WS][2][TN];
+  u32x4_t xr[XD][XI], xl[XD][SPLIT ? XI : 1];
   constexpr int XL = XI * (SPLIT ? 2 : 1);   // activation loads per thread and step
   // One of the XL activation loads of a step: chunk j % XI of plane j / XI.  Unconditional: past the split's last
   // step the loads re-read an earlier tile into a register set nobody stores any more.
@@ -211,10 +232,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
                          : min(min(kb, nk - 1) * TK + c16 * 8, a.K - 8) - c16 * 8;   // in bounds; columns at or past K are zeroed in store_x
     if (j < XI) r[j] = *(const u32x4_t*)(xsrc[j] + ko);
     else l[j - XI] = *(const u32x4_t*)(xsrc[j - XI] + a.x_lo + ko);
-  };
-  auto load_w1 = [&](u32x4_t& w, int kb, int k2, int t) {
-    const int kt = min(kb * 2 + k2, KT - 1);   // past the end: some valid tile, multiplied with zeros
-    w = wp[t][(size_t)kt * 64];   // (no non-temporal hint here: the other row tiles re-read the weights through L2; with it the GEMMs of the batched configurations took 8-11 % longer)
   };
   // (plain: every row of the tile is live and K is a multiple of the step: nothing to zero)
   auto store_x = [&](const u32x4_t (&r)[XI], const u32x4_t (&l)[SPLIT ? XI : 1], int buf, int kb, bool plain = false) __attribute__((always_inline)) {
@@ -241,12 +258,6 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // All memory requests are issued one at a time between the MFMA pairs: a burst of all of them at one place
   // keeps the address unit busy for as long as the MFMAs of the step take, with every wavefront of the
   // workgroup waiting in it at the same time.
-#pragma unroll
-  for (int st_ = 0; st_ < WS - 1; ++st_)
-#pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-      for (int t = 0; t < TN; ++t) load_w1(wst[st_][k2][t], kb0 + st_, k2, t);
 #pragma unroll
   for (int d = 0; d < 2; ++d)
 #pragma unroll
