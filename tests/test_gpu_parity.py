@@ -278,6 +278,17 @@ def test_small_bf16_wide_windows_run_the_tiled_gemm(monkeypatch, tile_wc):
     assert rep.max_logit_err_draft <= H.LOGIT_RTOL
 
 
+def test_tiled_gemm_with_k_that_ends_in_half_a_step():
+    """d_model 480 and d_ffn 1504 are multiples of 32 but not of the tiled GEMM's K step of 64: every projection ends
+    in a half-filled step (columns past K zeroed when the activation tile is staged, the weight tile index clamped),
+    on full 128-row tiles (8 x 32 verifier rows) as on the ragged draft tile."""
+    cfg = I.ModelCfg("small-bf16-k-tail", 2, 480, 8, 4, 128, 1504, 32000)
+    case = H.make_case(cfg, 8, 16, [60, 33, 97, 16, 70, 41, 52, 85], seed=17, synthetic_kv=True, page_size=16, room=96, norm_jitter=0.1)
+    run, rep = run_steps(case, 2)
+    print("k tail:", rep)
+    assert rep.max_logit_err_draft <= H.LOGIT_RTOL and rep.max_logit_err_verify <= H.LOGIT_RTOL
+
+
 def test_k_split_hand_over_when_no_split_waits(monkeypatch):
     """The K splits of a tile of the tiled GEMM share its merge after a bounded wait; a split whose wait runs out
     hands its share to the split that arrives last.  With the wait set to zero polls every split but the last gives
