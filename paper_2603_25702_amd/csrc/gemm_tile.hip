@@ -583,10 +583,15 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   constexpr int COLS = (EPI == SEPI_SWIGLU ? 2 : 4) * WC;   // 16-feature tiles per workgroup
   // Three forms of the launch.  (1) plain: blockIdx = (column tile, first row tile, K split).  (2) xcd_order, see
   // above.  (3) stream_k (= row tiles of the launch): 3/2 tiles per workgroup.  A launch of 1.5 x as many tiles as
-  // compute units otherwise runs two rounds, the second half empty; here workgroups 2j and 2j + 1 take tiles 3j and
-  // 3j + 2 whole and then one half of K of tile 3j + 1 each, so both arrive at the shared tile together and merge
-  // it as two splits (per XCD: its column tiles as in (2), tiles numbered row tile fastest, pairs = workgroups w, w + 8).  In every form a workgroup walks on over the row tiles past
-  // the expected ones (device-side row count above m_hint) as whole tiles.
+  // compute units otherwise runs two rounds, the second half empty; here every workgroup takes one tile whole and
+  // then one half of K of a tile it shares with its neighbour on the XCD (workgroups w and w + 8), so both arrive at
+  // the shared tile together and merge it as two splits.  Per XCD: its column tiles as in (2), tiles numbered row
+  // tile fastest; its P workgroups take the first P tiles whole and the last P / 2 as halves.  Both parts are whole
+  // columns (the host checks that the row tiles divide P / 2), so the weights of a column are read in one of the two
+  // phases only, by all its row tiles at the same time.  (With the shared tile taken out of the middle of every
+  // three, each column's weights had left the XCD's L2 between the phases and came in from memory twice: 551 MB
+  // fetched per launch of the 8 B model's gate / up projection against 201 MB of weights.)  In every form a
+  // workgroup walks on over the row tiles past the expected ones (device-side row count above m_hint) as whole tiles.
   const int w = blockIdx.x, sk_rows = a.stream_k, sk_cols = (a.NT + COLS - 1) / COLS;
   int bx = blockIdx.x, by = blockIdx.y;
   if (a.xcd_order) {
@@ -602,11 +607,11 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
     if (sk_rows > 0) {
       ncol = sk_cols; z = 0; ks = 1;
       if (it < 2) {
-        // pairs are formed inside an XCD (workgroups w and w + 8), and XCD w % 8 owns the column tiles c % 8 == w % 8
-        const int pair = w >> 4, role = (w >> 3) & 1;
-        const int t = 3 * pair + (it == 0 ? 2 * role : 1);   // tile of this XCD's list, row tile fastest
+        // XCD w % 8 owns the column tiles c % 8 == w % 8; wl: this workgroup among the P of its XCD
+        const int wl = w >> 3, P = (int)gridDim.x >> 3;
+        const int t = it == 0 ? wl : P + (wl >> 1);   // tile of this XCD's list, row tile fastest
         tx = (t / sk_rows) * 8 + (w & 7); ty = t % sk_rows; open_end = false;
-        if (it == 1) { z = role; ks = 2; }
+        if (it == 1) { z = wl & 1; ks = 2; }
       } else {
         const int t = w + (it - 2) * (int)gridDim.x;
         tx = t % sk_cols; ty = sk_rows + t / sk_cols;
@@ -664,7 +669,7 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   b.merge_spins = sp ? atoi(sp) : 96;            // polls of about 1 us each
   b.xcd_order = a.grouped == GROUP_NONE && KS == 1 && grid.y > 1;
   b.stream_k = 0;
-  if (b.xcd_order && WC == 4 && a.tile_partials && a.coop_wgs > 0 && 2 * live == 3LL * a.coop_wgs && (a.coop_wgs & 15) == 0 && (col_tiles & 7) == 0 &&
+  if (b.xcd_order && WC == 4 && a.tile_partials && a.coop_wgs > 0 && 2 * live == 3LL * a.coop_wgs && (a.coop_wgs & 15) == 0 && (col_tiles & 7) == 0 && (a.coop_wgs / 16) % hint_tiles == 0 &&
       live <= a.tile_counter_cap && live * 2 * (WC / 2) <= a.tile_partial_cap && nk >= 8) {
     b.stream_k = hint_tiles;   // see the kernel: 3/2 tiles per workgroup, one workgroup per compute unit
     b.xcd_order = 0;
