@@ -600,9 +600,21 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
     by = s_ % (int)gridDim.y;
     if (bx * COLS >= a.NT) return;   // padding of the grid
   }
+  // (4) split_xcd: K splits dealt to XCDs.  In the plain order XCD i % 8 gets the column tiles c % 8 == i % 8 with all
+  // their K splits, so every XCD reads all of the activation (for the 8 B model's down projection 8 x 12.6 MB, as
+  // much as the weights).  Here XCD x takes split x % KS only, i.e. 1 / KS of the activation's columns, and among
+  // the 8 / KS XCDs of a split each takes whole columns of tiles, all row tiles of a column next to each other.
+  int bz = blockIdx.z;
+  if (a.split_xcd) {
+    const int i = blockIdx.x + (int)gridDim.x * (blockIdx.y + (int)gridDim.y * blockIdx.z), xcd = i & 7, s_ = i >> 3;
+    const int KSg = gridDim.z, Q = 8 / KSg;
+    bz = xcd % KSg;
+    bx = (xcd / KSg) * ((int)gridDim.x / Q) + s_ / (int)gridDim.y;
+    by = s_ % (int)gridDim.y;
+  }
   const bool wait_ok = sk_rows > 0 || (long long)gridDim.x * gridDim.y * gridDim.z <= (long long)a.coop_wgs;
   for (int it = 0;; ++it) {
-    int tx = bx, ty = by + it * (int)gridDim.y, z = blockIdx.z, ks = gridDim.z, ncol = gridDim.x;
+    int tx = bx, ty = by + it * (int)gridDim.y, z = bz, ks = gridDim.z, ncol = gridDim.x;
     bool open_end = true;   // the items of this kind end with the first row tile that does not exist
     if (sk_rows > 0) {
       ncol = sk_cols; z = 0; ks = 1;
@@ -669,6 +681,9 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   b.merge_spins = sp ? atoi(sp) : 96;            // polls of about 1 us each
   b.xcd_order = a.grouped == GROUP_NONE && KS == 1 && grid.y > 1;
   b.stream_k = 0;
+  // K splits dealt to XCDs (see the kernel): splits that divide the 8 XCDs, whole columns of tiles per XCD
+  b.split_xcd = a.grouped == GROUP_NONE && KS > 1 && 8 % KS == 0 && col_tiles % (8 / KS) == 0 &&
+                ((long long)col_tiles * hint_tiles * KS) % 8 == 0;
   if (b.xcd_order && WC == 4 && a.tile_partials && a.coop_wgs > 0 && 2 * live == 3LL * a.coop_wgs && (a.coop_wgs & 15) == 0 && (col_tiles & 7) == 0 && (a.coop_wgs / 16) % hint_tiles == 0 &&
       live <= a.tile_counter_cap && live * 2 * (WC / 2) <= a.tile_partial_cap && nk >= 8) {
     b.stream_k = hint_tiles;   // see the kernel: 3/2 tiles per workgroup, one workgroup per compute unit

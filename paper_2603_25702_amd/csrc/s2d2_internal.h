@@ -246,6 +246,7 @@ struct GemmStreamArgs {
   int32_t merge_spins;      // set by the tile kernel's launcher: polls a K split waits for the other splits of its tile before it gives its share up
   int32_t stream_k;         // set by the tile kernel's launcher: 0, or the row tiles of a launch that runs 3/2 tiles per workgroup
   int32_t xcd_order;        // set by the tile kernel's launcher: tiles are re-dealt so that the row tiles of a column share an XCD
+  int32_t split_xcd;        // set by the tile kernel's launcher: K split z runs on the XCDs x with x % splits == z
   int32_t coop_wgs;         // compute units: a launch of at most that many workgroups of the tile kernel is resident at once (0: unknown)
   // streaming kernel, paired K split of the residual-add GEMM: pair_cap x 256 (value, tag) words, zero between
   // launches; *pair_status is set when a bounded wait ran out
