@@ -28,12 +28,12 @@ HEADLINE, OTHERS = 4, (2, 3, 5)
 # step, from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (rocprofv3 --pmc on this file with
 # the default operand mode; a plain copy of 1 GiB reads FETCH_SIZE = 524300 KiB and WRITE_SIZE = 1048576 KiB, so
 # bytes = FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024).  Averages over all GEMM launches of two steps.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31224525, 3: 100320256, 4: 236669235, 5: 352978086}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31224525, 3: 95358566, 4: 213542810, 5: 347591630}
 STEP_TRAFFIC_BYTES = {   # all kernels of a step: (FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024) summed over the step's launches
     2: (1690673.1 + 3417419.0 + 3216.1) * 2048 + (44688.0 + 56515.1 + 649.7) * 1024,
-    3: (3967059.3 + 11933104.5 + 41642.2) * 2048 + (1853746.8 + 4544816.7 + 10579.1) * 1024,
-    4: (20326843.4 + 28221173.4 + 159397.5) * 2048 + (3799021.3 + 10583106.5 + 29411.1) * 1024,
-    5: (4899115.8 + 278935.1 + 30224857.3 + 2673851.5) * 2048 + (2784093.8 + 14287.5 + 8608570.6 + 839222.2) * 1024,
+    3: (3967109.2 + 11181117.4 + 41642.0) * 2048 + (1853674.0 + 4643587.1 + 10579.1) * 1024,
+    4: (20327476.1 + 24789656.0 + 159398.2) * 2048 + (3799307.8 + 10896656.2 + 29411.1) * 1024,
+    5: (4899160.5 + 278935.0 + 29611804.2 + 2673851.1) * 2048 + (2784022.2 + 14287.5 + 8772114.3 + 839218.6) * 1024,
 }
 
 
