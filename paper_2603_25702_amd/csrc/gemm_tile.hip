@@ -469,29 +469,49 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // contiguous bytes), device-coherent write-through stores and loads around the tile's counter word (a
   // __threadfence pair per workgroup instead made the launches 60 % slower: the fences are cache-wide); 16-row
   // blocks past the tile's rows are neither written nor read.
+  //
+  // When the splits wait for each other (wait_ok), a split's own share never travels: the accumulators of units
+  // z, z + KS, ... are parked in LDS behind the operand buffers (the merge addresses them with run-time unit numbers,
+  // which registers cannot be) and only the other (KS - 1) / KS of the tile are written, and as much read back.  The
+  // write-through partials are what the tail of a split launch consists of: from the slowest split's last K step to
+  // "all partials there" 8-10 us with four splits and 17 us with eight (clock stamps of every workgroup), at 4 MB
+  // per XCD and launch.  A split that gives its share up writes it out first.
   const size_t tile_id = (size_t)ty * ncol + bx;
-  {
-    uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
+  const bool keep_own = wait_ok && !SPLIT;   // (with two planes the operand buffers leave no room)
+  constexpr int NU = RBN * FT;
+  unsigned own_mask = 0;                      // units of this split's share
+  if (keep_own)
+    for (int u = z; u < NU; u += KS) own_mask |= 1u << u;
+  uint64_t* mine = (uint64_t*)a.tile_partials + (tile_id * KS + z) * (32 * NTH) + tid;
+  uint8_t* own_lds = s_xd + 3 * XBUF + wave * 8192 + lane * 16;   // [slot][lane] 16 bytes; slot = (index of the unit in the share) * NACC + accumulator
+  auto store_partial = [&](int rb, int t, const f32x4_t& v) __attribute__((always_inline)) {
+    __hip_atomic_store(mine + ((rb * TN + t) * 2) * NTH, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mine + ((rb * TN + t) * 2 + 1) * NTH, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
 #pragma unroll
-    for (int rb = 0; rb < RBN; ++rb) {
-      if (rb * 16 >= Mloc) continue;   // uniform over the wavefront
+  for (int rb = 0; rb < RBN; ++rb) {
+    if (rb * 16 >= Mloc) continue;   // uniform over the wavefront
 #pragma unroll
-      for (int t = 0; t < TN; ++t) {
-        const f32x4_t v = acc[rb][t];
-        __hip_atomic_store(mine + ((rb * TN + t) * 2) * NTH, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(mine + ((rb * TN + t) * 2 + 1) * NTH, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+    for (int t = 0; t < TN; ++t) {
+      const int u = rb * FT + t / NACC;
+      if ((own_mask >> u) & 1) *(f32x4_t*)(own_lds + (__builtin_popcount(own_mask & ((1u << u) - 1)) * NACC + t % NACC) * 1024) = acc[rb][t];
+      else store_partial(rb, t, acc[rb][t]);
     }
   }
   __builtin_amdgcn_s_waitcnt(0);   // write-through stores completed before the arrival is counted
   __syncthreads();
   // Counter word of the tile: bits 0-7 arrivals, bits 8-15 workgroups that are done with the word (the last of them
   // clears it for the next launch), bits 16-23 shares given up (bit 16 + z: split z will not finish its share).
+  int* ctr = &a.tile_counters[tile_id];
+  auto done_with_word = [&]() __attribute__((always_inline)) {
+    const int done = __hip_atomic_fetch_add(ctr, 1 << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (((done >> 8) & 0xff) == KS - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
   if (tid == 0) {
-    int* ctr = &a.tile_counters[tile_id];
     int share = 0;
+    bool giving_up = false;
     const int prev = __hip_atomic_fetch_add(ctr, wait_ok ? 1 : 1 + (1 << (16 + z)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((prev & 0xff) == KS - 1) {
       share = (1 << z) | ((prev >> 16) & 0xff);   // the last arrival: its own share and every share given up so far
@@ -501,15 +521,33 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
         __builtin_amdgcn_s_sleep(8);
         all = (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
       }
-      if (!all)   // give the share up; if everybody has arrived in the meantime, nobody will take it: keep it
-        all = (__hip_atomic_fetch_or(ctr, 1 << (16 + z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
       if (all) share = 1 << z;
+      else giving_up = true;
     }
-    const int done = __hip_atomic_fetch_add(ctr, 1 << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (((done >> 8) & 0xff) == KS - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_share = share;
+    if (!giving_up) done_with_word();
+    s_share = giving_up ? -1 : share;
   }
   __syncthreads();
+  if (s_share < 0) {   // (uniform) give the share up: write it out of its parking place, and only then say so
+#pragma unroll
+    for (int rb = 0; rb < RBN; ++rb) {
+      if (rb * 16 >= Mloc) continue;
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        const int u = rb * FT + t / NACC;
+        if ((own_mask >> u) & 1)
+          store_partial(rb, t, *(const f32x4_t*)(own_lds + (__builtin_popcount(own_mask & ((1u << u) - 1)) * NACC + t % NACC) * 1024));
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) {   // if everybody has arrived in the meantime, nobody will take the share: keep it
+      const bool all = (__hip_atomic_fetch_or(ctr, 1 << (16 + z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) == KS;
+      done_with_word();
+      s_share = all ? 1 << z : 0;
+    }
+    __syncthreads();
+  }
   S2D2_TTS(3);
   const int share = s_share;
   if (!share) return true;
@@ -518,13 +556,14 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
   // The partials of all units of a share and of all splits are requested together (at most 128 registers) and
   // added in split order: one memory round trip per share.
   const uint64_t* src0 = (const uint64_t*)a.tile_partials + (tile_id * KS) * (32 * NTH) + tid;
-  constexpr int NU = RBN * FT;
   auto merge = [&](auto ksm_tag) __attribute__((always_inline)) {
     constexpr int KSM = decltype(ksm_tag)::value;   // KS <= KSM
     constexpr int BU = 32 / (NACC * KSM) < NU / 2 ? 32 / (NACC * KSM) : NU / 2;   // units per round: a whole share (at most NU / 2 units) within 128 registers
     for (int zs = 0; zs < KS; ++zs) {
       if (!((share >> zs) & 1)) continue;
-      for (int u0 = zs; u0 < NU; u0 += KS * BU) {
+      const bool parked = keep_own && zs == z;   // this split's own term waits in LDS
+      int slot0 = 0;
+      for (int u0 = zs; u0 < NU; u0 += KS * BU, slot0 += BU) {
         uint64_t v[BU][NACC][KSM][2];
 #pragma unroll
         for (int j = 0; j < BU; ++j) {
@@ -536,8 +575,10 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
             for (int zz = 0; zz < KSM; ++zz)
 #pragma unroll
               for (int e = 0; e < 2; ++e)
-                v[j][c][zz][e] = (ok && zz < KS) ? __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + ((rb * TN + NACC * t + c) * 2 + e) * NTH,
-                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                v[j][c][zz][e] = !(ok && zz < KS) ? 0ull
+                                 : (parked && zz == z) ? *(const uint64_t*)(own_lds + ((slot0 + j) * NACC + c) * 1024 + e * 8)
+                                 : __hip_atomic_load(src0 + (size_t)zz * (32 * NTH) + ((rb * TN + NACC * t + c) * 2 + e) * NTH,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
         for (int j = 0; j < BU; ++j) {
@@ -693,7 +734,8 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   if (b.xcd_order) grid.x = (grid.x + 7) / 8 * 8;
   const int opm = operand_mode(a.x_lo);
   // three activation tiles in LDS (54 KB; 102 KB with two planes, above the 64 KB a kernel gets without asking)
-  const unsigned lds = 3u * TM * ((opm == OPM_BF16X2 ? 256 : 128) + 16);
+  // (one plane: plus 8 KB per wavefront in which a K split parks its own share of the accumulators)
+  const unsigned lds = 3u * TM * ((opm == OPM_BF16X2 ? 256 : 128) + 16) + (opm == OPM_BF16X2 ? 0u : 2u * WC * 8192u);
   static bool lds_set[3][64];
   const int oi = opm == OPM_F16 ? 0 : opm == OPM_BF16X2 ? 1 : 2;
   int dev = 0;
