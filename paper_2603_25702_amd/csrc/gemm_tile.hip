@@ -739,7 +739,7 @@ static void launch_tile(hipStream_t st, const GemmStreamArgs& a, int row_tiles) 
   static bool lds_set[3][64];
   const int oi = opm == OPM_F16 ? 0 : opm == OPM_BF16X2 ? 1 : 2;
   int dev = 0;
-  hipGetDevice(&dev);
+  if (hipGetDevice(&dev) != hipSuccess) dev = -1;
   if (dev >= 0 && dev < 64 && !lds_set[oi][dev]) {
     const void* fn = opm == OPM_F16      ? (const void*)gemm_tile_kernel<EPI, PRO, OPM_F16, WC>
                      : opm == OPM_BF16X2 ? (const void*)gemm_tile_kernel<EPI, PRO, OPM_BF16X2, WC>
