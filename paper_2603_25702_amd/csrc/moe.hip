@@ -67,36 +67,59 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict_
 }
 
 // One workgroup: group offsets, the list of 128-row tiles, the expert-sorted slot list; re-arms the counters.
+// A thread keeps its slots' choices in registers between the two passes and requests them eight at a time (read one
+// per loop iteration, 16 K slots cost 32 dependent L2 round trips per thread); the tile list is written by one thread
+// per expert after a scan that touches LDS only.
 __global__ __launch_bounds__(1024) void moe_group_kernel(int E, int top_k, const int32_t* __restrict__ m_count,
                                                          const int32_t* __restrict__ choice,
                                                          int32_t* __restrict__ sorted, int32_t* __restrict__ tile_expert,
                                                          int32_t* __restrict__ tile_row0, int32_t* __restrict__ tile_rows,
                                                          int32_t* __restrict__ n_tiles, int tile_cap) {
-  __shared__ int s_off[MOE_MAX_E + 1];
+  __shared__ int s_off[MOE_MAX_E + 1], s_tile0[MOE_MAX_E + 1];
   __shared__ int s_cnt[MOE_MAX_E], s_fill[MOE_MAX_E];
   const int tid = threadIdx.x;
   const int total = *m_count * top_k;
+  constexpr int KEEP = 24;   // slots per thread held in registers (24 K slots); the rest is read again in the second pass
+  int mine[KEEP];
+#pragma unroll
+  for (int j0 = 0; j0 < KEEP; j0 += 8) {
+#pragma unroll
+    for (int j = j0; j < j0 + 8; ++j) mine[j] = (tid + j * 1024 < total) ? choice[tid + j * 1024] : -1;
+  }
   for (int e = tid; e < E; e += 1024) { s_cnt[e] = 0; s_fill[e] = 0; }
   __syncthreads();
-  for (int i = tid; i < total; i += 1024) atomicAdd(&s_cnt[choice[i]], 1);
+#pragma unroll
+  for (int j = 0; j < KEEP; ++j)
+    if (mine[j] >= 0) atomicAdd(&s_cnt[mine[j]], 1);
+  for (int i = tid + KEEP * 1024; i < total; i += 1024) atomicAdd(&s_cnt[choice[i]], 1);
   __syncthreads();
-  if (tid == 0) {
+  if (tid == 0) {   // offsets of the groups and of their tiles
     int run = 0, t = 0;
     for (int e = 0; e < E; ++e) {
       const int c = s_cnt[e];
       s_off[e] = run;
-      for (int r0 = 0; r0 < c && t < tile_cap; r0 += 128, ++t) {
-        tile_expert[t] = e;
-        tile_row0[t] = run + r0;
-        tile_rows[t] = min(128, c - r0);
-      }
+      s_tile0[e] = t;
       run += c;
+      t += (c + 127) >> 7;
     }
     s_off[E] = run;
-    *n_tiles = t;
+    s_tile0[E] = t;
+    *n_tiles = min(t, tile_cap);
   }
   __syncthreads();
-  for (int i = tid; i < total; i += 1024) {
+  for (int e = tid; e < E; e += 1024) {
+    const int c = s_cnt[e], run = s_off[e];
+    int t = s_tile0[e];
+    for (int r0 = 0; r0 < c && t < tile_cap; r0 += 128, ++t) {
+      tile_expert[t] = e;
+      tile_row0[t] = run + r0;
+      tile_rows[t] = min(128, c - r0);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < KEEP; ++j)
+    if (mine[j] >= 0) sorted[s_off[mine[j]] + atomicAdd(&s_fill[mine[j]], 1)] = tid + j * 1024;
+  for (int i = tid + KEEP * 1024; i < total; i += 1024) {
     const int e = choice[i];
     sorted[s_off[e] + atomicAdd(&s_fill[e], 1)] = i;
   }
