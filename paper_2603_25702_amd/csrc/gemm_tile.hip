@@ -87,9 +87,10 @@ __device__ unsigned long long g_tile_ts[1024];   // [128 + 3 id + k]: start, loo
 // One row tile (index ty) of the workgroup's column tile and K split; false: there is no such row tile.
 template <int EPI, int PRO, int OPM, int WC>
 // z of KS: this workgroup's share of K; ncol: column tiles of the launch (numbering of the tiles' counters and
-// partials); wait_ok: every workgroup of the launch is resident at once, so the splits of a tile may wait for each other.
+// partials); wait_ok: every workgroup of the launch is resident at once, so the splits of a tile may wait for each other;
+// same_rows: the row maps in LDS are already those of row tile ty (the workgroup's previous item had the same rows).
 __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const int bx, const int ty, const int z, const int KS,
-                                               const int ncol, const bool wait_ok) {
+                                               const int ncol, const bool wait_ok, const bool same_rows) {
   constexpr bool SPLIT = OPM == OPM_BF16X2;       // the activations come as two bf16 planes
   constexpr int NTH = 128 * WC;                   // 2 WC wavefronts side by side, each all 128 rows x 32 features
   constexpr int RBN = TM / 16, TN = 2;            // 16-row blocks and 16-feature accumulator columns of a wavefront
@@ -153,7 +154,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     const int r = tid / TPR, hf = tid % TPR;
     int xrow = -1, orow = -1, ssrow = 0;
     float ow = 1.f;
-    if (r < Mloc) {
+    if (r < Mloc && !same_rows) {
       const int s = m0 + r;
       if (a.grouped == GROUP_GATHER) {          // expert gate/up: X row of the token, output in sorted order
         xrow = a.sorted[s] / a.top_k; ssrow = xrow; orow = s;
@@ -167,7 +168,7 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
     // (one round up to 64 TPR partials per row), not a chain of L2 round trips
     const float* pp = PRO == SPRO_BF16S ? a.ss_part + (size_t)ssrow * a.ss_stride : nullptr;
     const bool vec = PRO == SPRO_BF16S && (a.ss_count & 3) == 0 && (a.ss_stride & 3) == 0;
-    const int n4 = (PRO == SPRO_BF16S && r < Mloc && vec) ? a.ss_count >> 2 : 0;
+    const int n4 = (PRO == SPRO_BF16S && r < Mloc && vec && !same_rows) ? a.ss_count >> 2 : 0;
     float4 t[16];
     if (PRO == SPRO_BF16S) {
 #pragma unroll
@@ -190,13 +191,13 @@ __device__ __forceinline__ bool gemm_tile_body(const GemmStreamArgs& a, const in
 #pragma unroll
         for (int j = 0; j < 16; ++j) v += (t[j].x + t[j].y) + (t[j].z + t[j].w);
       }
-      if (!vec && r < Mloc)
+      if (!vec && r < Mloc && !same_rows)
         for (int i = hf; i < a.ss_count; i += TPR) v += pp[i];
 #pragma unroll
       for (int off = 1; off < TPR; off <<= 1) v += __shfl_xor(v, off, 64);
       rs *= 1.0f / sqrtf(v / (float)a.K + a.eps);
     }
-    if (hf == 0) { s_xrow[r] = xrow; s_orow[r] = orow; s_rs[r] = rs; }
+    if (hf == 0 && !same_rows) { s_xrow[r] = xrow; s_orow[r] = orow; s_rs[r] = rs; }
   }
   __syncthreads();
 
@@ -627,9 +628,10 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
   // compute units otherwise runs two rounds, the second half empty; here every workgroup takes one tile whole and
   // then one half of K of a tile it shares with its neighbour on the XCD (workgroups w and w + 8), so both arrive at
   // the shared tile together and merge it as two splits.  Per XCD: its column tiles as in (2), tiles numbered row
-  // tile fastest; its P workgroups take the first P tiles whole and the last P / 2 as halves.  Both parts are whole
-  // columns (the host checks that the row tiles divide P / 2), so the weights of a column are read in one of the two
-  // phases only, by all its row tiles at the same time.  (With the shared tile taken out of the middle of every
+  // tile fastest; its P workgroups take the first P tiles whole and the last P / 2 as halves, a workgroup's whole tile
+  // and its half being of the same row tile, the pair of a shared tile being the workgroups of that row tile with
+  // neighbouring whole columns.  Both parts are whole columns (the host checks that the row tiles divide P / 2), so
+  // the weights of a column are read in one of the two phases only, by all its row tiles at the same time.  (With the shared tile taken out of the middle of every
   // three, each column's weights had left the XCD's L2 between the phases and came in from memory twice: 551 MB
   // fetched per launch of the 8 B model's gate / up projection against 201 MB of weights.)  In every form a
   // workgroup walks on over the row tiles past the expected ones (device-side row count above m_hint) as whole tiles.
@@ -654,23 +656,28 @@ __global__ __launch_bounds__(128 * WC, 2) void gemm_tile_kernel(const GemmStream
     by = s_ % (int)gridDim.y;
   }
   const bool wait_ok = sk_rows > 0 || (long long)gridDim.x * gridDim.y * gridDim.z <= (long long)a.coop_wgs;
+  bool did_prev = false;
   for (int it = 0;; ++it) {
     int tx = bx, ty = by + it * (int)gridDim.y, z = bz, ks = gridDim.z, ncol = gridDim.x;
     bool open_end = true;   // the items of this kind end with the first row tile that does not exist
     if (sk_rows > 0) {
       ncol = sk_cols; z = 0; ks = 1;
       if (it < 2) {
-        // XCD w % 8 owns the column tiles c % 8 == w % 8; wl: this workgroup among the P of its XCD
-        const int wl = w >> 3, P = (int)gridDim.x >> 3;
-        const int t = it == 0 ? wl : P + (wl >> 1);   // tile of this XCD's list, row tile fastest
-        tx = (t / sk_rows) * 8 + (w & 7); ty = t % sk_rows; open_end = false;
-        if (it == 1) { z = wl & 1; ks = 2; }
+        // XCD w % 8 owns the column tiles c % 8 == w % 8; wl: this workgroup among the P of its XCD, cw: the columns
+        // of its list that are taken whole.  Both items of a workgroup are of the same row tile, so the row maps
+        // (and the sums behind 1/rms) of the first serve the second.
+        const int wl = w >> 3, P = (int)gridDim.x >> 3, cw = P / sk_rows, q = wl / sk_rows;
+        ty = wl % sk_rows;
+        tx = (it == 0 ? q : cw + (q >> 1)) * 8 + (w & 7);
+        open_end = false;
+        if (it == 1) { z = q & 1; ks = 2; }
       } else {
         const int t = w + (it - 2) * (int)gridDim.x;
         tx = t % sk_cols; ty = sk_rows + t / sk_cols;
       }
     }
-    const bool did = gemm_tile_body<EPI, PRO, OPM, WC>(a, tx, ty, z, ks, ncol, wait_ok);
+    const bool did = gemm_tile_body<EPI, PRO, OPM, WC>(a, tx, ty, z, ks, ncol, wait_ok, sk_rows > 0 && it == 1 && did_prev);
+    did_prev = did;
     if (did) __syncthreads();   // the next tile reuses the LDS arrays
     else if (open_end) break;
   }
