@@ -28,11 +28,11 @@ HEADLINE, OTHERS = 4, (2, 3, 5)
 # step, from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (rocprofv3 --pmc on this file with
 # the default operand mode; a plain copy of 1 GiB reads FETCH_SIZE = 524300 KiB and WRITE_SIZE = 1048576 KiB, so
 # bytes = FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024).  Averages over all GEMM launches of two steps.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31224525, 3: 89565184, 4: 199377306, 5: 340076037}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {2: 31224525, 3: 89565184, 4: 199932416, 5: 340076037}
 STEP_TRAFFIC_BYTES = {   # all kernels of a step: (FETCH_SIZE KiB * 2048 + WRITE_SIZE KiB * 1024) summed over the step's launches
     2: (1690673.1 + 3417419.0 + 3216.1) * 2048 + (44688.0 + 56515.1 + 649.7) * 1024,
     3: (3967161.5 + 10775508.1 + 41642.3) * 2048 + (1853479.4 + 3814144.6 + 10579.1) * 1024,
-    4: (20326794.5 + 23841388.2 + 159398.6) * 2048 + (3800861.3 + 8781488.8 + 29411.1) * 1024,
+    4: (20326794.5 + 23919422.5 + 159398.6) * 2048 + (3800861.3 + 8782625.1 + 29411.1) * 1024,
     5: (4899233.2 + 278935.0 + 29215321.8 + 2673974.5) * 2048 + (2783471.0 + 14287.5 + 8082510.8 + 839212.4) * 1024,
 }
 
